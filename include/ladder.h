@@ -1,0 +1,178 @@
+/*
+ * ladder.h -- C-ABI of the MI355X (gfx950) Ladder-Residual shard forward.
+ *
+ * One context = one tensor-parallel rank's shard (or n_real_shards emulated
+ * ranks) of a stack of N Ladder-Residual Transformer layers, 2N modules
+ * (odd m = attention of layer (m+1)/2, even m = SwiGLU MLP of layer m/2), on
+ * ONE GPU.  The paper's blocking AllReduce is replaced by a local sum of the
+ * rank partial sums (computed shards + caller-supplied synthetic partials of
+ * the ranks that are not computed) that runs on an internal side stream, with
+ * HIP events playing the role of the paper's AsyncAllReduce handles
+ * (Algorithm 1).  Nothing crosses a GPU boundary.
+ *
+ * Conventions
+ *   - row-vector convention y = x W; every matrix handed in is row-major
+ *     [in_features][out_features].
+ *   - all head counts and the SwiGLU intermediate size are PER-SHARD sizes.
+ *   - "T" below = the storage dtype selected by ladder_config.dtype
+ *     (LADDER_FP32: float, LADDER_BF16: bfloat16 bit pattern in uint16).
+ *   - every pointer named "device" is a HIP device pointer of the current
+ *     device; config / weight-descriptor structs are host memory.
+ *   - calls enqueue work on the stream given to ladder_init (plus the
+ *     internal side stream, joined back before the call returns to the
+ *     stream) and return without synchronising; outputs are valid once the
+ *     caller has synchronised that stream.
+ *   - every entry point returns 0 or a negative LADDER_E_* code; nothing
+ *     throws or aborts across the boundary; a failed call leaves the
+ *     context's position unchanged.  ladder_last_error gives a text.
+ *   - a context is not thread-safe.
+ */
+#ifndef LADDER_H_
+#define LADDER_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ladder_ctx ladder_ctx; /* opaque, owned by the library */
+
+enum { LADDER_FP32 = 0, LADDER_BF16 = 1 };
+enum { LADDER_WIRING_LADDER = 0, LADDER_WIRING_STANDARD = 1 };
+enum { LADDER_PATH_AUTO = 0, LADDER_PATH_GENERIC = 1 };
+
+enum {
+  LADDER_OK = 0,
+  LADDER_E_ARG = -1,      /* null pointer, non-positive size, unknown enum */
+  LADDER_E_SHAPE = -2,    /* sizes that do not fit each other or the limits */
+  LADDER_E_STATE = -3,    /* call order: decode before prefill / load_kv, layer not loaded */
+  LADDER_E_OVERFLOW = -4, /* position + new tokens > max_seq */
+  LADDER_E_HIP = -5       /* a HIP runtime call failed (text in ladder_last_error) */
+};
+
+typedef struct {
+  int32_t n_layers;       /* N */
+  int32_t hidden;         /* H, replicated on every rank; multiple of 8 */
+  int32_t n_q_heads;      /* local query heads; multiple of n_kv_heads */
+  int32_t n_kv_heads;     /* local KV heads */
+  int32_t head_dim;       /* d, even, <= 256 */
+  int32_t inter;          /* local SwiGLU intermediate size */
+  int32_t tp_degree;      /* R */
+  int32_t n_real_shards;  /* 1..R shards computed by this context; the other R - n_real_shards
+                             ranks contribute synthetic partial sums (ladder_set_peer_partials) */
+  int32_t max_batch;      /* largest B of any call */
+  int32_t max_seq;        /* KV-cache capacity in positions per sequence */
+  int32_t max_tokens;     /* largest T of a prefill call (workspaces hold max_batch*max_tokens rows) */
+  int32_t dtype;          /* LADDER_FP32 | LADDER_BF16: storage type T of weights, inputs, KV cache, peers */
+  int32_t wiring;         /* LADDER_WIRING_LADDER: module m reads x_{m-2} (Eq. 2);
+                             LADDER_WIRING_STANDARD: module m reads x_{m-1} (Eq. 1) */
+  int32_t n_standard_layers; /* hybrid: with wiring LADDER, the first n_standard_layers layers still use
+                                the standard wiring (the paper's hybrid keeps ladder for the upper layers) */
+  int32_t reduce_on_side_stream; /* 1: reduce + residual add overlap the next module on a side stream;
+                                    0: everything in order on the caller's stream (same results) */
+  int32_t peer_pool;      /* number of distinct synthetic peer sets; module m uses set m % peer_pool */
+  int32_t peer_rows;      /* rows of each synthetic peer tensor (>= rows of any call), 0 if no peers */
+  int32_t kernel_path;    /* LADDER_PATH_AUTO: MFMA/streaming kernels when dtype and sizes allow;
+                             LADDER_PATH_GENERIC: the plain kernels (any size, both dtypes) */
+  float rms_eps;          /* RMSNorm epsilon (inside the square root) */
+  float rope_theta;       /* rotary base; pair (2j,2j+1) turns by pos * theta^(-2j/d) */
+} ladder_config;
+
+/* Device pointers to ONE shard of ONE layer (caller-owned; read only inside ladder_load_layer,
+ * which copies / repacks them; they may be freed afterwards).  Section "Tensor Parallelism
+ * Background": first matmuls are split along the output dimension, second along the input one. */
+typedef struct {
+  const void* attn_norm; /* T [H]            gain of AttentionNorm (Algorithm 1) */
+  const void* wq;        /* T [H][nq*d]      this shard's query-head columns */
+  const void* wk;        /* T [H][nkv*d] */
+  const void* wv;        /* T [H][nkv*d] */
+  const void* wo;        /* T [nq*d][H]      rows of the same query heads */
+  const void* mlp_norm;  /* T [H]            gain of MLPNorm */
+  const void* w_gate;    /* T [H][I] */
+  const void* w_up;      /* T [H][I] */
+  const void* w_down;    /* T [I][H] */
+} ladder_layer_weights;
+
+/* Creates a context: validates the configuration, allocates the repacked-weight store, the KV
+ * cache, workspaces, the side stream and events on the current device.
+ *   cfg        host pointer.
+ *   hip_stream the caller's hipStream_t (NULL = the null stream); all work is ordered on it.
+ *   out        receives the context.
+ * Errors: LADDER_E_ARG, LADDER_E_SHAPE, LADDER_E_HIP (then *out is NULL). */
+int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out);
+
+/* Copies / repacks one shard of one layer into the context (enqueued on the caller's stream).
+ * layer in [0, N), shard in [0, n_real_shards).  Every (layer, shard) must be loaded before the
+ * first forward call (else LADDER_E_STATE there). */
+int ladder_load_layer(ladder_ctx* ctx, int32_t layer, int32_t shard, const ladder_layer_weights* w);
+
+/* Synthetic partial sums of the ranks that are not computed: device T
+ * [peer_pool][R - n_real_shards][peer_rows][H], caller-owned, NOT copied: it must stay valid and
+ * unchanged while forward calls use it.  Row b*T + t of a set is added for token t of sequence b.
+ * NULL switches the peers off.  LADDER_E_SHAPE if the configuration has no peers. */
+int ladder_set_peer_partials(ladder_ctx* ctx, const void* peers);
+
+/* Fills the KV cache of (layer, shard) with caller-made content instead of a prefill:
+ * k, v device T [B][nkv][S][d] (k already rotated).  Sets the context position to S once every
+ * (layer, shard) has been given the same B and S.  LADDER_E_SHAPE / LADDER_E_OVERFLOW on misfit. */
+int ladder_load_kv(ladder_ctx* ctx, int32_t layer, int32_t shard, const void* k, const void* v,
+                   int32_t B, int32_t S);
+
+/* Prefill: resets the position to 0 and runs modules 1..2N (Eq. 2 / Algorithm 1, or Eq. 1 per the
+ * wiring) on T tokens of each of B sequences with causal attention, filling the KV cache; position
+ * becomes T.
+ *   x_in   device T   [B][T][H]  input embeddings x_0.
+ *   x_out  device f32 [B][T][H]  x_2N = residual + last attention output + last MLP output.
+ * Errors: LADDER_E_ARG, LADDER_E_SHAPE (B > max_batch, T > max_tokens, B*T > peer_rows),
+ * LADDER_E_OVERFLOW (T > max_seq), LADDER_E_STATE (a layer is not loaded), LADDER_E_HIP. */
+int ladder_prefill(ladder_ctx* ctx, const void* x_in, int32_t B, int32_t T, void* x_out);
+
+/* One decode step: one new embedding per sequence at the current position (the batch size is the
+ * one of the preceding prefill / load_kv); appends to the cache; position += 1.
+ *   x_in   device T   [B][H]
+ *   x_out  device f32 [B][H]
+ * Errors: LADDER_E_STATE (no prefill / load_kv yet), LADDER_E_OVERFLOW (cache full), others as above. */
+int ladder_decode_step(ladder_ctx* ctx, const void* x_in, void* x_out);
+
+/* Releases everything the context owns (synchronises its streams first).  NULL is a no-op. */
+void ladder_free(ladder_ctx* ctx);
+
+/* ---- helpers ---------------------------------------------------------------------------- */
+
+/* Text of the last error of this context (or of the last failed ladder_init when ctx is NULL).
+ * The pointer stays valid until the next failing call. */
+const char* ladder_last_error(const ladder_ctx* ctx);
+
+/* Current number of cached positions per sequence and current batch size (0 before any
+ * prefill / load_kv).  LADDER_E_ARG on NULL. */
+int ladder_position(const ladder_ctx* ctx, int32_t* pos, int32_t* batch);
+
+/* Device bytes the context holds (weights store + KV cache + workspaces). */
+size_t ladder_device_bytes(const ladder_ctx* ctx);
+
+/* Per-kernel timing for measurement.  With profiling on, every kernel launch is bracketed by HIP
+ * events on the stream it is launched on; ladder_profile_read synchronises, folds the events
+ * recorded since the last read into per-class totals and returns them.
+ *   cls        one of LADDER_K_*;  launches / total_ms receive the totals (may be NULL).
+ * Profiling changes no result; it slows the call (events between launches). */
+enum {
+  LADDER_K_REDUCE_NORM = 0, /* partial-sum reduce + residual add + RMSNorm (side stream) */
+  LADDER_K_GEMV = 1,        /* decode weight-streaming skinny GEMM (all four projections) */
+  LADDER_K_GEMM = 2,        /* prefill MFMA GEMM */
+  LADDER_K_ROPE_APPEND = 3,
+  LADDER_K_ATTN_DECODE = 4, /* split-KV decode attention + combine */
+  LADDER_K_ATTN_PREFILL = 5,
+  LADDER_K_GENERIC = 6,     /* plain kernels (fp32 / any-size path) */
+  LADDER_K_OTHER = 7,
+  LADDER_K_COUNT = 8
+};
+int ladder_profile_enable(ladder_ctx* ctx, int32_t on);
+int ladder_profile_read(ladder_ctx* ctx, int32_t cls, int64_t* launches, double* total_ms);
+int ladder_profile_reset(ladder_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LADDER_H_ */

@@ -1,0 +1,661 @@
+// Host side of the C-ABI: configuration checks, memory plan, weight loading, and the per-module
+// schedule of the Ladder-Residual forward (Algorithm 1 / Eq. 2) on two HIP streams.
+//
+// Schedule.  Module m (1..2N) runs on the caller's stream and writes its partial sums into
+// parts[m%2].  "AsyncAllReduce(m)" = reduce_norm on the side stream: it waits for the event recorded
+// after module m, folds the partial sums (computed shards, split-K slots, synthetic peers) into the
+// fp32 residual x in place (x_m = x_{m-1} + sum), and emits the RMS-normed input of the module(s)
+// that read x_m: module m+2 with the ladder wiring, module m+1 with the standard wiring.  The event
+// recorded after it is the handle; module m+lag waits on it.  Hence with the ladder wiring
+// reduce(m) overlaps module m+1, which is the decoupling the architecture buys.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/ladder.h"
+#include "common.h"
+
+namespace {
+
+std::string g_init_error;
+
+struct ProfRec {
+  int cls;
+  hipEvent_t start, stop;
+};
+
+struct LayerStore {
+  // generic path: raw copies, T [K][N]
+  char *wq = nullptr, *wk = nullptr, *wv = nullptr, *wo = nullptr, *wg = nullptr, *wu = nullptr, *wd = nullptr;
+  // streaming / MFMA path: packed tiles
+  char *pqkv = nullptr, *po = nullptr, *pgu = nullptr, *pd = nullptr;
+  char *cache_k = nullptr, *cache_v = nullptr;
+  bool loaded = false;
+  int kv_B = 0, kv_S = 0;
+};
+
+}  // namespace
+
+struct ladder_ctx {
+  ladder_config cfg;
+  bool bf16 = false, fast = false;
+  size_t esz = 4;
+  int n_mod = 0, n_peers = 0, s_cap = 0, rows_cap = 0, nqkv = 0;
+  hipStream_t main = nullptr, side = nullptr;
+  hipEvent_t ev_mod[2] = {nullptr, nullptr}, ev_red[2] = {nullptr, nullptr};
+  std::vector<void*> allocs;
+  size_t dev_bytes = 0;
+  std::vector<LayerStore> store;  // [layer * n_real + shard]
+  std::vector<char*> gain_attn, gain_mlp;  // per layer, T [H]
+  std::vector<char> gains_loaded;
+  float *cos_tab = nullptr, *sin_tab = nullptr;
+  const char* peers = nullptr;
+  // workspaces
+  float* x = nullptr;
+  char* y[2] = {nullptr, nullptr};
+  float* parts[2] = {nullptr, nullptr};
+  size_t parts_cap = 0;  // elements per parity buffer
+  float* qkv = nullptr;
+  size_t qkv_cap = 0;
+  char *qbuf = nullptr, *obuf = nullptr, *act = nullptr;
+  float* gu = nullptr;
+  float *att_o = nullptr, *att_ml = nullptr;
+  int pos = 0, batch = 0;
+  std::string err;
+  // profiling
+  bool prof = false;
+  std::vector<ProfRec> prof_pending;
+  std::vector<hipEvent_t> prof_pool;
+  long long prof_n[LADDER_K_COUNT] = {};
+  double prof_ms[LADDER_K_COUNT] = {};
+};
+
+namespace {
+
+int fail(ladder_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  else g_init_error = msg;
+  return code;
+}
+
+#define HIP_TRY(c, expr)                                                                        \
+  do {                                                                                          \
+    hipError_t e_ = (expr);                                                                     \
+    if (e_ != hipSuccess)                                                                       \
+      return fail((c), LADDER_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));        \
+  } while (0)
+
+int dev_alloc(ladder_ctx* c, void** p, size_t bytes, bool zero) {
+  *p = nullptr;
+  if (bytes == 0) bytes = 16;
+  HIP_TRY(c, hipMalloc(p, bytes));
+  c->allocs.push_back(*p);
+  c->dev_bytes += bytes;
+  if (zero) HIP_TRY(c, hipMemsetAsync(*p, 0, bytes, c->main));
+  return LADDER_OK;
+}
+
+// launch bracketed by profiling events when enabled
+template <typename F>
+hipError_t timed(ladder_ctx* c, int cls, hipStream_t s, F&& f) {
+  if (!c->prof) return f();
+  hipEvent_t e[2];
+  for (int i = 0; i < 2; ++i) {
+    if (!c->prof_pool.empty()) {
+      e[i] = c->prof_pool.back();
+      c->prof_pool.pop_back();
+    } else {
+      hipError_t r = hipEventCreate(&e[i]);
+      if (r != hipSuccess) return r;
+    }
+  }
+  hipError_t r = hipEventRecord(e[0], s);
+  if (r != hipSuccess) return r;
+  r = f();
+  if (r != hipSuccess) return r;
+  r = hipEventRecord(e[1], s);
+  c->prof_pending.push_back({cls, e[0], e[1]});
+  return r;
+}
+
+int lag_of(const ladder_ctx* c, int m) {  // module m reads x_{m - lag}
+  if (c->cfg.wiring == LADDER_WIRING_STANDARD) return 1;
+  return (m - 1) / 2 < c->cfg.n_standard_layers ? 1 : 2;
+}
+
+int gemv_ksplit(int N, int K, bool allow) {
+  if (!allow) return 1;
+  const int NT = N / 16, KT = K / 32;
+  int ks = 1;
+  while (NT * ks < 512 && KT / (ks * 2) >= 32 && ks < 8) ks *= 2;
+  return ks;
+}
+
+int check_config(const ladder_config* g, std::string& why) {
+  if (g->n_layers <= 0 || g->hidden <= 0 || g->n_q_heads <= 0 || g->n_kv_heads <= 0 || g->head_dim <= 0 ||
+      g->inter <= 0 || g->tp_degree <= 0 || g->n_real_shards <= 0 || g->max_batch <= 0 || g->max_seq <= 0 ||
+      g->max_tokens <= 0) {
+    why = "sizes must be positive";
+    return LADDER_E_ARG;
+  }
+  if (g->dtype != LADDER_FP32 && g->dtype != LADDER_BF16) { why = "unknown dtype"; return LADDER_E_ARG; }
+  if (g->wiring != LADDER_WIRING_LADDER && g->wiring != LADDER_WIRING_STANDARD) { why = "unknown wiring"; return LADDER_E_ARG; }
+  if (g->kernel_path != LADDER_PATH_AUTO && g->kernel_path != LADDER_PATH_GENERIC) { why = "unknown kernel_path"; return LADDER_E_ARG; }
+  if (!(g->rms_eps > 0.f) || !(g->rope_theta > 0.f)) { why = "rms_eps and rope_theta must be positive"; return LADDER_E_ARG; }
+  if (g->n_standard_layers < 0 || g->n_standard_layers > g->n_layers) { why = "n_standard_layers out of range"; return LADDER_E_SHAPE; }
+  if (g->hidden % 8) { why = "hidden must be a multiple of 8"; return LADDER_E_SHAPE; }
+  if (g->n_q_heads % g->n_kv_heads) { why = "n_q_heads must be a multiple of n_kv_heads"; return LADDER_E_SHAPE; }
+  if (g->head_dim % 2 || g->head_dim > 256) { why = "head_dim must be even and <= 256"; return LADDER_E_SHAPE; }
+  if (g->n_real_shards > g->tp_degree) { why = "n_real_shards exceeds tp_degree"; return LADDER_E_SHAPE; }
+  if (g->max_tokens > g->max_seq) { why = "max_tokens exceeds max_seq"; return LADDER_E_SHAPE; }
+  if (g->peer_pool < 0 || g->peer_rows < 0) { why = "peer_pool / peer_rows negative"; return LADDER_E_ARG; }
+  if (g->tp_degree > g->n_real_shards && g->peer_pool > 0 && g->peer_rows <= 0) { why = "peer_rows must be positive when peers are used"; return LADDER_E_SHAPE; }
+  if ((long long)g->max_batch * g->max_tokens > (1ll << 24)) { why = "max_batch * max_tokens too large"; return LADDER_E_SHAPE; }
+  return LADDER_OK;
+}
+
+bool fast_shapes_ok(const ladder_config* g) {
+  const int gq = g->n_q_heads / g->n_kv_heads;
+  return g->dtype == LADDER_BF16 && g->hidden % 32 == 0 && (g->n_q_heads * g->head_dim) % 32 == 0 &&
+         g->inter % 32 == 0 && (g->head_dim == 64 || g->head_dim == 128) &&
+         (gq == 1 || gq == 2 || gq == 4 || gq == 8);
+}
+
+int collect_profile(ladder_ctx* c) {
+  if (c->prof_pending.empty()) return LADDER_OK;
+  HIP_TRY(c, hipStreamSynchronize(c->main));
+  HIP_TRY(c, hipStreamSynchronize(c->side));
+  for (auto& r : c->prof_pending) {
+    float ms = 0.f;
+    HIP_TRY(c, hipEventElapsedTime(&ms, r.start, r.stop));
+    c->prof_n[r.cls] += 1;
+    c->prof_ms[r.cls] += ms;
+    c->prof_pool.push_back(r.start);
+    c->prof_pool.push_back(r.stop);
+  }
+  c->prof_pending.clear();
+  return LADDER_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// one module's compute on the main stream; writes parts[m%2]; returns the number of slots written
+// ---------------------------------------------------------------------------------------------
+int run_module(ladder_ctx* c, int m, int B, int T, int pos0, int* n_slots) {
+  const ladder_config& g = c->cfg;
+  const int rows = B * T, H = g.hidden, d = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, I = g.inter;
+  const int layer = (m - 1) / 2, par = m & 1;
+  const bool is_attn = (m & 1) == 1;
+  const char* yin = c->y[par];
+  float* pout = c->parts[par];
+  const size_t pstride = (size_t)rows * H;
+  hipStream_t s = c->main;
+  const bool skinny = rows <= 64;
+  int slots = 0;
+  for (int r = 0; r < g.n_real_shards; ++r) {
+    LayerStore& L = c->store[(size_t)layer * g.n_real_shards + r];
+    if (is_attn) {
+      int qkv_slots = 1;
+      if (!c->fast) {
+        const int nqd = nq * d, nkd = nkv * d;
+        HIP_TRY(c, timed(c, LADDER_K_GENERIC, s, [&] { return launch_gemm_generic(yin, L.wq, c->qkv, rows, nqd, H, c->nqkv, 0, c->bf16, s); }));
+        HIP_TRY(c, timed(c, LADDER_K_GENERIC, s, [&] { return launch_gemm_generic(yin, L.wk, c->qkv, rows, nkd, H, c->nqkv, nqd, c->bf16, s); }));
+        HIP_TRY(c, timed(c, LADDER_K_GENERIC, s, [&] { return launch_gemm_generic(yin, L.wv, c->qkv, rows, nkd, H, c->nqkv, nqd + nkd, c->bf16, s); }));
+      } else if (skinny) {
+        GemvArgs a{};
+        a.x = (const bf16_t*)yin; a.ldx = H; a.wp = L.pqkv; a.M = rows; a.K = H; a.N = c->nqkv;
+        a.ksplit = gemv_ksplit(c->nqkv, H, true);
+        a.out = c->qkv; a.out_stride = (size_t)rows * c->nqkv; a.slot0 = 0; a.epilogue = 0;
+        qkv_slots = a.ksplit;
+        HIP_TRY(c, timed(c, LADDER_K_GEMV, s, [&] { return launch_gemv(a, s); }));
+      } else {
+        GemmArgs a{};
+        a.x = (const bf16_t*)yin; a.ldx = H; a.wp = L.pqkv; a.M = rows; a.K = H; a.N = c->nqkv; a.out = c->qkv; a.epilogue = 0;
+        HIP_TRY(c, timed(c, LADDER_K_GEMM, s, [&] { return launch_gemm_mfma(a, s); }));
+      }
+      RopeAppendArgs ra{};
+      ra.qkv = c->qkv; ra.n_parts = qkv_slots; ra.part_stride = (size_t)rows * c->nqkv;
+      ra.q_out = c->qbuf; ra.cache_k = L.cache_k; ra.cache_v = L.cache_v;
+      ra.cos_tab = c->cos_tab; ra.sin_tab = c->sin_tab;
+      ra.B = B; ra.T = T; ra.pos0 = pos0; ra.nq = nq; ra.nkv = nkv; ra.d = d; ra.max_seq = c->s_cap; ra.pos_dev = nullptr;
+      HIP_TRY(c, timed(c, LADDER_K_ROPE_APPEND, s, [&] { return launch_rope_append(ra, c->bf16, s); }));
+      if (!c->fast) {
+        AttnGenericArgs aa{c->qbuf, L.cache_k, L.cache_v, c->obuf, B, T, pos0, nq, nkv, d, c->s_cap};
+        HIP_TRY(c, timed(c, LADDER_K_GENERIC, s, [&] { return launch_attn_generic(aa, c->bf16, s); }));
+      } else if (T == 1) {
+        AttnDecodeArgs aa{};
+        aa.q = (const bf16_t*)c->qbuf; aa.cache_k = (const bf16_t*)L.cache_k; aa.cache_v = (const bf16_t*)L.cache_v;
+        aa.part_o = c->att_o; aa.part_ml = c->att_ml; aa.o = (bf16_t*)c->obuf;
+        aa.B = B; aa.nq = nq; aa.nkv = nkv; aa.d = d; aa.max_seq = c->s_cap; aa.n_pos = pos0 + 1;
+        int chunk = 32;
+        for (int cand : {128, 64}) {
+          if ((long long)B * nkv * ((aa.n_pos + cand - 1) / cand) >= 256) { chunk = cand; break; }
+        }
+        aa.chunk = chunk; aa.n_chunks = (aa.n_pos + chunk - 1) / chunk; aa.pos_dev = nullptr;
+        HIP_TRY(c, timed(c, LADDER_K_ATTN_DECODE, s, [&] { return launch_attn_decode(aa, s); }));
+      } else {
+        AttnPrefillArgs aa{(const bf16_t*)c->qbuf, (const bf16_t*)L.cache_k, (const bf16_t*)L.cache_v,
+                           (bf16_t*)c->obuf, B, T, pos0, nq, nkv, d, c->s_cap};
+        HIP_TRY(c, timed(c, LADDER_K_ATTN_PREFILL, s, [&] { return launch_attn_prefill(aa, s); }));
+      }
+      const int nqd = nq * d;
+      if (!c->fast) {
+        HIP_TRY(c, timed(c, LADDER_K_GENERIC, s, [&] { return launch_gemm_generic(c->obuf, L.wo, pout + slots * pstride, rows, H, nqd, H, 0, c->bf16, s); }));
+        slots += 1;
+      } else if (skinny) {
+        GemvArgs a{};
+        a.x = (const bf16_t*)c->obuf; a.ldx = nqd; a.wp = L.po; a.M = rows; a.K = nqd; a.N = H;
+        a.ksplit = gemv_ksplit(H, nqd, true);
+        a.out = pout; a.out_stride = pstride; a.slot0 = slots; a.epilogue = 0;
+        HIP_TRY(c, timed(c, LADDER_K_GEMV, s, [&] { return launch_gemv(a, s); }));
+        slots += a.ksplit;
+      } else {
+        GemmArgs a{};
+        a.x = (const bf16_t*)c->obuf; a.ldx = nqd; a.wp = L.po; a.M = rows; a.K = nqd; a.N = H; a.out = pout + slots * pstride; a.epilogue = 0;
+        HIP_TRY(c, timed(c, LADDER_K_GEMM, s, [&] { return launch_gemm_mfma(a, s); }));
+        slots += 1;
+      }
+    } else {
+      if (!c->fast) {
+        HIP_TRY(c, timed(c, LADDER_K_GENERIC, s, [&] { return launch_gemm_generic(yin, L.wg, c->gu, rows, I, H, 2 * I, 0, c->bf16, s); }));
+        HIP_TRY(c, timed(c, LADDER_K_GENERIC, s, [&] { return launch_gemm_generic(yin, L.wu, c->gu, rows, I, H, 2 * I, I, c->bf16, s); }));
+        HIP_TRY(c, timed(c, LADDER_K_GENERIC, s, [&] { return launch_swiglu(c->gu, c->act, rows, I, c->bf16, s); }));
+        HIP_TRY(c, timed(c, LADDER_K_GENERIC, s, [&] { return launch_gemm_generic(c->act, L.wd, pout + slots * pstride, rows, H, I, H, 0, c->bf16, s); }));
+        slots += 1;
+      } else if (skinny) {
+        GemvArgs a{};
+        a.x = (const bf16_t*)yin; a.ldx = H; a.wp = L.pgu; a.M = rows; a.K = H; a.N = 2 * I; a.ksplit = 1;
+        a.act = (bf16_t*)c->act; a.epilogue = 1;
+        HIP_TRY(c, timed(c, LADDER_K_GEMV, s, [&] { return launch_gemv(a, s); }));
+        GemvArgs b{};
+        b.x = (const bf16_t*)c->act; b.ldx = I; b.wp = L.pd; b.M = rows; b.K = I; b.N = H;
+        b.ksplit = gemv_ksplit(H, I, true);
+        b.out = pout; b.out_stride = pstride; b.slot0 = slots; b.epilogue = 0;
+        HIP_TRY(c, timed(c, LADDER_K_GEMV, s, [&] { return launch_gemv(b, s); }));
+        slots += b.ksplit;
+      } else {
+        GemmArgs a{};
+        a.x = (const bf16_t*)yin; a.ldx = H; a.wp = L.pgu; a.M = rows; a.K = H; a.N = 2 * I; a.act = (bf16_t*)c->act; a.epilogue = 1;
+        HIP_TRY(c, timed(c, LADDER_K_GEMM, s, [&] { return launch_gemm_mfma(a, s); }));
+        GemmArgs b{};
+        b.x = (const bf16_t*)c->act; b.ldx = I; b.wp = L.pd; b.M = rows; b.K = I; b.N = H; b.out = pout + slots * pstride; b.epilogue = 0;
+        HIP_TRY(c, timed(c, LADDER_K_GEMM, s, [&] { return launch_gemm_mfma(b, s); }));
+        slots += 1;
+      }
+    }
+  }
+  *n_slots = slots;
+  return LADDER_OK;
+}
+
+// reduce(m): x += partial sums of module m (+ peers); emit the normed inputs of the modules that read x_m.
+// m == 0: x = emb, emit inputs of the modules that read x_0.
+int run_reduce(ladder_ctx* c, int m, int rows, int n_slots, const void* emb, float* x_out, hipStream_t s) {
+  const ladder_config& g = c->cfg;
+  ReduceNormArgs a{};
+  a.x = c->x; a.emb = emb; a.rows = rows; a.H = g.hidden; a.eps = g.rms_eps;
+  if (m > 0) {
+    a.parts = c->parts[m & 1]; a.n_parts = n_slots; a.part_stride = (size_t)rows * g.hidden;
+    if (c->peers && c->n_peers > 0) {
+      const size_t set = (size_t)(m % g.peer_pool);
+      a.peers = c->peers + set * c->n_peers * (size_t)g.peer_rows * g.hidden * c->esz;
+      a.n_peers = c->n_peers; a.peer_stride = (size_t)g.peer_rows * g.hidden;
+    }
+  }
+  // consumers of x_m: module m+1 if its lag is 1 (m == 0: module 1 always), module m+2 if its lag is 2
+  // (m == 0: module 2 always -- modules 1 and 2 both read x_0)
+  int consumers[2], nc = 0;
+  if (m + 1 <= c->n_mod && (m == 0 || lag_of(c, m + 1) == 1)) consumers[nc++] = m + 1;
+  if (m + 2 <= c->n_mod && ((m == 0 && lag_of(c, 2) == 2) || (m > 0 && lag_of(c, m + 2) == 2))) consumers[nc++] = m + 2;
+  for (int i = 0; i < nc; ++i) {
+    const int cm = consumers[i], layer = (cm - 1) / 2;
+    void* out = c->y[cm & 1];
+    const void* gain = (cm & 1) ? c->gain_attn[layer] : c->gain_mlp[layer];
+    if (i == 0) { a.out_a = out; a.gain_a = gain; }
+    else { a.out_b = out; a.gain_b = gain; }
+  }
+  a.x_out = x_out;
+  HIP_TRY(c, timed(c, LADDER_K_REDUCE_NORM, s, [&] { return launch_reduce_norm(a, c->bf16, s); }));
+  return LADDER_OK;
+}
+
+int forward(ladder_ctx* c, const void* x_in, int B, int T, int pos0, void* x_out) {
+  const int rows = B * T;
+  const bool side = c->cfg.reduce_on_side_stream != 0;
+  int rc = run_reduce(c, 0, rows, 0, x_in, c->n_mod == 0 ? (float*)x_out : nullptr, c->main);
+  if (rc) return rc;
+  for (int m = 1; m <= c->n_mod; ++m) {
+    const int src = m - lag_of(c, m);
+    if (side && src >= 1) HIP_TRY(c, hipStreamWaitEvent(c->main, c->ev_red[src & 1], 0));
+    int n_slots = 0;
+    rc = run_module(c, m, B, T, pos0, &n_slots);
+    if (rc) return rc;
+    hipStream_t rs = c->main;
+    if (side) {
+      HIP_TRY(c, hipEventRecord(c->ev_mod[m & 1], c->main));
+      HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_mod[m & 1], 0));
+      rs = c->side;
+    }
+    rc = run_reduce(c, m, rows, n_slots, nullptr, m == c->n_mod ? (float*)x_out : nullptr, rs);
+    if (rc) return rc;
+    if (side) HIP_TRY(c, hipEventRecord(c->ev_red[m & 1], c->side));
+  }
+  if (side) HIP_TRY(c, hipStreamWaitEvent(c->main, c->ev_red[c->n_mod & 1], 0));  // join
+  return LADDER_OK;
+}
+
+int all_loaded(ladder_ctx* c) {
+  for (auto& L : c->store)
+    if (!L.loaded) return fail(c, LADDER_E_STATE, "a (layer, shard) has not been given to ladder_load_layer");
+  for (char v : c->gains_loaded)
+    if (!v) return fail(c, LADDER_E_STATE, "norm gains missing: shard 0 of a layer has not been loaded");
+  return LADDER_OK;
+}
+
+}  // namespace
+
+// =================================================================================================
+extern "C" {
+
+int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !out) return fail(nullptr, LADDER_E_ARG, "null argument");
+  std::string why;
+  int rc = check_config(cfg, why);
+  if (rc) return fail(nullptr, rc, why);
+  ladder_ctx* c = new ladder_ctx();
+  c->cfg = *cfg;
+  const ladder_config& g = c->cfg;
+  c->bf16 = g.dtype == LADDER_BF16;
+  c->esz = c->bf16 ? 2 : 4;
+  c->fast = g.kernel_path == LADDER_PATH_AUTO && fast_shapes_ok(cfg);
+  c->n_mod = 2 * g.n_layers;
+  c->n_peers = (g.peer_pool > 0) ? g.tp_degree - g.n_real_shards : 0;
+  c->s_cap = (g.max_seq + 127) / 128 * 128;
+  c->rows_cap = g.max_batch * g.max_tokens;
+  c->nqkv = (g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim;
+  c->main = (hipStream_t)hip_stream;
+
+  auto bail = [&](int code) {
+    std::string msg = c->err;
+    ladder_free(c);
+    g_init_error = msg;
+    return code;
+  };
+#define INIT_TRY(expr)          \
+  do {                          \
+    int rc_ = (expr);           \
+    if (rc_) return bail(rc_);  \
+  } while (0)
+#define INIT_HIP(expr)                                                                       \
+  do {                                                                                       \
+    hipError_t e_ = (expr);                                                                  \
+    if (e_ != hipSuccess) {                                                                  \
+      c->err = std::string(#expr) + ": " + hipGetErrorString(e_);                            \
+      return bail(LADDER_E_HIP);                                                             \
+    }                                                                                        \
+  } while (0)
+
+  INIT_HIP(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+  for (int i = 0; i < 2; ++i) {
+    INIT_HIP(hipEventCreateWithFlags(&c->ev_mod[i], hipEventDisableTiming));
+    INIT_HIP(hipEventCreateWithFlags(&c->ev_red[i], hipEventDisableTiming));
+  }
+  const int H = g.hidden, d = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, I = g.inter;
+  const size_t esz = c->esz;
+  c->store.resize((size_t)g.n_layers * g.n_real_shards);
+  c->gain_attn.resize(g.n_layers);
+  c->gain_mlp.resize(g.n_layers);
+  c->gains_loaded.assign(g.n_layers, 0);
+
+  // weights: one allocation for the whole model
+  size_t per_shard;
+  if (c->fast) {
+    per_shard = packed_tiles_bytes(H, c->nqkv) + packed_tiles_bytes(nq * d, H) + packed_tiles_bytes(H, 2 * I) +
+                packed_tiles_bytes(I, H);
+  } else {
+    per_shard = ((size_t)H * c->nqkv + (size_t)nq * d * H + 3 * (size_t)H * I) * esz;
+    per_shard = (per_shard + 255) / 256 * 256;
+  }
+  char* wbase = nullptr;
+  INIT_TRY(dev_alloc(c, (void**)&wbase, per_shard * c->store.size(), false));
+  char* gbase = nullptr;
+  INIT_TRY(dev_alloc(c, (void**)&gbase, (size_t)g.n_layers * 2 * H * esz, false));
+  // KV cache: K rows [B][nkv][s_cap][d]; V transposed [B][nkv][d][s_cap]; zero-filled so that no
+  // kernel ever reads an uninitialised bit pattern
+  const size_t kv_one = (size_t)g.max_batch * nkv * c->s_cap * d * esz;
+  char* kvbase = nullptr;
+  INIT_TRY(dev_alloc(c, (void**)&kvbase, kv_one * 2 * c->store.size(), true));
+  for (size_t i = 0; i < c->store.size(); ++i) {
+    LayerStore& L = c->store[i];
+    char* p = wbase + per_shard * i;
+    if (c->fast) {
+      L.pqkv = p; p += packed_tiles_bytes(H, c->nqkv);
+      L.po = p; p += packed_tiles_bytes(nq * d, H);
+      L.pgu = p; p += packed_tiles_bytes(H, 2 * I);
+      L.pd = p;
+    } else {
+      L.wq = p; p += (size_t)H * nq * d * esz;
+      L.wk = p; p += (size_t)H * nkv * d * esz;
+      L.wv = p; p += (size_t)H * nkv * d * esz;
+      L.wo = p; p += (size_t)nq * d * H * esz;
+      L.wg = p; p += (size_t)H * I * esz;
+      L.wu = p; p += (size_t)H * I * esz;
+      L.wd = p;
+    }
+    L.cache_k = kvbase + kv_one * 2 * i;
+    L.cache_v = L.cache_k + kv_one;
+  }
+  for (int l = 0; l < g.n_layers; ++l) {
+    c->gain_attn[l] = gbase + (size_t)(2 * l) * H * esz;
+    c->gain_mlp[l] = gbase + (size_t)(2 * l + 1) * H * esz;
+  }
+  // rotary tables, made on the host in double precision
+  {
+    const int half = d / 2;
+    std::vector<float> ct((size_t)c->s_cap * half), st((size_t)c->s_cap * half);
+    for (int j = 0; j < half; ++j) {
+      const double inv_freq = pow((double)g.rope_theta, -2.0 * j / (double)d);
+      for (int p = 0; p < c->s_cap; ++p) {
+        const double ang = (double)p * inv_freq;
+        ct[(size_t)p * half + j] = (float)cos(ang);
+        st[(size_t)p * half + j] = (float)sin(ang);
+      }
+    }
+    INIT_TRY(dev_alloc(c, (void**)&c->cos_tab, ct.size() * 4, false));
+    INIT_TRY(dev_alloc(c, (void**)&c->sin_tab, st.size() * 4, false));
+    INIT_HIP(hipMemcpy(c->cos_tab, ct.data(), ct.size() * 4, hipMemcpyHostToDevice));
+    INIT_HIP(hipMemcpy(c->sin_tab, st.data(), st.size() * 4, hipMemcpyHostToDevice));
+  }
+  // workspaces
+  // rows x slots of the partial-sum buffers: a skinny call (rows <= 64) may use up to 8 split-K slots
+  // per shard, a wide call uses one
+  const size_t rows = (size_t)c->rows_cap;
+  const size_t skinny_rows = rows < 64 ? rows : 64;
+  const size_t row_slots = rows > 8 * skinny_rows ? rows : 8 * skinny_rows;
+  INIT_TRY(dev_alloc(c, (void**)&c->x, rows * H * 4, false));
+  for (int i = 0; i < 2; ++i) INIT_TRY(dev_alloc(c, (void**)&c->y[i], rows * H * esz, false));
+  c->parts_cap = (size_t)g.n_real_shards * H * row_slots;
+  for (int i = 0; i < 2; ++i) INIT_TRY(dev_alloc(c, (void**)&c->parts[i], c->parts_cap * 4, false));
+  c->qkv_cap = (size_t)c->nqkv * row_slots;
+  INIT_TRY(dev_alloc(c, (void**)&c->qkv, c->qkv_cap * 4, false));
+  INIT_TRY(dev_alloc(c, (void**)&c->qbuf, rows * nq * d * esz, false));
+  INIT_TRY(dev_alloc(c, (void**)&c->obuf, rows * nq * d * esz, false));
+  INIT_TRY(dev_alloc(c, (void**)&c->act, rows * I * esz, false));
+  if (!c->fast) INIT_TRY(dev_alloc(c, (void**)&c->gu, rows * 2 * I * 4, false));
+  if (c->fast) {
+    const size_t chunks = (size_t)(c->s_cap / 32);
+    const size_t gq = nq / nkv;
+    INIT_TRY(dev_alloc(c, (void**)&c->att_o, (size_t)g.max_batch * nkv * chunks * gq * d * 4, false));
+    INIT_TRY(dev_alloc(c, (void**)&c->att_ml, (size_t)g.max_batch * nkv * chunks * gq * 2 * 4, false));
+  }
+#undef INIT_TRY
+#undef INIT_HIP
+  *out = c;
+  return LADDER_OK;
+}
+
+int ladder_load_layer(ladder_ctx* c, int32_t layer, int32_t shard, const ladder_layer_weights* w) {
+  if (!c) return LADDER_E_ARG;
+  if (!w || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_gate || !w->w_up || !w->w_down)
+    return fail(c, LADDER_E_ARG, "null weight pointer");
+  const ladder_config& g = c->cfg;
+  if (layer < 0 || layer >= g.n_layers || shard < 0 || shard >= g.n_real_shards)
+    return fail(c, LADDER_E_SHAPE, "layer / shard out of range");
+  if (shard == 0 && (!w->attn_norm || !w->mlp_norm)) return fail(c, LADDER_E_ARG, "null gain pointer");
+  const int H = g.hidden, d = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, I = g.inter;
+  const size_t esz = c->esz;
+  LayerStore& L = c->store[(size_t)layer * g.n_real_shards + shard];
+  hipStream_t s = c->main;
+  if (shard == 0) {
+    HIP_TRY(c, hipMemcpyAsync(c->gain_attn[layer], w->attn_norm, H * esz, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(c->gain_mlp[layer], w->mlp_norm, H * esz, hipMemcpyDeviceToDevice, s));
+    c->gains_loaded[layer] = 1;
+  }
+  if (c->fast) {
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wq, L.pqkv, H, nq * d, c->nqkv, 0, 0, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wk, L.pqkv, H, nkv * d, c->nqkv, nq * d, 0, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wv, L.pqkv, H, nkv * d, c->nqkv, (nq + nkv) * d, 0, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wo, L.po, nq * d, H, H, 0, 0, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_gate, L.pgu, H, I, 2 * I, 0, 1, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_up, L.pgu, H, I, 2 * I, 0, 2, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_down, L.pd, I, H, H, 0, 0, s));
+  } else {
+    HIP_TRY(c, hipMemcpyAsync(L.wq, w->wq, (size_t)H * nq * d * esz, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(L.wk, w->wk, (size_t)H * nkv * d * esz, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(L.wv, w->wv, (size_t)H * nkv * d * esz, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(L.wo, w->wo, (size_t)nq * d * H * esz, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(L.wg, w->w_gate, (size_t)H * I * esz, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(L.wu, w->w_up, (size_t)H * I * esz, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(L.wd, w->w_down, (size_t)I * H * esz, hipMemcpyDeviceToDevice, s));
+  }
+  L.loaded = true;
+  return LADDER_OK;
+}
+
+int ladder_set_peer_partials(ladder_ctx* c, const void* peers) {
+  if (!c) return LADDER_E_ARG;
+  if (peers && c->n_peers == 0) return fail(c, LADDER_E_SHAPE, "this configuration has no synthetic peers");
+  c->peers = (const char*)peers;
+  return LADDER_OK;
+}
+
+int ladder_load_kv(ladder_ctx* c, int32_t layer, int32_t shard, const void* k, const void* v, int32_t B, int32_t S) {
+  if (!c) return LADDER_E_ARG;
+  if (!k || !v) return fail(c, LADDER_E_ARG, "null k / v");
+  const ladder_config& g = c->cfg;
+  if (layer < 0 || layer >= g.n_layers || shard < 0 || shard >= g.n_real_shards)
+    return fail(c, LADDER_E_SHAPE, "layer / shard out of range");
+  if (B <= 0 || B > g.max_batch || S <= 0) return fail(c, LADDER_E_SHAPE, "B or S out of range");
+  if (S > g.max_seq) return fail(c, LADDER_E_OVERFLOW, "S exceeds max_seq");
+  LayerStore& L = c->store[(size_t)layer * g.n_real_shards + shard];
+  HIP_TRY(c, launch_load_kv(k, v, L.cache_k, L.cache_v, B, g.n_kv_heads, S, g.head_dim, c->s_cap, c->bf16, c->main));
+  L.kv_B = B;
+  L.kv_S = S;
+  bool all = true;
+  for (auto& X : c->store) all = all && X.kv_B == B && X.kv_S == S;
+  if (all) {
+    c->pos = S;
+    c->batch = B;
+  }
+  return LADDER_OK;
+}
+
+int ladder_prefill(ladder_ctx* c, const void* x_in, int32_t B, int32_t T, void* x_out) {
+  if (!c) return LADDER_E_ARG;
+  if (!x_in || !x_out) return fail(c, LADDER_E_ARG, "null x_in / x_out");
+  const ladder_config& g = c->cfg;
+  if (B <= 0 || T <= 0) return fail(c, LADDER_E_ARG, "B and T must be positive");
+  if (B > g.max_batch) return fail(c, LADDER_E_SHAPE, "B exceeds max_batch");
+  if (T > g.max_seq) return fail(c, LADDER_E_OVERFLOW, "T exceeds max_seq");
+  if (T > g.max_tokens) return fail(c, LADDER_E_SHAPE, "T exceeds max_tokens");
+  if (c->peers && B * T > g.peer_rows) return fail(c, LADDER_E_SHAPE, "B*T exceeds peer_rows");
+  int rc = all_loaded(c);
+  if (rc) return rc;
+  rc = forward(c, x_in, B, T, 0, x_out);
+  if (rc) return rc;
+  for (auto& X : c->store) { X.kv_B = 0; X.kv_S = 0; }
+  c->pos = T;
+  c->batch = B;
+  return LADDER_OK;
+}
+
+int ladder_decode_step(ladder_ctx* c, const void* x_in, void* x_out) {
+  if (!c) return LADDER_E_ARG;
+  if (!x_in || !x_out) return fail(c, LADDER_E_ARG, "null x_in / x_out");
+  if (c->batch <= 0 || c->pos <= 0) return fail(c, LADDER_E_STATE, "decode before prefill / load_kv");
+  if (c->pos + 1 > c->cfg.max_seq) return fail(c, LADDER_E_OVERFLOW, "KV cache is full");
+  if (c->peers && c->batch > c->cfg.peer_rows) return fail(c, LADDER_E_SHAPE, "batch exceeds peer_rows");
+  int rc = all_loaded(c);
+  if (rc) return rc;
+  rc = forward(c, x_in, c->batch, 1, c->pos, x_out);
+  if (rc) return rc;
+  c->pos += 1;
+  return LADDER_OK;
+}
+
+void ladder_free(ladder_ctx* c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->main);
+  if (c->side) {
+    (void)hipStreamSynchronize(c->side);
+    (void)hipStreamDestroy(c->side);
+  }
+  for (auto& r : c->prof_pending) {
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  for (auto e : c->prof_pool) (void)hipEventDestroy(e);
+  for (int i = 0; i < 2; ++i) {
+    if (c->ev_mod[i]) (void)hipEventDestroy(c->ev_mod[i]);
+    if (c->ev_red[i]) (void)hipEventDestroy(c->ev_red[i]);
+  }
+  for (void* p : c->allocs) (void)hipFree(p);
+  delete c;
+}
+
+const char* ladder_last_error(const ladder_ctx* c) { return c ? c->err.c_str() : g_init_error.c_str(); }
+
+int ladder_position(const ladder_ctx* c, int32_t* pos, int32_t* batch) {
+  if (!c) return LADDER_E_ARG;
+  if (pos) *pos = c->pos;
+  if (batch) *batch = c->batch;
+  return LADDER_OK;
+}
+
+size_t ladder_device_bytes(const ladder_ctx* c) { return c ? c->dev_bytes : 0; }
+
+int ladder_profile_enable(ladder_ctx* c, int32_t on) {
+  if (!c) return LADDER_E_ARG;
+  if (!on) {
+    int rc = collect_profile(c);
+    if (rc) return rc;
+  }
+  c->prof = on != 0;
+  return LADDER_OK;
+}
+
+int ladder_profile_read(ladder_ctx* c, int32_t cls, int64_t* launches, double* total_ms) {
+  if (!c) return LADDER_E_ARG;
+  if (cls < 0 || cls >= LADDER_K_COUNT) return fail(c, LADDER_E_ARG, "unknown kernel class");
+  int rc = collect_profile(c);
+  if (rc) return rc;
+  if (launches) *launches = c->prof_n[cls];
+  if (total_ms) *total_ms = c->prof_ms[cls];
+  return LADDER_OK;
+}
+
+int ladder_profile_reset(ladder_ctx* c) {
+  if (!c) return LADDER_E_ARG;
+  int rc = collect_profile(c);
+  if (rc) return rc;
+  for (int i = 0; i < LADDER_K_COUNT; ++i) {
+    c->prof_n[i] = 0;
+    c->prof_ms[i] = 0.0;
+  }
+  return LADDER_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,302 @@
+// Prefill-shape kernels of the bf16 path (gfx950): MFMA GEMM on the packed weight tiles and causal
+// GQA flash attention over the cache, both on v_mfma_f32_16x16x32_bf16.
+#include "common.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+
+__device__ __forceinline__ f32x4_t mfma16(const uint4 a, const uint4 b, const f32x4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
+                                                 0, 0, 0);
+}
+
+// ------------------------------------------------------------------------------------------------
+// C[M][N] = X[M][K] W[K][N].  Workgroup tile: BM = 16*WM rows x 256 columns, 4 wavefronts side by
+// side along N (64 columns = 4 weight tiles each).  The weights are the MFMA A operand and come
+// straight from global memory in their packed tile order (1 KiB coalesced per wave load, each tile
+// read by exactly one wave of the workgroup); the activations are the B operand, staged once per
+// workgroup through double-buffered LDS and shared by the 4 waves.  Output element (m, n) sits in
+// lane (n%16)/4*16 + m%16, register n%4, so a lane stores 4 consecutive columns.
+// ------------------------------------------------------------------------------------------------
+#define GEMM_BK 64
+#define GEMM_LDS_STRIDE (GEMM_BK + 8)  // bf16 elements per LDS row (pad against bank conflicts)
+#define GEMM_GROUP_M 16
+
+template <int WM>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
+  constexpr int BM = 16 * WM;
+  constexpr int XV = BM * 8 / 256;  // uint4 per thread per K step of the X tile
+  __shared__ __attribute__((aligned(16))) bf16_t xs[2][BM][GEMM_LDS_STRIDE];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int b = lane & 15, q = lane >> 4;
+  const int KT = a.K >> 5, NT = a.N >> 4;
+  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + 255) / 256;
+  // grouped rasterisation: GROUP_M row blocks share one column block back to back
+  const int per_group = GEMM_GROUP_M * tiles_n;
+  const int group = blockIdx.x / per_group, in_group = blockIdx.x % per_group;
+  const int gm = min(GEMM_GROUP_M, tiles_m - group * GEMM_GROUP_M);
+  const int m_blk = group * GEMM_GROUP_M + in_group % gm;
+  const int n_blk = in_group / gm;
+  const int m0 = m_blk * BM;
+  const int nt0 = n_blk * 16 + wave * 4;
+
+  f32x4_t acc[4][WM];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int mt = 0; mt < WM; ++mt) acc[j][mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  const uint4* wp = reinterpret_cast<const uint4*>(a.wp);
+  uint4 xg[XV];
+  uint4 w0[4][2], w1[4][2];
+
+  auto load_x = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < XV; ++i) {
+      const int idx = tid + i * 256, row = idx >> 3, seg = idx & 7;
+      const int m = m0 + row, k = k0 + seg * 8;
+      xg[i] = (m < a.M && k < a.K) ? *reinterpret_cast<const uint4*>(a.x + (size_t)m * a.ldx + k) : zero4;
+    }
+  };
+  auto store_x = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < XV; ++i) {
+      const int idx = tid + i * 256, row = idx >> 3, seg = idx & 7;
+      *reinterpret_cast<uint4*>(&xs[buf][row][seg * 8]) = xg[i];
+    }
+  };
+  auto load_w = [&](uint4 (&w)[4][2], int kt) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+        w[j][s] = (nt0 + j < NT && kt + s < KT) ? wp[((size_t)(nt0 + j) * KT + kt + s) * 64 + lane] : zero4;
+  };
+  auto compute = [&](const uint4 (&w)[4][2], int buf) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int mt = 0; mt < WM; ++mt) {
+        const uint4 xb = *reinterpret_cast<const uint4*>(&xs[buf][mt * 16 + b][s * 32 + q * 8]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j][mt] = mfma16(w[j][s], xb, acc[j][mt]);
+      }
+  };
+
+  const int nsteps = (a.K + GEMM_BK - 1) / GEMM_BK;
+  load_x(0);
+  load_w(w0, 0);
+  store_x(0);
+  __syncthreads();
+  for (int it = 0; it < nsteps; it += 2) {
+    // even step: operands in w0 / buffer 0, prefetch into w1 / buffer 1
+    const bool more1 = it + 1 < nsteps;
+    if (more1) { load_x((it + 1) * GEMM_BK); load_w(w1, (it + 1) * 2); }
+    compute(w0, 0);
+    if (more1) store_x(1);
+    __syncthreads();
+    if (!more1) break;
+    const bool more2 = it + 2 < nsteps;
+    if (more2) { load_x((it + 2) * GEMM_BK); load_w(w0, (it + 2) * 2); }
+    compute(w1, 1);
+    if (more2) store_x(0);
+    __syncthreads();
+  }
+
+  if (a.epilogue == 0) {
+#pragma unroll
+    for (int mt = 0; mt < WM; ++mt) {
+      const int m = m0 + mt * 16 + b;
+      if (m >= a.M) continue;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (nt0 + j >= NT) continue;
+        const int n = (nt0 + j) * 16 + 4 * q;
+        *reinterpret_cast<float4*>(a.out + (size_t)m * a.N + n) =
+            make_float4(acc[j][mt][0], acc[j][mt][1], acc[j][mt][2], acc[j][mt][3]);
+      }
+    }
+  } else {
+    // SwiGLU: tile columns 0..7 = gate columns 8nt..8nt+7 (lanes q = 0, 1), columns 8..15 = the matching
+    // up columns (lanes q = 2, 3): lane + 32 holds the up partner of this lane's gate value.
+    const int I = a.N >> 1;
+#pragma unroll
+    for (int mt = 0; mt < WM; ++mt) {
+      const int m = m0 + mt * 16 + b;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float r4[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float g = acc[j][mt][r];
+          const float u = __shfl(acc[j][mt][r], (lane + 32) & 63, 64);
+          r4[r] = g / (1.0f + __expf(-g)) * u;
+        }
+        if (q < 2 && m < a.M && nt0 + j < NT) {
+          uint2 pk;
+          pk.x = (uint32_t)f32_to_bf16(r4[0]) | ((uint32_t)f32_to_bf16(r4[1]) << 16);
+          pk.y = (uint32_t)f32_to_bf16(r4[2]) | ((uint32_t)f32_to_bf16(r4[3]) << 16);
+          *reinterpret_cast<uint2*>(a.act + (size_t)m * I + (nt0 + j) * 8 + 4 * q) = pk;
+        }
+      }
+    }
+  }
+}
+
+hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
+  if (a.M <= 0 || (a.K & 31) || (a.N & 15)) return hipErrorInvalidValue;
+  const int tiles_n = (a.N + 255) / 256;
+  if (a.M > 64) {
+    const int tiles_m = (a.M + 127) / 128;
+    hipLaunchKernelGGL(gemm_mfma_kernel<8>, dim3(tiles_m * tiles_n), dim3(256), 0, s, a);
+  } else {
+    const int tiles_m = (a.M + 63) / 64;
+    hipLaunchKernelGGL(gemm_mfma_kernel<4>, dim3(tiles_m * tiles_n), dim3(256), 0, s, a);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Causal GQA flash attention for T new tokens per sequence over the cache (which already holds
+// them).  Everything is computed transposed so that no operand needs a shuffle:
+//   S^T[key][query] = K Q^T       A = K tile (16 keys x 32 dims, straight from the row-major K cache),
+//                                 B = Q^T (16 queries x 32 dims, kept in registers);
+//   a lane then owns, for ITS query (lane%16), keys 4*(lane/16)+r of each 16-key tile: the softmax
+//   statistics of a query need two shuffles, and the lane's 8 probabilities of a 32-key block are,
+//   as they stand, the B operand of
+//   O^T[dim][query] = V^T P^T     A = V^T tile (16 dims x 32 keys) from the transposed V cache, with
+//                                 the same key order (two 8-byte loads per lane).
+// One wavefront owns QT tiles of 16 queries of one q head; a workgroup = 4 wavefronts.
+// ------------------------------------------------------------------------------------------------
+template <int D, int QT>
+__global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a) {
+  constexpr int DS = D / 32;  // 32-dim slabs
+  constexpr int DT = D / 16;  // 16-dim output tiles
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int b = lane & 15, q = lane >> 4;
+  const int n_qblk = gridDim.x;
+  const int qblk = n_qblk - 1 - blockIdx.x;  // longest rows first
+  const int h = blockIdx.y, bi = blockIdx.z;
+  const int kvh = h / (a.nq / a.nkv);
+  const int t0 = (qblk * 4 + wave) * QT * 16;
+  if (t0 >= a.T) return;
+  const float scale = 1.0f / sqrtf((float)D);
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
+  uint4 qreg[QT][DS];
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    const int t = t0 + qt * 16 + b;
+#pragma unroll
+    for (int s = 0; s < DS; ++s)
+      qreg[qt][s] = t < a.T ? *reinterpret_cast<const uint4*>(a.q + ((size_t)bi * a.T + t) * a.nq * D + h * D +
+                                                              s * 32 + q * 8)
+                            : zero4;
+  }
+  f32x4_t oacc[QT][DT];
+  float mrun[QT], lrun[QT];
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    mrun[qt] = -INFINITY;
+    lrun[qt] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) oacc[qt][dt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+  }
+  const bf16_t* kc = a.cache_k + ((size_t)bi * a.nkv + kvh) * a.max_seq * D;
+  const bf16_t* vc = a.cache_v + ((size_t)bi * a.nkv + kvh) * D * a.max_seq;
+  const int last_t = min(a.T, t0 + QT * 16) - 1;
+  const int n_keys = a.pos0 + last_t + 1;
+
+  for (int kb = 0; kb < n_keys; kb += 32) {
+    uint4 kreg[2][DS];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int s = 0; s < DS; ++s)
+        kreg[t][s] = *reinterpret_cast<const uint4*>(kc + (size_t)(kb + 16 * t + b) * D + s * 32 + q * 8);
+    uint4 vreg[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const bf16_t* vp = vc + (size_t)(dt * 16 + b) * a.max_seq + kb + 4 * q;
+      const uint2 lo = *reinterpret_cast<const uint2*>(vp);
+      const uint2 hi = *reinterpret_cast<const uint2*>(vp + 16);
+      vreg[dt] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    }
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+      f32x4_t st[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        st[t] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < DS; ++s) st[t] = mfma16(kreg[t][s], qreg[qt][s], st[t]);
+      }
+      const int qpos = a.pos0 + t0 + qt * 16 + b;
+      float sv[8];
+      float mloc = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int key = kb + 16 * t + 4 * q + r;
+          const float v = key <= qpos ? st[t][r] * scale : -INFINITY;
+          sv[t * 4 + r] = v;
+          mloc = fmaxf(mloc, v);
+        }
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 16, 64));
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+      const float mnew = fmaxf(mrun[qt], mloc);   // finite from the first block on (key 0 is always visible)
+      const float corr = __expf(mrun[qt] - mnew);
+      float psum = 0.f;
+      float pv[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        pv[e] = __expf(sv[e] - mnew);
+        psum += pv[e];
+      }
+      lrun[qt] = lrun[qt] * corr + psum;
+      mrun[qt] = mnew;
+      uint4 pb;
+      pb.x = (uint32_t)f32_to_bf16(pv[0]) | ((uint32_t)f32_to_bf16(pv[1]) << 16);
+      pb.y = (uint32_t)f32_to_bf16(pv[2]) | ((uint32_t)f32_to_bf16(pv[3]) << 16);
+      pb.z = (uint32_t)f32_to_bf16(pv[4]) | ((uint32_t)f32_to_bf16(pv[5]) << 16);
+      pb.w = (uint32_t)f32_to_bf16(pv[6]) | ((uint32_t)f32_to_bf16(pv[7]) << 16);
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) oacc[qt][dt][r] *= corr;
+        oacc[qt][dt] = mfma16(vreg[dt], pb, oacc[qt][dt]);
+      }
+    }
+  }
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    float l = lrun[qt];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    const float inv = 1.0f / l;
+    const int t = t0 + qt * 16 + b;
+    if (t < a.T) {
+      bf16_t* op = a.o + ((size_t)bi * a.T + t) * a.nq * D + h * D;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16(oacc[qt][dt][0] * inv) | ((uint32_t)f32_to_bf16(oacc[qt][dt][1] * inv) << 16);
+        pk.y = (uint32_t)f32_to_bf16(oacc[qt][dt][2] * inv) | ((uint32_t)f32_to_bf16(oacc[qt][dt][3] * inv) << 16);
+        *reinterpret_cast<uint2*>(op + dt * 16 + 4 * q) = pk;
+      }
+    }
+  }
+}
+
+hipError_t launch_attn_prefill(const AttnPrefillArgs& a, hipStream_t s) {
+  constexpr int QT = 2;
+  const int bq = 4 * QT * 16;
+  const dim3 grid((a.T + bq - 1) / bq, a.nq, a.B);
+  if (a.d == 128) hipLaunchKernelGGL((attn_prefill_kernel<128, QT>), grid, dim3(256), 0, s, a);
+  else if (a.d == 64) hipLaunchKernelGGL((attn_prefill_kernel<64, QT>), grid, dim3(256), 0, s, a);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}

@@ -1,0 +1,194 @@
+"""ctypes binding of libladder.so (the C-ABI declared in include/ladder.h).
+
+Argument marshalling only: every step of the forward runs in the HIP kernels of
+the library.  PyTorch tensors are used as device memory (``data_ptr()``) and
+for the stream handle.  Loading fails loudly when the library has not been
+built (run ``python -c "import __graft_entry__ as g; g.build()"``); there is no
+fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libladder.so")
+
+LADDER_FP32, LADDER_BF16 = 0, 1
+LADDER_WIRING_LADDER, LADDER_WIRING_STANDARD = 0, 1
+LADDER_PATH_AUTO, LADDER_PATH_GENERIC = 0, 1
+LADDER_OK, LADDER_E_ARG, LADDER_E_SHAPE, LADDER_E_STATE, LADDER_E_OVERFLOW, LADDER_E_HIP = 0, -1, -2, -3, -4, -5
+(LADDER_K_REDUCE_NORM, LADDER_K_GEMV, LADDER_K_GEMM, LADDER_K_ROPE_APPEND, LADDER_K_ATTN_DECODE,
+ LADDER_K_ATTN_PREFILL, LADDER_K_GENERIC, LADDER_K_OTHER, LADDER_K_COUNT) = range(9)
+KERNEL_CLASS_NAMES = ["reduce_norm", "gemv", "gemm", "rope_append", "attn_decode", "attn_prefill", "generic", "other"]
+
+
+class ladder_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "inter", "tp_degree", "n_real_shards",
+        "max_batch", "max_seq", "max_tokens", "dtype", "wiring", "n_standard_layers", "reduce_on_side_stream",
+        "peer_pool", "peer_rows", "kernel_path")] + [("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class ladder_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in (
+        "attn_norm", "wq", "wk", "wv", "wo", "mlp_norm", "w_gate", "w_up", "w_down")]
+
+
+EXPORTS = {
+    "ladder_init": (C.c_int, [C.POINTER(ladder_config), C.c_void_p, C.POINTER(C.c_void_p)]),
+    "ladder_load_layer": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(ladder_layer_weights)]),
+    "ladder_set_peer_partials": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "ladder_load_kv": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]),
+    "ladder_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]),
+    "ladder_decode_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "ladder_free": (None, [C.c_void_p]),
+    "ladder_last_error": (C.c_char_p, [C.c_void_p]),
+    "ladder_position": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "ladder_device_bytes": (C.c_size_t, [C.c_void_p]),
+    "ladder_profile_enable": (C.c_int, [C.c_void_p, C.c_int32]),
+    "ladder_profile_read": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
+    "ladder_profile_reset": (C.c_int, [C.c_void_p]),
+}
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it is not there (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                               "(hipcc --offload-arch=gfx950); there is no fallback path")
+        handle = C.CDLL(LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+class LadderError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"ladder error {code}: {text}")
+        self.code = code
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def make_config(**kw) -> ladder_config:
+    cfg = ladder_config()
+    defaults = dict(tp_degree=1, n_real_shards=1, dtype=LADDER_BF16, wiring=LADDER_WIRING_LADDER,
+                    n_standard_layers=0, reduce_on_side_stream=1, peer_pool=0, peer_rows=0,
+                    kernel_path=LADDER_PATH_AUTO, rms_eps=1e-5, rope_theta=1e4)
+    defaults.update(kw)
+    known = {n for n, _ in ladder_config._fields_}
+    for k, v in defaults.items():
+        if k not in known:
+            raise KeyError(k)
+        setattr(cfg, k, v)
+    return cfg
+
+
+def config_for(w, **override) -> ladder_config:
+    """ladder_config of a seeded workload (paper_2501_06589_amd.inputs.Workload)."""
+    kw = dict(n_layers=w.n_layers, hidden=w.hidden, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
+              head_dim=w.head_dim, inter=w.inter, tp_degree=w.tp_degree, n_real_shards=w.n_real_shards,
+              max_batch=w.batch, max_seq=w.max_seq, max_tokens=max(w.prefill, 1),
+              dtype=LADDER_FP32 if w.dtype == "fp32" else LADDER_BF16,
+              peer_pool=w.peer_pool if w.n_peers else 0,
+              peer_rows=w.batch * max(w.prefill, 1) if w.n_peers else 0,
+              rms_eps=w.rms_eps, rope_theta=w.rope_theta)
+    kw.update(override)
+    return make_config(**kw)
+
+
+class Ladder:
+    """Owner of one ladder_ctx.  Methods carry the C entry points' names without the prefix."""
+
+    def __init__(self, cfg: ladder_config, stream: Optional[int] = None):
+        import torch
+        self._lib = lib()
+        self.cfg = cfg
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        h = C.c_void_p()
+        rc = self._lib.ladder_init(C.byref(cfg), C.c_void_p(stream), C.byref(h))
+        if rc != LADDER_OK:
+            raise LadderError(rc, (self._lib.ladder_last_error(None) or b"").decode())
+        self._h = h
+        self._keep = []          # tensors the library references without copying (peers)
+
+    # -- error helper
+    def _check(self, rc: int):
+        if rc != LADDER_OK:
+            raise LadderError(rc, (self._lib.ladder_last_error(self._h) or b"").decode())
+
+    def load_layer(self, layer: int, shard: int, tensors: Dict[str, "object"]):
+        w = ladder_layer_weights()
+        for name, _ in ladder_layer_weights._fields_:
+            t = tensors.get(name)
+            if t is not None and not t.is_contiguous():
+                raise ValueError(f"{name} must be contiguous")
+            setattr(w, name, _ptr(t))
+        self._check(self._lib.ladder_load_layer(self._h, layer, shard, C.byref(w)))
+
+    def set_peer_partials(self, peers):
+        self._keep = [peers]
+        self._check(self._lib.ladder_set_peer_partials(self._h, _ptr(peers)))
+
+    def load_kv(self, layer: int, shard: int, k, v):
+        b, _, s, _ = k.shape
+        self._check(self._lib.ladder_load_kv(self._h, layer, shard, _ptr(k.contiguous()), _ptr(v.contiguous()), b, s))
+
+    def prefill(self, x_in, x_out=None):
+        import torch
+        b, t, h = x_in.shape
+        if x_out is None:
+            x_out = torch.empty((b, t, h), dtype=torch.float32, device=x_in.device)
+        self._check(self._lib.ladder_prefill(self._h, _ptr(x_in), b, t, _ptr(x_out)))
+        return x_out
+
+    def decode_step(self, x_in, x_out=None):
+        import torch
+        if x_out is None:
+            x_out = torch.empty(x_in.shape, dtype=torch.float32, device=x_in.device)
+        self._check(self._lib.ladder_decode_step(self._h, _ptr(x_in), _ptr(x_out)))
+        return x_out
+
+    def position(self) -> Tuple[int, int]:
+        p, b = C.c_int32(), C.c_int32()
+        self._check(self._lib.ladder_position(self._h, C.byref(p), C.byref(b)))
+        return p.value, b.value
+
+    def device_bytes(self) -> int:
+        return int(self._lib.ladder_device_bytes(self._h))
+
+    def profile_enable(self, on: bool):
+        self._check(self._lib.ladder_profile_enable(self._h, 1 if on else 0))
+
+    def profile_reset(self):
+        self._check(self._lib.ladder_profile_reset(self._h))
+
+    def profile_read(self) -> Dict[str, Tuple[int, float]]:
+        out = {}
+        for cls, name in enumerate(KERNEL_CLASS_NAMES):
+            n, ms = C.c_int64(), C.c_double()
+            self._check(self._lib.ladder_profile_read(self._h, cls, C.byref(n), C.byref(ms)))
+            out[name] = (n.value, ms.value)
+        return out
+
+    def free(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            self._lib.ladder_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass

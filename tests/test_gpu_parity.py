@@ -1,0 +1,125 @@
+"""GPU parity: the HIP path (through the C-ABI) against the CPU oracle on the same seeded inputs.
+
+Tolerances (max |gpu - oracle| / RMS(oracle) on the final x_2N of every call):
+fp32 storage 1e-4, bf16 storage 2e-2.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2501_06589_amd import inputs, ladder
+
+pytestmark = pytest.mark.gpu
+
+TOL_FP32 = 1e-4
+TOL_BF16 = 2e-2
+
+TINY = inputs.WORKLOADS["tiny"]
+# small bf16 shapes that take the streaming / MFMA kernels (sizes multiple of 32, d in {64,128})
+SMALL_BF16 = TINY.with_(name="small_bf16", dtype="bf16", hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64,
+                        inter=352, tp_degree=2, n_real_shards=2, batch=2, prefill=40, decode_steps=4)
+
+
+@pytest.fixture(scope="module")
+def harness():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_harness
+    return gpu_harness
+
+
+def test_tiny_fp32_full(harness):
+    """The tiny workload end to end: 2 ladder layers, R = 2 real shards, prefill 32 + 8 decode steps."""
+    res = harness.run_case(TINY)
+    assert len(res.errs) == 9 and max(res.errs) < TOL_FP32, res.errs
+
+
+@pytest.mark.parametrize("wiring,nstd", [(ladder.LADDER_WIRING_STANDARD, 0), (ladder.LADDER_WIRING_LADDER, 1)])
+def test_tiny_fp32_standard_and_hybrid_wiring(harness, wiring, nstd):
+    res = harness.run_case(TINY.with_(n_layers=3), decode_steps=2, wiring=wiring, n_standard_layers=nstd)
+    assert max(res.errs) < TOL_FP32, res.errs
+
+
+def test_tiny_fp32_with_synthetic_peers_and_ragged_batch(harness):
+    w = TINY.with_(name="tiny_peers", tp_degree=4, n_real_shards=2, batch=3, prefill=17, peer_pool=3)
+    res = harness.run_case(w, decode_steps=3)
+    assert max(res.errs) < TOL_FP32, res.errs
+
+
+def test_side_stream_and_inline_reduce_are_bit_identical(harness):
+    w = TINY.with_(name="tiny_peers", tp_degree=4, n_real_shards=2, batch=2, peer_pool=2)
+    a = harness.run_case(w, decode_steps=3, gpu_only=True, reduce_on_side_stream=1)
+    b = harness.run_case(w, decode_steps=3, gpu_only=True, reduce_on_side_stream=0)
+    for x, y in zip(a.gpu, b.gpu):
+        assert np.array_equal(x, y)
+    # and run to run
+    c = harness.run_case(w, decode_steps=3, gpu_only=True, reduce_on_side_stream=1)
+    for x, y in zip(a.gpu, c.gpu):
+        assert np.array_equal(x, y)
+
+
+def test_small_bf16_generic_kernels(harness):
+    res = harness.run_case(SMALL_BF16, kernel_path=ladder.LADDER_PATH_GENERIC)
+    assert max(res.errs) < TOL_BF16, res.errs
+
+
+def test_small_bf16_streaming_kernels(harness):
+    """rows = 80 > 64 at prefill: MFMA GEMM + flash attention; decode: skinny GEMM + split-KV attention."""
+    res = harness.run_case(SMALL_BF16)
+    assert max(res.errs) < TOL_BF16, res.errs
+
+
+def test_small_bf16_skinny_prefill(harness):
+    """rows <= 64 at prefill: the skinny GEMM also serves short prefills; ragged T."""
+    res = harness.run_case(SMALL_BF16.with_(name="small_bf16_skinny", batch=3, prefill=13), decode_steps=2)
+    assert max(res.errs) < TOL_BF16, res.errs
+
+
+def test_bf16_d128_group8_with_peers_and_preloaded_cache(harness):
+    """The 70B-shard geometry scaled down: 8 q heads on 1 kv head, d = 128, synthetic peers,
+    synthetic KV cache instead of a prefill, several attention chunks."""
+    w = inputs.WORKLOADS["70b_r8_decode"].with_(name="r8_small", n_layers=3, hidden=512, inter=448, batch=4,
+                                                decode_steps=3)
+    res = harness.run_case(w, kv_preload=300)
+    assert len(res.errs) == 3 and max(res.errs) < TOL_BF16, res.errs
+
+
+def test_bf16_d128_prefill_ragged_rows(harness):
+    w = inputs.WORKLOADS["70b_r4_prefill"].with_(name="r4_small", n_layers=2, hidden=512, inter=512, batch=3,
+                                                 prefill=150, decode_steps=2)
+    res = harness.run_case(w)
+    assert max(res.errs) < TOL_BF16, res.errs
+
+
+def test_error_codes_on_the_gpu(harness):
+    w = TINY
+    ctx = ladder.Ladder(ladder.config_for(w))
+    x = torch.zeros((1, 4, w.hidden), device="cuda:0")
+    with pytest.raises(ladder.LadderError) as e:
+        ctx.prefill(x)                                   # layers not loaded
+    assert e.value.code == ladder.LADDER_E_STATE
+    with pytest.raises(ladder.LadderError) as e:
+        ctx.decode_step(x[:, 0].contiguous())            # decode before prefill
+    assert e.value.code == ladder.LADDER_E_STATE
+    tensors = harness.make_tensors(w)
+    for i in range(w.n_layers):
+        for r in range(w.n_real_shards):
+            ctx.load_layer(i, r, {k: v.to("cuda:0") for k, v in tensors[i][r].items()})
+    with pytest.raises(ladder.LadderError) as e:
+        ctx.prefill(torch.zeros((2, 4, w.hidden), device="cuda:0"))      # B > max_batch
+    assert e.value.code == ladder.LADDER_E_SHAPE
+    with pytest.raises(ladder.LadderError) as e:
+        ctx.prefill(torch.zeros((1, 33, w.hidden), device="cuda:0"))     # T > max_tokens
+    assert e.value.code == ladder.LADDER_E_SHAPE
+    assert ctx.position() == (0, 0)                      # failed calls leave the state alone
+    ctx.prefill(torch.zeros((1, w.prefill, w.hidden), device="cuda:0"))
+    for _ in range(w.decode_steps):
+        ctx.decode_step(x[:, 0].contiguous())
+    with pytest.raises(ladder.LadderError) as e:
+        ctx.decode_step(x[:, 0].contiguous())            # cache full
+    assert e.value.code == ladder.LADDER_E_OVERFLOW
+    assert ctx.position() == (w.max_seq, 1)
+    with pytest.raises(ladder.LadderError) as e:
+        ctx.set_peer_partials(x)                         # configuration without peers
+    assert e.value.code == ladder.LADDER_E_SHAPE
+    ctx.free()
