@@ -1,0 +1,257 @@
+#!/usr/bin/env python3
+"""Throughput of the Ladder-Residual shard forward on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 70b_r8_decode] [--mode decode|prefill]
+
+mode decode (default): a step = one decode step of the whole block stack (all 2N modules: norm, QKV,
+rotary + cache append, split-KV attention, O projection, SwiGLU MLP, partial-sum reduce + residual add
+on the side stream) for one batch.  Workload 70b_r8_decode: 80 layers of a 70B-shaped TP rank at
+R = 8 (hidden 8192, 8 q / 1 kv heads, d = 128, intermediate 3584), batch 4, synthetic KV cache of
+1024 positions, 7 synthetic peer partial sums per module.  All inputs are seeded, synthetic and
+resident in HBM before the timed region.
+mode prefill: a step = one prefill call (workload 70b_r4_prefill: 16 x 2048 tokens).
+
+Prints ONE JSON line: the contract fields plus "roofline" (dominant kernel, measured with HIP events
+around every launch in an instrumented pass right after the timed one) and "cpu_baseline" (the CPU
+oracle timed on a bounded sample of the same workload).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def build_context(w, device, extra_seq, peers_rows, **override):
+    import torch
+    from paper_2501_06589_amd import inputs, ladder
+    cfg = ladder.config_for(w, max_seq=w.prefill + w.kv_preload + extra_seq, **override)
+    ctx = ladder.Ladder(cfg)
+    t0 = time.time()
+    for i in range(w.n_layers):
+        for r in range(w.n_real_shards):
+            ctx.load_layer(i, r, inputs.layer_weights(w, i, r, device))
+        if i % 16 == 15:
+            torch.cuda.synchronize()
+            log(f"[bench] weights: {i + 1}/{w.n_layers} layers generated and packed ({time.time() - t0:.1f}s)")
+    peers = inputs.peer_partials(w, peers_rows, device) if w.n_peers else None
+    if peers is not None:
+        ctx.set_peer_partials(peers)
+    torch.cuda.synchronize()
+    return ctx
+
+
+def decode_algorithmic_bytes(w, s_mean):
+    """Bytes one decode step must move: every weight once, the visible KV cache once, peers once."""
+    weights = w.n_layers * w.n_real_shards * w.params_per_layer() * 2
+    kv = w.n_layers * w.n_real_shards * w.batch * w.n_kv_heads * w.head_dim * 2 * 2 * s_mean
+    peers = 2 * w.n_layers * w.n_peers * w.batch * w.hidden * 2
+    return weights, kv, peers
+
+
+def cpu_baseline_decode(w, device, n_layers_sample, kv_len):
+    """The oracle as it stands, one decode step on the first n_layers_sample layers of the workload."""
+    import numpy as np
+    import torch
+    from oracle import from_torch
+    from oracle import ladder_oracle as lo
+    from paper_2501_06589_amd import inputs
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    ws = w.with_(n_layers=n_layers_sample)
+    cfg = from_torch.config_from_workload(ws)
+    layers = [from_torch.layer_from_tensors([{k: v.cpu() for k, v in inputs.layer_weights(ws, i, r, device).items()}
+                                             for r in range(ws.n_real_shards)]) for i in range(n_layers_sample)]
+    state = lo.State.empty(cfg, ws.n_real_shards, ws.batch, kv_len + 2)
+    for i in range(n_layers_sample):
+        for r in range(ws.n_real_shards):
+            k, v = inputs.kv_cache(ws, i, r, ws.batch, kv_len, device)
+            from_torch.load_kv(state, i, r, k, v)
+    state.pos = kv_len
+    peers = inputs.peer_partials(ws, ws.batch, device)
+    opeers = from_torch.to_f64(peers) if peers is not None else None
+    e = from_torch.to_f64(inputs.embeddings(ws, ws.batch, 1, inputs.SEED_DECODE0, device))
+    t0 = time.perf_counter()
+    lo.forward_eq2(e, layers, cfg, state, opeers)
+    dt = time.perf_counter() - t0
+    full_step_s = dt * w.n_layers / n_layers_sample
+    return {"value": w.batch / full_step_s, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"one decode step (batch {w.batch}, {kv_len} cached positions) of the first {n_layers_sample} "
+                      f"of {w.n_layers} layers in {dt:.2f} s, scaled linearly to {w.n_layers} layers"}
+
+
+def run_decode(args):
+    import torch
+    from paper_2501_06589_amd import inputs, ladder
+    w = inputs.WORKLOADS[args.workload]
+    if args.layers:
+        w = w.with_(n_layers=args.layers)
+    dev = "cuda:0"
+    prof_steps = 8
+    total_steps = args.warmup + args.steps + prof_steps
+    ctx = build_context(w, dev, total_steps, w.batch, max_tokens=max(w.prefill, 1))
+    if w.kv_preload:
+        for i in range(w.n_layers):
+            for r in range(w.n_real_shards):
+                k, v = inputs.kv_cache(w, i, r, w.batch, w.kv_preload, dev)
+                ctx.load_kv(i, r, k, v)
+    else:
+        ctx.prefill(inputs.embeddings(w, w.batch, w.prefill, inputs.SEED_PREFILL, dev))
+    xs = torch.stack([inputs.embeddings(w, w.batch, 1, inputs.SEED_DECODE0 + i, dev)[:, 0] for i in range(total_steps)])
+    out = torch.empty((w.batch, w.hidden), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    log(f"[bench] context ready: {ctx.device_bytes() / 2**30:.2f} GiB on device")
+    for i in range(args.warmup):
+        ctx.decode_step(xs[i], out)
+    torch.cuda.synchronize()
+    pos_start = ctx.position()[0]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ctx.decode_step(xs[args.warmup + i], out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    pos_end = ctx.position()[0]
+    assert torch.isfinite(out).all()
+    ms_per_step = dt * 1e3 / args.steps
+    tokens_per_s = w.batch * args.steps / dt
+    s_mean = (pos_start + pos_end + 1) / 2.0           # visible positions averaged over the timed steps
+    wb, kvb, pb = decode_algorithmic_bytes(w, s_mean)
+    step_bytes = wb + kvb + pb
+
+    # instrumented pass: HIP events around every launch, on the stream it is launched on
+    ctx.profile_enable(True)
+    ctx.profile_reset()
+    for i in range(prof_steps):
+        ctx.decode_step(xs[args.warmup + args.steps + i], out)
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    n_gemv, ms_gemv = prof["gemv"]
+    gemv_bytes_per_launch = wb / (4 * w.n_layers * w.n_real_shards)   # 4 projections per layer and shard
+    avg_ms = ms_gemv / max(n_gemv, 1)
+    achieved = gemv_bytes_per_launch / (avg_ms * 1e-3) / 1e9 if n_gemv else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"gemv_hbm_traffic_{w.name}.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+    roofline = {"bound": "hbm", "kernel": "gemv_mfma_kernel (decode weight-streaming skinny GEMM)",
+                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": traffic, "algorithmic_bytes_per_launch": gemv_bytes_per_launch,
+                "avg_launch_ms": avg_ms, "launches": n_gemv}
+    per_class = {k: {"launches": n, "avg_us": (ms / n * 1e3 if n else 0.0), "ms_per_step": ms / prof_steps}
+                 for k, (n, ms) in prof.items() if n}
+    ctx.free()
+    del ctx
+    torch.cuda.empty_cache()
+    cpu = cpu_baseline_decode(w, dev, min(args.cpu_layers, w.n_layers), w.kv_preload or w.prefill) if not args.no_cpu else None
+    return {
+        "metric": "decode_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "n_layers": w.n_layers, "hidden": w.hidden, "n_q_heads": w.n_q_heads,
+                   "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "inter": w.inter, "tp_degree": w.tp_degree,
+                   "batch": w.batch, "kv_positions": [pos_start, pos_end], "peers": w.n_peers},
+        "hbm": {"algorithmic_bytes_per_step": step_bytes, "weights": wb, "kv": kvb, "peers": pb,
+                "achieved_GBps_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9,
+                "frac_of_peak_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "roofline": roofline, "kernel_classes": per_class, "cpu_baseline": cpu,
+    }
+
+
+def run_prefill(args):
+    import torch
+    from paper_2501_06589_amd import inputs, ladder
+    w = inputs.WORKLOADS[args.workload]
+    if args.layers:
+        w = w.with_(n_layers=args.layers)
+    dev = "cuda:0"
+    rows = w.batch * w.prefill
+    ctx = build_context(w, dev, 8, rows)
+    x = inputs.embeddings(w, w.batch, w.prefill, inputs.SEED_PREFILL, dev)
+    out = torch.empty((w.batch, w.prefill, w.hidden), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    log(f"[bench] context ready: {ctx.device_bytes() / 2**30:.2f} GiB on device")
+    for _ in range(args.warmup):
+        ctx.prefill(x, out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.prefill(x, out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert torch.isfinite(out).all()
+    ms_per_step = dt * 1e3 / args.steps
+    gemm_flops = 2.0 * w.n_layers * w.n_real_shards * w.params_per_layer() * rows
+    attn_flops = w.n_layers * w.n_real_shards * w.batch * w.n_q_heads * 4.0 * w.head_dim * (w.prefill * (w.prefill + 1) / 2)
+    ctx.profile_enable(True)
+    ctx.profile_reset()
+    ctx.prefill(x, out)
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    n_gemm, ms_gemm = prof["gemm"]
+    flops_per_launch = gemm_flops / (4 * w.n_layers * w.n_real_shards)
+    avg_ms = ms_gemm / max(n_gemm, 1)
+    achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12 if n_gemm else 0.0
+    roofline = {"bound": "mfma", "kernel": "gemm_mfma_kernel (prefill bf16 MFMA GEMM)", "achieved": achieved,
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": None, "algorithmic_flops_per_launch": flops_per_launch, "avg_launch_ms": avg_ms,
+                "launches": n_gemm}
+    per_class = {k: {"launches": n, "avg_us": (ms / n * 1e3 if n else 0.0), "ms_per_step": ms}
+                 for k, (n, ms) in prof.items() if n}
+    ctx.free()
+    return {
+        "metric": "prefill_tokens_per_s", "value": rows * args.steps / dt, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "n_layers": w.n_layers, "hidden": w.hidden, "n_q_heads": w.n_q_heads,
+                   "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "inter": w.inter, "tp_degree": w.tp_degree,
+                   "batch": w.batch, "prefill_tokens": w.prefill, "peers": w.n_peers},
+        "mfma": {"gemm_flops": gemm_flops, "attention_flops": attn_flops,
+                 "whole_prefill_TFLOPs": (gemm_flops + attn_flops) / (ms_per_step * 1e-3) / 1e12,
+                 "frac_of_peak_whole_prefill": (gemm_flops + attn_flops) / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+        "roofline": roofline, "kernel_classes": per_class, "cpu_baseline": None,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--mode", choices=["decode", "prefill"], default="decode")
+    ap.add_argument("--workload", default=None)
+    ap.add_argument("--layers", type=int, default=0, help="debug: truncate the stack (result is then not the metric)")
+    ap.add_argument("--cpu-layers", type=int, default=16, help="layers of the oracle's timed sample")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (one process, one MI355X); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if args.mode == "decode":
+        args.workload = args.workload or "70b_r8_decode"
+        args.steps = 256 if args.steps is None else args.steps
+        args.warmup = 16 if args.warmup is None else args.warmup
+        res = run_decode(args)
+    else:
+        args.workload = args.workload or "70b_r4_prefill"
+        args.steps = 3 if args.steps is None else args.steps
+        args.warmup = 1 if args.warmup is None else args.warmup
+        res = run_prefill(args)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

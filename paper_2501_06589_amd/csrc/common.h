@@ -122,6 +122,10 @@ struct GemvArgs {
   bf16_t* act;             // epilogue 1 (ksplit must be 1): SwiGLU -> bf16 [M][N/2]
   int epilogue;
 };
+// launch shape of the skinny GEMM for a problem: column tiles per workgroup, wavefronts per workgroup,
+// k tiles per register buffer, workgroups along K (1 unless allow_ksplit)
+struct GemvPlan { int tn, waves, u, ksplit; };
+GemvPlan gemv_plan(int M, int N, int K, bool allow_ksplit);
 hipError_t launch_gemv(const GemvArgs& a, hipStream_t s);
 
 struct AttnDecodeArgs {

@@ -48,111 +48,164 @@ hipError_t launch_repack_tiles(const bf16_t* src, void* dst, int K, int N, int N
 
 // ------------------------------------------------------------------------------------------------
 // Weight-streaming skinny GEMM  out[m][n] = sum_k x[m][k] W[k][n]  for M <= 16*MT rows.
-// HBM-bound: every weight byte is read once, as one coalesced 1 KiB tile per wavefront load, and
-// goes straight into the A operand of a 16x16x32 bf16 MFMA; the B operand is the matching
-// 16 rows x 32 k slice of x (rows >= M are zero), read from L1/L2.  A workgroup owns one 16-column
-// tile and a K range; its 4 wavefronts split that range, keep UNROLL tiles in flight each, and
-// add up through LDS.  Summation order is fixed (wave 0..3, then ksplit slots by the consumer).
+// HBM-bound: every weight byte is read once, as one coalesced 1 KiB tile per wavefront load
+// (non-temporal: the stream must not evict x from the caches), and goes straight into the A operand
+// of a 16x16x32 bf16 MFMA; the B operand is the matching 16 rows x 32 k slice of x (rows >= M zeroed),
+// read from L1/L2 once per k tile and shared by the wave's TN column tiles.  A workgroup owns TN
+// adjacent 16-column tiles and a K range; its WAVES wavefronts split that range and add up through
+// LDS in a fixed order (wave 0.., then the ksplit slots by the consumer).
+// Latency hiding is explicit: two register buffers of U k-tiles each, the next batch is always in
+// flight while the current one is multiplied.  All loads are unconditional (addresses clamped into
+// the wave's range, contributions masked at use) and the K loop is wave-uniform, so the compiler can
+// count outstanding loads exactly instead of draining them.
 // ------------------------------------------------------------------------------------------------
-#define GEMV_WAVES 4
-#define GEMV_UNROLL 8
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 
-template <int MT>
-__global__ __launch_bounds__(GEMV_WAVES * 64) void gemv_mfma_kernel(GemvArgs a) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+template <int MT, int WAVES, int U, int TN>
+__global__ __launch_bounds__(WAVES * 64) void gemv_mfma_kernel(GemvArgs a) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int b = lane & 15, q = lane >> 4;
-  const int nt = blockIdx.x, ks = blockIdx.y;
-  const int KT = (a.K + 31) >> 5;
+  const int nt0 = blockIdx.x * TN, ks = blockIdx.y;
+  const int KT = a.K >> 5;
   const int kt_per_wg = (KT + a.ksplit - 1) / a.ksplit;
   const int wg0 = ks * kt_per_wg;
   const int wg1 = min(KT, wg0 + kt_per_wg);
-  const int per_wave = (wg1 - wg0 + GEMV_WAVES - 1) / GEMV_WAVES;
+  const int per_wave = (wg1 - wg0 + WAVES - 1) / WAVES;
   const int kt0 = wg0 + wave * per_wave;
   const int kt1 = min(wg1, kt0 + per_wave);
 
-  f32x4_t acc[MT];
+  f32x4_t acc[TN][MT];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) acc[mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[j][mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
-  const uint4* wptr = reinterpret_cast<const uint4*>(a.wp) + ((size_t)nt * KT) * 64 + lane;
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
-  for (int kt = kt0; kt < kt1; kt += GEMV_UNROLL) {
-    uint4 wv[GEMV_UNROLL];
-    uint4 xv[MT][GEMV_UNROLL];
+  const u32x4_t* wptr = reinterpret_cast<const u32x4_t*>(a.wp) + ((size_t)nt0 * KT) * 64 + lane;
+  const bf16_t* xptr[MT];
+  bool rowok[MT];
 #pragma unroll
-    for (int u = 0; u < GEMV_UNROLL; ++u) {
-      const bool in = kt + u < kt1;
-      wv[u] = in ? wptr[(size_t)(kt + u) * 64] : zero4;
+  for (int mt = 0; mt < MT; ++mt) {
+    rowok[mt] = mt * 16 + b < a.M;
+    xptr[mt] = a.x + (size_t)min(mt * 16 + b, a.M - 1) * a.ldx + q * 8;
+  }
+  u32x4_t wa[TN][U], wb[TN][U], xa[MT][U], xb[MT][U];
+  auto load = [&](u32x4_t (&wv)[TN][U], u32x4_t (&xv)[MT][U], int kt) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int ktc = min(kt + u, kt1 - 1);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) wv[j][u] = __builtin_nontemporal_load(wptr + ((size_t)j * KT + ktc) * 64);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) xv[mt][u] = *reinterpret_cast<const u32x4_t*>(xptr[mt] + (size_t)ktc * 32);
     }
+  };
+  auto fma = [&](const u32x4_t (&wv)[TN][U], const u32x4_t (&xv)[MT][U], int kt) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int row = mt * 16 + b;
+    for (int u = 0; u < U; ++u) {
+      const bool kok = kt + u < kt1;
 #pragma unroll
-      for (int u = 0; u < GEMV_UNROLL; ++u) {
-        const bool in = (kt + u < kt1) && (row < a.M);
-        xv[mt][u] = in ? *reinterpret_cast<const uint4*>(a.x + (size_t)row * a.ldx + (kt + u) * 32 + q * 8) : zero4;
+      for (int mt = 0; mt < MT; ++mt) {
+        const u32x4_t xz = (kok && rowok[mt]) ? xv[mt][u] : (u32x4_t){0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wv[j][u]),
+                                                              __builtin_bit_cast(bf16x8_t, xz), acc[j][mt], 0, 0, 0);
       }
     }
-#pragma unroll
-    for (int u = 0; u < GEMV_UNROLL; ++u) {
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wv[u]),
-                                                          __builtin_bit_cast(bf16x8_t, xv[mt][u]), acc[mt], 0, 0, 0);
+  };
+  if (kt0 < kt1) {
+    load(wa, xa, kt0);
+    for (int kt = kt0; kt < kt1; kt += 2 * U) {
+      load(wb, xb, kt + U);
+      __builtin_amdgcn_sched_barrier(0);
+      fma(wa, xa, kt);
+      __builtin_amdgcn_sched_barrier(0);
+      load(wa, xa, kt + 2 * U);
+      __builtin_amdgcn_sched_barrier(0);
+      fma(wb, xb, kt + U);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
-  // acc[mt][r] = out[row = mt*16 + b][col = nt*16 + 4q + r]
-  __shared__ float red[GEMV_WAVES][MT][16][17];  // [wave][mt][col in tile][row in tile]
+  // acc[j][mt][r] = out[row = mt*16 + b][col = (nt0 + j)*16 + 4q + r]; reduce over the waves through LDS,
+  // 4 (tile, row-tile) slots per round
+  constexpr int SLOTS = TN * MT, PER_ROUND = SLOTS < 4 ? SLOTS : 4;
+  __shared__ float red[WAVES][PER_ROUND][16][17];  // [wave][slot][col in tile][row in tile]
+  const int I = a.N >> 1;
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
+  for (int s0 = 0; s0 < SLOTS; s0 += PER_ROUND) {
+    if (s0 > 0) __syncthreads();
 #pragma unroll
-    for (int r = 0; r < 4; ++r) red[wave][mt][4 * q + r][b] = acc[mt][r];
-  __syncthreads();
-
-  if (a.epilogue == 0) {
-    // thread t -> (mt, row, col): coalesced along columns
-    for (int i = threadIdx.x; i < MT * 256; i += GEMV_WAVES * 64) {
-      const int mt = i >> 8, row16 = (i >> 4) & 15, col16 = i & 15;
-      const int row = mt * 16 + row16, col = nt * 16 + col16;
-      if (row < a.M && col < a.N) {
-        float s = 0.f;
+    for (int s = 0; s < PER_ROUND; ++s) {
+      const int j = (s0 + s) / MT, mt = (s0 + s) % MT;
 #pragma unroll
-        for (int w = 0; w < GEMV_WAVES; ++w) s += red[w][mt][col16][row16];
-        a.out[(size_t)(a.slot0 + ks) * a.out_stride + (size_t)row * a.N + col] = s;
-      }
+      for (int r = 0; r < 4; ++r) red[wave][s][4 * q + r][b] = acc[j][mt][r];
     }
-  } else {
-    // SwiGLU: tile columns 0..7 are gate columns 8nt..8nt+7, columns 8..15 the matching up columns
-    const int I = a.N >> 1;
-    for (int i = threadIdx.x; i < MT * 128; i += GEMV_WAVES * 64) {
-      const int mt = i >> 7, row16 = (i >> 3) & 15, c8 = i & 7;
-      const int row = mt * 16 + row16, col = nt * 8 + c8;
-      if (row < a.M && col < I) {
-        float g = 0.f, u = 0.f;
+    __syncthreads();
+    if (a.epilogue == 0) {
+      for (int i = threadIdx.x; i < PER_ROUND * 256; i += WAVES * 64) {
+        const int s = i >> 8, row16 = (i >> 4) & 15, col16 = i & 15;
+        const int j = (s0 + s) / MT, mt = (s0 + s) % MT;
+        const int row = mt * 16 + row16, col = (nt0 + j) * 16 + col16;
+        if (row < a.M && col < a.N) {
+          float v = 0.f;
 #pragma unroll
-        for (int w = 0; w < GEMV_WAVES; ++w) {
-          g += red[w][mt][c8][row16];
-          u += red[w][mt][c8 + 8][row16];
+          for (int w = 0; w < WAVES; ++w) v += red[w][s][col16][row16];
+          a.out[(size_t)(a.slot0 + ks) * a.out_stride + (size_t)row * a.N + col] = v;
         }
-        a.act[(size_t)row * I + col] = f32_to_bf16(g / (1.0f + __expf(-g)) * u);
+      }
+    } else {
+      // SwiGLU: tile columns 0..7 are gate columns 8nt..8nt+7, columns 8..15 the matching up columns
+      for (int i = threadIdx.x; i < PER_ROUND * 128; i += WAVES * 64) {
+        const int s = i >> 7, row16 = (i >> 3) & 15, c8 = i & 7;
+        const int j = (s0 + s) / MT, mt = (s0 + s) % MT;
+        const int row = mt * 16 + row16, col = (nt0 + j) * 8 + c8;
+        if (row < a.M && col < I) {
+          float g = 0.f, u = 0.f;
+#pragma unroll
+          for (int w = 0; w < WAVES; ++w) {
+            g += red[w][s][c8][row16];
+            u += red[w][s][c8 + 8][row16];
+          }
+          a.act[(size_t)row * I + col] = f32_to_bf16(g / (1.0f + __expf(-g)) * u);
+        }
       }
     }
   }
 }
 
-hipError_t launch_gemv(const GemvArgs& a, hipStream_t s) {
-  if (a.M <= 0 || a.M > 64 || a.ksplit < 1) return hipErrorInvalidValue;
-  if (a.epilogue == 1 && a.ksplit != 1) return hipErrorInvalidValue;
-  dim3 grid((a.N + 15) / 16, a.ksplit), block(GEMV_WAVES * 64);
-  const int mt = (a.M + 15) / 16;
-  switch (mt) {
-    case 1: hipLaunchKernelGGL(gemv_mfma_kernel<1>, grid, block, 0, s, a); break;
-    case 2: hipLaunchKernelGGL(gemv_mfma_kernel<2>, grid, block, 0, s, a); break;
-    case 3: hipLaunchKernelGGL(gemv_mfma_kernel<3>, grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL(gemv_mfma_kernel<4>, grid, block, 0, s, a); break;
-  }
+GemvPlan gemv_plan(int M, int N, int K, bool allow_ksplit) {
+  GemvPlan p;
+  const int NT = N / 16, KT = K / 32;
+  p.tn = (NT <= 192 && NT % 4 == 0) ? 4 : 2;
+  p.waves = KT >= 64 ? 8 : 4;
+  const int groups = NT / p.tn;
+  p.ksplit = 1;
+  if (allow_ksplit)
+    while (groups * p.ksplit * p.waves < 1536 && KT / (p.ksplit * 2 * p.waves) >= 8 && p.ksplit < 8) p.ksplit *= 2;
+  p.u = (M <= 16 && p.waves == 4 && p.tn == 2) ? 4 : 2;
+  return p;
+}
+
+template <int MT>
+static hipError_t launch_gemv_mt(const GemvArgs& a, const GemvPlan& p, hipStream_t s) {
+  const dim3 grid(a.N / 16 / p.tn, a.ksplit), block(p.waves * 64);
+  if (p.waves == 8 && p.tn == 2) hipLaunchKernelGGL((gemv_mfma_kernel<MT, 8, 2, 2>), grid, block, 0, s, a);
+  else if (p.waves == 8 && p.tn == 4) hipLaunchKernelGGL((gemv_mfma_kernel<MT, 8, 2, 4>), grid, block, 0, s, a);
+  else if (p.waves == 4 && p.tn == 4) hipLaunchKernelGGL((gemv_mfma_kernel<MT, 4, 2, 4>), grid, block, 0, s, a);
+  else if (p.u == 4) hipLaunchKernelGGL((gemv_mfma_kernel<MT, 4, 4, 2>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((gemv_mfma_kernel<MT, 4, 2, 2>), grid, block, 0, s, a);
   return hipGetLastError();
+}
+
+hipError_t launch_gemv(const GemvArgs& a, hipStream_t s) {
+  if (a.M <= 0 || a.M > 64 || (a.N & 31) || (a.K & 31)) return hipErrorInvalidValue;
+  GemvPlan p = gemv_plan(a.M, a.N, a.K, a.epilogue == 0);
+  if (a.ksplit != p.ksplit) return hipErrorInvalidValue;  // the caller sizes its slots from the same plan
+  const int mt = (a.M + 15) / 16;
+  if (mt == 1) return launch_gemv_mt<1>(a, p, s);
+  if (mt == 2) return launch_gemv_mt<2>(a, p, s);
+  return launch_gemv_mt<4>(a, p, s);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -278,25 +331,38 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeArgs a) {
   }
 }
 
-// combine: one workgroup of D threads per (sequence, q head)
+// combine: one workgroup of D threads per (sequence, q head); the chunk statistics go through LDS
+// so that no thread walks a chain of dependent global loads
 template <int D>
 __global__ void attn_combine_kernel(AttnDecodeArgs a) {
-  const int h = blockIdx.x, bi = blockIdx.y;
+  __shared__ float wgt[512];
+  __shared__ float stat[2];
+  const int h = blockIdx.x, bi = blockIdx.y, t = threadIdx.x;
   const int g = a.nq / a.nkv;
   const int kvh = h / g, hg = h % g;
+  const int n_pos = a.pos_dev ? (*a.pos_dev + 1) : a.n_pos;
+  const int nc = min(a.n_chunks, (n_pos + a.chunk - 1) / a.chunk);   // chunks that hold visible positions
   const size_t base = ((size_t)bi * a.nkv + kvh) * a.n_chunks;
-  float m = -INFINITY;
-  for (int c = 0; c < a.n_chunks; ++c) m = fmaxf(m, a.part_ml[((base + c) * g + hg) * 2]);
-  float l = 0.f, o = 0.f;
-  for (int c = 0; c < a.n_chunks; ++c) {
-    const float mc = a.part_ml[((base + c) * g + hg) * 2], lc = a.part_ml[((base + c) * g + hg) * 2 + 1];
-    if (lc > 0.f) {
-      const float w = __expf(mc - m);
-      l += lc * w;
-      o += a.part_o[((base + c) * g + hg) * D + threadIdx.x] * w;
+  for (int c = t; c < nc; c += D) wgt[c] = a.part_ml[((base + c) * g + hg) * 2];
+  __syncthreads();
+  if (t < 64) {   // first wavefront: max, then weights and the normaliser
+    float m = -INFINITY;
+    for (int c = t; c < nc; c += 64) m = fmaxf(m, wgt[c]);
+    m = wave_max(m);
+    float l = 0.f;
+    for (int c = t; c < nc; c += 64) {
+      const float w = __expf(wgt[c] - m);
+      wgt[c] = w;
+      l += a.part_ml[((base + c) * g + hg) * 2 + 1] * w;
     }
+    l = wave_sum(l);
+    if (t == 0) stat[0] = l;
   }
-  a.o[(size_t)bi * a.nq * D + h * D + threadIdx.x] = f32_to_bf16(o / l);
+  __syncthreads();
+  float o = 0.f;
+#pragma unroll 8
+  for (int c = 0; c < nc; ++c) o += a.part_o[((base + c) * g + hg) * D + t] * wgt[c];
+  a.o[(size_t)bi * a.nq * D + h * D + t] = f32_to_bf16(o / stat[0]);
 }
 
 template <int D, int G>

@@ -126,13 +126,6 @@ int lag_of(const ladder_ctx* c, int m) {  // module m reads x_{m - lag}
   return (m - 1) / 2 < c->cfg.n_standard_layers ? 1 : 2;
 }
 
-int gemv_ksplit(int N, int K, bool allow) {
-  if (!allow) return 1;
-  const int NT = N / 16, KT = K / 32;
-  int ks = 1;
-  while (NT * ks < 512 && KT / (ks * 2) >= 32 && ks < 8) ks *= 2;
-  return ks;
-}
 
 int check_config(const ladder_config* g, std::string& why) {
   if (g->n_layers <= 0 || g->hidden <= 0 || g->n_q_heads <= 0 || g->n_kv_heads <= 0 || g->head_dim <= 0 ||
@@ -206,7 +199,7 @@ int run_module(ladder_ctx* c, int m, int B, int T, int pos0, int* n_slots) {
       } else if (skinny) {
         GemvArgs a{};
         a.x = (const bf16_t*)yin; a.ldx = H; a.wp = L.pqkv; a.M = rows; a.K = H; a.N = c->nqkv;
-        a.ksplit = gemv_ksplit(c->nqkv, H, true);
+        a.ksplit = gemv_plan(rows, c->nqkv, H, true).ksplit;
         a.out = c->qkv; a.out_stride = (size_t)rows * c->nqkv; a.slot0 = 0; a.epilogue = 0;
         qkv_slots = a.ksplit;
         HIP_TRY(c, timed(c, LADDER_K_GEMV, s, [&] { return launch_gemv(a, s); }));
@@ -247,7 +240,7 @@ int run_module(ladder_ctx* c, int m, int B, int T, int pos0, int* n_slots) {
       } else if (skinny) {
         GemvArgs a{};
         a.x = (const bf16_t*)c->obuf; a.ldx = nqd; a.wp = L.po; a.M = rows; a.K = nqd; a.N = H;
-        a.ksplit = gemv_ksplit(H, nqd, true);
+        a.ksplit = gemv_plan(rows, H, nqd, true).ksplit;
         a.out = pout; a.out_stride = pstride; a.slot0 = slots; a.epilogue = 0;
         HIP_TRY(c, timed(c, LADDER_K_GEMV, s, [&] { return launch_gemv(a, s); }));
         slots += a.ksplit;
@@ -271,7 +264,7 @@ int run_module(ladder_ctx* c, int m, int B, int T, int pos0, int* n_slots) {
         HIP_TRY(c, timed(c, LADDER_K_GEMV, s, [&] { return launch_gemv(a, s); }));
         GemvArgs b{};
         b.x = (const bf16_t*)c->act; b.ldx = I; b.wp = L.pd; b.M = rows; b.K = I; b.N = H;
-        b.ksplit = gemv_ksplit(H, I, true);
+        b.ksplit = gemv_plan(rows, H, I, true).ksplit;
         b.out = pout; b.out_stride = pstride; b.slot0 = slots; b.epilogue = 0;
         HIP_TRY(c, timed(c, LADDER_K_GEMV, s, [&] { return launch_gemv(b, s); }));
         slots += b.ksplit;
