@@ -102,7 +102,8 @@ def run_decode(args):
     dev = "cuda:0"
     prof_steps = 8
     total_steps = args.warmup + args.steps + prof_steps
-    ctx = build_context(w, dev, total_steps, w.batch, max_tokens=max(w.prefill, 1))
+    ctx = build_context(w, dev, total_steps, w.batch, max_tokens=max(w.prefill, 1),
+                        decode_graph=1 if args.graph else 0, overlap_modules=0 if args.no_overlap else 1)
     if w.kv_preload:
         for i in range(w.n_layers):
             for r in range(w.n_real_shards):
@@ -235,6 +236,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="debug: truncate the stack (result is then not the metric)")
     ap.add_argument("--cpu-layers", type=int, default=16, help="layers of the oracle's timed sample")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--graph", action="store_true", help="replay decode steps from a captured HIP graph instead of eager launches")
+    ap.add_argument("--no-overlap", action="store_true", help="one compute stream instead of attention / MLP streams")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (one process, one MI355X); "

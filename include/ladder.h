@@ -76,6 +76,11 @@ typedef struct {
   int32_t peer_rows;      /* rows of each synthetic peer tensor (>= rows of any call), 0 if no peers */
   int32_t kernel_path;    /* LADDER_PATH_AUTO: MFMA/streaming kernels when dtype and sizes allow;
                              LADDER_PATH_GENERIC: the plain kernels (any size, both dtypes) */
+  int32_t overlap_modules; /* 1: attention modules and MLP modules run on two internal streams, so that
+                              module m+1 (which under the ladder wiring needs only x_{m-1}) can execute
+                              while module m still runs; 0: one compute stream.  Same results. */
+  int32_t decode_graph;   /* 1: a decode step of the bf16 streaming path is captured once into a HIP graph
+                             (all streams) and replayed, removing the per-launch host cost; 0: eager launches */
   float rms_eps;          /* RMSNorm epsilon (inside the square root) */
   float rope_theta;       /* rotary base; pair (2j,2j+1) turns by pos * theta^(-2j/d) */
 } ladder_config;

@@ -10,6 +10,7 @@
 // reduce(m) overlaps module m+1, which is the decoupling the architecture buys.
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <string>
@@ -44,8 +45,15 @@ struct ladder_ctx {
   bool bf16 = false, fast = false;
   size_t esz = 4;
   int n_mod = 0, n_peers = 0, s_cap = 0, rows_cap = 0, nqkv = 0;
-  hipStream_t main = nullptr, side = nullptr;
+  // caller's stream (fences only) and the internal streams: s_attn runs the attention modules (and
+  // everything else when nothing overlaps), s_mlp the MLP modules, side the reduces
+  hipStream_t main = nullptr, s_attn = nullptr, s_mlp = nullptr, side = nullptr;
   hipEvent_t ev_mod[2] = {nullptr, nullptr}, ev_red[2] = {nullptr, nullptr};
+  hipEvent_t ev_begin = nullptr, ev_end = nullptr, ev_fork = nullptr;
+  int* pos_dev = nullptr;       // device copy of the position, read by the decode kernels
+  char* emb_stage = nullptr;    // T [max_batch][H]: decode input staged for the captured graph
+  hipGraphExec_t graph_exec = nullptr;
+  int graph_batch = 0;
   std::vector<void*> allocs;
   size_t dev_bytes = 0;
   std::vector<LayerStore> store;  // [layer * n_real + shard]
@@ -74,6 +82,20 @@ struct ladder_ctx {
 };
 
 namespace {
+
+// LADDER_DEBUG=1 in the environment: host-side progress lines on stderr
+bool debug_on() {
+  static const bool on = getenv("LADDER_DEBUG") != nullptr;
+  return on;
+}
+#define DBG(...)                                   \
+  do {                                             \
+    if (debug_on()) {                              \
+      fprintf(stderr, "[ladder] " __VA_ARGS__);    \
+      fprintf(stderr, "\n");                       \
+      fflush(stderr);                              \
+    }                                              \
+  } while (0)
 
 int fail(ladder_ctx* c, int code, const std::string& msg) {
   if (c) c->err = msg;
@@ -144,6 +166,7 @@ int check_config(const ladder_config* g, std::string& why) {
   if (g->head_dim % 2 || g->head_dim > 256) { why = "head_dim must be even and <= 256"; return LADDER_E_SHAPE; }
   if (g->n_real_shards > g->tp_degree) { why = "n_real_shards exceeds tp_degree"; return LADDER_E_SHAPE; }
   if (g->max_tokens > g->max_seq) { why = "max_tokens exceeds max_seq"; return LADDER_E_SHAPE; }
+  if ((g->decode_graph != 0 && g->decode_graph != 1) || (g->overlap_modules != 0 && g->overlap_modules != 1)) { why = "decode_graph / overlap_modules must be 0 or 1"; return LADDER_E_ARG; }
   if (g->peer_pool < 0 || g->peer_rows < 0) { why = "peer_pool / peer_rows negative"; return LADDER_E_ARG; }
   if (g->tp_degree > g->n_real_shards && g->peer_pool > 0 && g->peer_rows <= 0) { why = "peer_rows must be positive when peers are used"; return LADDER_E_SHAPE; }
   if ((long long)g->max_batch * g->max_tokens > (1ll << 24)) { why = "max_batch * max_tokens too large"; return LADDER_E_SHAPE; }
@@ -154,12 +177,14 @@ bool fast_shapes_ok(const ladder_config* g) {
   const int gq = g->n_q_heads / g->n_kv_heads;
   return g->dtype == LADDER_BF16 && g->hidden % 32 == 0 && (g->n_q_heads * g->head_dim) % 32 == 0 &&
          g->inter % 32 == 0 && (g->head_dim == 64 || g->head_dim == 128) &&
-         (gq == 1 || gq == 2 || gq == 4 || gq == 8);
+         (gq == 1 || gq == 2 || gq == 4 || gq == 8) && g->max_seq <= 65536;
 }
 
 int collect_profile(ladder_ctx* c) {
   if (c->prof_pending.empty()) return LADDER_OK;
   HIP_TRY(c, hipStreamSynchronize(c->main));
+  HIP_TRY(c, hipStreamSynchronize(c->s_attn));
+  HIP_TRY(c, hipStreamSynchronize(c->s_mlp));
   HIP_TRY(c, hipStreamSynchronize(c->side));
   for (auto& r : c->prof_pending) {
     float ms = 0.f;
@@ -176,7 +201,7 @@ int collect_profile(ladder_ctx* c) {
 // ---------------------------------------------------------------------------------------------
 // one module's compute on the main stream; writes parts[m%2]; returns the number of slots written
 // ---------------------------------------------------------------------------------------------
-int run_module(ladder_ctx* c, int m, int B, int T, int pos0, int* n_slots) {
+int run_module(ladder_ctx* c, int m, int B, int T, int pos0, hipStream_t s, int* n_slots) {
   const ladder_config& g = c->cfg;
   const int rows = B * T, H = g.hidden, d = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, I = g.inter;
   const int layer = (m - 1) / 2, par = m & 1;
@@ -184,8 +209,8 @@ int run_module(ladder_ctx* c, int m, int B, int T, int pos0, int* n_slots) {
   const char* yin = c->y[par];
   float* pout = c->parts[par];
   const size_t pstride = (size_t)rows * H;
-  hipStream_t s = c->main;
   const bool skinny = rows <= 64;
+  const bool dev_pos = c->fast && T == 1;  // decode kernels of the bf16 path read the position from device memory
   int slots = 0;
   for (int r = 0; r < g.n_real_shards; ++r) {
     LayerStore& L = c->store[(size_t)layer * g.n_real_shards + r];
@@ -212,7 +237,7 @@ int run_module(ladder_ctx* c, int m, int B, int T, int pos0, int* n_slots) {
       ra.qkv = c->qkv; ra.n_parts = qkv_slots; ra.part_stride = (size_t)rows * c->nqkv;
       ra.q_out = c->qbuf; ra.cache_k = L.cache_k; ra.cache_v = L.cache_v;
       ra.cos_tab = c->cos_tab; ra.sin_tab = c->sin_tab;
-      ra.B = B; ra.T = T; ra.pos0 = pos0; ra.nq = nq; ra.nkv = nkv; ra.d = d; ra.max_seq = c->s_cap; ra.pos_dev = nullptr;
+      ra.B = B; ra.T = T; ra.pos0 = pos0; ra.nq = nq; ra.nkv = nkv; ra.d = d; ra.max_seq = c->s_cap; ra.pos_dev = dev_pos ? c->pos_dev : nullptr;
       HIP_TRY(c, timed(c, LADDER_K_ROPE_APPEND, s, [&] { return launch_rope_append(ra, c->bf16, s); }));
       if (!c->fast) {
         AttnGenericArgs aa{c->qbuf, L.cache_k, L.cache_v, c->obuf, B, T, pos0, nq, nkv, d, c->s_cap};
@@ -222,11 +247,14 @@ int run_module(ladder_ctx* c, int m, int B, int T, int pos0, int* n_slots) {
         aa.q = (const bf16_t*)c->qbuf; aa.cache_k = (const bf16_t*)L.cache_k; aa.cache_v = (const bf16_t*)L.cache_v;
         aa.part_o = c->att_o; aa.part_ml = c->att_ml; aa.o = (bf16_t*)c->obuf;
         aa.B = B; aa.nq = nq; aa.nkv = nkv; aa.d = d; aa.max_seq = c->s_cap; aa.n_pos = pos0 + 1;
+        // launch shape fixed by the cache capacity (not the current position) so that a captured step
+        // stays valid as the sequence grows; workgroups past the visible range exit at once
         int chunk = 32;
         for (int cand : {128, 64}) {
-          if ((long long)B * nkv * ((aa.n_pos + cand - 1) / cand) >= 256) { chunk = cand; break; }
+          if ((long long)B * nkv * ((g.max_seq + cand - 1) / cand) >= 256) { chunk = cand; break; }
         }
-        aa.chunk = chunk; aa.n_chunks = (aa.n_pos + chunk - 1) / chunk; aa.pos_dev = nullptr;
+        while (chunk < 128 && (g.max_seq + chunk - 1) / chunk > 512) chunk *= 2;  // combine holds <= 512 chunk weights
+        aa.chunk = chunk; aa.n_chunks = (g.max_seq + chunk - 1) / chunk; aa.pos_dev = c->pos_dev;
         HIP_TRY(c, timed(c, LADDER_K_ATTN_DECODE, s, [&] { return launch_attn_decode(aa, s); }));
       } else {
         AttnPrefillArgs aa{(const bf16_t*)c->qbuf, (const bf16_t*)L.cache_k, (const bf16_t*)L.cache_v,
@@ -314,29 +342,114 @@ int run_reduce(ladder_ctx* c, int m, int rows, int n_slots, const void* emb, flo
   return LADDER_OK;
 }
 
-int forward(ladder_ctx* c, const void* x_in, int B, int T, int pos0, void* x_out) {
+// the 2N modules and their reduces on the internal streams; does not touch the caller's stream.
+// Stream plan:
+//   overlap_modules: odd (attention) modules and their reduces on s_attn, even (MLP) modules and their
+//     reduces on s_mlp.  Under the ladder wiring module m+1 needs only x_{m-1}, so it executes while
+//     module m and reduce(m) still run on the other stream; reduce(m) waits for reduce(m-1) (the
+//     residual is updated in place, in module order) through an event.
+//   else reduce_on_side_stream: all modules on s_attn, all reduces on the side stream.
+//   else: everything in order on s_attn.
+int forward_body(ladder_ctx* c, const void* x_in, int B, int T, int pos0, void* x_out) {
   const int rows = B * T;
-  const bool side = c->cfg.reduce_on_side_stream != 0;
-  int rc = run_reduce(c, 0, rows, 0, x_in, c->n_mod == 0 ? (float*)x_out : nullptr, c->main);
+  const bool overlap = c->cfg.overlap_modules != 0;
+  const bool side = !overlap && c->cfg.reduce_on_side_stream != 0;
+  hipStream_t s0 = c->s_attn;
+  auto module_stream = [&](int m) { return (overlap && (m & 1) == 0) ? c->s_mlp : s0; };
+  auto reduce_stream = [&](int m) { return m == 0 ? s0 : (overlap ? module_stream(m) : (side ? c->side : s0)); };
+  int rc = run_reduce(c, 0, rows, 0, x_in, c->n_mod == 0 ? (float*)x_out : nullptr, s0);
   if (rc) return rc;
+  if (overlap && c->n_mod >= 2) {  // fork: the MLP stream starts once x_0 and its normed copies exist
+    HIP_TRY(c, hipEventRecord(c->ev_fork, s0));
+    HIP_TRY(c, hipStreamWaitEvent(c->s_mlp, c->ev_fork, 0));
+  }
   for (int m = 1; m <= c->n_mod; ++m) {
+    DBG("module %d", m);
+    hipStream_t sm = module_stream(m), rs = reduce_stream(m);
     const int src = m - lag_of(c, m);
-    if (side && src >= 1) HIP_TRY(c, hipStreamWaitEvent(c->main, c->ev_red[src & 1], 0));
+    if (src >= 1 && reduce_stream(src) != sm) HIP_TRY(c, hipStreamWaitEvent(sm, c->ev_red[src & 1], 0));
     int n_slots = 0;
-    rc = run_module(c, m, B, T, pos0, &n_slots);
+    rc = run_module(c, m, B, T, pos0, sm, &n_slots);
     if (rc) return rc;
-    hipStream_t rs = c->main;
-    if (side) {
-      HIP_TRY(c, hipEventRecord(c->ev_mod[m & 1], c->main));
-      HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_mod[m & 1], 0));
-      rs = c->side;
+    if (rs != sm) {
+      HIP_TRY(c, hipEventRecord(c->ev_mod[m & 1], sm));
+      HIP_TRY(c, hipStreamWaitEvent(rs, c->ev_mod[m & 1], 0));
     }
+    if (m >= 2 && reduce_stream(m - 1) != rs) HIP_TRY(c, hipStreamWaitEvent(rs, c->ev_red[(m - 1) & 1], 0));
     rc = run_reduce(c, m, rows, n_slots, nullptr, m == c->n_mod ? (float*)x_out : nullptr, rs);
     if (rc) return rc;
-    if (side) HIP_TRY(c, hipEventRecord(c->ev_red[m & 1], c->side));
+    if (overlap || side) HIP_TRY(c, hipEventRecord(c->ev_red[m & 1], rs));
   }
-  if (side) HIP_TRY(c, hipStreamWaitEvent(c->main, c->ev_red[c->n_mod & 1], 0));  // join
+  // join: the last reduce is after every module and every earlier reduce
+  if (c->n_mod >= 1 && reduce_stream(c->n_mod) != s0) HIP_TRY(c, hipStreamWaitEvent(s0, c->ev_red[c->n_mod & 1], 0));
   return LADDER_OK;
+}
+
+__global__ void set_pos_kernel(int* p, int v) { *p = v; }
+__global__ void inc_pos_kernel(int* p) { *p += 1; }
+
+int fence_in(ladder_ctx* c) {
+  HIP_TRY(c, hipEventRecord(c->ev_begin, c->main));
+  HIP_TRY(c, hipStreamWaitEvent(c->s_attn, c->ev_begin, 0));
+  return LADDER_OK;
+}
+int fence_out(ladder_ctx* c) {
+  HIP_TRY(c, hipEventRecord(c->ev_end, c->s_attn));
+  HIP_TRY(c, hipStreamWaitEvent(c->main, c->ev_end, 0));
+  return LADDER_OK;
+}
+
+int forward(ladder_ctx* c, const void* x_in, int B, int T, int pos0, void* x_out) {
+  int rc = fence_in(c);
+  if (rc) return rc;
+  rc = forward_body(c, x_in, B, T, pos0, x_out);
+  if (rc) return rc;
+  return fence_out(c);
+}
+
+// one decode step replayed from a captured graph: stage the input, launch, copy the result out
+int decode_graph_step(ladder_ctx* c, const void* x_in, void* x_out) {
+  const int B = c->batch, H = c->cfg.hidden;
+  if (!c->graph_exec || c->graph_batch != B) {
+    if (c->graph_exec) {
+      HIP_TRY(c, hipGraphExecDestroy(c->graph_exec));
+      c->graph_exec = nullptr;
+    }
+    hipGraph_t graph = nullptr;
+    DBG("capture: begin (batch %d)", B);
+    HIP_TRY(c, hipStreamBeginCapture(c->s_attn, hipStreamCaptureModeThreadLocal));
+    int rc = forward_body(c, c->emb_stage, B, 1, 0, nullptr);
+    DBG("capture: body recorded rc=%d", rc);
+    if (rc == LADDER_OK) {
+      DBG("capture: inc_pos");
+      hipLaunchKernelGGL(inc_pos_kernel, dim3(1), dim3(1), 0, c->s_attn, c->pos_dev);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) rc = fail(c, LADDER_E_HIP, std::string("inc_pos: ") + hipGetErrorString(e));
+    }
+    hipError_t ee = hipStreamEndCapture(c->s_attn, &graph);
+    DBG("capture: end -> %s", hipGetErrorString(ee));
+    if (rc) {
+      if (graph) (void)hipGraphDestroy(graph);
+      return rc;
+    }
+    if (ee != hipSuccess) return fail(c, LADDER_E_HIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(ee));
+    hipError_t ei = hipGraphInstantiate(&c->graph_exec, graph, nullptr, nullptr, 0);
+    DBG("capture: instantiate -> %s", hipGetErrorString(ei));
+    (void)hipGraphDestroy(graph);
+    if (ei != hipSuccess) {
+      c->graph_exec = nullptr;
+      return fail(c, LADDER_E_HIP, std::string("hipGraphInstantiate: ") + hipGetErrorString(ei));
+    }
+    c->graph_batch = B;
+  }
+  int rc = fence_in(c);
+  if (rc) return rc;
+  HIP_TRY(c, hipMemcpyAsync(c->emb_stage, x_in, (size_t)B * H * c->esz, hipMemcpyDeviceToDevice, c->s_attn));
+  DBG("graph launch");
+  HIP_TRY(c, hipGraphLaunch(c->graph_exec, c->s_attn));
+  DBG("graph launched");
+  HIP_TRY(c, hipMemcpyAsync(x_out, c->x, (size_t)B * H * 4, hipMemcpyDeviceToDevice, c->s_attn));
+  return fence_out(c);
 }
 
 int all_loaded(ladder_ctx* c) {
@@ -391,7 +504,12 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
     }                                                                                        \
   } while (0)
 
+  INIT_HIP(hipStreamCreateWithFlags(&c->s_attn, hipStreamNonBlocking));
+  INIT_HIP(hipStreamCreateWithFlags(&c->s_mlp, hipStreamNonBlocking));
   INIT_HIP(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+  INIT_HIP(hipEventCreateWithFlags(&c->ev_begin, hipEventDisableTiming));
+  INIT_HIP(hipEventCreateWithFlags(&c->ev_end, hipEventDisableTiming));
+  INIT_HIP(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
   for (int i = 0; i < 2; ++i) {
     INIT_HIP(hipEventCreateWithFlags(&c->ev_mod[i], hipEventDisableTiming));
     INIT_HIP(hipEventCreateWithFlags(&c->ev_red[i], hipEventDisableTiming));
@@ -469,6 +587,8 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
   const size_t skinny_rows = rows < 64 ? rows : 64;
   const size_t row_slots = rows > 8 * skinny_rows ? rows : 8 * skinny_rows;
   INIT_TRY(dev_alloc(c, (void**)&c->x, rows * H * 4, false));
+  INIT_TRY(dev_alloc(c, (void**)&c->pos_dev, 256, true));
+  INIT_TRY(dev_alloc(c, (void**)&c->emb_stage, (size_t)g.max_batch * H * esz, false));
   for (int i = 0; i < 2; ++i) INIT_TRY(dev_alloc(c, (void**)&c->y[i], rows * H * esz, false));
   c->parts_cap = (size_t)g.n_real_shards * H * row_slots;
   for (int i = 0; i < 2; ++i) INIT_TRY(dev_alloc(c, (void**)&c->parts[i], c->parts_cap * 4, false));
@@ -552,6 +672,8 @@ int ladder_load_kv(ladder_ctx* c, int32_t layer, int32_t shard, const void* k, c
   if (all) {
     c->pos = S;
     c->batch = B;
+    hipLaunchKernelGGL(set_pos_kernel, dim3(1), dim3(1), 0, c->main, c->pos_dev, S);
+    HIP_TRY(c, hipGetLastError());
   }
   return LADDER_OK;
 }
@@ -572,6 +694,8 @@ int ladder_prefill(ladder_ctx* c, const void* x_in, int32_t B, int32_t T, void* 
   for (auto& X : c->store) { X.kv_B = 0; X.kv_S = 0; }
   c->pos = T;
   c->batch = B;
+  hipLaunchKernelGGL(set_pos_kernel, dim3(1), dim3(1), 0, c->main, c->pos_dev, T);
+  HIP_TRY(c, hipGetLastError());
   return LADDER_OK;
 }
 
@@ -583,8 +707,15 @@ int ladder_decode_step(ladder_ctx* c, const void* x_in, void* x_out) {
   if (c->peers && c->batch > c->cfg.peer_rows) return fail(c, LADDER_E_SHAPE, "batch exceeds peer_rows");
   int rc = all_loaded(c);
   if (rc) return rc;
-  rc = forward(c, x_in, c->batch, 1, c->pos, x_out);
-  if (rc) return rc;
+  if (c->fast && c->cfg.decode_graph && !c->prof) {
+    rc = decode_graph_step(c, x_in, x_out);
+    if (rc) return rc;
+  } else {
+    rc = forward(c, x_in, c->batch, 1, c->pos, x_out);
+    if (rc) return rc;
+    hipLaunchKernelGGL(inc_pos_kernel, dim3(1), dim3(1), 0, c->main, c->pos_dev);
+    HIP_TRY(c, hipGetLastError());
+  }
   c->pos += 1;
   return LADDER_OK;
 }
@@ -592,10 +723,16 @@ int ladder_decode_step(ladder_ctx* c, const void* x_in, void* x_out) {
 void ladder_free(ladder_ctx* c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->main);
-  if (c->side) {
-    (void)hipStreamSynchronize(c->side);
-    (void)hipStreamDestroy(c->side);
+  for (hipStream_t* st : {&c->s_attn, &c->s_mlp, &c->side}) {
+    if (*st) {
+      (void)hipStreamSynchronize(*st);
+      (void)hipStreamDestroy(*st);
+    }
   }
+  if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
+  if (c->ev_begin) (void)hipEventDestroy(c->ev_begin);
+  if (c->ev_end) (void)hipEventDestroy(c->ev_end);
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
   for (auto& r : c->prof_pending) {
     (void)hipEventDestroy(r.start);
     (void)hipEventDestroy(r.stop);

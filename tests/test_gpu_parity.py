@@ -123,3 +123,28 @@ def test_error_codes_on_the_gpu(harness):
         ctx.set_peer_partials(x)                         # configuration without peers
     assert e.value.code == ladder.LADDER_E_SHAPE
     ctx.free()
+
+
+def test_graph_replay_overlap_and_eager_are_bit_identical(harness):
+    """A decode step replayed from the captured HIP graph (three streams), the same step launched
+    eagerly, and the single-compute-stream schedule all give the same bits; several replays, with
+    eager work and synchronisations in between (the harness copies every output to the host)."""
+    w = inputs.WORKLOADS["70b_r8_decode"].with_(name="r8_small", n_layers=3, hidden=512, inter=448, batch=4,
+                                                decode_steps=6)
+    ref = harness.run_case(w, kv_preload=100, gpu_only=True, decode_graph=0, overlap_modules=0,
+                           reduce_on_side_stream=0)
+    for kw in (dict(decode_graph=1, overlap_modules=1, reduce_on_side_stream=1),
+               dict(decode_graph=1, overlap_modules=0, reduce_on_side_stream=1),
+               dict(decode_graph=0, overlap_modules=1, reduce_on_side_stream=1),
+               dict(decode_graph=1, overlap_modules=1, reduce_on_side_stream=0)):
+        got = harness.run_case(w, kv_preload=100, gpu_only=True, **kw)
+        assert len(got.gpu) == len(ref.gpu) == 6
+        for x, y in zip(got.gpu, ref.gpu):
+            assert np.array_equal(x, y), kw
+
+
+def test_graph_decode_after_prefill_matches_oracle(harness):
+    """Prefill (eager) then graph-replayed decode steps, crossing an attention-chunk boundary."""
+    w = SMALL_BF16.with_(name="small_bf16_graph", prefill=60, decode_steps=8)
+    res = harness.run_case(w, decode_graph=1, overlap_modules=1)
+    assert max(res.errs) < TOL_BF16, res.errs
