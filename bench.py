@@ -103,7 +103,8 @@ def run_decode(args):
     prof_steps = 8
     total_steps = args.warmup + args.steps + prof_steps
     ctx = build_context(w, dev, total_steps, w.batch, max_tokens=max(w.prefill, 1),
-                        decode_graph=1 if args.graph else 0, overlap_modules=0 if args.no_overlap else 1)
+                        decode_graph=1 if args.graph else 0, overlap_modules=0 if args.no_overlap else 1,
+                        decode_fused=0 if args.no_fused else 1)
     if w.kv_preload:
         for i in range(w.n_layers):
             for r in range(w.n_real_shards):
@@ -139,15 +140,23 @@ def run_decode(args):
         ctx.decode_step(xs[args.warmup + args.steps + i], out)
     prof = ctx.profile_read()
     ctx.profile_enable(False)
-    n_gemv, ms_gemv = prof["gemv"]
-    gemv_bytes_per_launch = wb / (4 * w.n_layers * w.n_real_shards)   # 4 projections per layer and shard
+    if prof.get("fused_decode", (0, 0.0))[0]:
+        # fused path: every launch is the same kernel (one or two projections and/or the attention of
+        # one layer); algorithmic bytes of a step (weights + visible KV + peers) over its launches
+        kernel_name = "fused_decode_kernel (decode: weight-streaming skinny GEMM jobs + split-KV attention job)"
+        n_gemv, ms_gemv = prof["fused_decode"]
+        gemv_bytes_per_launch = step_bytes / (n_gemv / prof_steps)
+    else:
+        kernel_name = "gemv_mfma_kernel (decode weight-streaming skinny GEMM)"
+        n_gemv, ms_gemv = prof["gemv"]
+        gemv_bytes_per_launch = wb / (4 * w.n_layers * w.n_real_shards)   # 4 projections per layer and shard
     avg_ms = ms_gemv / max(n_gemv, 1)
     achieved = gemv_bytes_per_launch / (avg_ms * 1e-3) / 1e9 if n_gemv else 0.0
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"gemv_hbm_traffic_{w.name}.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
-    roofline = {"bound": "hbm", "kernel": "gemv_mfma_kernel (decode weight-streaming skinny GEMM)",
+    roofline = {"bound": "hbm", "kernel": kernel_name,
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "traffic": traffic, "algorithmic_bytes_per_launch": gemv_bytes_per_launch,
                 "avg_launch_ms": avg_ms, "launches": n_gemv}
@@ -238,6 +247,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--graph", action="store_true", help="replay decode steps from a captured HIP graph instead of eager launches")
     ap.add_argument("--no-overlap", action="store_true", help="one compute stream instead of attention / MLP streams")
+    ap.add_argument("--no-fused", action="store_true", help="one kernel per operation instead of the fused decode launches")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (one process, one MI355X); "

@@ -81,6 +81,10 @@ typedef struct {
                               while module m still runs; 0: one compute stream.  Same results. */
   int32_t decode_graph;   /* 1: a decode step of the bf16 streaming path is captured once into a HIP graph
                              (all streams) and replayed, removing the per-launch host cost; 0: eager launches */
+  int32_t decode_fused;   /* 1: decode steps of the bf16 streaming path (batch <= 16, one computed shard) use the
+                             fused launches: independent projections / attention of neighbouring modules
+                             share one launch, residual add, reduce, RMSNorm, rotary and the attention
+                             combine are epilogues / prologues; 0: one kernel per operation */
   float rms_eps;          /* RMSNorm epsilon (inside the square root) */
   float rope_theta;       /* rotary base; pair (2j,2j+1) turns by pos * theta^(-2j/d) */
 } ladder_config;
@@ -171,7 +175,8 @@ enum {
   LADDER_K_ATTN_PREFILL = 5,
   LADDER_K_GENERIC = 6,     /* plain kernels (fp32 / any-size path) */
   LADDER_K_OTHER = 7,
-  LADDER_K_COUNT = 8
+  LADDER_K_FUSED_DECODE = 8, /* fused decode launches (projection(s) and/or attention of one step) */
+  LADDER_K_COUNT = 9
 };
 int ladder_profile_enable(ladder_ctx* ctx, int32_t on);
 int ladder_profile_read(ladder_ctx* ctx, int32_t cls, int64_t* launches, double* total_ms);

@@ -52,7 +52,7 @@ struct ReduceNormArgs {
   int n_peers;
   size_t peer_stride;      // elements
   void* out_a;             // T or null
-  const void* gain_a;      // T
+  const void* gain_a;      // T, or null = no gain (it has been folded into the consumer's weights)
   void* out_b;
   const void* gain_b;
   float* x_out;            // f32 or null
@@ -107,8 +107,10 @@ static inline size_t packed_tiles_bytes(int K, int N) {
 // Repack src (bf16 [K][N], row stride N) into dst tiles at column-tile offset: column n of src becomes
 // packed column map(n).  mode 0: n -> col0 + n.  mode 1 (gate) / 2 (up): SwiGLU interleave,
 // n -> 16*(n/8) + (n%8) + (mode==2 ? 8 : 0), so each 16-wide tile holds 8 gate and the 8 matching up columns.
+// row_gain (bf16 [K], may be null): W[k][n] is multiplied by row_gain[k] before packing -- the RMSNorm
+// gain of the activations this projection reads, folded into the weights.
 hipError_t launch_repack_tiles(const bf16_t* src, void* dst, int K, int N, int N_total, int col0, int mode,
-                               hipStream_t s);
+                               const bf16_t* row_gain, hipStream_t s);
 
 struct GemvArgs {
   const bf16_t* x;         // bf16 [M][ldx]

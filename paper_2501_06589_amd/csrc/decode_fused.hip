@@ -1,0 +1,451 @@
+// Fused decode path of the bf16 storage type (gfx950), batch <= 16, one computed shard.
+//
+// One launch runs up to two independent JOBS side by side (workgroups pick their job from the
+// block index).  Under the ladder wiring module m+1 needs only x_{m-1}, so the MLP projections of
+// layer l and the attention-side work of layer l+1 have no dependency on each other: putting them
+// into ONE launch keeps HBM streaming while the small, latency-bound attention work runs, with no
+// stream, event or graph edge in between.  A decode step is three launches per layer:
+//     { qkv_{l+1} (+ RMSNorm, rotary, cache append) , down_l (+ residual add) }
+//     { attention_{l+1} , gate/up_{l+1} (+ RMSNorm, SwiGLU) }
+//     { o_{l+1} (+ residual add) }
+// Everything that used to be a kernel of its own is an epilogue or a prologue here, and none of it
+// needs one workgroup to talk to another (a device-wide release fence per workgroup was measured to
+// cost more than the whole projection):
+//   * "wait(); residual += out" of Algorithm 1 with the all-reduce written as a sum over rank partial
+//     sums (Eq. 2) is the epilogue of the module's last projection: x_m = x_{m-1} + h_m + sum(peers),
+//     written to a ring of three residual buffers (x_{m-1} is still read by the job that runs beside);
+//   * RMSNorm: the gain is folded into the rows of the following projection's weights when they are
+//     packed; a workgroup of that projection owns the whole K range, so it sees every element of the
+//     rows it multiplies: it feeds the bf16 copy of x to the matrix core, accumulates the rows' sums of
+//     squares from the same loads, and scales its outputs by 1/rms at the end (the factor commutes with
+//     the product);
+//   * rotary embedding + KV append: epilogue of the QKV projection;
+//   * attention: one workgroup per (sequence, kv head); its 8 wavefronts share out the visible
+//     positions, each with a running softmax on the matrix cores, and merge through LDS, so nothing is
+//     left to combine across workgroups; only when the cache is long enough to be split do the splits
+//     meet through an arrival ticket.
+// All sums are taken in a fixed order, so results are bit-reproducible run to run.
+#include <hip/hip_ext.h>
+
+#include "common.h"
+#include "decode_fused.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
+
+#define FUSED_THREADS 512
+#define FUSED_WAVES 8
+#define FUSED_U 2
+#define FUSED_TN 2
+#define FUSED_LDS_FLOATS 9216
+
+__device__ __forceinline__ float ld_coherent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+}
+
+__device__ __forceinline__ void unpack8f(const uint4 v, float f[8]) {
+  f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+  f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+  f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+  f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+}
+
+// ------------------------------------------------------------------------------------------------
+// skinny GEMM job: see gemv_mfma_kernel for the streaming scheme (same tiles, same pipeline).
+// A workgroup owns TN adjacent 16-column tiles and the whole K range; U k-tiles per register buffer.
+// (U, TN) = (2, 2) for the wide projections; (8, 1) for the QKV projection, which has few columns
+// and therefore needs more bytes in flight per wavefront to pull its share of the bandwidth.
+// ------------------------------------------------------------------------------------------------
+template <bool NORMED, int U, int TN>
+__device__ void gemv_job(const GemvJob& j, int grp, float* smem) {
+  constexpr int WAVES = FUSED_WAVES;
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int b = lane & 15, q = lane >> 4;
+  const int nt0 = grp * TN;
+  const int KT = j.K >> 5;
+  const int per_wave = (KT + WAVES - 1) / WAVES;
+  const int kt0 = wave * per_wave;
+  const int kt1 = min(KT, kt0 + per_wave);
+
+  f32x4_t acc[TN];
+#pragma unroll
+  for (int t = 0; t < TN; ++t) acc[t] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+  float ss = 0.f;  // NORMED: this lane's share of its row's sum of squares
+  const u32x4_t* wptr = reinterpret_cast<const u32x4_t*>(j.wp) + ((size_t)nt0 * KT) * 64 + lane;
+  const bool rowok = b < j.M;
+  const int rowc = min(b, j.M - 1);
+
+  const bf16_t* xbp = j.xb + (size_t)rowc * j.ldx + q * 8;
+
+  u32x4_t wa[TN][U], wb[TN][U], xa[U], xb[U];
+  auto load = [&](u32x4_t (&wv)[TN][U], u32x4_t (&xv)[U], int kt) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int ktc = min(kt + u, kt1 - 1);
+#pragma unroll
+      for (int t = 0; t < TN; ++t) wv[t][u] = __builtin_nontemporal_load(wptr + ((size_t)t * KT + ktc) * 64);
+      xv[u] = *reinterpret_cast<const u32x4_t*>(xbp + (size_t)ktc * 32);
+    }
+  };
+  auto fma = [&](const u32x4_t (&wv)[TN][U], const u32x4_t (&xv)[U], int kt) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool ok = rowok && (kt + u < kt1);
+      u32x4_t xz = xv[u];
+      if (NORMED) {  // the operand is the bf16 copy of the residual stream: its squares give the row's rms
+        float s8 = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float lo = __uint_as_float(xz[e] << 16), hi = __uint_as_float(xz[e] & 0xFFFF0000u);
+          s8 = fmaf(lo, lo, s8);
+          s8 = fmaf(hi, hi, s8);
+        }
+        ss += ok ? s8 : 0.f;
+      }
+      if (!ok) xz = (u32x4_t){0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int t = 0; t < TN; ++t)
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wv[t][u]),
+                                                        __builtin_bit_cast(bf16x8_t, xz), acc[t], 0, 0, 0);
+    }
+  };
+  if (kt0 < kt1) {
+    load(wa, xa, kt0);
+    for (int kt = kt0; kt < kt1; kt += 2 * U) {
+      load(wb, xb, kt + U);
+      __builtin_amdgcn_sched_barrier(0);
+      fma(wa, xa, kt);
+      __builtin_amdgcn_sched_barrier(0);
+      load(wa, xa, kt + 2 * U);
+      __builtin_amdgcn_sched_barrier(0);
+      fma(wb, xb, kt + U);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  // cross-wave sums through LDS: red[wave][tile][col in tile][row], ssq[wave][row]
+  float* red = smem;                            // WAVES * TN * 16 * 17 floats
+  float* ssq = smem + WAVES * TN * 16 * 17;     // WAVES * 16 floats
+#pragma unroll
+  for (int t = 0; t < TN; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[((wave * TN + t) * 16 + 4 * q + r) * 17 + b] = acc[t][r];
+  if (NORMED) {
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    if (q == 0) ssq[wave * 16 + b] = ss;
+  }
+  __syncthreads();
+  auto out_of = [&](int t, int col16, int row16) {  // finished output element: wave sums, then 1/rms of the row
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) v += red[((w * TN + t) * 16 + col16) * 17 + row16];
+    if (NORMED) {
+      float s = 0.f;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) s += ssq[w * 16 + row16];
+      v *= 1.0f / sqrtf(s / (float)j.K + j.eps);
+    }
+    return v;
+  };
+
+  if (j.epi == EPI_SWIGLU) {
+    // tile columns 0..7 = gate columns 8nt..8nt+7, columns 8..15 = the matching up columns
+    const int I = j.N >> 1;
+    if (tid < TN * 128) {
+      const int t = tid >> 7, row = (tid >> 3) & 15, c8 = tid & 7;
+      const int col = (nt0 + t) * 8 + c8;
+      if (row < j.M && col < I) {
+        const float g = out_of(t, c8, row), u = out_of(t, c8 + 8, row);
+        j.act[(size_t)row * I + col] = f32_to_bf16(g / (1.0f + __expf(-g)) * u);
+      }
+    }
+    return;
+  }
+
+  if (j.epi == EPI_RESIDUAL) {
+    if (tid < TN * 256) {
+      const int t = tid >> 8, row = (tid >> 4) & 15, col16 = tid & 15;
+      const int col = (nt0 + t) * 16 + col16;
+      if (row < j.M) {
+        float v = j.x_old[(size_t)row * j.N + col] + out_of(t, col16, row);
+        for (int p = 0; p < j.n_peers; ++p) v += bf16_to_f32(j.peers[p * j.peer_stride + (size_t)row * j.N + col]);
+        j.x_new[(size_t)row * j.N + col] = v;
+        j.xh_new[(size_t)row * j.N + col] = f32_to_bf16(v);   // what the projections that read x_m multiply
+      }
+    }
+    return;
+  }
+
+  // EPI_QKV_ROPE: TN*8 adjacent pairs in this workgroup's columns, all inside one head
+  if (tid < 16 * TN * 8) {
+    const int row = tid / (TN * 8), pr = tid % (TN * 8);
+    if (row < j.M) {
+      const int col = grp * (TN * 16) + 2 * pr;
+      const int c16 = (2 * pr) & 15, t = (2 * pr) >> 4;
+      float e = out_of(t, c16, row), o = out_of(t, c16 + 1, row);
+      const int pos = *j.pos_dev;
+      const int head = col / j.d, jj = (col % j.d) >> 1;
+      if (head < j.nq + j.nkv) {
+        const float c = j.cos_tab[(size_t)pos * (j.d >> 1) + jj], sn = j.sin_tab[(size_t)pos * (j.d >> 1) + jj];
+        const float re = e * c - o * sn, ro = e * sn + o * c;
+        e = re;
+        o = ro;
+      }
+      if (head < j.nq) {
+        *reinterpret_cast<uint32_t*>(j.q_out + (size_t)row * j.nq * j.d + col) = pack_bf16(e, o);
+      } else if (head < j.nq + j.nkv) {
+        const int kvh = head - j.nq;
+        *reinterpret_cast<uint32_t*>(j.cache_k + (((size_t)row * j.nkv + kvh) * j.max_seq + pos) * j.d + 2 * jj) =
+            pack_bf16(e, o);
+      } else {
+        const int kvh = head - j.nq - j.nkv;
+        bf16_t* vt = j.cache_v + (((size_t)row * j.nkv + kvh) * j.d + 2 * jj) * j.max_seq + pos;
+        vt[0] = f32_to_bf16(e);
+        vt[j.max_seq] = f32_to_bf16(o);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// decode attention job (MFMA, computed transposed as in the prefill kernel):
+//   S^T[key][head] = K Q^T        A = K tile (16 keys x 32 dims, straight from the K cache rows),
+//                                 B = Q^T (the G heads of this kv head as columns, rest zero);
+//   O^T[dim][head] = V^T P^T      A = V^T tile (16 dims x 32 keys, from the transposed V cache),
+//                                 B = the lane's own 8 probabilities of the 32-key block.
+// The 8 wavefronts take the 32-key blocks of the split round robin, each with its own running
+// softmax and no barrier in the loop; they merge once, through LDS, at the end.
+// ------------------------------------------------------------------------------------------------
+template <int D, int G>
+__device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag) {
+  constexpr int DS = D / 32, DT = D / 16;
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int b = lane & 15, q = lane >> 4;
+  const int sp = lb % a.n_splits, kvh = (lb / a.n_splits) % a.nkv, bi = lb / (a.n_splits * a.nkv);
+  const int n_pos = *a.pos_dev + 1;
+  const int pbeg = sp * a.split_len;
+  if (pbeg >= n_pos) return;  // nothing visible in this split: the workgroup leaves, no ticket taken
+  const int pend = min(n_pos, pbeg + a.split_len);
+  const float scale = 1.0f / sqrtf((float)D);
+
+  const bf16_t* kc = a.cache_k + ((size_t)bi * a.nkv + kvh) * a.max_seq * D;
+  const bf16_t* vc = a.cache_v + ((size_t)bi * a.nkv + kvh) * D * a.max_seq;
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  uint4 qreg[DS];
+  {
+    const bf16_t* qg = a.q + (size_t)bi * a.nq * D + (size_t)(kvh * G + min(b, G - 1)) * D;
+#pragma unroll
+    for (int s = 0; s < DS; ++s) {
+      const uint4 v = *reinterpret_cast<const uint4*>(qg + s * 32 + q * 8);
+      qreg[s] = b < G ? v : zero4;
+    }
+  }
+  f32x4_t oacc[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) oacc[dt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+  float mrun = -INFINITY, lrun = 0.f;
+
+  for (int kb = pbeg + 32 * wave; kb < pend; kb += 32 * FUSED_WAVES) {
+    uint4 kreg[2][DS];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int s = 0; s < DS; ++s)
+        kreg[t][s] = *reinterpret_cast<const uint4*>(kc + (size_t)(kb + 16 * t + b) * D + s * 32 + q * 8);
+    uint4 vreg[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const bf16_t* vp = vc + (size_t)(dt * 16 + b) * a.max_seq + kb + 4 * q;
+      const uint2 lo = *reinterpret_cast<const uint2*>(vp);
+      const uint2 hi = *reinterpret_cast<const uint2*>(vp + 16);
+      vreg[dt] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    }
+    f32x4_t st[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      st[t] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < DS; ++s)
+        st[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kreg[t][s]),
+                                                       __builtin_bit_cast(bf16x8_t, qreg[s]), st[t], 0, 0, 0);
+    }
+    float sv[8], mloc = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int key = kb + 16 * t + 4 * q + r;
+        const float v = key < pend ? st[t][r] * scale : -INFINITY;   // positions past the new token: masked
+        sv[t * 4 + r] = v;
+        mloc = fmaxf(mloc, v);
+      }
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 16, 64));
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+    const float mnew = fmaxf(mrun, mloc);      // finite: key kb itself is < pend
+    const float corr = __expf(mrun - mnew);
+    float pv[8], psum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      pv[e] = __expf(sv[e] - mnew);
+      psum += pv[e];
+    }
+    lrun = lrun * corr + psum;
+    mrun = mnew;
+    uint4 pb;
+    pb.x = pack_bf16(pv[0], pv[1]); pb.y = pack_bf16(pv[2], pv[3]);
+    pb.z = pack_bf16(pv[4], pv[5]); pb.w = pack_bf16(pv[6], pv[7]);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) oacc[dt][r] *= corr;
+      oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vreg[dt]),
+                                                        __builtin_bit_cast(bf16x8_t, pb), oacc[dt], 0, 0, 0);
+    }
+  }
+  // per-wave (max, sum, O^T) -> LDS; oacc[dt][r] = O^T[dim = dt*16 + 4q + r][head b]
+  lrun += __shfl_xor(lrun, 16, 64);
+  lrun += __shfl_xor(lrun, 32, 64);
+  float* wm = smem;                          // [WAVES][16]
+  float* wl = wm + FUSED_WAVES * 16;         // [WAVES][16]
+  float* wo = wl + FUSED_WAVES * 16;         // [WAVES][G][D]
+  float* wgt = wo + FUSED_WAVES * G * D;     // [G][n_splits] (merge of splits only); overlaps nothing above
+  if (q == 0) { wm[wave * 16 + b] = mrun; wl[wave * 16 + b] = lrun; }
+  if (b < G) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) wo[(wave * G + b) * D + dt * 16 + 4 * q + r] = oacc[dt][r];
+  }
+  __syncthreads();
+  const size_t pbase = ((size_t)bi * a.nkv + kvh) * a.n_splits;
+  for (int i = tid; i < G * D; i += FUSED_THREADS) {
+    const int h = i / D, dim = i % D;
+    float m = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < FUSED_WAVES; ++w) m = fmaxf(m, wm[w * 16 + h]);
+    float l = 0.f, o = 0.f;
+#pragma unroll
+    for (int w = 0; w < FUSED_WAVES; ++w) {
+      const float f = __expf(wm[w * 16 + h] - m);   // 0 for a wave that saw no block
+      l += wl[w * 16 + h] * f;
+      o += wo[(w * G + h) * D + dim] * f;
+    }
+    if (a.n_splits == 1) {
+      a.o[(size_t)bi * a.nq * D + (size_t)(kvh * G + h) * D + dim] = f32_to_bf16(o / l);
+    } else {
+      a.part_o[((pbase + sp) * G + h) * D + dim] = o;
+      if (dim == 0) {
+        a.part_ml[((pbase + sp) * G + h) * 2 + 0] = m;
+        a.part_ml[((pbase + sp) * G + h) * 2 + 1] = l;
+      }
+    }
+  }
+  if (a.n_splits == 1) return;
+
+  // several splits: the last one to arrive merges them (fixed order)
+  const int n_active = min(a.n_splits, (n_pos + a.split_len - 1) / a.split_len);
+  __syncthreads();
+  if (tid == 0) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    const unsigned t = atomicAdd(a.tickets + bi * a.nkv + kvh, 1u);
+    *s_flag = t;
+    if (t == (unsigned)n_active - 1) a.tickets[bi * a.nkv + kvh] = 0u;  // ready for the next launch
+  }
+  __syncthreads();
+  if (*s_flag != (unsigned)n_active - 1) return;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  float* hl = wl;  // reuse
+  for (int h = wave; h < G; h += FUSED_WAVES) {
+    float m = -INFINITY;
+    for (int s = lane; s < n_active; s += 64) m = fmaxf(m, ld_coherent(a.part_ml + ((pbase + s) * G + h) * 2));
+    m = wave_max(m);
+    float l = 0.f;
+    for (int s = lane; s < n_active; s += 64) {
+      const float w = __expf(ld_coherent(a.part_ml + ((pbase + s) * G + h) * 2) - m);
+      wgt[h * a.n_splits + s] = w;
+      l += ld_coherent(a.part_ml + ((pbase + s) * G + h) * 2 + 1) * w;
+    }
+    l = wave_sum(l);
+    if (lane == 0) hl[h] = l;
+  }
+  __syncthreads();
+  for (int i = tid; i < G * D; i += FUSED_THREADS) {
+    const int h = i / D;
+    float o = 0.f;
+    for (int s = 0; s < n_active; ++s) o += ld_coherent(a.part_o + (pbase + s) * G * D + i) * wgt[h * a.n_splits + s];
+    a.o[(size_t)bi * a.nq * D + (size_t)kvh * G * D + i] = f32_to_bf16(o / hl[h]);
+  }
+}
+
+template <int D, int G>
+__global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(FusedArgs fa) {
+  __shared__ float smem[FUSED_LDS_FLOATS];
+  __shared__ unsigned s_flag;
+  int lb = blockIdx.x, job = 0;
+  if (lb >= fa.block_end[0]) {
+    lb -= fa.block_end[0];
+    job = 1;
+  }
+  if (fa.kind[job] == JOB_ATTN) {
+    attn_job<D, G>(fa.a, lb, smem, &s_flag);
+  } else {
+    const GemvJob& j = fa.g[job];
+    if (j.epi == EPI_QKV_ROPE) gemv_job<true, 4, 1>(j, lb, smem);
+    else if (j.normed) gemv_job<true, 2, 2>(j, lb, smem);
+    else gemv_job<false, 2, 2>(j, lb, smem);
+  }
+}
+
+// x_0 = embeddings: fp32 for the residual chain, bf16 copy for the projections
+__global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ emb, float* __restrict__ x0,
+                                                    bf16_t* __restrict__ xh0, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) {
+    x0[i] = bf16_to_f32(emb[i]);
+    xh0[i] = emb[i];
+  }
+}
+
+hipError_t launch_embed(const bf16_t* emb, float* x0, bf16_t* xh0, int n, hipStream_t s, hipEvent_t ev0,
+                        hipEvent_t ev1) {
+  const dim3 grid((n + 255) / 256), block(256);
+  if (ev0 || ev1) hipExtLaunchKernelGGL(embed_kernel, grid, block, 0, s, ev0, ev1, 0, emb, x0, xh0, n);
+  else hipLaunchKernelGGL(embed_kernel, grid, block, 0, s, emb, x0, xh0, n);
+  return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+  const dim3 block(FUSED_THREADS);
+  // with events: the dispatch itself carries them, so their distance is the kernel's own run time
+#define FUSED_LAUNCH(GQ)                                                                                    \
+  do {                                                                                                      \
+    if (ev0 || ev1) hipExtLaunchKernelGGL((fused_decode_kernel<D, GQ>), grid, block, 0, s, ev0, ev1, 0, fa); \
+    else hipLaunchKernelGGL((fused_decode_kernel<D, GQ>), grid, block, 0, s, fa);                           \
+  } while (0)
+  switch (g) {
+    case 1: FUSED_LAUNCH(1); break;
+    case 2: FUSED_LAUNCH(2); break;
+    case 4: FUSED_LAUNCH(4); break;
+    case 8: FUSED_LAUNCH(8); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef FUSED_LAUNCH
+  return hipGetLastError();
+}
+
+hipError_t launch_fused_decode(const FusedArgs& fa, int d, int g, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+  const int total = fa.block_end[fa.n_jobs - 1];
+  if (total <= 0) return hipErrorInvalidValue;
+  if (d == 128) return launch_fused_d<128>(fa, g, dim3(total), s, ev0, ev1);
+  if (d == 64) return launch_fused_d<64>(fa, g, dim3(total), s, ev0, ev1);
+  return hipErrorInvalidValue;
+}

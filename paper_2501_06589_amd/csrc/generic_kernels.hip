@@ -71,12 +71,14 @@ __global__ void reduce_norm_kernel(ReduceNormArgs a) {
     float v[4], g[4], y[4];
     load4<float>(xr + i, v);  // this thread's own writes
     if (oa) {
-      load4<T>(ga + i, g);
+      if (ga) load4<T>(ga + i, g);
+      else g[0] = g[1] = g[2] = g[3] = 1.f;
       for (int e = 0; e < 4; ++e) y[e] = v[e] * rs * g[e];
       store4<T>(oa + (size_t)row * H + i, y);
     }
     if (ob) {
-      load4<T>(gb + i, g);
+      if (gb) load4<T>(gb + i, g);
+      else g[0] = g[1] = g[2] = g[3] = 1.f;
       for (int e = 0; e < 4; ++e) y[e] = v[e] * rs * g[e];
       store4<T>(ob + (size_t)row * H + i, y);
     }

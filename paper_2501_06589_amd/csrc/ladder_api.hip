@@ -18,6 +18,7 @@
 
 #include "../../include/ladder.h"
 #include "common.h"
+#include "decode_fused.h"
 
 namespace {
 
@@ -71,6 +72,15 @@ struct ladder_ctx {
   char *qbuf = nullptr, *obuf = nullptr, *act = nullptr;
   float* gu = nullptr;
   float *att_o = nullptr, *att_ml = nullptr;
+  // fused decode path: ring of three residual buffers (x_m lives in ring[m % 3]), arrival tickets, and
+  // the launch list of one step
+  bool fused = false;
+  float* x_ring[3] = {nullptr, nullptr, nullptr};
+  bf16_t* xh_ring[3] = {nullptr, nullptr, nullptr};   // bf16 copies: the operand of the projections
+  unsigned* tk_att = nullptr;     // arrival tickets of split attention, [max_batch][nkv]
+  std::vector<FusedArgs> fused_plan;
+  int fused_plan_batch = 0;
+  const char* fused_plan_peers = nullptr;
   int pos = 0, batch = 0;
   std::string err;
   // profiling
@@ -167,6 +177,7 @@ int check_config(const ladder_config* g, std::string& why) {
   if (g->n_real_shards > g->tp_degree) { why = "n_real_shards exceeds tp_degree"; return LADDER_E_SHAPE; }
   if (g->max_tokens > g->max_seq) { why = "max_tokens exceeds max_seq"; return LADDER_E_SHAPE; }
   if ((g->decode_graph != 0 && g->decode_graph != 1) || (g->overlap_modules != 0 && g->overlap_modules != 1)) { why = "decode_graph / overlap_modules must be 0 or 1"; return LADDER_E_ARG; }
+  if (g->decode_fused != 0 && g->decode_fused != 1) { why = "decode_fused must be 0 or 1"; return LADDER_E_ARG; }
   if (g->peer_pool < 0 || g->peer_rows < 0) { why = "peer_pool / peer_rows negative"; return LADDER_E_ARG; }
   if (g->tp_degree > g->n_real_shards && g->peer_pool > 0 && g->peer_rows <= 0) { why = "peer_rows must be positive when peers are used"; return LADDER_E_SHAPE; }
   if ((long long)g->max_batch * g->max_tokens > (1ll << 24)) { why = "max_batch * max_tokens too large"; return LADDER_E_SHAPE; }
@@ -333,7 +344,8 @@ int run_reduce(ladder_ctx* c, int m, int rows, int n_slots, const void* emb, flo
   for (int i = 0; i < nc; ++i) {
     const int cm = consumers[i], layer = (cm - 1) / 2;
     void* out = c->y[cm & 1];
-    const void* gain = (cm & 1) ? c->gain_attn[layer] : c->gain_mlp[layer];
+    // packed-weight path: the gain lives in the consumer's weights
+    const void* gain = c->fast ? nullptr : ((cm & 1) ? (const void*)c->gain_attn[layer] : (const void*)c->gain_mlp[layer]);
     if (i == 0) { a.out_a = out; a.gain_a = gain; }
     else { a.out_b = out; a.gain_b = gain; }
   }
@@ -388,6 +400,151 @@ int forward_body(ladder_ctx* c, const void* x_in, int B, int T, int pos0, void* 
 __global__ void set_pos_kernel(int* p, int v) { *p = v; }
 __global__ void inc_pos_kernel(int* p) { *p += 1; }
 
+// ---------------------------------------------------------------------------------------------
+// fused decode path: the launch list of one step (see decode_fused.hip)
+// ---------------------------------------------------------------------------------------------
+bool fused_usable(const ladder_ctx* c) {
+  const ladder_config& g = c->cfg;
+  return c->fast && g.decode_fused != 0 && g.n_real_shards == 1 && g.max_batch <= 16 && g.max_seq <= 65536 &&
+         g.hidden % 32 == 0;
+}
+
+void build_fused_plan(ladder_ctx* c, int B) {
+  const ladder_config& g = c->cfg;
+  const int H = g.hidden, d = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, I = g.inter, N = g.n_layers;
+  const int nqd = nq * d;
+  // attention: one workgroup per (sequence, kv head) up to 2048 cached positions, split beyond that
+  const int split_len = 2048;
+  const int n_splits = (g.max_seq + split_len - 1) / split_len;
+  auto layer = [&](int l) -> LayerStore& { return c->store[(size_t)(l - 1)]; };  // l = 1..N (one shard)
+
+  auto job_qkv = [&](int l, int src) {
+    GemvJob j{};
+    j.xb = c->xh_ring[src % 3]; j.ldx = H; j.normed = 1; j.eps = g.rms_eps;
+    j.wp = layer(l).pqkv; j.M = B; j.K = H; j.N = c->nqkv;
+    j.n_groups = c->nqkv / 16; j.epi = EPI_QKV_ROPE;
+    j.q_out = (bf16_t*)c->qbuf;
+    j.cache_k = (bf16_t*)layer(l).cache_k; j.cache_v = (bf16_t*)layer(l).cache_v;
+    j.cos_tab = c->cos_tab; j.sin_tab = c->sin_tab; j.pos_dev = c->pos_dev;
+    j.nq = nq; j.nkv = nkv; j.d = d; j.max_seq = c->s_cap;
+    return j;
+  };
+  auto residual = [&](GemvJob& j, int m) {
+    j.N = H; j.n_groups = H / 32; j.epi = EPI_RESIDUAL;
+    j.x_old = c->x_ring[(m - 1) % 3]; j.x_new = c->x_ring[m % 3]; j.xh_new = c->xh_ring[m % 3];
+    if (c->peers && c->n_peers > 0) {
+      j.peers = (const bf16_t*)c->peers + (size_t)(m % g.peer_pool) * c->n_peers * (size_t)g.peer_rows * H;
+      j.n_peers = c->n_peers; j.peer_stride = (size_t)g.peer_rows * H;
+    }
+  };
+  auto job_o = [&](int l, int m) {
+    GemvJob j{};
+    j.xb = (const bf16_t*)c->obuf; j.ldx = nqd; j.wp = layer(l).po; j.M = B; j.K = nqd;
+    residual(j, m);
+    return j;
+  };
+  auto job_gu = [&](int l, int src) {
+    GemvJob j{};
+    j.xb = c->xh_ring[src % 3]; j.ldx = H; j.normed = 1; j.eps = g.rms_eps;
+    j.wp = layer(l).pgu; j.M = B; j.K = H; j.N = 2 * I;
+    j.n_groups = 2 * I / 32; j.epi = EPI_SWIGLU; j.act = (bf16_t*)c->act;
+    return j;
+  };
+  auto job_dn = [&](int l, int m) {
+    GemvJob j{};
+    j.xb = (const bf16_t*)c->act; j.ldx = I; j.wp = layer(l).pd; j.M = B; j.K = I;
+    residual(j, m);
+    return j;
+  };
+  auto job_att = [&](int l) {
+    AttnJob a{};
+    a.q = (const bf16_t*)c->qbuf; a.cache_k = (const bf16_t*)layer(l).cache_k; a.cache_v = (const bf16_t*)layer(l).cache_v;
+    a.part_o = c->att_o; a.part_ml = c->att_ml; a.o = (bf16_t*)c->obuf; a.tickets = c->tk_att;
+    a.B = B; a.nq = nq; a.nkv = nkv; a.max_seq = c->s_cap; a.n_splits = n_splits; a.split_len = split_len;
+    a.pos_dev = c->pos_dev;
+    return a;
+  };
+  auto blocks_of = [&](const GemvJob& j) { return j.n_groups; };
+  auto one = [&](const GemvJob& j) {
+    FusedArgs f{};
+    f.n_jobs = 1; f.kind[0] = JOB_GEMV; f.g[0] = j; f.block_end[0] = blocks_of(j); f.block_end[1] = f.block_end[0];
+    return f;
+  };
+  auto two = [&](const GemvJob& small, const GemvJob& big) {  // the latency-bound job takes the low block indices
+    FusedArgs f{};
+    f.n_jobs = 2; f.kind[0] = JOB_GEMV; f.kind[1] = JOB_GEMV; f.g[0] = small; f.g[1] = big;
+    f.block_end[0] = blocks_of(small); f.block_end[1] = f.block_end[0] + blocks_of(big);
+    return f;
+  };
+  auto att = [&](int l, const GemvJob* beside) {
+    FusedArgs f{};
+    f.kind[0] = JOB_ATTN; f.a = job_att(l); f.block_end[0] = n_splits * nkv * B; f.n_jobs = 1; f.block_end[1] = f.block_end[0];
+    if (beside) {
+      f.n_jobs = 2; f.kind[1] = JOB_GEMV; f.g[1] = *beside; f.block_end[1] = f.block_end[0] + blocks_of(*beside);
+    }
+    return f;
+  };
+  auto src_of = [&](int m) { const int s = m - lag_of(c, m); return s < 0 ? 0 : s; };
+
+  std::vector<FusedArgs>& plan = c->fused_plan;
+  plan.clear();
+  const bool all_ladder = g.wiring == LADDER_WIRING_LADDER && g.n_standard_layers == 0;
+  if (all_ladder) {
+    // modules 1 and 2 both read x_0; then, layer by layer, the MLP of layer l runs beside the attention of l+1
+    plan.push_back(two(job_qkv(1, 0), job_gu(1, 0)));
+    plan.push_back(att(1, nullptr));
+    plan.push_back(one(job_o(1, 1)));
+    for (int l = 1; l < N; ++l) {
+      plan.push_back(two(job_qkv(l + 1, 2 * l - 1), job_dn(l, 2 * l)));
+      GemvJob gu = job_gu(l + 1, 2 * l);
+      plan.push_back(att(l + 1, &gu));
+      plan.push_back(one(job_o(l + 1, 2 * l + 1)));
+    }
+    plan.push_back(one(job_dn(N, 2 * N)));
+  } else {
+    for (int l = 1; l <= N; ++l) {
+      plan.push_back(one(job_qkv(l, src_of(2 * l - 1))));
+      plan.push_back(att(l, nullptr));
+      plan.push_back(one(job_o(l, 2 * l - 1)));
+      plan.push_back(one(job_gu(l, src_of(2 * l))));
+      plan.push_back(one(job_dn(l, 2 * l)));
+    }
+  }
+  c->fused_plan_batch = B;
+  c->fused_plan_peers = c->peers;
+}
+
+// one decode step on stream s: x_0 from `emb`, the launch list, x_2N left in ring[2N % 3]
+int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s) {
+  const ladder_config& g = c->cfg;
+  if (c->fused_plan.empty() || c->fused_plan_batch != B || c->fused_plan_peers != c->peers) build_fused_plan(c, B);
+  auto events = [&](hipEvent_t (&e)[2]) -> hipError_t {
+    e[0] = e[1] = nullptr;
+    if (!c->prof) return hipSuccess;
+    for (int i = 0; i < 2; ++i) {
+      if (!c->prof_pool.empty()) {
+        e[i] = c->prof_pool.back();
+        c->prof_pool.pop_back();
+      } else {
+        hipError_t r = hipEventCreate(&e[i]);
+        if (r != hipSuccess) return r;
+      }
+    }
+    return hipSuccess;
+  };
+  hipEvent_t e[2];
+  HIP_TRY(c, events(e));
+  HIP_TRY(c, launch_embed((const bf16_t*)emb, c->x_ring[0], c->xh_ring[0], B * g.hidden, s, e[0], e[1]));
+  if (c->prof) c->prof_pending.push_back({LADDER_K_OTHER, e[0], e[1]});
+  const int gq = g.n_q_heads / g.n_kv_heads;
+  for (const FusedArgs& fa : c->fused_plan) {
+    HIP_TRY(c, events(e));
+    HIP_TRY(c, launch_fused_decode(fa, g.head_dim, gq, s, e[0], e[1]));
+    if (c->prof) c->prof_pending.push_back({LADDER_K_FUSED_DECODE, e[0], e[1]});
+  }
+  return LADDER_OK;
+}
+
 int fence_in(ladder_ctx* c) {
   HIP_TRY(c, hipEventRecord(c->ev_begin, c->main));
   HIP_TRY(c, hipStreamWaitEvent(c->s_attn, c->ev_begin, 0));
@@ -418,7 +575,7 @@ int decode_graph_step(ladder_ctx* c, const void* x_in, void* x_out) {
     hipGraph_t graph = nullptr;
     DBG("capture: begin (batch %d)", B);
     HIP_TRY(c, hipStreamBeginCapture(c->s_attn, hipStreamCaptureModeThreadLocal));
-    int rc = forward_body(c, c->emb_stage, B, 1, 0, nullptr);
+    int rc = c->fused ? fused_body(c, c->emb_stage, B, c->s_attn) : forward_body(c, c->emb_stage, B, 1, 0, nullptr);
     DBG("capture: body recorded rc=%d", rc);
     if (rc == LADDER_OK) {
       DBG("capture: inc_pos");
@@ -448,7 +605,21 @@ int decode_graph_step(ladder_ctx* c, const void* x_in, void* x_out) {
   DBG("graph launch");
   HIP_TRY(c, hipGraphLaunch(c->graph_exec, c->s_attn));
   DBG("graph launched");
-  HIP_TRY(c, hipMemcpyAsync(x_out, c->x, (size_t)B * H * 4, hipMemcpyDeviceToDevice, c->s_attn));
+  const float* result = c->fused ? c->x_ring[c->n_mod % 3] : c->x;
+  HIP_TRY(c, hipMemcpyAsync(x_out, result, (size_t)B * H * 4, hipMemcpyDeviceToDevice, c->s_attn));
+  return fence_out(c);
+}
+
+// one decode step of the fused path, launched eagerly
+int decode_fused_step(ladder_ctx* c, const void* x_in, void* x_out) {
+  const int B = c->batch, H = c->cfg.hidden;
+  int rc = fence_in(c);
+  if (rc) return rc;
+  rc = fused_body(c, x_in, B, c->s_attn);
+  if (rc) return rc;
+  HIP_TRY(c, hipMemcpyAsync(x_out, c->x_ring[c->n_mod % 3], (size_t)B * H * 4, hipMemcpyDeviceToDevice, c->s_attn));
+  hipLaunchKernelGGL(inc_pos_kernel, dim3(1), dim3(1), 0, c->s_attn, c->pos_dev);
+  HIP_TRY(c, hipGetLastError());
   return fence_out(c);
 }
 
@@ -603,6 +774,15 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
     const size_t gq = nq / nkv;
     INIT_TRY(dev_alloc(c, (void**)&c->att_o, (size_t)g.max_batch * nkv * chunks * gq * d * 4, false));
     INIT_TRY(dev_alloc(c, (void**)&c->att_ml, (size_t)g.max_batch * nkv * chunks * gq * 2 * 4, false));
+    c->fused = fused_usable(c);
+    if (c->fused) {
+      for (int i = 0; i < 3; ++i) {
+        INIT_TRY(dev_alloc(c, (void**)&c->x_ring[i], (size_t)16 * H * 4, true));
+        INIT_TRY(dev_alloc(c, (void**)&c->xh_ring[i], (size_t)16 * H * 2, true));
+      }
+      // arrival tickets start at zero and are put back to zero by the last arrival of every launch
+      INIT_TRY(dev_alloc(c, (void**)&c->tk_att, (size_t)g.max_batch * nkv * 4, true));
+    }
   }
 #undef INIT_TRY
 #undef INIT_HIP
@@ -628,13 +808,17 @@ int ladder_load_layer(ladder_ctx* c, int32_t layer, int32_t shard, const ladder_
     c->gains_loaded[layer] = 1;
   }
   if (c->fast) {
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wq, L.pqkv, H, nq * d, c->nqkv, 0, 0, s));
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wk, L.pqkv, H, nkv * d, c->nqkv, nq * d, 0, s));
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wv, L.pqkv, H, nkv * d, c->nqkv, (nq + nkv) * d, 0, s));
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wo, L.po, nq * d, H, H, 0, 0, s));
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_gate, L.pgu, H, I, 2 * I, 0, 1, s));
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_up, L.pgu, H, I, 2 * I, 0, 2, s));
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_down, L.pd, I, H, H, 0, 0, s));
+    // the RMSNorm gains are folded into the rows of the projections that read the normed stream
+    // (every shard's call must therefore carry the gains; they are replicated across ranks)
+    if (!w->attn_norm || !w->mlp_norm) return fail(c, LADDER_E_ARG, "null gain pointer");
+    const bf16_t *ga = (const bf16_t*)w->attn_norm, *gm = (const bf16_t*)w->mlp_norm;
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wq, L.pqkv, H, nq * d, c->nqkv, 0, 0, ga, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wk, L.pqkv, H, nkv * d, c->nqkv, nq * d, 0, ga, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wv, L.pqkv, H, nkv * d, c->nqkv, (nq + nkv) * d, 0, ga, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wo, L.po, nq * d, H, H, 0, 0, nullptr, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_gate, L.pgu, H, I, 2 * I, 0, 1, gm, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_up, L.pgu, H, I, 2 * I, 0, 2, gm, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_down, L.pd, I, H, H, 0, 0, nullptr, s));
   } else {
     HIP_TRY(c, hipMemcpyAsync(L.wq, w->wq, (size_t)H * nq * d * esz, hipMemcpyDeviceToDevice, s));
     HIP_TRY(c, hipMemcpyAsync(L.wk, w->wk, (size_t)H * nkv * d * esz, hipMemcpyDeviceToDevice, s));
@@ -709,6 +893,9 @@ int ladder_decode_step(ladder_ctx* c, const void* x_in, void* x_out) {
   if (rc) return rc;
   if (c->fast && c->cfg.decode_graph && !c->prof) {
     rc = decode_graph_step(c, x_in, x_out);
+    if (rc) return rc;
+  } else if (c->fused) {
+    rc = decode_fused_step(c, x_in, x_out);
     if (rc) return rc;
   } else {
     rc = forward(c, x_in, c->batch, 1, c->pos, x_out);

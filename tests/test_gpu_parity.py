@@ -132,12 +132,12 @@ def test_graph_replay_overlap_and_eager_are_bit_identical(harness):
     w = inputs.WORKLOADS["70b_r8_decode"].with_(name="r8_small", n_layers=3, hidden=512, inter=448, batch=4,
                                                 decode_steps=6)
     ref = harness.run_case(w, kv_preload=100, gpu_only=True, decode_graph=0, overlap_modules=0,
-                           reduce_on_side_stream=0)
+                           reduce_on_side_stream=0, decode_fused=0)
     for kw in (dict(decode_graph=1, overlap_modules=1, reduce_on_side_stream=1),
                dict(decode_graph=1, overlap_modules=0, reduce_on_side_stream=1),
                dict(decode_graph=0, overlap_modules=1, reduce_on_side_stream=1),
                dict(decode_graph=1, overlap_modules=1, reduce_on_side_stream=0)):
-        got = harness.run_case(w, kv_preload=100, gpu_only=True, **kw)
+        got = harness.run_case(w, kv_preload=100, gpu_only=True, decode_fused=0, **kw)
         assert len(got.gpu) == len(ref.gpu) == 6
         for x, y in zip(got.gpu, ref.gpu):
             assert np.array_equal(x, y), kw
@@ -147,4 +147,38 @@ def test_graph_decode_after_prefill_matches_oracle(harness):
     """Prefill (eager) then graph-replayed decode steps, crossing an attention-chunk boundary."""
     w = SMALL_BF16.with_(name="small_bf16_graph", prefill=60, decode_steps=8)
     res = harness.run_case(w, decode_graph=1, overlap_modules=1)
+    assert max(res.errs) < TOL_BF16, res.errs
+
+
+# ---- fused decode launches ----------------------------------------------------------------------
+R8_SMALL = inputs.WORKLOADS["70b_r8_decode"].with_(name="r8_small", n_layers=3, hidden=512, inter=448, batch=4,
+                                                   decode_steps=6)
+
+
+@pytest.mark.parametrize("wiring,nstd", [(ladder.LADDER_WIRING_LADDER, 0), (ladder.LADDER_WIRING_STANDARD, 0),
+                                         (ladder.LADDER_WIRING_LADDER, 2)])
+def test_fused_decode_matches_oracle(harness, wiring, nstd):
+    """Fused launches (ladder: paired jobs; standard / hybrid: one job per launch) against the oracle,
+    with synthetic peers, preloaded cache, decode crossing a 32-position chunk boundary (125 -> 131)."""
+    res = harness.run_case(R8_SMALL, kv_preload=125, wiring=wiring, n_standard_layers=nstd, decode_fused=1)
+    assert len(res.errs) == 6 and max(res.errs) < TOL_BF16, res.errs
+
+
+def test_fused_decode_graph_and_eager_bit_identical_and_reproducible(harness):
+    a = harness.run_case(R8_SMALL, kv_preload=125, gpu_only=True, decode_fused=1, decode_graph=0)
+    b = harness.run_case(R8_SMALL, kv_preload=125, gpu_only=True, decode_fused=1, decode_graph=1)
+    c = harness.run_case(R8_SMALL, kv_preload=125, gpu_only=True, decode_fused=1, decode_graph=0)
+    for x, y, z in zip(a.gpu, b.gpu, c.gpu):
+        assert np.array_equal(x, y) and np.array_equal(x, z)
+
+
+def test_fused_decode_other_geometries(harness):
+    """d = 64 with 2 q heads per kv head, batch 2, after a real prefill; and batch 16 with d = 128, 4 per group."""
+    w = SMALL_BF16.with_(name="small_bf16_fused", tp_degree=1, n_real_shards=1, n_q_heads=4, n_kv_heads=2, prefill=40,
+                         decode_steps=4)
+    res = harness.run_case(w, decode_fused=1)
+    assert max(res.errs) < TOL_BF16, res.errs
+    w = inputs.WORKLOADS["70b_r4_prefill"].with_(name="r4_b16", n_layers=2, hidden=512, n_q_heads=8, n_kv_heads=2,
+                                                 inter=512, batch=16, prefill=0, kv_preload=70, decode_steps=3)
+    res = harness.run_case(w, kv_preload=70, decode_fused=1)
     assert max(res.errs) < TOL_BF16, res.errs
