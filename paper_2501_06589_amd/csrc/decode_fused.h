@@ -15,10 +15,12 @@ struct GemvJob {
   const bf16_t* xb;
   int ldx;
   int normed;
+  int xlds;                // 1: x is small enough (M * (K + 8) * 2 bytes <= FUSED_MAX_LDS_BYTES) to be staged in LDS
   float eps;
   const void* wp;
   int M, K, N;
-  int n_groups;            // workgroups: N / 32 (N / 16 for EPI_QKV_ROPE)
+  int group0, n_groups;    // this job's workgroups own the 16-column tiles [group0, group0 + n_groups);
+                           // a projection may be cut over two launches
   int epi;
   // EPI_SWIGLU: act[m][N/2] bf16
   bf16_t* act;
@@ -56,8 +58,11 @@ struct AttnJob {
   const int* pos_dev;      // position of the new token; positions 0..*pos_dev are visible
 };
 
+#define FUSED_MAX_LDS_BYTES (72 * 1024)
+
 struct FusedArgs {
   int n_jobs;              // 1 or 2
+  int lds_bytes;           // dynamic LDS of the launch = the largest need of its jobs
   int kind[2];             // JOB_GEMV | JOB_ATTN (at most one attention job, described by `a`)
   int block_end[2];        // cumulative workgroup counts: job 0 = [0, block_end[0]), job 1 = [block_end[0], block_end[1])
   GemvJob g[2];
@@ -65,5 +70,8 @@ struct FusedArgs {
 };
 
 hipError_t launch_fused_decode(const FusedArgs& fa, int d, int g, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+hipError_t fused_decode_prepare(int d, int g);   // once per context, before the first launch
+size_t fused_attn_lds_bytes(int d, int g);
+size_t fused_gemv_lds_bytes(int M, int K, bool xlds);
 hipError_t launch_embed(const bf16_t* emb, float* x0, bf16_t* xh0, int n, hipStream_t s, hipEvent_t ev0,
                         hipEvent_t ev1);

@@ -36,9 +36,9 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 
 #define FUSED_THREADS 512
 #define FUSED_WAVES 8
-#define FUSED_U 2
-#define FUSED_TN 2
-#define FUSED_LDS_FLOATS 9216
+#define FUSED_U 4    // k tiles per register buffer (two buffers): 8 KiB of weights in flight per wavefront
+#define FUSED_TN 1   // 16-column tiles per workgroup: many small workgroups keep every CU streaming
+#define FUSED_LDS_FLOATS 9216   // attention job: per-wave statistics and outputs
 
 __device__ __forceinline__ float ld_coherent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -58,12 +58,17 @@ __device__ __forceinline__ void unpack8f(const uint4 v, float f[8]) {
 // ------------------------------------------------------------------------------------------------
 // skinny GEMM job: see gemv_mfma_kernel for the streaming scheme (same tiles, same pipeline).
 // A workgroup owns TN adjacent 16-column tiles and the whole K range; U k-tiles per register buffer.
-// (U, TN) = (2, 2) for the wide projections; (8, 1) for the QKV projection, which has few columns
-// and therefore needs more bytes in flight per wavefront to pull its share of the bandwidth.
+// A wavefront's streaming rate is its bytes in flight over the memory latency, so the launch time is
+// set by the workgroup with the most bytes: one tile per workgroup keeps the jobs of a launch even
+// and the number of streaming workgroups high.
 // ------------------------------------------------------------------------------------------------
-template <bool NORMED, int U, int TN>
-__device__ void gemv_job(const GemvJob& j, int grp, float* smem) {
+// XLDS: the x operand (M rows x K, bf16) is staged once per workgroup in LDS instead of travelling
+// through registers next to the weights; the registers it frees hold twice as many weight tiles in
+// flight (memory latency under load was measured at ~5 us, so bandwidth = bytes in flight / 5 us).
+template <bool NORMED, int U, int TN, bool XLDS>
+__device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
   constexpr int WAVES = FUSED_WAVES;
+  const int grp = j.group0 + lb;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int b = lane & 15, q = lane >> 4;
@@ -82,22 +87,27 @@ __device__ void gemv_job(const GemvJob& j, int grp, float* smem) {
   const int rowc = min(b, j.M - 1);
 
   const bf16_t* xbp = j.xb + (size_t)rowc * j.ldx + q * 8;
+  const int xs_stride = j.K + 8;                                   // bf16 elements per LDS row (padded)
+  const bf16_t* xs = reinterpret_cast<const bf16_t*>(smem) + (size_t)rowc * xs_stride + q * 8;
 
-  u32x4_t wa[TN][U], wb[TN][U], xa[U], xb[U];
-  auto load = [&](u32x4_t (&wv)[TN][U], u32x4_t (&xv)[U], int kt) {
+  constexpr int XU = XLDS ? 1 : U;
+  u32x4_t wa[TN][U], wb[TN][U], xa[XU], xb[XU];
+  auto load = [&](u32x4_t (&wv)[TN][U], u32x4_t (&xv)[XU], int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int ktc = min(kt + u, kt1 - 1);
 #pragma unroll
       for (int t = 0; t < TN; ++t) wv[t][u] = __builtin_nontemporal_load(wptr + ((size_t)t * KT + ktc) * 64);
-      xv[u] = *reinterpret_cast<const u32x4_t*>(xbp + (size_t)ktc * 32);
+      if (!XLDS) xv[u] = *reinterpret_cast<const u32x4_t*>(xbp + (size_t)ktc * 32);
     }
   };
-  auto fma = [&](const u32x4_t (&wv)[TN][U], const u32x4_t (&xv)[U], int kt) {
+  auto fma = [&](const u32x4_t (&wv)[TN][U], const u32x4_t (&xv)[XU], int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool ok = rowok && (kt + u < kt1);
-      u32x4_t xz = xv[u];
+      u32x4_t xz;
+      if (XLDS) xz = *reinterpret_cast<const u32x4_t*>(xs + (size_t)min(kt + u, kt1 - 1) * 32);
+      else xz = xv[u];
       if (NORMED) {  // the operand is the bf16 copy of the residual stream: its squares give the row's rms
         float s8 = 0.f;
 #pragma unroll
@@ -115,8 +125,17 @@ __device__ void gemv_job(const GemvJob& j, int grp, float* smem) {
                                                         __builtin_bit_cast(bf16x8_t, xz), acc[t], 0, 0, 0);
     }
   };
+  if (kt0 < kt1) load(wa, xa, kt0);   // the first weight tiles are on their way while x is staged
+  if (XLDS) {
+    bf16_t* xw = reinterpret_cast<bf16_t*>(smem);
+    const int segs = j.K >> 3;         // 16-byte segments per row
+    for (int row = 0; row < j.M; ++row)
+      for (int sg = tid; sg < segs; sg += FUSED_THREADS)
+        *reinterpret_cast<u32x4_t*>(xw + (size_t)row * xs_stride + sg * 8) =
+            *reinterpret_cast<const u32x4_t*>(j.xb + (size_t)row * j.ldx + sg * 8);
+    __syncthreads();
+  }
   if (kt0 < kt1) {
-    load(wa, xa, kt0);
     for (int kt = kt0; kt < kt1; kt += 2 * U) {
       load(wb, xb, kt + U);
       __builtin_amdgcn_sched_barrier(0);
@@ -130,6 +149,7 @@ __device__ void gemv_job(const GemvJob& j, int grp, float* smem) {
   }
 
   // cross-wave sums through LDS: red[wave][tile][col in tile][row], ssq[wave][row]
+  if (XLDS) __syncthreads();                    // every wave is done with the staged x: its space is reused
   float* red = smem;                            // WAVES * TN * 16 * 17 floats
   float* ssq = smem + WAVES * TN * 16 * 17;     // WAVES * 16 floats
 #pragma unroll
@@ -387,7 +407,7 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
 
 template <int D, int G>
 __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(FusedArgs fa) {
-  __shared__ float smem[FUSED_LDS_FLOATS];
+  extern __shared__ float smem[];   // fa.lds_bytes: the largest need of the launch's jobs
   __shared__ unsigned s_flag;
   int lb = blockIdx.x, job = 0;
   if (lb >= fa.block_end[0]) {
@@ -398,9 +418,13 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(FusedArg
     attn_job<D, G>(fa.a, lb, smem, &s_flag);
   } else {
     const GemvJob& j = fa.g[job];
-    if (j.epi == EPI_QKV_ROPE) gemv_job<true, 4, 1>(j, lb, smem);
-    else if (j.normed) gemv_job<true, 2, 2>(j, lb, smem);
-    else gemv_job<false, 2, 2>(j, lb, smem);
+    if (j.xlds) {
+      if (j.normed) gemv_job<true, 2 * FUSED_U, FUSED_TN, true>(j, lb, smem);
+      else gemv_job<false, 2 * FUSED_U, FUSED_TN, true>(j, lb, smem);
+    } else {
+      if (j.normed) gemv_job<true, FUSED_U, FUSED_TN, false>(j, lb, smem);
+      else gemv_job<false, FUSED_U, FUSED_TN, false>(j, lb, smem);
+    }
   }
 }
 
@@ -428,8 +452,10 @@ static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStrea
   // with events: the dispatch itself carries them, so their distance is the kernel's own run time
 #define FUSED_LAUNCH(GQ)                                                                                    \
   do {                                                                                                      \
-    if (ev0 || ev1) hipExtLaunchKernelGGL((fused_decode_kernel<D, GQ>), grid, block, 0, s, ev0, ev1, 0, fa); \
-    else hipLaunchKernelGGL((fused_decode_kernel<D, GQ>), grid, block, 0, s, fa);                           \
+    if (ev0 || ev1)                                                                                          \
+      hipExtLaunchKernelGGL((fused_decode_kernel<D, GQ>), grid, block, fa.lds_bytes, s, ev0, ev1, 0, fa);    \
+    else                                                                                                    \
+      hipLaunchKernelGGL((fused_decode_kernel<D, GQ>), grid, block, fa.lds_bytes, s, fa);                    \
   } while (0)
   switch (g) {
     case 1: FUSED_LAUNCH(1); break;
@@ -442,7 +468,34 @@ static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStrea
   return hipGetLastError();
 }
 
+// LDS a job needs: the attention job's merge area, the GEMV job's cross-wave sums, or the staged x
+size_t fused_attn_lds_bytes(int d, int g) { return (size_t)(2 * FUSED_WAVES * 16 + FUSED_WAVES * g * d + g * 64) * 4; }
+size_t fused_gemv_lds_bytes(int M, int K, bool xlds) {
+  const size_t red = (size_t)(FUSED_WAVES * FUSED_TN * 16 * 17 + FUSED_WAVES * 16) * 4;
+  const size_t xs = xlds ? (size_t)M * (K + 8) * 2 : 0;
+  return red > xs ? red : xs;
+}
+
+// dynamic LDS above 64 KiB has to be allowed per kernel, once (outside any stream capture)
+template <int D>
+static hipError_t prepare_d(int g) {
+  const int bytes = FUSED_MAX_LDS_BYTES;
+  switch (g) {
+    case 1: return hipFuncSetAttribute((const void*)fused_decode_kernel<D, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    case 2: return hipFuncSetAttribute((const void*)fused_decode_kernel<D, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    case 4: return hipFuncSetAttribute((const void*)fused_decode_kernel<D, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    case 8: return hipFuncSetAttribute((const void*)fused_decode_kernel<D, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  }
+  return hipErrorInvalidValue;
+}
+hipError_t fused_decode_prepare(int d, int g) {
+  if (d == 128) return prepare_d<128>(g);
+  if (d == 64) return prepare_d<64>(g);
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_fused_decode(const FusedArgs& fa, int d, int g, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+  if (fa.lds_bytes <= 0 || fa.lds_bytes > FUSED_MAX_LDS_BYTES) return hipErrorInvalidValue;
   const int total = fa.block_end[fa.n_jobs - 1];
   if (total <= 0) return hipErrorInvalidValue;
   if (d == 128) return launch_fused_d<128>(fa, g, dim3(total), s, ev0, ev1);

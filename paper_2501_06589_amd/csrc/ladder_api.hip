@@ -14,6 +14,7 @@
 #include <string.h>
 
 #include <string>
+#include <algorithm>
 #include <vector>
 
 #include "../../include/ladder.h"
@@ -413,9 +414,12 @@ void build_fused_plan(ladder_ctx* c, int B) {
   const ladder_config& g = c->cfg;
   const int H = g.hidden, d = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, I = g.inter, N = g.n_layers;
   const int nqd = nq * d;
-  // attention: one workgroup per (sequence, kv head) up to 2048 cached positions, split beyond that
-  const int split_len = 2048;
-  const int n_splits = (g.max_seq + split_len - 1) / split_len;
+  // attention: about 24 workgroups per launch; a (sequence, kv head) is cut into splits of positions
+  // (multiples of 64) that meet through an arrival ticket when there is more than one
+  int n_splits = (24 + B * nkv - 1) / (B * nkv);
+  n_splits = std::max(1, std::min(n_splits, (g.max_seq + 63) / 64));
+  const int split_len = ((g.max_seq + n_splits - 1) / n_splits + 63) / 64 * 64;
+  n_splits = (g.max_seq + split_len - 1) / split_len;
   auto layer = [&](int l) -> LayerStore& { return c->store[(size_t)(l - 1)]; };  // l = 1..N (one shard)
 
   auto job_qkv = [&](int l, int src) {
@@ -430,7 +434,7 @@ void build_fused_plan(ladder_ctx* c, int B) {
     return j;
   };
   auto residual = [&](GemvJob& j, int m) {
-    j.N = H; j.n_groups = H / 32; j.epi = EPI_RESIDUAL;
+    j.N = H; j.n_groups = H / 16; j.epi = EPI_RESIDUAL;
     j.x_old = c->x_ring[(m - 1) % 3]; j.x_new = c->x_ring[m % 3]; j.xh_new = c->xh_ring[m % 3];
     if (c->peers && c->n_peers > 0) {
       j.peers = (const bf16_t*)c->peers + (size_t)(m % g.peer_pool) * c->n_peers * (size_t)g.peer_rows * H;
@@ -447,7 +451,17 @@ void build_fused_plan(ladder_ctx* c, int B) {
     GemvJob j{};
     j.xb = c->xh_ring[src % 3]; j.ldx = H; j.normed = 1; j.eps = g.rms_eps;
     j.wp = layer(l).pgu; j.M = B; j.K = H; j.N = 2 * I;
-    j.n_groups = 2 * I / 32; j.epi = EPI_SWIGLU; j.act = (bf16_t*)c->act;
+    j.n_groups = 2 * I / 16; j.epi = EPI_SWIGLU; j.act = (bf16_t*)c->act;
+    return j;
+  };
+  // the gate/up projection cut in two column ranges (it is the largest stream and depends on nothing
+  // recent, so a part of it rides along with each of the two launches that would otherwise be short)
+  const int gu_groups = 2 * I / 16;
+  const int gu_first = std::max(1, std::min(gu_groups - 1, (int)(gu_groups * 0.42)));
+  auto job_gu_part = [&](int l, int src, int part) {
+    GemvJob j = job_gu(l, src);
+    if (part == 0) { j.group0 = 0; j.n_groups = gu_first; }
+    else { j.group0 = gu_first; j.n_groups = gu_groups - gu_first; }
     return j;
   };
   auto job_dn = [&](int l, int m) {
@@ -465,22 +479,35 @@ void build_fused_plan(ladder_ctx* c, int B) {
     return a;
   };
   auto blocks_of = [&](const GemvJob& j) { return j.n_groups; };
-  auto one = [&](const GemvJob& j) {
+  auto with_lds = [&](GemvJob j) {   // stage x in LDS when it fits
+    // measured slower than the register path on the 70B-shard shapes (6.2 vs 4.9 ms per step), so off
+    j.xlds = 0;
+    return j;
+  };
+  auto lds_of = [&](const GemvJob& j) { return (int)fused_gemv_lds_bytes(j.M, j.K, j.xlds != 0); };
+  auto one = [&](const GemvJob& j0) {
     FusedArgs f{};
+    const GemvJob j = with_lds(j0);
     f.n_jobs = 1; f.kind[0] = JOB_GEMV; f.g[0] = j; f.block_end[0] = blocks_of(j); f.block_end[1] = f.block_end[0];
+    f.lds_bytes = lds_of(j);
     return f;
   };
-  auto two = [&](const GemvJob& small, const GemvJob& big) {  // the latency-bound job takes the low block indices
+  auto two = [&](const GemvJob& small0, const GemvJob& big0) {  // the latency-bound job takes the low block indices
     FusedArgs f{};
+    const GemvJob small = with_lds(small0), big = with_lds(big0);
     f.n_jobs = 2; f.kind[0] = JOB_GEMV; f.kind[1] = JOB_GEMV; f.g[0] = small; f.g[1] = big;
     f.block_end[0] = blocks_of(small); f.block_end[1] = f.block_end[0] + blocks_of(big);
+    f.lds_bytes = std::max(lds_of(small), lds_of(big));
     return f;
   };
   auto att = [&](int l, const GemvJob* beside) {
     FusedArgs f{};
     f.kind[0] = JOB_ATTN; f.a = job_att(l); f.block_end[0] = n_splits * nkv * B; f.n_jobs = 1; f.block_end[1] = f.block_end[0];
+    f.lds_bytes = (int)fused_attn_lds_bytes(d, nq / nkv);
     if (beside) {
-      f.n_jobs = 2; f.kind[1] = JOB_GEMV; f.g[1] = *beside; f.block_end[1] = f.block_end[0] + blocks_of(*beside);
+      const GemvJob j = with_lds(*beside);
+      f.n_jobs = 2; f.kind[1] = JOB_GEMV; f.g[1] = j; f.block_end[1] = f.block_end[0] + blocks_of(j);
+      f.lds_bytes = std::max(f.lds_bytes, lds_of(j));
     }
     return f;
   };
@@ -490,16 +517,19 @@ void build_fused_plan(ladder_ctx* c, int B) {
   plan.clear();
   const bool all_ladder = g.wiring == LADDER_WIRING_LADDER && g.n_standard_layers == 0;
   if (all_ladder) {
-    // modules 1 and 2 both read x_0; then, layer by layer, the MLP of layer l runs beside the attention of l+1
-    plan.push_back(two(job_qkv(1, 0), job_gu(1, 0)));
+    // modules 1 and 2 both read x_0; then, layer by layer, the MLP of layer l runs beside the attention
+    // side of layer l+1:  { o_l , gate/up_l (first part) }  { qkv_{l+1} , gate/up_l (rest) }
+    //                     { attention_{l+1} , down_l }
+    plan.push_back(one(job_qkv(1, 0)));
     plan.push_back(att(1, nullptr));
-    plan.push_back(one(job_o(1, 1)));
     for (int l = 1; l < N; ++l) {
-      plan.push_back(two(job_qkv(l + 1, 2 * l - 1), job_dn(l, 2 * l)));
-      GemvJob gu = job_gu(l + 1, 2 * l);
-      plan.push_back(att(l + 1, &gu));
-      plan.push_back(one(job_o(l + 1, 2 * l + 1)));
+      plan.push_back(two(job_o(l, 2 * l - 1), job_gu_part(l, 2 * l - 2, 0)));
+      plan.push_back(two(job_qkv(l + 1, 2 * l - 1), job_gu_part(l, 2 * l - 2, 1)));
+      GemvJob dn = job_dn(l, 2 * l);
+      plan.push_back(att(l + 1, &dn));
     }
+    plan.push_back(two(job_o(N, 2 * N - 1), job_gu_part(N, 2 * N - 2, 0)));
+    plan.push_back(one(job_gu_part(N, 2 * N - 2, 1)));
     plan.push_back(one(job_dn(N, 2 * N)));
   } else {
     for (int l = 1; l <= N; ++l) {
@@ -776,6 +806,7 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
     INIT_TRY(dev_alloc(c, (void**)&c->att_ml, (size_t)g.max_batch * nkv * chunks * gq * 2 * 4, false));
     c->fused = fused_usable(c);
     if (c->fused) {
+      INIT_HIP(fused_decode_prepare(d, gq));
       for (int i = 0; i < 3; ++i) {
         INIT_TRY(dev_alloc(c, (void**)&c->x_ring[i], (size_t)16 * H * 4, true));
         INIT_TRY(dev_alloc(c, (void**)&c->xh_ring[i], (size_t)16 * H * 2, true));

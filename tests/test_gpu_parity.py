@@ -160,7 +160,7 @@ R8_SMALL = inputs.WORKLOADS["70b_r8_decode"].with_(name="r8_small", n_layers=3, 
 def test_fused_decode_matches_oracle(harness, wiring, nstd):
     """Fused launches (ladder: paired jobs; standard / hybrid: one job per launch) against the oracle,
     with synthetic peers, preloaded cache, decode crossing a 32-position chunk boundary (125 -> 131)."""
-    res = harness.run_case(R8_SMALL, kv_preload=125, wiring=wiring, n_standard_layers=nstd, decode_fused=1)
+    res = harness.run_case(R8_SMALL, kv_preload=125 if nstd else 700, wiring=wiring, n_standard_layers=nstd, decode_fused=1)
     assert len(res.errs) == 6 and max(res.errs) < TOL_BF16, res.errs
 
 
