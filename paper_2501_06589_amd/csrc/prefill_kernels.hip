@@ -4,6 +4,13 @@
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
+
+// workgroup tile of the large-M GEMM: 16 row tiles (256 x 256) at one wave per SIMD, or 8 (128 x 256) at two
+#ifndef GEMM_WM_LARGE
+#define GEMM_WM_LARGE 8
+#define GEMM_WAVES_LARGE 2
+#endif
 
 __device__ __forceinline__ f32x4_t mfma16(const uint4 a, const uint4 b, const f32x4_t c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
@@ -15,18 +22,26 @@ __device__ __forceinline__ f32x4_t mfma16(const uint4 a, const uint4 b, const f3
 // side along N (64 columns = 4 weight tiles each).  The weights are the MFMA A operand and come
 // straight from global memory in their packed tile order (1 KiB coalesced per wave load, each tile
 // read by exactly one wave of the workgroup); the activations are the B operand, staged once per
-// workgroup through double-buffered LDS and shared by the 4 waves.  Output element (m, n) sits in
-// lane (n%16)/4*16 + m%16, register n%4, so a lane stores 4 consecutive columns.
+// workgroup through double-buffered LDS and shared by the 4 waves.  One k tile (32) per stage: the
+// next stage's weights and activations are requested before the MFMAs of the current one.
+// Output element (m, n) sits in lane (n%16)/4*16 + m%16, register n%4: a lane stores 4 consecutive
+// columns.
+// All global loads are unconditional (row / tile / k indices clamped into range): a guarded load makes
+// the compiler drain every outstanding load before the MFMAs.  What a clamped load brings in is
+// neutralised later: rows >= M become zeros when the X tile is written to LDS, columns >= N are never
+// stored, and the stage past the end is never multiplied.
 // ------------------------------------------------------------------------------------------------
-#define GEMM_BK 64
-#define GEMM_LDS_STRIDE (GEMM_BK + 8)  // bf16 elements per LDS row (pad against bank conflicts)
+#define GEMM_BK 32
+#define GEMM_LDS_STRIDE (GEMM_BK + 8)  // bf16 elements per LDS row: 80 bytes, conflict-free 16-byte reads
 #define GEMM_GROUP_M 16
 
-template <int WM>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
+template <int WM, int MIN_WAVES>
+__global__ __launch_bounds__(256, MIN_WAVES) void gemm_mfma_kernel(GemmArgs a) {
   constexpr int BM = 16 * WM;
-  constexpr int XV = BM * 8 / 256;  // uint4 per thread per K step of the X tile
-  __shared__ __attribute__((aligned(16))) bf16_t xs[2][BM][GEMM_LDS_STRIDE];
+  constexpr int XV = BM * 4 / 256;  // 16-byte segments per thread per stage of the X tile (BM rows x 64 bytes)
+  static_assert(XV >= 1, "tile too small");
+  extern __shared__ __attribute__((aligned(16))) bf16_t xs_raw[];   // [2][BM][GEMM_LDS_STRIDE]
+  bf16_t (*xs)[BM][GEMM_LDS_STRIDE] = reinterpret_cast<bf16_t (*)[BM][GEMM_LDS_STRIDE]>(xs_raw);
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int b = lane & 15, q = lane >> 4;
@@ -47,61 +62,69 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
 #pragma unroll
     for (int mt = 0; mt < WM; ++mt) acc[j][mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
-  const uint4* wp = reinterpret_cast<const uint4*>(a.wp);
-  uint4 xg[XV];
-  uint4 w0[4][2], w1[4][2];
-
-  auto load_x = [&](int k0) {
+  // per-thread source addresses of the X tile (row clamped) and of the 4 weight tiles (tile clamped)
+  const bf16_t* xsrc[XV];
+  bool xok[XV];
 #pragma unroll
-    for (int i = 0; i < XV; ++i) {
-      const int idx = tid + i * 256, row = idx >> 3, seg = idx & 7;
-      const int m = m0 + row, k = k0 + seg * 8;
-      xg[i] = (m < a.M && k < a.K) ? *reinterpret_cast<const uint4*>(a.x + (size_t)m * a.ldx + k) : zero4;
-    }
+  for (int i = 0; i < XV; ++i) {
+    const int idx = tid + i * 256, row = idx >> 2, seg = idx & 3;
+    xok[i] = m0 + row < a.M;
+    xsrc[i] = a.x + (size_t)min(m0 + row, a.M - 1) * a.ldx + seg * 8;
+  }
+  const u32x4_t* wsrc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    wsrc[j] = reinterpret_cast<const u32x4_t*>(a.wp) + (size_t)min(nt0 + j, NT - 1) * KT * 64 + lane;
+
+  u32x4_t xg[XV], w0[4], w1[4];
+  auto load_stage = [&](u32x4_t (&w)[4], int kt) {
+    const int ktc = min(kt, KT - 1);
+#pragma unroll
+    for (int i = 0; i < XV; ++i) xg[i] = *reinterpret_cast<const u32x4_t*>(xsrc[i] + (size_t)ktc * 32);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w[j] = wsrc[j][(size_t)ktc * 64];
   };
   auto store_x = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < XV; ++i) {
-      const int idx = tid + i * 256, row = idx >> 3, seg = idx & 7;
-      *reinterpret_cast<uint4*>(&xs[buf][row][seg * 8]) = xg[i];
+      const int idx = tid + i * 256, row = idx >> 2, seg = idx & 3;
+      *reinterpret_cast<u32x4_t*>(&xs[buf][row][seg * 8]) = xok[i] ? xg[i] : (u32x4_t){0u, 0u, 0u, 0u};
     }
   };
-  auto load_w = [&](uint4 (&w)[4][2], int kt) {
+  // LDS fragments are read two row tiles ahead of the MFMAs that consume them; the scheduling barriers
+  // keep that distance (left alone, the compiler hoists every read to the top and runs out of registers)
+  auto compute = [&](const u32x4_t (&w)[4], int buf) {
+    auto frag = [&](int mt) { return *reinterpret_cast<const u32x4_t*>(&xs[buf][mt * 16 + b][q * 8]); };
+    u32x4_t f0 = frag(0), f1 = frag(1), f2;
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int mt = 0; mt < WM; ++mt) {
+      f2 = frag(mt + 2 < WM ? mt + 2 : WM - 1);
 #pragma unroll
-      for (int s = 0; s < 2; ++s)
-        w[j][s] = (nt0 + j < NT && kt + s < KT) ? wp[((size_t)(nt0 + j) * KT + kt + s) * 64 + lane] : zero4;
-  };
-  auto compute = [&](const uint4 (&w)[4][2], int buf) {
-#pragma unroll
-    for (int s = 0; s < 2; ++s)
-#pragma unroll
-      for (int mt = 0; mt < WM; ++mt) {
-        const uint4 xb = *reinterpret_cast<const uint4*>(&xs[buf][mt * 16 + b][s * 32 + q * 8]);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[j][mt] = mfma16(w[j][s], xb, acc[j][mt]);
-      }
+      for (int j = 0; j < 4; ++j)
+        acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w[j]),
+                                                            __builtin_bit_cast(bf16x8_t, f0), acc[j][mt], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      f0 = f1;
+      f1 = f2;
+    }
   };
 
-  const int nsteps = (a.K + GEMM_BK - 1) / GEMM_BK;
-  load_x(0);
-  load_w(w0, 0);
+  load_stage(w0, 0);
   store_x(0);
   __syncthreads();
-  for (int it = 0; it < nsteps; it += 2) {
-    // even step: operands in w0 / buffer 0, prefetch into w1 / buffer 1
-    const bool more1 = it + 1 < nsteps;
-    if (more1) { load_x((it + 1) * GEMM_BK); load_w(w1, (it + 1) * 2); }
+  for (int kt = 0; kt < KT; kt += 2) {
+    load_stage(w1, kt + 1);
+    __builtin_amdgcn_sched_barrier(0);
     compute(w0, 0);
-    if (more1) store_x(1);
+    __builtin_amdgcn_sched_barrier(0);
+    store_x(1);
     __syncthreads();
-    if (!more1) break;
-    const bool more2 = it + 2 < nsteps;
-    if (more2) { load_x((it + 2) * GEMM_BK); load_w(w0, (it + 2) * 2); }
+    if (kt + 1 >= KT) break;
+    load_stage(w0, kt + 2);
+    __builtin_amdgcn_sched_barrier(0);
     compute(w1, 1);
-    if (more2) store_x(0);
+    __builtin_amdgcn_sched_barrier(0);
+    store_x(0);
     __syncthreads();
   }
 
@@ -145,17 +168,20 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
   }
 }
 
-hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
-  if (a.M <= 0 || (a.K & 31) || (a.N & 15)) return hipErrorInvalidValue;
-  const int tiles_n = (a.N + 255) / 256;
-  if (a.M > 64) {
-    const int tiles_m = (a.M + 127) / 128;
-    hipLaunchKernelGGL(gemm_mfma_kernel<8>, dim3(tiles_m * tiles_n), dim3(256), 0, s, a);
-  } else {
-    const int tiles_m = (a.M + 63) / 64;
-    hipLaunchKernelGGL(gemm_mfma_kernel<4>, dim3(tiles_m * tiles_n), dim3(256), 0, s, a);
-  }
+template <int WM, int MIN_WAVES>
+static hipError_t launch_gemm_wm(const GemmArgs& a, hipStream_t s) {
+  constexpr int BM = 16 * WM;
+  const size_t lds = (size_t)2 * BM * GEMM_LDS_STRIDE * sizeof(bf16_t);
+  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + 255) / 256;
+  hipLaunchKernelGGL((gemm_mfma_kernel<WM, MIN_WAVES>), dim3(tiles_m * tiles_n), dim3(256), lds, s, a);
   return hipGetLastError();
+}
+
+hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
+  if (a.M <= 0 || (a.K & 31) || (a.N & 15) || a.K < 32) return hipErrorInvalidValue;
+  if (a.M >= 1024) return launch_gemm_wm<GEMM_WM_LARGE, GEMM_WAVES_LARGE>(a, s);
+  if (a.M > 64) return launch_gemm_wm<8, 2>(a, s);   // 128 x 256
+  return launch_gemm_wm<4, 2>(a, s);                 //  64 x 256
 }
 
 // ------------------------------------------------------------------------------------------------
