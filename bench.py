@@ -104,7 +104,8 @@ def run_decode(args):
     total_steps = args.warmup + args.steps + prof_steps
     ctx = build_context(w, dev, total_steps, w.batch, max_tokens=max(w.prefill, 1),
                         decode_graph=1 if args.graph else 0, overlap_modules=0 if args.no_overlap else 1,
-                        decode_fused=0 if args.no_fused else 1)
+                        decode_fused=0 if args.no_fused else 1,
+                        wiring=ladder.LADDER_WIRING_STANDARD if args.wiring == "standard" else ladder.LADDER_WIRING_LADDER)
     if w.kv_preload:
         for i in range(w.n_layers):
             for r in range(w.n_real_shards):
@@ -247,6 +248,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--graph", action="store_true", help="replay decode steps from a captured HIP graph instead of eager launches")
     ap.add_argument("--no-overlap", action="store_true", help="one compute stream instead of attention / MLP streams")
+    ap.add_argument("--wiring", choices=["ladder", "standard"], default="ladder",
+                    help="residual wiring of the stack (the metric is quoted on ladder; standard is the paper's Eq. 1 baseline)")
     ap.add_argument("--no-fused", action="store_true", help="one kernel per operation instead of the fused decode launches")
     args = ap.parse_args()
     if args.gpus != 1:

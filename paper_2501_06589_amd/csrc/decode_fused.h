@@ -15,12 +15,12 @@ struct GemvJob {
   const bf16_t* xb;
   int ldx;
   int normed;
-  int xlds;                // 1: x is small enough (M * (K + 8) * 2 bytes <= FUSED_MAX_LDS_BYTES) to be staged in LDS
   float eps;
   const void* wp;
   int M, K, N;
-  int group0, n_groups;    // this job's workgroups own the 16-column tiles [group0, group0 + n_groups);
-                           // a projection may be cut over two launches
+  int tn;                  // 16-column tiles per workgroup: 1 (0 means 1) or 2
+  int group0, n_groups;    // this job's workgroups own the tile groups [group0, group0 + n_groups), tn tiles
+                           // each; a projection may be cut over two launches
   int epi;
   // EPI_SWIGLU: act[m][N/2] bf16
   bf16_t* act;
@@ -72,6 +72,6 @@ struct FusedArgs {
 hipError_t launch_fused_decode(const FusedArgs& fa, int d, int g, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t fused_decode_prepare(int d, int g);   // once per context, before the first launch
 size_t fused_attn_lds_bytes(int d, int g);
-size_t fused_gemv_lds_bytes(int M, int K, bool xlds);
+size_t fused_gemv_lds_bytes();
 hipError_t launch_embed(const bf16_t* emb, float* x0, bf16_t* xh0, int n, hipStream_t s, hipEvent_t ev0,
                         hipEvent_t ev1);

@@ -37,12 +37,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 #define FUSED_THREADS 512
 #define FUSED_WAVES 8
 #define FUSED_U 4    // k tiles per register buffer (two buffers): 8 KiB of weights in flight per wavefront
-#define FUSED_TN 1   // 16-column tiles per workgroup: many small workgroups keep every CU streaming
 #define FUSED_LDS_FLOATS 9216   // attention job: per-wave statistics and outputs
-
-__device__ __forceinline__ float ld_coherent(const float* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
@@ -62,10 +57,7 @@ __device__ __forceinline__ void unpack8f(const uint4 v, float f[8]) {
 // set by the workgroup with the most bytes: one tile per workgroup keeps the jobs of a launch even
 // and the number of streaming workgroups high.
 // ------------------------------------------------------------------------------------------------
-// XLDS: the x operand (M rows x K, bf16) is staged once per workgroup in LDS instead of travelling
-// through registers next to the weights; the registers it frees hold twice as many weight tiles in
-// flight (memory latency under load was measured at ~5 us, so bandwidth = bytes in flight / 5 us).
-template <bool NORMED, int U, int TN, bool XLDS>
+template <bool NORMED, int U, int TN>
 __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
   constexpr int WAVES = FUSED_WAVES;
   const int grp = j.group0 + lb;
@@ -87,27 +79,22 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
   const int rowc = min(b, j.M - 1);
 
   const bf16_t* xbp = j.xb + (size_t)rowc * j.ldx + q * 8;
-  const int xs_stride = j.K + 8;                                   // bf16 elements per LDS row (padded)
-  const bf16_t* xs = reinterpret_cast<const bf16_t*>(smem) + (size_t)rowc * xs_stride + q * 8;
 
-  constexpr int XU = XLDS ? 1 : U;
-  u32x4_t wa[TN][U], wb[TN][U], xa[XU], xb[XU];
-  auto load = [&](u32x4_t (&wv)[TN][U], u32x4_t (&xv)[XU], int kt) {
+  u32x4_t wa[TN][U], wb[TN][U], xa[U], xb[U];
+  auto load = [&](u32x4_t (&wv)[TN][U], u32x4_t (&xv)[U], int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int ktc = min(kt + u, kt1 - 1);
 #pragma unroll
       for (int t = 0; t < TN; ++t) wv[t][u] = __builtin_nontemporal_load(wptr + ((size_t)t * KT + ktc) * 64);
-      if (!XLDS) xv[u] = *reinterpret_cast<const u32x4_t*>(xbp + (size_t)ktc * 32);
+      xv[u] = *reinterpret_cast<const u32x4_t*>(xbp + (size_t)ktc * 32);
     }
   };
-  auto fma = [&](const u32x4_t (&wv)[TN][U], const u32x4_t (&xv)[XU], int kt) {
+  auto fma = [&](const u32x4_t (&wv)[TN][U], const u32x4_t (&xv)[U], int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool ok = rowok && (kt + u < kt1);
-      u32x4_t xz;
-      if (XLDS) xz = *reinterpret_cast<const u32x4_t*>(xs + (size_t)min(kt + u, kt1 - 1) * 32);
-      else xz = xv[u];
+      u32x4_t xz = xv[u];
       if (NORMED) {  // the operand is the bf16 copy of the residual stream: its squares give the row's rms
         float s8 = 0.f;
 #pragma unroll
@@ -125,16 +112,33 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
                                                         __builtin_bit_cast(bf16x8_t, xz), acc[t], 0, 0, 0);
     }
   };
-  if (kt0 < kt1) load(wa, xa, kt0);   // the first weight tiles are on their way while x is staged
-  if (XLDS) {
-    bf16_t* xw = reinterpret_cast<bf16_t*>(smem);
-    const int segs = j.K >> 3;         // 16-byte segments per row
-    for (int row = 0; row < j.M; ++row)
-      for (int sg = tid; sg < segs; sg += FUSED_THREADS)
-        *reinterpret_cast<u32x4_t*>(xw + (size_t)row * xs_stride + sg * 8) =
-            *reinterpret_cast<const u32x4_t*>(j.xb + (size_t)row * j.ldx + sg * 8);
-    __syncthreads();
+  // The epilogue's own operands do not depend on the product: they are requested now, before the
+  // weight stream, so their memory latency is hidden behind it instead of trailing the last tile.
+  constexpr int PRE_PEERS = 8;
+  float pre_old = 0.f, pre_cos = 0.f, pre_sin = 0.f;
+  uint16_t pre_peer[PRE_PEERS];
+  int pre_pos = 0;
+  if (j.epi == EPI_RESIDUAL) {
+    if (tid < TN * 256) {
+      const int t = tid >> 8, row = min((tid >> 4) & 15, j.M - 1), col = (nt0 + t) * 16 + (tid & 15);
+      pre_old = j.x_old[(size_t)row * j.N + col];
+      if (j.n_peers > 0) {
+#pragma unroll
+        for (int p = 0; p < PRE_PEERS; ++p)
+          pre_peer[p] = j.peers[min(p, j.n_peers - 1) * j.peer_stride + (size_t)row * j.N + col];
+      }
+    }
+  } else if (j.epi == EPI_QKV_ROPE) {
+    pre_pos = *j.pos_dev;
+    if (tid < 16 * TN * 8) {
+      const int pr = tid % (TN * 8);
+      const int jj = ((grp * (TN * 16) + 2 * pr) % j.d) >> 1;
+      pre_cos = j.cos_tab[(size_t)pre_pos * (j.d >> 1) + jj];
+      pre_sin = j.sin_tab[(size_t)pre_pos * (j.d >> 1) + jj];
+    }
   }
+
+  if (kt0 < kt1) load(wa, xa, kt0);
   if (kt0 < kt1) {
     for (int kt = kt0; kt < kt1; kt += 2 * U) {
       load(wb, xb, kt + U);
@@ -149,7 +153,6 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
   }
 
   // cross-wave sums through LDS: red[wave][tile][col in tile][row], ssq[wave][row]
-  if (XLDS) __syncthreads();                    // every wave is done with the staged x: its space is reused
   float* red = smem;                            // WAVES * TN * 16 * 17 floats
   float* ssq = smem + WAVES * TN * 16 * 17;     // WAVES * 16 floats
 #pragma unroll
@@ -194,8 +197,11 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
       const int t = tid >> 8, row = (tid >> 4) & 15, col16 = tid & 15;
       const int col = (nt0 + t) * 16 + col16;
       if (row < j.M) {
-        float v = j.x_old[(size_t)row * j.N + col] + out_of(t, col16, row);
-        for (int p = 0; p < j.n_peers; ++p) v += bf16_to_f32(j.peers[p * j.peer_stride + (size_t)row * j.N + col]);
+        float v = pre_old + out_of(t, col16, row);
+#pragma unroll
+        for (int p = 0; p < PRE_PEERS; ++p)
+          if (p < j.n_peers) v += bf16_to_f32(pre_peer[p]);
+        for (int p = PRE_PEERS; p < j.n_peers; ++p) v += bf16_to_f32(j.peers[p * j.peer_stride + (size_t)row * j.N + col]);
         j.x_new[(size_t)row * j.N + col] = v;
         j.xh_new[(size_t)row * j.N + col] = f32_to_bf16(v);   // what the projections that read x_m multiply
       }
@@ -210,10 +216,10 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
       const int col = grp * (TN * 16) + 2 * pr;
       const int c16 = (2 * pr) & 15, t = (2 * pr) >> 4;
       float e = out_of(t, c16, row), o = out_of(t, c16 + 1, row);
-      const int pos = *j.pos_dev;
+      const int pos = pre_pos;
       const int head = col / j.d, jj = (col % j.d) >> 1;
       if (head < j.nq + j.nkv) {
-        const float c = j.cos_tab[(size_t)pos * (j.d >> 1) + jj], sn = j.sin_tab[(size_t)pos * (j.d >> 1) + jj];
+        const float c = pre_cos, sn = pre_sin;
         const float re = e * c - o * sn, ro = e * sn + o * c;
         e = re;
         o = ro;
@@ -336,7 +342,6 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
   float* wm = smem;                          // [WAVES][16]
   float* wl = wm + FUSED_WAVES * 16;         // [WAVES][16]
   float* wo = wl + FUSED_WAVES * 16;         // [WAVES][G][D]
-  float* wgt = wo + FUSED_WAVES * G * D;     // [G][n_splits] (merge of splits only); overlaps nothing above
   if (q == 0) { wm[wave * 16 + b] = mrun; wl[wave * 16 + b] = lrun; }
   if (b < G) {
 #pragma unroll
@@ -382,33 +387,66 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
   __syncthreads();
   if (*s_flag != (unsigned)n_active - 1) return;
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-  float* hl = wl;  // reuse
-  for (int h = wave; h < G; h += FUSED_WAVES) {
-    float m = -INFINITY;
-    for (int s = lane; s < n_active; s += 64) m = fmaxf(m, ld_coherent(a.part_ml + ((pbase + s) * G + h) * 2));
-    m = wave_max(m);
-    float l = 0.f;
-    for (int s = lane; s < n_active; s += 64) {
-      const float w = __expf(ld_coherent(a.part_ml + ((pbase + s) * G + h) * 2) - m);
-      wgt[h * a.n_splits + s] = w;
-      l += ld_coherent(a.part_ml + ((pbase + s) * G + h) * 2 + 1) * w;
-    }
-    l = wave_sum(l);
-    if (lane == 0) hl[h] = l;
-  }
-  __syncthreads();
+  // After the acquire the other splits' partial results are ordinary memory.  Every thread merges its
+  // own output elements from all splits, eight splits per pass with all of the pass's loads issued
+  // together (one memory round trip per pass), in split order.
+  constexpr int SP = 8;
   for (int i = tid; i < G * D; i += FUSED_THREADS) {
     const int h = i / D;
-    float o = 0.f;
-    for (int s = 0; s < n_active; ++s) o += ld_coherent(a.part_o + (pbase + s) * G * D + i) * wgt[h * a.n_splits + s];
-    a.o[(size_t)bi * a.nq * D + (size_t)kvh * G * D + i] = f32_to_bf16(o / hl[h]);
+    float m = -INFINITY, l = 0.f, o = 0.f;
+    for (int s0 = 0; s0 < n_active; s0 += SP) {
+      float ms[SP], ls[SP], os[SP];
+#pragma unroll
+      for (int k = 0; k < SP; ++k) {
+        const int s = min(s0 + k, n_active - 1);
+        ms[k] = a.part_ml[((pbase + s) * G + h) * 2 + 0];
+        ls[k] = a.part_ml[((pbase + s) * G + h) * 2 + 1];
+        os[k] = a.part_o[(pbase + s) * G * D + i];
+      }
+      float mnew = m;
+#pragma unroll
+      for (int k = 0; k < SP; ++k) mnew = fmaxf(mnew, s0 + k < n_active ? ms[k] : -INFINITY);
+      const float f0 = __expf(m - mnew);   // 0 on the first pass (m = -inf, mnew finite: split 0 saw a key)
+      l *= f0;
+      o *= f0;
+#pragma unroll
+      for (int k = 0; k < SP; ++k) {
+        const float f = s0 + k < n_active ? __expf(ms[k] - mnew) : 0.f;
+        l += ls[k] * f;
+        o += os[k] * f;
+      }
+      m = mnew;
+    }
+    a.o[(size_t)bi * a.nq * D + (size_t)kvh * G * D + i] = f32_to_bf16(o / l);
   }
 }
+
+#ifdef FUSED_TRACE
+// development builds only: per-workgroup start / end time (100 MHz counter) and hardware placement
+__device__ unsigned long long* g_fused_trace;
+struct FusedTraceScope {
+  unsigned long long t0;
+  __device__ FusedTraceScope() : t0(wall_clock64()) {}
+  __device__ ~FusedTraceScope() {
+    if (threadIdx.x == 0 && g_fused_trace) {
+      unsigned hw, xcc;
+      asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+      asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+      g_fused_trace[blockIdx.x * 4 + 0] = t0;
+      g_fused_trace[blockIdx.x * 4 + 1] = wall_clock64();
+      g_fused_trace[blockIdx.x * 4 + 2] = ((unsigned long long)xcc << 32) | hw;
+    }
+  }
+};
+#endif
 
 template <int D, int G>
 __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(FusedArgs fa) {
   extern __shared__ float smem[];   // fa.lds_bytes: the largest need of the launch's jobs
   __shared__ unsigned s_flag;
+#ifdef FUSED_TRACE
+  FusedTraceScope trace_scope;
+#endif
   int lb = blockIdx.x, job = 0;
   if (lb >= fa.block_end[0]) {
     lb -= fa.block_end[0];
@@ -418,12 +456,12 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(FusedArg
     attn_job<D, G>(fa.a, lb, smem, &s_flag);
   } else {
     const GemvJob& j = fa.g[job];
-    if (j.xlds) {
-      if (j.normed) gemv_job<true, 2 * FUSED_U, FUSED_TN, true>(j, lb, smem);
-      else gemv_job<false, 2 * FUSED_U, FUSED_TN, true>(j, lb, smem);
+    if (j.tn == 2) {
+      if (j.normed) gemv_job<true, FUSED_U / 2, 2>(j, lb, smem);
+      else gemv_job<false, FUSED_U / 2, 2>(j, lb, smem);
     } else {
-      if (j.normed) gemv_job<true, FUSED_U, FUSED_TN, false>(j, lb, smem);
-      else gemv_job<false, FUSED_U, FUSED_TN, false>(j, lb, smem);
+      if (j.normed) gemv_job<true, FUSED_U, 1>(j, lb, smem);
+      else gemv_job<false, FUSED_U, 1>(j, lb, smem);
     }
   }
 }
@@ -468,12 +506,10 @@ static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStrea
   return hipGetLastError();
 }
 
-// LDS a job needs: the attention job's merge area, the GEMV job's cross-wave sums, or the staged x
+// LDS a job needs: the attention job's merge area or the GEMV job's cross-wave sums
 size_t fused_attn_lds_bytes(int d, int g) { return (size_t)(2 * FUSED_WAVES * 16 + FUSED_WAVES * g * d + g * 64) * 4; }
-size_t fused_gemv_lds_bytes(int M, int K, bool xlds) {
-  const size_t red = (size_t)(FUSED_WAVES * FUSED_TN * 16 * 17 + FUSED_WAVES * 16) * 4;
-  const size_t xs = xlds ? (size_t)M * (K + 8) * 2 : 0;
-  return red > xs ? red : xs;
+size_t fused_gemv_lds_bytes() {
+  return (size_t)(FUSED_WAVES * 2 * 16 * 17 + FUSED_WAVES * 16) * 4;   // sized for two-tile workgroups
 }
 
 // dynamic LDS above 64 KiB has to be allowed per kernel, once (outside any stream capture)

@@ -445,6 +445,8 @@ void build_fused_plan(ladder_ctx* c, int B) {
     GemvJob j{};
     j.xb = (const bf16_t*)c->obuf; j.ldx = nqd; j.wp = layer(l).po; j.M = B; j.K = nqd;
     residual(j, m);
+    // its K range is short: two tiles per workgroup halve the number of (latency-bound) workgroups
+    if (j.n_groups % 2 == 0) { j.tn = 2; j.n_groups /= 2; }
     return j;
   };
   auto job_gu = [&](int l, int src) {
@@ -457,7 +459,7 @@ void build_fused_plan(ladder_ctx* c, int B) {
   // the gate/up projection cut in two column ranges (it is the largest stream and depends on nothing
   // recent, so a part of it rides along with each of the two launches that would otherwise be short)
   const int gu_groups = 2 * I / 16;
-  const int gu_first = std::max(1, std::min(gu_groups - 1, (int)(gu_groups * 0.42)));
+  const int gu_first = std::max(1, std::min(gu_groups - 1, gu_groups / 4));
   auto job_gu_part = [&](int l, int src, int part) {
     GemvJob j = job_gu(l, src);
     if (part == 0) { j.group0 = 0; j.n_groups = gu_first; }
@@ -479,25 +481,22 @@ void build_fused_plan(ladder_ctx* c, int B) {
     return a;
   };
   auto blocks_of = [&](const GemvJob& j) { return j.n_groups; };
-  auto with_lds = [&](GemvJob j) {   // stage x in LDS when it fits
-    // measured slower than the register path on the 70B-shard shapes (6.2 vs 4.9 ms per step), so off
-    j.xlds = 0;
-    return j;
-  };
-  auto lds_of = [&](const GemvJob& j) { return (int)fused_gemv_lds_bytes(j.M, j.K, j.xlds != 0); };
+  auto lds_of = [&](const GemvJob&) { return (int)fused_gemv_lds_bytes(); };
   auto one = [&](const GemvJob& j0) {
     FusedArgs f{};
-    const GemvJob j = with_lds(j0);
+    const GemvJob j = j0;
     f.n_jobs = 1; f.kind[0] = JOB_GEMV; f.g[0] = j; f.block_end[0] = blocks_of(j); f.block_end[1] = f.block_end[0];
     f.lds_bytes = lds_of(j);
     return f;
   };
-  auto two = [&](const GemvJob& small0, const GemvJob& big0) {  // the latency-bound job takes the low block indices
+  // Workgroups are dispatched in block order and a CU holds two of them: the job whose workgroups run
+  // longest (whole-K streams over hidden) goes first so that each lands on a CU of its own, and the
+  // short ones fill the second slots.
+  auto two = [&](const GemvJob& first, const GemvJob& second) {
     FusedArgs f{};
-    const GemvJob small = with_lds(small0), big = with_lds(big0);
-    f.n_jobs = 2; f.kind[0] = JOB_GEMV; f.kind[1] = JOB_GEMV; f.g[0] = small; f.g[1] = big;
-    f.block_end[0] = blocks_of(small); f.block_end[1] = f.block_end[0] + blocks_of(big);
-    f.lds_bytes = std::max(lds_of(small), lds_of(big));
+    f.n_jobs = 2; f.kind[0] = JOB_GEMV; f.kind[1] = JOB_GEMV; f.g[0] = first; f.g[1] = second;
+    f.block_end[0] = blocks_of(first); f.block_end[1] = f.block_end[0] + blocks_of(second);
+    f.lds_bytes = std::max(lds_of(first), lds_of(second));
     return f;
   };
   auto att = [&](int l, const GemvJob* beside) {
@@ -505,7 +504,7 @@ void build_fused_plan(ladder_ctx* c, int B) {
     f.kind[0] = JOB_ATTN; f.a = job_att(l); f.block_end[0] = n_splits * nkv * B; f.n_jobs = 1; f.block_end[1] = f.block_end[0];
     f.lds_bytes = (int)fused_attn_lds_bytes(d, nq / nkv);
     if (beside) {
-      const GemvJob j = with_lds(*beside);
+      const GemvJob j = *beside;
       f.n_jobs = 2; f.kind[1] = JOB_GEMV; f.g[1] = j; f.block_end[1] = f.block_end[0] + blocks_of(j);
       f.lds_bytes = std::max(f.lds_bytes, lds_of(j));
     }
@@ -523,12 +522,12 @@ void build_fused_plan(ladder_ctx* c, int B) {
     plan.push_back(one(job_qkv(1, 0)));
     plan.push_back(att(1, nullptr));
     for (int l = 1; l < N; ++l) {
-      plan.push_back(two(job_o(l, 2 * l - 1), job_gu_part(l, 2 * l - 2, 0)));
+      plan.push_back(two(job_gu_part(l, 2 * l - 2, 0), job_o(l, 2 * l - 1)));
       plan.push_back(two(job_qkv(l + 1, 2 * l - 1), job_gu_part(l, 2 * l - 2, 1)));
       GemvJob dn = job_dn(l, 2 * l);
       plan.push_back(att(l + 1, &dn));
     }
-    plan.push_back(two(job_o(N, 2 * N - 1), job_gu_part(N, 2 * N - 2, 0)));
+    plan.push_back(two(job_gu_part(N, 2 * N - 2, 0), job_o(N, 2 * N - 1)));
     plan.push_back(one(job_gu_part(N, 2 * N - 2, 1)));
     plan.push_back(one(job_dn(N, 2 * N)));
   } else {
