@@ -317,7 +317,200 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// The same computation with the K / V^T tiles of a 32-key block staged once per workgroup in LDS
+// (double buffered) and shared by its 4 wavefronts, each of which owns QT tiles of 16 queries of
+// one q head.  With grouped-query attention the wavefronts of a workgroup are HW = min(G, 4) q heads
+// of ONE kv head over the same query block, so they walk exactly the same keys.  Per block a
+// wavefront issues 64 matrix instructions against 16 KiB of LDS reads; the running-max rescale of the
+// output accumulators (the largest vector cost) is skipped for a tile whenever no lane's maximum moved.
+// ------------------------------------------------------------------------------------------------
+template <int D, int HW, int QT>
+__global__ __launch_bounds__(256, QT <= 3 ? 2 : 1) void attn_prefill_lds_kernel(AttnPrefillArgs a) {
+  constexpr int DS = D / 32, DT = D / 16;
+  constexpr int QW = 4 / HW;                 // query sub-blocks (of QT * 16) per workgroup
+  constexpr int KROW = D * 2 + 16;           // bytes per staged K row (key): 16-byte pad, conflict-free b128 reads
+  constexpr int VROW = 64 + 16;              // bytes per staged V^T row (dim): 32 keys + pad
+  constexpr int KBYTES = 32 * KROW, VBYTES = D * VROW;
+  constexpr int SEGS = D / 64;               // 16-byte segments per thread and tile
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2][KBYTES + VBYTES];
+
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int b = lane & 15, q = lane >> 4;
+  const int qblk = (int)gridDim.x - 1 - (int)blockIdx.x;   // longest rows first
+  const int h = blockIdx.y * HW + wave % HW, bi = blockIdx.z;
+  const int kvh = h / (a.nq / a.nkv);
+  const int t0 = (qblk * QW + wave / HW) * (QT * 16);       // this wavefront's first query
+  const float scale = 1.0f / sqrtf((float)D);
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
+  uint4 qreg[QT][DS];
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    const int t = min(t0 + qt * 16 + b, a.T - 1);           // rows past T: a valid address, never stored
+#pragma unroll
+    for (int s = 0; s < DS; ++s)
+      qreg[qt][s] = *reinterpret_cast<const uint4*>(a.q + ((size_t)bi * a.T + t) * a.nq * D + h * D + s * 32 + q * 8);
+  }
+  f32x4_t oacc[QT][DT];
+  float mrun[QT], lrun[QT];
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    mrun[qt] = -INFINITY;
+    lrun[qt] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) oacc[qt][dt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+  }
+  const bf16_t* kc = a.cache_k + ((size_t)bi * a.nkv + kvh) * a.max_seq * D;
+  const bf16_t* vc = a.cache_v + ((size_t)bi * a.nkv + kvh) * D * a.max_seq;
+  const int wg_last_t = min(a.T, (qblk + 1) * QW * QT * 16) - 1;
+  const int n_keys = a.pos0 + wg_last_t + 1;                 // keys the workgroup walks (same for all its waves)
+  const int my_last = a.pos0 + min(a.T - 1, t0 + QT * 16 - 1);  // last position this wavefront's queries see
+  const int n_blk = (n_keys + 31) / 32;
+
+  u32x4_t kst[SEGS], vst[SEGS];
+  auto fetch = [&](int blk) {   // global -> registers (unconditional: blk is clamped by the caller)
+    const int kb = blk * 32;
+#pragma unroll
+    for (int i = 0; i < SEGS; ++i) {
+      const int seg = tid + 256 * i;
+      const int krow = seg / (D / 8), kcx = seg % (D / 8);
+      kst[i] = *reinterpret_cast<const u32x4_t*>(kc + (size_t)(kb + krow) * D + kcx * 8);
+      const int vrow = seg >> 2, vcx = seg & 3;
+      vst[i] = *reinterpret_cast<const u32x4_t*>(vc + (size_t)vrow * a.max_seq + kb + vcx * 8);
+    }
+  };
+  auto stash = [&](int buf) {   // registers -> LDS
+#pragma unroll
+    for (int i = 0; i < SEGS; ++i) {
+      const int seg = tid + 256 * i;
+      const int krow = seg / (D / 8), kcx = seg % (D / 8);
+      *reinterpret_cast<u32x4_t*>(&lds[buf][krow * KROW + kcx * 16]) = kst[i];
+      const int vrow = seg >> 2, vcx = seg & 3;
+      *reinterpret_cast<u32x4_t*>(&lds[buf][KBYTES + vrow * VROW + vcx * 16]) = vst[i];
+    }
+  };
+
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int blk = 0; blk < n_blk; ++blk) {
+    const int buf = blk & 1;
+    const int kb = blk * 32;
+    fetch(min(blk + 1, n_blk - 1));   // next block's tiles travel while this one is computed
+    if (kb <= my_last && t0 < a.T) {
+      const unsigned char* kl = &lds[buf][0];
+      const unsigned char* vl = &lds[buf][KBYTES];
+      f32x4_t st[QT][2];
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) st[qt][0] = st[qt][1] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+          const uint4 kf = *reinterpret_cast<const uint4*>(kl + (16 * t + b) * KROW + s * 64 + q * 16);
+#pragma unroll
+          for (int qt = 0; qt < QT; ++qt) st[qt][t] = mfma16(kf, qreg[qt][s], st[qt][t]);
+        }
+      uint4 pb[QT];
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) {
+        const int qpos = a.pos0 + t0 + qt * 16 + b;
+        float sv[8];
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int key = kb + 16 * t + 4 * q + r;
+            const float v = key <= qpos ? st[qt][t][r] * scale : -INFINITY;
+            sv[t * 4 + r] = v;
+            mloc = fmaxf(mloc, v);
+          }
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 16, 64));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+        const float mnew = fmaxf(mrun[qt], mloc);   // finite from the first block on (key 0 is always visible)
+        const float corr = __expf(mrun[qt] - mnew);  // exactly 1 when the maximum did not move
+        float psum = 0.f;
+        float pv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          pv[e] = __expf(sv[e] - mnew);
+          psum += pv[e];
+        }
+        lrun[qt] = lrun[qt] * corr + psum;
+        mrun[qt] = mnew;
+        pb[qt].x = (uint32_t)f32_to_bf16(pv[0]) | ((uint32_t)f32_to_bf16(pv[1]) << 16);
+        pb[qt].y = (uint32_t)f32_to_bf16(pv[2]) | ((uint32_t)f32_to_bf16(pv[3]) << 16);
+        pb[qt].z = (uint32_t)f32_to_bf16(pv[4]) | ((uint32_t)f32_to_bf16(pv[5]) << 16);
+        pb[qt].w = (uint32_t)f32_to_bf16(pv[6]) | ((uint32_t)f32_to_bf16(pv[7]) << 16);
+        if (__any(corr != 1.0f)) {   // wave-uniform: some query of the tile has a new maximum
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) oacc[qt][dt][r] *= corr;
+        }
+      }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        const unsigned char* vp = vl + (dt * 16 + b) * VROW + q * 8;
+        const uint2 lo = *reinterpret_cast<const uint2*>(vp);
+        const uint2 hi = *reinterpret_cast<const uint2*>(vp + 32);
+        const uint4 vf = make_uint4(lo.x, lo.y, hi.x, hi.y);
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) oacc[qt][dt] = mfma16(vf, pb[qt], oacc[qt][dt]);
+      }
+    }
+    stash(buf ^ 1);   // that buffer was last read before the previous barrier
+    __syncthreads();
+  }
+  if (t0 >= a.T) return;
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    float l = lrun[qt];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    const float inv = 1.0f / l;
+    const int t = t0 + qt * 16 + b;
+    if (t < a.T) {
+      bf16_t* op = a.o + ((size_t)bi * a.T + t) * a.nq * D + h * D;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16(oacc[qt][dt][0] * inv) | ((uint32_t)f32_to_bf16(oacc[qt][dt][1] * inv) << 16);
+        pk.y = (uint32_t)f32_to_bf16(oacc[qt][dt][2] * inv) | ((uint32_t)f32_to_bf16(oacc[qt][dt][3] * inv) << 16);
+        *reinterpret_cast<uint2*>(op + dt * 16 + 4 * q) = pk;
+      }
+    }
+  }
+}
+
+#ifndef ATTN_LDS_QT
+#define ATTN_LDS_QT 3   // 16-query tiles per wavefront.  Measured on 16 x 2048 tokens, 16 q / 2 kv heads, d = 128:
+                        // 2 tiles 0.80 ms, 3 tiles 0.55 ms, 4 tiles 1.45 ms per layer (4 leaves one wavefront
+                        // per SIMD, which cannot hide the global -> LDS latency; 2 doubles the LDS reads per flop)
+#endif
+template <int D>
+static hipError_t launch_attn_prefill_lds(const AttnPrefillArgs& a, hipStream_t s) {
+  const int g = a.nq / a.nkv;
+  const int hw = g >= 4 && g % 4 == 0 ? 4 : (g % 2 == 0 ? 2 : 1);
+  constexpr int QT = ATTN_LDS_QT;
+  const int qrows = (4 / hw) * QT * 16;
+  const dim3 grid((a.T + qrows - 1) / qrows, a.nq / hw, a.B), block(256);
+  if (hw == 4) hipLaunchKernelGGL((attn_prefill_lds_kernel<D, 4, QT>), grid, block, 0, s, a);
+  else if (hw == 2) hipLaunchKernelGGL((attn_prefill_lds_kernel<D, 2, QT>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((attn_prefill_lds_kernel<D, 1, QT>), grid, block, 0, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_attn_prefill(const AttnPrefillArgs& a, hipStream_t s) {
+  // long prompts: the LDS-shared kernel (its reads run to the end of the last 32-key block, which the
+  // cache capacity, a multiple of 128, always covers); short ones keep more workgroups with the direct one
+  if (a.T >= 256 && (a.max_seq & 31) == 0) {
+    if (a.d == 128) return launch_attn_prefill_lds<128>(a, s);
+    if (a.d == 64) return launch_attn_prefill_lds<64>(a, s);
+    return hipErrorInvalidValue;
+  }
   constexpr int QT = 2;
   const int bq = 4 * QT * 16;
   const dim3 grid((a.T + bq - 1) / bq, a.nq, a.B);

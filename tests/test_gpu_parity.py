@@ -91,6 +91,18 @@ def test_bf16_d128_prefill_ragged_rows(harness):
     assert max(res.errs) < TOL_BF16, res.errs
 
 
+@pytest.mark.parametrize("nq,nkv,d,T", [(8, 1, 128, 300), (4, 2, 64, 257), (2, 2, 128, 290)])
+def test_bf16_long_prefill_lds_attention(harness, nq, nkv, d, T):
+    """Prompts of 256 tokens and more take the LDS-shared flash-attention kernel: 4, 2 and 1 q heads per
+    workgroup (8, 2 and 1 q heads per kv head), d = 128 and 64, ragged last query and key blocks, and a
+    decode step over the cache it filled."""
+    w = inputs.WORKLOADS["70b_r4_prefill"].with_(name=f"long_prefill_{nq}_{nkv}_{d}", n_layers=2, hidden=256, inter=256,
+                                                 n_q_heads=nq, n_kv_heads=nkv, head_dim=d, batch=2, prefill=T,
+                                                 decode_steps=1)
+    res = harness.run_case(w)
+    assert max(res.errs) < TOL_BF16, res.errs
+
+
 def test_error_codes_on_the_gpu(harness):
     w = TINY
     ctx = ladder.Ladder(ladder.config_for(w))
