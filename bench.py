@@ -51,6 +51,18 @@ def build_context(w, device, extra_seq, peers_rows, **override):
     return ctx
 
 
+def read_profiled_traffic(kernel, workload):
+    """HBM bytes per launch of the dominant kernel as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by
+    a known-size copy): the figure of the committed summary profiles/<kernel>_hbm_traffic_<workload>.md, which
+    states it on a line 'traffic_bytes_per_launch: <number>'.  None if there is no such summary."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"{kernel}_hbm_traffic_{workload}.md")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+    return float(m.group(1)) if m else None
+
+
 def decode_algorithmic_bytes(w, s_mean):
     """Bytes one decode step must move: every weight once, the visible KV cache once, peers once."""
     weights = w.n_layers * w.n_real_shards * w.params_per_layer() * 2
@@ -117,6 +129,13 @@ def run_decode(args):
     out = torch.empty((w.batch, w.hidden), dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
     log(f"[bench] context ready: {ctx.device_bytes() / 2**30:.2f} GiB on device")
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            ctx.calibration_copy(dst, src)    # calibration_copy_kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         ctx.decode_step(xs[i], out)
     torch.cuda.synchronize()
@@ -153,10 +172,7 @@ def run_decode(args):
         gemv_bytes_per_launch = wb / (4 * w.n_layers * w.n_real_shards)   # 4 projections per layer and shard
     avg_ms = ms_gemv / max(n_gemv, 1)
     achieved = gemv_bytes_per_launch / (avg_ms * 1e-3) / 1e9 if n_gemv else 0.0
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"gemv_hbm_traffic_{w.name}.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+    traffic = read_profiled_traffic("fused_decode" if prof.get("fused_decode", (0, 0.0))[0] else "gemv", w.name)
     roofline = {"bound": "hbm", "kernel": kernel_name,
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "traffic": traffic, "algorithmic_bytes_per_launch": gemv_bytes_per_launch,
@@ -250,6 +266,9 @@ def main():
     ap.add_argument("--no-overlap", action="store_true", help="one compute stream instead of attention / MLP streams")
     ap.add_argument("--wiring", choices=["ladder", "standard"], default="ladder",
                     help="residual wiring of the stack (the metric is quoted on ladder; standard is the paper's Eq. 1 baseline)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="before the steps, run 4 plain copy kernels of 1 GiB (read 1 GiB, write 1 GiB each): "
+                         "the known-size dispatches that scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--no-fused", action="store_true", help="one kernel per operation instead of the fused decode launches")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -6,9 +6,13 @@
  * (odd m = attention of layer (m+1)/2, even m = SwiGLU MLP of layer m/2), on
  * ONE GPU.  The paper's blocking AllReduce is replaced by a local sum of the
  * rank partial sums (computed shards + caller-supplied synthetic partials of
- * the ranks that are not computed) that runs on an internal side stream, with
- * HIP events playing the role of the paper's AsyncAllReduce handles
- * (Algorithm 1).  Nothing crosses a GPU boundary.
+ * the ranks that are not computed).  In the one-kernel-per-operation
+ * schedules that sum runs on internal streams with HIP events playing the
+ * role of the paper's AsyncAllReduce handles (Algorithm 1); in the fused
+ * decode schedule it is the epilogue of the module's last projection and
+ * the overlap Algorithm 1 obtains from the handles comes from putting the
+ * independent work of neighbouring modules into one launch.  Nothing crosses
+ * a GPU boundary.
  *
  * Conventions
  *   - row-vector convention y = x W; every matrix handed in is row-major
@@ -18,10 +22,11 @@
  *     (LADDER_FP32: float, LADDER_BF16: bfloat16 bit pattern in uint16).
  *   - every pointer named "device" is a HIP device pointer of the current
  *     device; config / weight-descriptor structs are host memory.
- *   - calls enqueue work on the stream given to ladder_init (plus the
- *     internal side stream, joined back before the call returns to the
- *     stream) and return without synchronising; outputs are valid once the
- *     caller has synchronised that stream.
+ *   - calls are ordered on the stream given to ladder_init: the work runs on
+ *     the context's own streams, which wait for that stream at entry and which
+ *     that stream waits for before the call returns; calls return without
+ *     synchronising; outputs are valid once the caller has synchronised the
+ *     stream.
  *   - every entry point returns 0 or a negative LADDER_E_* code; nothing
  *     throws or aborts across the boundary; a failed call leaves the
  *     context's position unchanged.  ladder_last_error gives a text.
@@ -71,7 +76,10 @@ typedef struct {
   int32_t n_standard_layers; /* hybrid: with wiring LADDER, the first n_standard_layers layers still use
                                 the standard wiring (the paper's hybrid keeps ladder for the upper layers) */
   int32_t reduce_on_side_stream; /* 1: reduce + residual add overlap the next module on a side stream;
-                                    0: everything in order on the caller's stream (same results) */
+                                    0: everything in order on one stream (same results).  Like
+                                    overlap_modules it applies to calls of at most 64 rows that do not take
+                                    the fused decode schedule; larger calls (prefill) always run in order:
+                                    their kernels fill the chip and measured slower when spread over streams */
   int32_t peer_pool;      /* number of distinct synthetic peer sets; module m uses set m % peer_pool */
   int32_t peer_rows;      /* rows of each synthetic peer tensor (>= rows of any call), 0 if no peers */
   int32_t kernel_path;    /* LADDER_PATH_AUTO: MFMA/streaming kernels when dtype and sizes allow;
@@ -80,11 +88,13 @@ typedef struct {
                               module m+1 (which under the ladder wiring needs only x_{m-1}) can execute
                               while module m still runs; 0: one compute stream.  Same results. */
   int32_t decode_graph;   /* 1: a decode step of the bf16 streaming path is captured once into a HIP graph
-                             (all streams) and replayed, removing the per-launch host cost; 0: eager launches */
-  int32_t decode_fused;   /* 1: decode steps of the bf16 streaming path (batch <= 16, one computed shard) use the
-                             fused launches: independent projections / attention of neighbouring modules
-                             share one launch, residual add, reduce, RMSNorm, rotary and the attention
-                             combine are epilogues / prologues; 0: one kernel per operation */
+                             and replayed (the position lives in device memory and is advanced by the
+                             graph itself); 0: eager launches.  Same results. */
+  int32_t decode_fused;   /* 1: decode steps of the bf16 streaming path (batch <= 16, one computed shard,
+                             max_seq <= 65536) use the fused launches: independent projections / attention
+                             of neighbouring modules share one launch; residual add, partial-sum reduce,
+                             RMSNorm, rotary, cache append and SwiGLU are epilogues / prologues;
+                             0: one kernel per operation */
   float rms_eps;          /* RMSNorm epsilon (inside the square root) */
   float rope_theta;       /* rotary base; pair (2j,2j+1) turns by pos * theta^(-2j/d) */
 } ladder_config;
@@ -114,7 +124,10 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out);
 
 /* Copies / repacks one shard of one layer into the context (enqueued on the caller's stream).
  * layer in [0, N), shard in [0, n_real_shards).  Every (layer, shard) must be loaded before the
- * first forward call (else LADDER_E_STATE there). */
+ * first forward call (else LADDER_E_STATE there).  All nine pointers are read for every shard: on
+ * the bf16 streaming path the two norm gains are multiplied into the rows of the packed QKV and
+ * gate/up weights (RMSNorm's gain commutes into the following projection), once, in fp32, before the
+ * rounding to bf16. */
 int ladder_load_layer(ladder_ctx* ctx, int32_t layer, int32_t shard, const ladder_layer_weights* w);
 
 /* Synthetic partial sums of the ranks that are not computed: device T
@@ -181,6 +194,13 @@ enum {
 int ladder_profile_enable(ladder_ctx* ctx, int32_t on);
 int ladder_profile_read(ladder_ctx* ctx, int32_t cls, int64_t* launches, double* total_ms);
 int ladder_profile_reset(ladder_ctx* ctx);
+
+/* Measurement helper: copies `bytes` bytes (a multiple of 16; both device pointers 16-byte aligned,
+ * caller-owned, not overlapping) with a plain copy kernel on the caller's stream.  It reads and writes
+ * exactly `bytes` bytes of HBM once, which is what hardware byte counters (rocprofv3 FETCH_SIZE /
+ * WRITE_SIZE) are scaled by when the traffic of the other kernels is measured.
+ * Errors: LADDER_E_ARG (NULL), LADDER_E_SHAPE (size / alignment), LADDER_E_HIP. */
+int ladder_calibration_copy(ladder_ctx* ctx, void* dst, const void* src, size_t bytes);
 
 #ifdef __cplusplus
 }

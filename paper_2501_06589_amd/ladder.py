@@ -50,6 +50,7 @@ EXPORTS = {
     "ladder_profile_enable": (C.c_int, [C.c_void_p, C.c_int32]),
     "ladder_profile_read": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
     "ladder_profile_reset": (C.c_int, [C.c_void_p]),
+    "ladder_calibration_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
 }
 
 _lib = None
@@ -173,6 +174,14 @@ class Ladder:
 
     def profile_reset(self):
         self._check(self._lib.ladder_profile_reset(self._h))
+
+    def calibration_copy(self, dst, src):
+        """Plain copy kernel over two same-sized device tensors (the known-size dispatch HBM counters are scaled by)."""
+        nbytes = src.numel() * src.element_size()
+        if dst.numel() * dst.element_size() != nbytes:
+            raise ValueError("calibration_copy: sizes differ")
+        self._check(self._lib.ladder_calibration_copy(self._h, C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()),
+                                                      C.c_size_t(nbytes)))
 
     def profile_read(self) -> Dict[str, Tuple[int, float]]:
         out = {}
