@@ -3,17 +3,18 @@
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 70b_r8_decode] [--mode decode|prefill]
 
-mode decode (default): a step = one decode step of the whole block stack (all 2N modules: norm, QKV,
-rotary + cache append, split-KV attention, O projection, SwiGLU MLP, partial-sum reduce + residual add
-on the side stream) for one batch.  Workload 70b_r8_decode: 80 layers of a 70B-shaped TP rank at
-R = 8 (hidden 8192, 8 q / 1 kv heads, d = 128, intermediate 3584), batch 4, synthetic KV cache of
-1024 positions, 7 synthetic peer partial sums per module.  All inputs are seeded, synthetic and
-resident in HBM before the timed region.
+mode decode (default): a step = one decode step of the whole block stack (all 2N modules: RMSNorm, QKV,
+rotary + cache append, split-KV attention, O projection, SwiGLU MLP, partial-sum reduce + residual add)
+for one batch, in the fused schedule (242 launches for 80 layers).  Workload 70b_r8_decode: 80 layers of
+a 70B-shaped TP rank at R = 8 (hidden 8192, 8 q / 1 kv heads, d = 128, intermediate 3584), batch 4,
+synthetic KV cache of 1024 positions, 7 synthetic peer partial sums per module.  All inputs are seeded,
+synthetic and resident in HBM before the timed region.
 mode prefill: a step = one prefill call (workload 70b_r4_prefill: 16 x 2048 tokens).
 
-Prints ONE JSON line: the contract fields plus "roofline" (dominant kernel, measured with HIP events
-around every launch in an instrumented pass right after the timed one) and "cpu_baseline" (the CPU
-oracle timed on a bounded sample of the same workload).
+Prints ONE JSON line: the contract fields plus "roofline" (dominant kernel: HIP events attached to every
+dispatch in an instrumented pass right after the timed one; "traffic" = HBM bytes per launch counted by
+rocprofv3, read from the committed summary under profiles/) and "cpu_baseline" (the CPU oracle timed on
+a bounded sample of the same workload).
 """
 import argparse
 import json
@@ -87,7 +88,7 @@ def cpu_baseline_decode(w, device, n_layers_sample, kv_len):
     cfg = from_torch.config_from_workload(ws)
     layers = [from_torch.layer_from_tensors([{k: v.cpu() for k, v in inputs.layer_weights(ws, i, r, device).items()}
                                              for r in range(ws.n_real_shards)]) for i in range(n_layers_sample)]
-    state = lo.State.empty(cfg, ws.n_real_shards, ws.batch, kv_len + 2)
+    state = lo.State.empty(cfg, ws.n_real_shards, ws.batch, kv_len + 4)
     for i in range(n_layers_sample):
         for r in range(ws.n_real_shards):
             k, v = inputs.kv_cache(ws, i, r, ws.batch, kv_len, device)
@@ -96,13 +97,17 @@ def cpu_baseline_decode(w, device, n_layers_sample, kv_len):
     peers = inputs.peer_partials(ws, ws.batch, device)
     opeers = from_torch.to_f64(peers) if peers is not None else None
     e = from_torch.to_f64(inputs.embeddings(ws, ws.batch, 1, inputs.SEED_DECODE0, device))
+    n_steps = 3
     t0 = time.perf_counter()
-    lo.forward_eq2(e, layers, cfg, state, opeers)
-    dt = time.perf_counter() - t0
+    for i in range(n_steps):
+        if i:
+            e = from_torch.to_f64(inputs.embeddings(ws, ws.batch, 1, inputs.SEED_DECODE0 + i, device))
+        lo.forward_eq2(e, layers, cfg, state, opeers)
+    dt = (time.perf_counter() - t0) / n_steps
     full_step_s = dt * w.n_layers / n_layers_sample
     return {"value": w.batch / full_step_s, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"one decode step (batch {w.batch}, {kv_len} cached positions) of the first {n_layers_sample} "
-                      f"of {w.n_layers} layers in {dt:.2f} s, scaled linearly to {w.n_layers} layers"}
+            "sample": f"{n_steps} decode steps (batch {w.batch}, {kv_len}+ cached positions) of the first {n_layers_sample} "
+                      f"of {w.n_layers} layers, {dt:.2f} s per step, scaled linearly to {w.n_layers} layers"}
 
 
 def run_decode(args):
@@ -260,7 +265,7 @@ def main():
     ap.add_argument("--mode", choices=["decode", "prefill"], default="decode")
     ap.add_argument("--workload", default=None)
     ap.add_argument("--layers", type=int, default=0, help="debug: truncate the stack (result is then not the metric)")
-    ap.add_argument("--cpu-layers", type=int, default=16, help="layers of the oracle's timed sample")
+    ap.add_argument("--cpu-layers", type=int, default=32, help="layers of the oracle's timed sample")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--graph", action="store_true", help="replay decode steps from a captured HIP graph instead of eager launches")
     ap.add_argument("--no-overlap", action="store_true", help="one compute stream instead of attention / MLP streams")

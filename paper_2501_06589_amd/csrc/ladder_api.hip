@@ -1,13 +1,21 @@
-// Host side of the C-ABI: configuration checks, memory plan, weight loading, and the per-module
-// schedule of the Ladder-Residual forward (Algorithm 1 / Eq. 2) on two HIP streams.
+// Host side of the C-ABI: configuration checks, memory plan, weight loading (repack into matrix-core
+// tiles, norm gains folded in), and the schedules of the Ladder-Residual forward (Algorithm 1 / Eq. 2).
 //
-// Schedule.  Module m (1..2N) runs on the caller's stream and writes its partial sums into
-// parts[m%2].  "AsyncAllReduce(m)" = reduce_norm on the side stream: it waits for the event recorded
-// after module m, folds the partial sums (computed shards, split-K slots, synthetic peers) into the
-// fp32 residual x in place (x_m = x_{m-1} + sum), and emits the RMS-normed input of the module(s)
-// that read x_m: module m+2 with the ladder wiring, module m+1 with the standard wiring.  The event
-// recorded after it is the handle; module m+lag waits on it.  Hence with the ladder wiring
-// reduce(m) overlaps module m+1, which is the decoupling the architecture buys.
+// All work runs on the context's own streams; the caller's stream is fenced in and out with events.
+//
+// Per-operation schedule (forward_body: prefill, fp32, several computed shards).  Module m (1..2N)
+// writes its partial sums into parts[m%2].  "AsyncAllReduce(m)" = reduce_norm: it waits for the event
+// recorded after module m, folds the partial sums (computed shards, split-K slots, synthetic peers)
+// into the fp32 residual x in place (x_m = x_{m-1} + sum), and emits the RMS-normed input of the
+// module(s) that read x_m: module m+2 with the ladder wiring, module m+1 with the standard wiring.
+// The event recorded after it is the handle; module m+lag waits on it.  For calls of at most 64 rows
+// the two module kinds may run on two streams (or the reduces on a side stream), so that with the
+// ladder wiring reduce(m) overlaps module m+1; larger calls run in order on one stream.
+//
+// Fused decode schedule (build_fused_plan / fused_body: bf16, batch <= 16, one computed shard).  A
+// decode step is a fixed list of launches of one kernel, each holding up to two independent jobs
+// (under the ladder wiring the MLP projections of layer l and the attention side of layer l+1);
+// reduce, residual add, RMSNorm, rotary and cache append are epilogues of the projections.
 #include <math.h>
 #include <stdio.h>
 #include <stdlib.h>
