@@ -59,13 +59,14 @@ struct AttnJob {
 };
 
 #define FUSED_MAX_LDS_BYTES (72 * 1024)
+#define FUSED_MAX_JOBS 3
 
 struct FusedArgs {
-  int n_jobs;              // 1 or 2
+  int n_jobs;              // 1 .. FUSED_MAX_JOBS
   int lds_bytes;           // dynamic LDS of the launch = the largest need of its jobs
-  int kind[2];             // JOB_GEMV | JOB_ATTN (at most one attention job, described by `a`)
-  int block_end[2];        // cumulative workgroup counts: job 0 = [0, block_end[0]), job 1 = [block_end[0], block_end[1])
-  GemvJob g[2];
+  int kind[FUSED_MAX_JOBS];       // JOB_GEMV | JOB_ATTN (at most one attention job, described by `a`)
+  int block_end[FUSED_MAX_JOBS];  // cumulative workgroup counts: job i = [block_end[i-1], block_end[i])
+  GemvJob g[FUSED_MAX_JOBS];
   AttnJob a;
 };
 

@@ -448,10 +448,12 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(FusedArg
   FusedTraceScope trace_scope;
 #endif
   int lb = blockIdx.x, job = 0;
-  if (lb >= fa.block_end[0]) {
-    lb -= fa.block_end[0];
-    job = 1;
-  }
+#pragma unroll
+  for (int i = 0; i + 1 < FUSED_MAX_JOBS; ++i)
+    if ((int)blockIdx.x >= fa.block_end[i]) {
+      lb = blockIdx.x - fa.block_end[i];
+      job = i + 1;
+    }
   if (fa.kind[job] == JOB_ATTN) {
     attn_job<D, G>(fa.a, lb, smem, &s_flag);
   } else {

@@ -89,6 +89,7 @@ struct ladder_ctx {
   unsigned* tk_att = nullptr;     // arrival tickets of split attention, [max_batch][nkv]
   std::vector<FusedArgs> fused_plan;
   int fused_plan_batch = 0;
+  int n_cu = 256;                 // compute units of the device (workgroup slots of a fused launch = 2 per CU)
   const char* fused_plan_peers = nullptr;
   int pos = 0, batch = 0;
   std::string err;
@@ -474,9 +475,11 @@ void build_fused_plan(ladder_ctx* c, int B) {
     return j;
   };
   // the gate/up projection cut in two column ranges (it is the largest stream and depends on nothing
-  // recent, so a part of it rides along with each of the two launches that would otherwise be short)
+  // recent, so a half of it rides along with each of the two launches that would otherwise be short;
+  // on the 70B-shard shape any cut that leaves at most one whole-K workgroup per CU in both launches,
+  // 46 % - 52 %, measured the same)
   const int gu_groups = 2 * I / 16;
-  const int gu_first = std::max(1, std::min(gu_groups - 1, gu_groups / 4));
+  const int gu_first = std::max(1, gu_groups / 2);
   auto job_gu_part = [&](int l, int src, int part) {
     GemvJob j = job_gu(l, src);
     if (part == 0) { j.group0 = 0; j.n_groups = gu_first; }
@@ -499,33 +502,46 @@ void build_fused_plan(ladder_ctx* c, int B) {
   };
   auto blocks_of = [&](const GemvJob& j) { return j.n_groups; };
   auto lds_of = [&](const GemvJob&) { return (int)fused_gemv_lds_bytes(); };
-  auto one = [&](const GemvJob& j0) {
+  // Jobs side by side in one launch, in dispatch order.  Workgroups are dispatched in block order and a
+  // CU holds two of them: the job whose workgroups run longest (whole-K streams over hidden) goes first
+  // so that each lands on a CU of its own, and the short ones fill the second slots.
+  auto several = [&](std::initializer_list<GemvJob> jobs) {
     FusedArgs f{};
-    const GemvJob j = j0;
-    f.n_jobs = 1; f.kind[0] = JOB_GEMV; f.g[0] = j; f.block_end[0] = blocks_of(j); f.block_end[1] = f.block_end[0];
-    f.lds_bytes = lds_of(j);
+    int i = 0, total = 0;
+    for (const GemvJob& j : jobs) {
+      if (blocks_of(j) <= 0) continue;
+      f.kind[i] = JOB_GEMV; f.g[i] = j; total += blocks_of(j); f.block_end[i] = total;
+      f.lds_bytes = std::max(f.lds_bytes, lds_of(j));
+      ++i;
+    }
+    f.n_jobs = i;
+    for (; i < FUSED_MAX_JOBS; ++i) f.block_end[i] = total;   // unused job slots: no block index reaches them
     return f;
   };
-  // Workgroups are dispatched in block order and a CU holds two of them: the job whose workgroups run
-  // longest (whole-K streams over hidden) goes first so that each lands on a CU of its own, and the
-  // short ones fill the second slots.
-  auto two = [&](const GemvJob& first, const GemvJob& second) {
-    FusedArgs f{};
-    f.n_jobs = 2; f.kind[0] = JOB_GEMV; f.kind[1] = JOB_GEMV; f.g[0] = first; f.g[1] = second;
-    f.block_end[0] = blocks_of(first); f.block_end[1] = f.block_end[0] + blocks_of(second);
-    f.lds_bytes = std::max(lds_of(first), lds_of(second));
-    return f;
-  };
+  auto one = [&](const GemvJob& j) { return several({j}); };
+  auto two = [&](const GemvJob& first, const GemvJob& second) { return several({first, second}); };
   auto att = [&](int l, const GemvJob* beside) {
     FusedArgs f{};
-    f.kind[0] = JOB_ATTN; f.a = job_att(l); f.block_end[0] = n_splits * nkv * B; f.n_jobs = 1; f.block_end[1] = f.block_end[0];
+    f.kind[0] = JOB_ATTN; f.a = job_att(l); f.block_end[0] = n_splits * nkv * B; f.n_jobs = 1;
     f.lds_bytes = (int)fused_attn_lds_bytes(d, nq / nkv);
     if (beside) {
-      const GemvJob j = *beside;
-      f.n_jobs = 2; f.kind[1] = JOB_GEMV; f.g[1] = j; f.block_end[1] = f.block_end[0] + blocks_of(j);
-      f.lds_bytes = std::max(f.lds_bytes, lds_of(j));
+      f.n_jobs = 2; f.kind[1] = JOB_GEMV; f.g[1] = *beside; f.block_end[1] = f.block_end[0] + blocks_of(*beside);
+      f.lds_bytes = std::max(f.lds_bytes, lds_of(*beside));
     }
+    for (int i = f.n_jobs; i < FUSED_MAX_JOBS; ++i) f.block_end[i] = f.block_end[f.n_jobs - 1];
     return f;
+  };
+  // { qkv , down }: when the two together exceed the resident workgroup slots (two per CU), the late
+  // down workgroups would start only after a slot frees and end the launch alone; as many of them as
+  // needed take two tiles instead, so that every workgroup of the launch is resident from the start.
+  auto qkv_down = [&](const GemvJob& qkv, const GemvJob& dn) {
+    const int slots = 2 * c->n_cu;
+    const int over = blocks_of(qkv) + blocks_of(dn) - slots;
+    if (over <= 0 || 2 * over > blocks_of(dn)) return two(qkv, dn);
+    GemvJob dbl = dn, sgl = dn;
+    dbl.tn = 2; dbl.group0 = 0; dbl.n_groups = over;                       // tiles [0, 2 * over)
+    sgl.group0 = 2 * over; sgl.n_groups = blocks_of(dn) - 2 * over;        // tiles [2 * over, end)
+    return several({qkv, dbl, sgl});
   };
   auto src_of = [&](int m) { const int s = m - lag_of(c, m); return s < 0 ? 0 : s; };
 
@@ -533,20 +549,18 @@ void build_fused_plan(ladder_ctx* c, int B) {
   plan.clear();
   const bool all_ladder = g.wiring == LADDER_WIRING_LADDER && g.n_standard_layers == 0;
   if (all_ladder) {
-    // modules 1 and 2 both read x_0; then, layer by layer, the MLP of layer l runs beside the attention
-    // side of layer l+1:  { o_l , gate/up_l (first part) }  { qkv_{l+1} , gate/up_l (rest) }
-    //                     { attention_{l+1} , down_l }
+    // modules 1 and 2 both read x_0; then three launches per layer, each pairing work of the two module
+    // chains that does not depend on each other:
+    //     { attention_l , gate/up_l (first part) }     { gate/up_l (rest) , o_l }     { qkv_{l+1} , down_l }
+    // The attention workgroups are few and latency bound: beside the largest weight stream they cost nothing.
     plan.push_back(one(job_qkv(1, 0)));
-    plan.push_back(att(1, nullptr));
-    for (int l = 1; l < N; ++l) {
-      plan.push_back(two(job_gu_part(l, 2 * l - 2, 0), job_o(l, 2 * l - 1)));
-      plan.push_back(two(job_qkv(l + 1, 2 * l - 1), job_gu_part(l, 2 * l - 2, 1)));
-      GemvJob dn = job_dn(l, 2 * l);
-      plan.push_back(att(l + 1, &dn));
+    for (int l = 1; l <= N; ++l) {
+      GemvJob gu_a = job_gu_part(l, 2 * l - 2, 0);
+      plan.push_back(att(l, &gu_a));
+      plan.push_back(two(job_gu_part(l, 2 * l - 2, 1), job_o(l, 2 * l - 1)));
+      if (l < N) plan.push_back(qkv_down(job_qkv(l + 1, 2 * l - 1), job_dn(l, 2 * l)));
+      else plan.push_back(one(job_dn(N, 2 * N)));
     }
-    plan.push_back(two(job_gu_part(N, 2 * N - 2, 0), job_o(N, 2 * N - 1)));
-    plan.push_back(one(job_gu_part(N, 2 * N - 2, 1)));
-    plan.push_back(one(job_dn(N, 2 * N)));
   } else {
     for (int l = 1; l <= N; ++l) {
       plan.push_back(one(job_qkv(l, src_of(2 * l - 1))));
@@ -823,6 +837,10 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
     c->fused = fused_usable(c);
     if (c->fused) {
       INIT_HIP(fused_decode_prepare(d, gq));
+      int dev_id = 0, n_cu = 0;
+      INIT_HIP(hipGetDevice(&dev_id));
+      INIT_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev_id));
+      if (n_cu > 0) c->n_cu = n_cu;
       for (int i = 0; i < 3; ++i) {
         INIT_TRY(dev_alloc(c, (void**)&c->x_ring[i], (size_t)16 * H * 4, true));
         INIT_TRY(dev_alloc(c, (void**)&c->xh_ring[i], (size_t)16 * H * 2, true));
