@@ -116,10 +116,13 @@ def run_decode(args):
     w = inputs.WORKLOADS[args.workload]
     if args.layers:
         w = w.with_(n_layers=args.layers)
+    if args.batch:
+        w = w.with_(batch=args.batch)
     dev = "cuda:0"
     prof_steps = 8
     total_steps = args.warmup + args.steps + prof_steps
-    ctx = build_context(w, dev, total_steps, w.batch, max_tokens=max(w.prefill, 1),
+    # the peer tensor must hold as many rows per set as the configuration announces (peer_rows)
+    ctx = build_context(w, dev, total_steps, w.batch * max(w.prefill, 1), max_tokens=max(w.prefill, 1),
                         decode_graph=1 if args.graph else 0, overlap_modules=0 if args.no_overlap else 1,
                         decode_fused=0 if args.no_fused else 1,
                         wiring=ladder.LADDER_WIRING_STANDARD if args.wiring == "standard" else ladder.LADDER_WIRING_LADDER)
@@ -208,6 +211,8 @@ def run_prefill(args):
     w = inputs.WORKLOADS[args.workload]
     if args.layers:
         w = w.with_(n_layers=args.layers)
+    if args.batch:
+        w = w.with_(batch=args.batch)
     dev = "cuda:0"
     rows = w.batch * w.prefill
     ctx = build_context(w, dev, 8, rows)
@@ -264,6 +269,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--mode", choices=["decode", "prefill"], default="decode")
     ap.add_argument("--workload", default=None)
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (1.2b / 8b are quoted at 1, 4, 16)")
     ap.add_argument("--layers", type=int, default=0, help="debug: truncate the stack (result is then not the metric)")
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers of the oracle's timed sample")
     ap.add_argument("--no-cpu", action="store_true")

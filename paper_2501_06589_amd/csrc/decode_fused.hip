@@ -1,13 +1,13 @@
 // Fused decode path of the bf16 storage type (gfx950), batch <= 16, one computed shard.
 //
-// One launch runs up to two independent JOBS side by side (workgroups pick their job from the
+// One launch runs up to three independent JOBS side by side (workgroups pick their job from the
 // block index).  Under the ladder wiring module m+1 needs only x_{m-1}, so the MLP projections of
-// layer l and the attention-side work of layer l+1 have no dependency on each other: putting them
+// layer l and the attention-side work around them have no dependency on each other: putting them
 // into ONE launch keeps HBM streaming while the small, latency-bound attention work runs, with no
 // stream, event or graph edge in between.  A decode step is three launches per layer:
+//     { attention_l , gate/up_l first half (+ RMSNorm, SwiGLU) }
+//     { gate/up_l second half , o_l (+ residual add) }
 //     { qkv_{l+1} (+ RMSNorm, rotary, cache append) , down_l (+ residual add) }
-//     { attention_{l+1} , gate/up_{l+1} (+ RMSNorm, SwiGLU) }
-//     { o_{l+1} (+ residual add) }
 // Everything that used to be a kernel of its own is an epilogue or a prologue here, and none of it
 // needs one workgroup to talk to another (a device-wide release fence per workgroup was measured to
 // cost more than the whole projection):
@@ -36,7 +36,9 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 
 #define FUSED_THREADS 512
 #define FUSED_WAVES 8
+#ifndef FUSED_U
 #define FUSED_U 4    // k tiles per register buffer (two buffers): 8 KiB of weights in flight per wavefront
+#endif
 #define FUSED_LDS_FLOATS 9216   // attention job: per-wave statistics and outputs
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {

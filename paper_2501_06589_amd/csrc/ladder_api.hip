@@ -432,9 +432,11 @@ void build_fused_plan(ladder_ctx* c, int B) {
   const ladder_config& g = c->cfg;
   const int H = g.hidden, d = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, I = g.inter, N = g.n_layers;
   const int nqd = nq * d;
-  // attention: about 24 workgroups per launch; a (sequence, kv head) is cut into splits of positions
-  // (multiples of 64) that meet through an arrival ticket when there is more than one
-  int n_splits = (24 + B * nkv - 1) / (B * nkv);
+  // attention: a (sequence, kv head) is cut into splits of positions (multiples of 64) that meet through
+  // an arrival ticket when there is more than one.  A split of 256 positions is one 32-key block per
+  // wavefront, i.e. one memory round trip; splits grow beyond that only when there would be more
+  // attention workgroups than CUs.
+  int n_splits = std::min((g.max_seq + 255) / 256, std::max(1, c->n_cu / (B * nkv)));
   n_splits = std::max(1, std::min(n_splits, (g.max_seq + 63) / 64));
   const int split_len = ((g.max_seq + n_splits - 1) / n_splits + 63) / 64 * 64;
   n_splits = (g.max_seq + split_len - 1) / split_len;

@@ -129,35 +129,61 @@ class Ladder:
         if rc != LADDER_OK:
             raise LadderError(rc, (self._lib.ladder_last_error(self._h) or b"").decode())
 
+    # -- the C side takes raw device pointers and cannot know how large the buffers behind them are:
+    #    sizes, storage type, device and contiguity are checked here, where the tensors are still tensors
+    def _want(self, name: str, t, numel: int, storage: bool = True):
+        import torch
+        if t is None:
+            raise ValueError(f"{name} is missing")
+        dt = (torch.float32 if self.cfg.dtype == LADDER_FP32 else torch.bfloat16) if storage else torch.float32
+        if not t.is_cuda or not t.is_contiguous() or t.dtype != dt or t.numel() != numel:
+            raise ValueError(f"{name}: need a contiguous {dt} device tensor of {numel} elements, got "
+                             f"{tuple(t.shape)} {t.dtype} on {t.device}")
+
     def load_layer(self, layer: int, shard: int, tensors: Dict[str, "object"]):
+        g = self.cfg
+        nqd, nkvd = g.n_q_heads * g.head_dim, g.n_kv_heads * g.head_dim
+        sizes = dict(attn_norm=g.hidden, wq=g.hidden * nqd, wk=g.hidden * nkvd, wv=g.hidden * nkvd, wo=nqd * g.hidden,
+                     mlp_norm=g.hidden, w_gate=g.hidden * g.inter, w_up=g.hidden * g.inter, w_down=g.inter * g.hidden)
         w = ladder_layer_weights()
         for name, _ in ladder_layer_weights._fields_:
-            t = tensors.get(name)
-            if t is not None and not t.is_contiguous():
-                raise ValueError(f"{name} must be contiguous")
-            setattr(w, name, _ptr(t))
+            self._want(name, tensors.get(name), sizes[name])
+            setattr(w, name, _ptr(tensors[name]))
         self._check(self._lib.ladder_load_layer(self._h, layer, shard, C.byref(w)))
 
     def set_peer_partials(self, peers):
+        g = self.cfg
+        n = g.peer_pool * (g.tp_degree - g.n_real_shards) * g.peer_rows * g.hidden
+        if peers is not None and n > 0:      # a configuration without peers: the library reports the misuse
+            self._want("peers", peers, n)
         self._keep = [peers]
         self._check(self._lib.ladder_set_peer_partials(self._h, _ptr(peers)))
 
     def load_kv(self, layer: int, shard: int, k, v):
+        g = self.cfg
         b, _, s, _ = k.shape
-        self._check(self._lib.ladder_load_kv(self._h, layer, shard, _ptr(k.contiguous()), _ptr(v.contiguous()), b, s))
+        k, v = k.contiguous(), v.contiguous()
+        self._want("k", k, b * g.n_kv_heads * s * g.head_dim)
+        self._want("v", v, b * g.n_kv_heads * s * g.head_dim)
+        self._check(self._lib.ladder_load_kv(self._h, layer, shard, _ptr(k), _ptr(v), b, s))
 
     def prefill(self, x_in, x_out=None):
         import torch
         b, t, h = x_in.shape
+        self._want("x_in", x_in, b * t * self.cfg.hidden)
         if x_out is None:
             x_out = torch.empty((b, t, h), dtype=torch.float32, device=x_in.device)
+        self._want("x_out", x_out, b * t * self.cfg.hidden, storage=False)
         self._check(self._lib.ladder_prefill(self._h, _ptr(x_in), b, t, _ptr(x_out)))
         return x_out
 
     def decode_step(self, x_in, x_out=None):
         import torch
+        _, batch = self.position()
+        self._want("x_in", x_in, max(batch, 1) * self.cfg.hidden)
         if x_out is None:
             x_out = torch.empty(x_in.shape, dtype=torch.float32, device=x_in.device)
+        self._want("x_out", x_out, max(batch, 1) * self.cfg.hidden, storage=False)
         self._check(self._lib.ladder_decode_step(self._h, _ptr(x_in), _ptr(x_out)))
         return x_out
 

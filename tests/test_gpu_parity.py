@@ -135,6 +135,18 @@ def test_error_codes_on_the_gpu(harness):
         ctx.set_peer_partials(x)                         # configuration without peers
     assert e.value.code == ladder.LADDER_E_SHAPE
     ctx.free()
+    # buffers that are smaller than the configuration announces never reach the library
+    wp = w.with_(name="tiny_peers", tp_degree=4, n_real_shards=2, peer_pool=2)
+    ctx = ladder.Ladder(ladder.config_for(wp))
+    good = inputs.peer_partials(wp, wp.batch * wp.prefill, "cuda:0")
+    ctx.set_peer_partials(good)
+    with pytest.raises(ValueError):
+        ctx.set_peer_partials(good[:, :, :1].contiguous())
+    with pytest.raises(ValueError):
+        ctx.prefill(torch.zeros((1, 4, w.hidden + 8), device="cuda:0"))
+    with pytest.raises(ValueError):
+        ctx.load_layer(0, 0, {k: v.to("cuda:0")[..., :-1].contiguous() for k, v in tensors[0][0].items()})
+    ctx.free()
 
 
 def test_graph_replay_overlap_and_eager_are_bit_identical(harness):
