@@ -124,7 +124,7 @@ def run_decode(args):
     # the peer tensor must hold as many rows per set as the configuration announces (peer_rows)
     ctx = build_context(w, dev, total_steps, w.batch * max(w.prefill, 1), max_tokens=max(w.prefill, 1),
                         decode_graph=1 if args.graph else 0, overlap_modules=0 if args.no_overlap else 1,
-                        decode_fused=0 if args.no_fused else 1,
+                        decode_fused=0 if args.no_fused else 1, reduce_delay_us=args.reduce_delay_us,
                         wiring=ladder.LADDER_WIRING_STANDARD if args.wiring == "standard" else ladder.LADDER_WIRING_LADDER)
     if w.kv_preload:
         for i in range(w.n_layers):
@@ -280,6 +280,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="before the steps, run 4 plain copy kernels of 1 GiB (read 1 GiB, write 1 GiB each): "
                          "the known-size dispatches that scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--reduce-delay-us", type=int, default=0,
+                    help="emulated all-reduce latency in front of every reduce (selects the per-operation schedule)")
     ap.add_argument("--no-fused", action="store_true", help="one kernel per operation instead of the fused decode launches")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -90,6 +90,7 @@ struct ladder_ctx {
   std::vector<FusedArgs> fused_plan;
   int fused_plan_batch = 0;
   int n_cu = 256;                 // compute units of the device (workgroup slots of a fused launch = 2 per CU)
+  int wall_khz = 100000;          // rate of the device's wall clock (delay_kernel)
   const char* fused_plan_peers = nullptr;
   int pos = 0, batch = 0;
   std::string err;
@@ -188,6 +189,7 @@ int check_config(const ladder_config* g, std::string& why) {
   if (g->max_tokens > g->max_seq) { why = "max_tokens exceeds max_seq"; return LADDER_E_SHAPE; }
   if ((g->decode_graph != 0 && g->decode_graph != 1) || (g->overlap_modules != 0 && g->overlap_modules != 1)) { why = "decode_graph / overlap_modules must be 0 or 1"; return LADDER_E_ARG; }
   if (g->decode_fused != 0 && g->decode_fused != 1) { why = "decode_fused must be 0 or 1"; return LADDER_E_ARG; }
+  if (g->reduce_delay_us < 0 || g->reduce_delay_us > 10000) { why = "reduce_delay_us must be in 0 .. 10000"; return LADDER_E_ARG; }
   if (g->peer_pool < 0 || g->peer_rows < 0) { why = "peer_pool / peer_rows negative"; return LADDER_E_ARG; }
   if (g->tp_degree > g->n_real_shards && g->peer_pool > 0 && g->peer_rows <= 0) { why = "peer_rows must be positive when peers are used"; return LADDER_E_SHAPE; }
   if ((long long)g->max_batch * g->max_tokens > (1ll << 24)) { why = "max_batch * max_tokens too large"; return LADDER_E_SHAPE; }
@@ -334,6 +336,17 @@ int run_module(ladder_ctx* c, int m, int B, int T, int pos0, hipStream_t s, int*
 
 // reduce(m): x += partial sums of module m (+ peers); emit the normed inputs of the modules that read x_m.
 // m == 0: x = emb, emit inputs of the modules that read x_0.
+// Timed wait standing in for the latency of a collective: one wavefront polls the constant-rate wall
+// clock until `ticks` have passed.  Bounded: it also leaves after a fixed number of polls (each poll
+// sleeps ~0.2 us, 2^20 polls ~ 0.2 s), so the kernel ends whatever the clock does.
+__global__ __launch_bounds__(64) void delay_kernel(unsigned long long ticks) {
+  const unsigned long long t0 = wall_clock64();
+  for (int i = 0; i < (1 << 20); ++i) {
+    if (wall_clock64() - t0 >= ticks) break;
+    __builtin_amdgcn_s_sleep(8);
+  }
+}
+
 int run_reduce(ladder_ctx* c, int m, int rows, int n_slots, const void* emb, float* x_out, hipStream_t s) {
   const ladder_config& g = c->cfg;
   ReduceNormArgs a{};
@@ -360,6 +373,13 @@ int run_reduce(ladder_ctx* c, int m, int rows, int n_slots, const void* emb, flo
     else { a.out_b = out; a.gain_b = gain; }
   }
   a.x_out = x_out;
+  if (m > 0 && g.reduce_delay_us > 0) {   // the emulated collective takes this long before its result is there
+    const unsigned long long ticks = (unsigned long long)g.reduce_delay_us * (unsigned long long)c->wall_khz / 1000ull;
+    HIP_TRY(c, timed(c, LADDER_K_OTHER, s, [&] {
+      hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(64), 0, s, ticks);
+      return hipGetLastError();
+    }));
+  }
   HIP_TRY(c, timed(c, LADDER_K_REDUCE_NORM, s, [&] { return launch_reduce_norm(a, c->bf16, s); }));
   return LADDER_OK;
 }
@@ -424,7 +444,7 @@ __global__ void inc_pos_kernel(int* p) { *p += 1; }
 // ---------------------------------------------------------------------------------------------
 bool fused_usable(const ladder_ctx* c) {
   const ladder_config& g = c->cfg;
-  return c->fast && g.decode_fused != 0 && g.n_real_shards == 1 && g.max_batch <= 16 && g.max_seq <= 65536 &&
+  return c->fast && g.decode_fused != 0 && g.reduce_delay_us == 0 && g.n_real_shards == 1 && g.max_batch <= 16 && g.max_seq <= 65536 &&
          g.hidden % 32 == 0;
 }
 
@@ -737,6 +757,11 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
     }                                                                                        \
   } while (0)
 
+  {
+    int dev_id = 0, khz = 0;
+    INIT_HIP(hipGetDevice(&dev_id));
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev_id) == hipSuccess && khz > 0) c->wall_khz = khz;
+  }
   INIT_HIP(hipStreamCreateWithFlags(&c->s_attn, hipStreamNonBlocking));
   INIT_HIP(hipStreamCreateWithFlags(&c->s_mlp, hipStreamNonBlocking));
   INIT_HIP(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));

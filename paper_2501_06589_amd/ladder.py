@@ -28,7 +28,8 @@ class ladder_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "inter", "tp_degree", "n_real_shards",
         "max_batch", "max_seq", "max_tokens", "dtype", "wiring", "n_standard_layers", "reduce_on_side_stream",
-        "peer_pool", "peer_rows", "kernel_path", "overlap_modules", "decode_graph", "decode_fused")] + [("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+        "peer_pool", "peer_rows", "kernel_path", "overlap_modules", "decode_graph", "decode_fused",
+        "reduce_delay_us")] + [("rms_eps", C.c_float), ("rope_theta", C.c_float)]
 
 
 class ladder_layer_weights(C.Structure):
@@ -85,7 +86,8 @@ def make_config(**kw) -> ladder_config:
     cfg = ladder_config()
     defaults = dict(tp_degree=1, n_real_shards=1, dtype=LADDER_BF16, wiring=LADDER_WIRING_LADDER,
                     n_standard_layers=0, reduce_on_side_stream=1, peer_pool=0, peer_rows=0,
-                    kernel_path=LADDER_PATH_AUTO, overlap_modules=1, decode_graph=0, decode_fused=1, rms_eps=1e-5, rope_theta=1e4)
+                    kernel_path=LADDER_PATH_AUTO, overlap_modules=1, decode_graph=0, decode_fused=1, reduce_delay_us=0,
+                    rms_eps=1e-5, rope_theta=1e4)
     defaults.update(kw)
     known = {n for n, _ in ladder_config._fields_}
     for k, v in defaults.items():

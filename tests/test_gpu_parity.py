@@ -174,6 +174,31 @@ def test_graph_decode_after_prefill_matches_oracle(harness):
     assert max(res.errs) < TOL_BF16, res.errs
 
 
+def test_emulated_reduce_latency_changes_time_not_results(harness):
+    """A timed wait in front of every reduce (the stand-in for a collective's latency): same bits, and under
+    the standard wiring, where nothing can overlap it, a call lasts at least 2N waits longer."""
+    import time
+    w = SMALL_BF16.with_(name="small_bf16_delay", n_layers=3, decode_steps=2)
+    ref = harness.run_case(w, gpu_only=True, decode_fused=0)
+    got = harness.run_case(w, gpu_only=True, decode_fused=1, reduce_delay_us=300)   # the delay selects the per-operation schedule
+    for x, y in zip(ref.gpu, got.gpu):
+        assert np.array_equal(x, y)
+    tensors = harness.make_tensors(w)
+    def decode_ms(delay):
+        ctx = harness.build_gpu(w, tensors, None, wiring=ladder.LADDER_WIRING_STANDARD, reduce_delay_us=delay)
+        ctx.prefill(inputs.embeddings(w, w.batch, w.prefill, inputs.SEED_PREFILL).to("cuda:0"))
+        x = inputs.embeddings(w, w.batch, 1, inputs.SEED_DECODE0)[:, 0].contiguous().to("cuda:0")
+        ctx.decode_step(x)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ctx.decode_step(x)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) * 1e3
+        ctx.free()
+        return dt
+    assert decode_ms(300) - decode_ms(0) > 0.8 * 6 * 0.3
+
+
 # ---- fused decode launches ----------------------------------------------------------------------
 R8_SMALL = inputs.WORKLOADS["70b_r8_decode"].with_(name="r8_small", n_layers=3, hidden=512, inter=448, batch=4,
                                                    decode_steps=6)
