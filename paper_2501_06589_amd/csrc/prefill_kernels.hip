@@ -47,9 +47,18 @@ __global__ __launch_bounds__(256, MIN_WAVES) void gemm_mfma_kernel(GemmArgs a) {
   const int b = lane & 15, q = lane >> 4;
   const int KT = a.K >> 5, NT = a.N >> 4;
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + 255) / 256;
+  // Workgroups are handed to the 8 XCDs round robin by block index and every XCD has its own L2: block
+  // index i is mapped to position (i % 8) * (n / 8) + i / 8 of the tile order, so that each XCD works
+  // through one contiguous eighth of it and neighbours in the order (which share operands) meet in one L2.
+#ifndef GEMM_NO_XCD_REMAP
+  const int nblk = gridDim.x, nblk8 = nblk & ~7;
+  const int bid = (int)blockIdx.x < nblk8 ? ((int)blockIdx.x & 7) * (nblk8 >> 3) + ((int)blockIdx.x >> 3) : (int)blockIdx.x;
+#else
+  const int bid = blockIdx.x;
+#endif
   // grouped rasterisation: GROUP_M row blocks share one column block back to back
   const int per_group = GEMM_GROUP_M * tiles_n;
-  const int group = blockIdx.x / per_group, in_group = blockIdx.x % per_group;
+  const int group = bid / per_group, in_group = bid % per_group;
   const int gm = min(GEMM_GROUP_M, tiles_m - group * GEMM_GROUP_M);
   const int m_blk = group * GEMM_GROUP_M + in_group % gm;
   const int n_blk = in_group / gm;
@@ -127,6 +136,8 @@ __global__ __launch_bounds__(256, MIN_WAVES) void gemm_mfma_kernel(GemmArgs a) {
     store_x(0);
     __syncthreads();
   }
+
+#endif
 
   if (a.epilogue == 0) {
 #pragma unroll
