@@ -137,8 +137,6 @@ __global__ __launch_bounds__(256, MIN_WAVES) void gemm_mfma_kernel(GemmArgs a) {
     __syncthreads();
   }
 
-#endif
-
   if (a.epilogue == 0) {
 #pragma unroll
     for (int mt = 0; mt < WM; ++mt) {
