@@ -5,8 +5,8 @@
 // layer l and the attention-side work around them have no dependency on each other: putting them
 // into ONE launch keeps HBM streaming while the small, latency-bound attention work runs, with no
 // stream, event or graph edge in between.  A decode step is three launches per layer:
-//     { attention_l , gate/up_l first half (+ RMSNorm, SwiGLU) }
-//     { gate/up_l second half , o_l (+ residual add) }
+//     { attention_l , gate/up_l (+ RMSNorm, SwiGLU) }
+//     { o_l (+ residual add) }
 //     { qkv_{l+1} (+ RMSNorm, rotary, cache append) , down_l (+ residual add) }
 // Everything that used to be a kernel of its own is an epilogue or a prologue here, and none of it
 // needs one workgroup to talk to another (a device-wide release fence per workgroup was measured to

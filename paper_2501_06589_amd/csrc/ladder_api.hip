@@ -496,18 +496,6 @@ void build_fused_plan(ladder_ctx* c, int B) {
     j.n_groups = 2 * I / 16; j.epi = EPI_SWIGLU; j.act = (bf16_t*)c->act;
     return j;
   };
-  // the gate/up projection cut in two column ranges (it is the largest stream and depends on nothing
-  // recent, so a half of it rides along with each of the two launches that would otherwise be short;
-  // on the 70B-shard shape any cut that leaves at most one whole-K workgroup per CU in both launches,
-  // 46 % - 52 %, measured the same)
-  const int gu_groups = 2 * I / 16;
-  const int gu_first = std::max(1, gu_groups / 2);
-  auto job_gu_part = [&](int l, int src, int part) {
-    GemvJob j = job_gu(l, src);
-    if (part == 0) { j.group0 = 0; j.n_groups = gu_first; }
-    else { j.group0 = gu_first; j.n_groups = gu_groups - gu_first; }
-    return j;
-  };
   auto job_dn = [&](int l, int m) {
     GemvJob j{};
     j.xb = (const bf16_t*)c->act; j.ldx = I; j.wp = layer(l).pd; j.M = B; j.K = I;
@@ -571,15 +559,17 @@ void build_fused_plan(ladder_ctx* c, int B) {
   plan.clear();
   const bool all_ladder = g.wiring == LADDER_WIRING_LADDER && g.n_standard_layers == 0;
   if (all_ladder) {
-    // modules 1 and 2 both read x_0; then three launches per layer, each pairing work of the two module
-    // chains that does not depend on each other:
-    //     { attention_l , gate/up_l (first part) }     { gate/up_l (rest) , o_l }     { qkv_{l+1} , down_l }
-    // The attention workgroups are few and latency bound: beside the largest weight stream they cost nothing.
+    // modules 1 and 2 both read x_0; then three launches per layer:
+    //     { attention_l , gate/up_l }     { o_l }     { qkv_{l+1} , down_l }
+    // Attention and gate/up, and the next layer's QKV and down, do not depend on each other under the
+    // ladder wiring.  The attention workgroups are few and latency bound: beside the largest weight stream
+    // they cost nothing.  (Cutting gate/up so that a part rides beside o_l measured 2 % slower in halves and
+    // up to 10 % slower for uneven cuts, which leave some CUs with two whole-K workgroups and others with one.)
     plan.push_back(one(job_qkv(1, 0)));
     for (int l = 1; l <= N; ++l) {
-      GemvJob gu_a = job_gu_part(l, 2 * l - 2, 0);
-      plan.push_back(att(l, &gu_a));
-      plan.push_back(two(job_gu_part(l, 2 * l - 2, 1), job_o(l, 2 * l - 1)));
+      GemvJob gu = job_gu(l, 2 * l - 2);
+      plan.push_back(att(l, &gu));
+      plan.push_back(one(job_o(l, 2 * l - 1)));
       if (l < N) plan.push_back(qkv_down(job_qkv(l + 1, 2 * l - 1), job_dn(l, 2 * l)));
       else plan.push_back(one(job_dn(N, 2 * N)));
     }
