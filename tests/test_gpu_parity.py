@@ -233,7 +233,7 @@ def test_fused_decode_other_geometries(harness):
     assert max(res.errs) < TOL_BF16, res.errs
 
 
-# ---- BASELINE sizes, in the launch configuration bench.py times ----------------------------------
+# ---- full sizes of the headline workloads, in the launch configuration bench.py times ----------------
 # bf16 matrix-core operands are rounded (unit roundoff 2^-9): every module output carries an error of
 # about 0.3 - 0.4 % of its own RMS, independent from module to module, so the error of x_2N relative to
 # its RMS grows like sqrt(2N) (measured at full width: 0.41 % rms at 4 modules, 2.7 % at 160; max over
