@@ -213,3 +213,31 @@ def kv_cache(w: Workload, layer: int, shard: int, batch: int, tokens: int, devic
     shp = (batch, w.n_kv_heads, tokens, w.head_dim)
     return [normal(seed, tensor_id(layer, shard, kind), shp, dtype=w.torch_dtype, device=device)
             for kind in (KV_K, KV_V)]
+
+
+# ---- generation head (token embedding, final norm, output projection) ---------------------------
+SEED_HEAD = 300
+SEED_PROMPT = 400
+HEAD_TABLE, HEAD_GAIN, HEAD_WLM = 1, 2, 3
+
+
+def head_weights(w: Workload, vocab: int, vocab_local: Optional[int] = None, shard: int = 0, device="cpu",
+                 seed: int = SEED_HEAD) -> Dict[str, torch.Tensor]:
+    """Token embedding table [vocab, hidden] ~ N(0,1), final norm gain [hidden] ~ 1 + 0.02 N(0,1) and this
+    rank's slice of the output projection [hidden, vocab_local] ~ N(0, 0.02^2) (vocabulary-parallel split:
+    rank `shard` owns columns shard * vocab_local ...)."""
+    dt = w.torch_dtype
+    vl = vocab if vocab_local is None else vocab_local
+    return {
+        "table": normal(seed, HEAD_TABLE, (vocab, w.hidden), dtype=dt, device=device),
+        "final_norm": normal(seed, HEAD_GAIN, (w.hidden,), std=0.02, mean=1.0, dtype=dt, device=device),
+        "w_lm": normal(seed, tensor_id(0, shard, HEAD_WLM), (w.hidden, vl), std=0.02, dtype=dt, device=device),
+    }
+
+
+def prompt_tokens(batch: int, tokens: int, vocab: int, device="cpu", seed: int = SEED_PROMPT) -> torch.Tensor:
+    """Seeded token ids [batch, tokens], int32, uniform over the vocabulary (from the same counter hash)."""
+    u = normal(seed, 0, (batch, tokens), dtype=torch.float64, device=device)
+    # the normal deviate's CDF is uniform: Phi(u) in (0, 1)
+    p = 0.5 * (1.0 + torch.erf(u / 2.0 ** 0.5))
+    return torch.clamp((p * vocab).to(torch.int64), 0, vocab - 1).to(torch.int32)
