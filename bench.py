@@ -144,13 +144,30 @@ def run_decode(args):
             ctx.calibration_copy(dst, src)    # calibration_copy_kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del src, dst
+    head_vocab, toks = None, None
+    if args.head:
+        vocab = 128256 if w.hidden >= 4096 else 32000          # Llama-3 / Llama-2 vocabulary sizes
+        head_vocab = (vocab, vocab // w.tp_degree)
+        hw = inputs.head_weights(w, vocab, vocab // w.tp_degree, device=dev)
+        ctx.load_head(hw["table"], hw["final_norm"], hw["w_lm"])
+        toks = inputs.prompt_tokens(w.batch, 1, vocab, dev)[:, 0].contiguous()
+        del hw
+
+    def step(i):
+        nonlocal toks
+        if args.head:
+            ctx.decode_step(ctx.embed(toks), out)
+            toks = ctx.head(out, want_logits=False)[1]
+        else:
+            ctx.decode_step(xs[i], out)
+
     for i in range(args.warmup):
-        ctx.decode_step(xs[i], out)
+        step(i)
     torch.cuda.synchronize()
     pos_start = ctx.position()[0]
     t0 = time.perf_counter()
     for i in range(args.steps):
-        ctx.decode_step(xs[args.warmup + i], out)
+        step(args.warmup + i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     pos_end = ctx.position()[0]
@@ -197,7 +214,8 @@ def run_decode(args):
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": w.name, "n_layers": w.n_layers, "hidden": w.hidden, "n_q_heads": w.n_q_heads,
                    "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "inter": w.inter, "tp_degree": w.tp_degree,
-                   "batch": w.batch, "kv_positions": [pos_start, pos_end], "peers": w.n_peers},
+                   "batch": w.batch, "kv_positions": [pos_start, pos_end], "peers": w.n_peers,
+                   **({"head_vocab": head_vocab[0], "head_vocab_local": head_vocab[1]} if head_vocab else {})},
         "hbm": {"algorithmic_bytes_per_step": step_bytes, "weights": wb, "kv": kvb, "peers": pb,
                 "achieved_GBps_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9,
                 "frac_of_peak_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
@@ -282,6 +300,9 @@ def main():
                          "the known-size dispatches that scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--reduce-delay-us", type=int, default=0,
                     help="emulated all-reduce latency in front of every reduce (selects the per-operation schedule)")
+    ap.add_argument("--head", action="store_true",
+                    help="decode mode: generate for real (token embedding -> stack -> final norm + output projection of "
+                         "this rank's vocabulary slice -> greedy token, fed back); the metric is quoted without it")
     ap.add_argument("--no-fused", action="store_true", help="one kernel per operation instead of the fused decode launches")
     args = ap.parse_args()
     if args.gpus != 1:

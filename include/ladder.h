@@ -165,6 +165,36 @@ int ladder_decode_step(ladder_ctx* ctx, const void* x_in, void* x_out);
 /* Releases everything the context owns (synchronises its streams first).  NULL is a no-op. */
 void ladder_free(ladder_ctx* ctx);
 
+/* ---- generation head (Llama-3 architecture around the block stack; the paper's engine is a prefill
+ *      followed by token-by-token decoding, sections "Inference Implementation" and "Setup") ------
+ *
+ * ladder_load_head copies the token-embedding table, and copies / repacks this rank's slice of the
+ * output projection (split along the vocabulary, the rule of section "Tensor Parallelism Background"
+ * for a first matmul; on the bf16 streaming path the final norm's gain is folded into its rows):
+ *   table       device T [vocab][H]
+ *   final_norm  device T [H]             gain of the RMSNorm in front of the output projection
+ *   w_lm        device T [H][vocab_local]
+ * All three are caller-owned and may be freed afterwards.  Once per context (LADDER_E_STATE again).
+ * Errors: LADDER_E_ARG, LADDER_E_SHAPE (sizes), LADDER_E_HIP. */
+int ladder_load_head(ladder_ctx* ctx, const void* table, const void* final_norm, const void* w_lm, int32_t vocab,
+                     int32_t vocab_local);
+
+/* Token embedding: x_out[r][:] = table[tokens[r]][:].
+ *   tokens  device int32 [rows]  (ids outside [0, vocab) are clamped into the table)
+ *   x_out   device T [rows][H]   rows <= max_batch * max_tokens; ready to be x_in of ladder_prefill
+ *                                ([B][T][H], rows = B*T) or ladder_decode_step ([B][H]).
+ * Enqueued on the caller's stream.  Errors: LADDER_E_ARG, LADDER_E_STATE (head not loaded), LADDER_E_SHAPE. */
+int ladder_embed(ladder_ctx* ctx, const int32_t* tokens, int32_t rows, void* x_out);
+
+/* Final RMSNorm + output projection + greedy sampling for one position per sequence:
+ * logits = rmsnorm(x, final_norm) . w_lm, token = index of the largest logit of this rank's slice
+ * (lowest index among equal maxima; the index is local to the slice).
+ *   x           device f32 [rows][H]    rows of x_2N (rows <= max_batch)
+ *   logits_out  device f32 [rows][vocab_local], or NULL
+ *   tokens_out  device int32 [rows], or NULL (not both NULL)
+ * Enqueued on the caller's stream.  Errors: LADDER_E_ARG, LADDER_E_STATE (head not loaded), LADDER_E_SHAPE. */
+int ladder_head(ladder_ctx* ctx, const float* x, int32_t rows, float* logits_out, int32_t* tokens_out);
+
 /* ---- helpers ---------------------------------------------------------------------------- */
 
 /* Text of the last error of this context (or of the last failed ladder_init when ctx is NULL).

@@ -96,6 +96,16 @@ hipError_t launch_attn_generic(const AttnGenericArgs& a, bool is_bf16, hipStream
 // act[m][i] (T) = silu(gu[m][i]) * gu[m][I + i];  gu: f32 [M][2I]
 hipError_t launch_swiglu(const float* gu, void* act, int M, int I, bool is_bf16, hipStream_t s);
 
+// ---- generation head ----------------------------------------------------------------------------
+// x_out[r][:] = table[tokens[r]][:]  (T [rows][H]); ids outside [0, vocab) are clamped into the table
+hipError_t launch_embed_gather(const int* tokens, const void* table, void* x_out, int rows, int H, int vocab,
+                               bool is_bf16, hipStream_t s);
+// y[r][:] = x[r][:] / sqrt(mean(x[r]^2) + eps) * gain   (gain may be null: folded into the projection); y: T
+hipError_t launch_head_norm(const float* x, const void* gain, void* y, int rows, int H, float eps, bool is_bf16,
+                            hipStream_t s);
+// tokens_out[r] = index of the largest of logits[r][0..V), the lowest index among equal maxima
+hipError_t launch_argmax(const float* logits, int* tokens_out, int rows, int V, hipStream_t s);
+
 // ---- bf16 streaming / MFMA path ----------------------------------------------------------------
 // Packed weight format ("tiles"): the [K][N] matrix is cut into tiles of 32 k x 16 n; tile (nt, kt)
 // is 1 KiB at ((nt*KT + kt)*64 + lane)*16 bytes, lane holding W[kt*32 + (lane/16)*8 + e][nt*16 + lane%16]

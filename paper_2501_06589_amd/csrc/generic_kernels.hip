@@ -315,3 +315,80 @@ hipError_t launch_load_kv(const void* k, const void* v, void* cache_k, void* cac
                        (float*)cache_k, (float*)cache_v, B, nkv, S, d, max_seq);
   return hipGetLastError();
 }
+
+// ------------------------------------------------------------------------------------------------
+// Generation head: token embedding (row gather), final RMSNorm, greedy sampling (first arg max).
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void embed_gather_kernel(const int* __restrict__ tokens, const T* __restrict__ table,
+                                                           T* __restrict__ out, int H, int vocab) {
+  const int r = blockIdx.x;
+  const int tok = min(max(tokens[r], 0), vocab - 1);
+  for (int i = threadIdx.x; i < H; i += 256) out[(size_t)r * H + i] = table[(size_t)tok * H + i];
+}
+
+hipError_t launch_embed_gather(const int* tokens, const void* table, void* x_out, int rows, int H, int vocab,
+                               bool is_bf16, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (is_bf16) hipLaunchKernelGGL(embed_gather_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, tokens, (const bf16_t*)table, (bf16_t*)x_out, H, vocab);
+  else hipLaunchKernelGGL(embed_gather_kernel<float>, dim3(rows), dim3(256), 0, s, tokens, (const float*)table, (float*)x_out, H, vocab);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void head_norm_kernel(const float* __restrict__ x, const T* __restrict__ gain,
+                                                        T* __restrict__ y, int H, float eps) {
+  __shared__ float part[4];
+  const float* xr = x + (size_t)blockIdx.x * H;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < H; i += 256) ss = fmaf(xr[i], xr[i], ss);
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float rs = 1.0f / sqrtf((part[0] + part[1] + part[2] + part[3]) / (float)H + eps);
+  for (int i = threadIdx.x; i < H; i += 256)
+    store_f(y + (size_t)blockIdx.x * H + i, xr[i] * rs * (gain ? load_f(gain + i) : 1.0f));
+}
+
+hipError_t launch_head_norm(const float* x, const void* gain, void* y, int rows, int H, float eps, bool is_bf16,
+                            hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (is_bf16) hipLaunchKernelGGL(head_norm_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, x, (const bf16_t*)gain, (bf16_t*)y, H, eps);
+  else hipLaunchKernelGGL(head_norm_kernel<float>, dim3(rows), dim3(256), 0, s, x, (const float*)gain, (float*)y, H, eps);
+  return hipGetLastError();
+}
+
+// one workgroup per row; a thread keeps the first maximum of its strided share, the merge prefers the
+// lower index among equal values, so the result is the first arg max of the row
+__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int* __restrict__ out, int V) {
+  __shared__ float bv[256];
+  __shared__ int bi[256];
+  const float* lr = logits + (size_t)blockIdx.x * V;
+  float best = -INFINITY;
+  int at = 0x7fffffff;
+  for (int i = threadIdx.x; i < V; i += 256) {
+    const float v = lr[i];
+    if (v > best || at == 0x7fffffff) { best = v; at = i; }   // strictly greater: the earliest index stays
+  }
+  bv[threadIdx.x] = best;
+  bi[threadIdx.x] = at;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) {
+      const float ov = bv[threadIdx.x + w];
+      const int oi = bi[threadIdx.x + w];
+      if (oi != 0x7fffffff && (bi[threadIdx.x] == 0x7fffffff || ov > bv[threadIdx.x] || (ov == bv[threadIdx.x] && oi < bi[threadIdx.x]))) {
+        bv[threadIdx.x] = ov;
+        bi[threadIdx.x] = oi;
+      }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[blockIdx.x] = bi[0] == 0x7fffffff ? 0 : bi[0];
+}
+
+hipError_t launch_argmax(const float* logits, int* tokens_out, int rows, int V, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(argmax_kernel, dim3(rows), dim3(256), 0, s, logits, tokens_out, V);
+  return hipGetLastError();
+}

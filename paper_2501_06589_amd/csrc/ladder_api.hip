@@ -91,6 +91,15 @@ struct ladder_ctx {
   int fused_plan_batch = 0;
   int n_cu = 256;                 // compute units of the device (workgroup slots of a fused launch = 2 per CU)
   int wall_khz = 100000;          // rate of the device's wall clock (delay_kernel)
+  // generation head (ladder_load_head)
+  char* head_table = nullptr;     // T [vocab][H]
+  char* head_gain = nullptr;      // T [H] (plain path; the streaming path folds it into head_wp)
+  char* head_w = nullptr;         // plain path: T [H][vocab_local]
+  char* head_wp = nullptr;        // streaming path: packed tiles
+  char* head_y = nullptr;         // T [max_batch][H] normed rows
+  float* head_logits = nullptr;   // f32 [max_batch][vocab_local]
+  int vocab = 0, vocab_local = 0;
+  bool head_fast = false;
   const char* fused_plan_peers = nullptr;
   int pos = 0, batch = 0;
   std::string err;
@@ -1043,6 +1052,73 @@ int ladder_profile_read(ladder_ctx* c, int32_t cls, int64_t* launches, double* t
   if (rc) return rc;
   if (launches) *launches = c->prof_n[cls];
   if (total_ms) *total_ms = c->prof_ms[cls];
+  return LADDER_OK;
+}
+
+int ladder_load_head(ladder_ctx* c, const void* table, const void* final_norm, const void* w_lm, int32_t vocab,
+                     int32_t vocab_local) {
+  if (!c) return LADDER_E_ARG;
+  if (!table || !final_norm || !w_lm) return fail(c, LADDER_E_ARG, "null table / final_norm / w_lm");
+  if (vocab <= 0 || vocab_local <= 0 || vocab_local > vocab) return fail(c, LADDER_E_SHAPE, "vocab sizes out of range");
+  if (c->head_table) return fail(c, LADDER_E_STATE, "the head is already loaded");
+  const ladder_config& g = c->cfg;
+  const int H = g.hidden;
+  const size_t esz = c->esz;
+  int rc;
+  if ((rc = dev_alloc(c, (void**)&c->head_table, (size_t)vocab * H * esz, false))) return rc;
+  if ((rc = dev_alloc(c, (void**)&c->head_y, (size_t)g.max_batch * H * esz, false))) return rc;
+  if ((rc = dev_alloc(c, (void**)&c->head_logits, (size_t)g.max_batch * vocab_local * 4, false))) return rc;
+  HIP_TRY(c, hipMemcpyAsync(c->head_table, table, (size_t)vocab * H * esz, hipMemcpyDeviceToDevice, c->main));
+  c->head_fast = c->fast && vocab_local % 16 == 0;
+  if (c->head_fast) {   // packed tiles with the final norm's gain folded into the rows, as for the block projections
+    if ((rc = dev_alloc(c, (void**)&c->head_wp, (size_t)H * vocab_local * 2, false))) return rc;
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w_lm, c->head_wp, H, vocab_local, vocab_local, 0, 0,
+                                   (const bf16_t*)final_norm, c->main));
+  } else {
+    if ((rc = dev_alloc(c, (void**)&c->head_w, (size_t)H * vocab_local * esz, false))) return rc;
+    if ((rc = dev_alloc(c, (void**)&c->head_gain, (size_t)H * esz, false))) return rc;
+    HIP_TRY(c, hipMemcpyAsync(c->head_w, w_lm, (size_t)H * vocab_local * esz, hipMemcpyDeviceToDevice, c->main));
+    HIP_TRY(c, hipMemcpyAsync(c->head_gain, final_norm, (size_t)H * esz, hipMemcpyDeviceToDevice, c->main));
+  }
+  c->vocab = vocab;
+  c->vocab_local = vocab_local;
+  return LADDER_OK;
+}
+
+int ladder_embed(ladder_ctx* c, const int32_t* tokens, int32_t rows, void* x_out) {
+  if (!c) return LADDER_E_ARG;
+  if (!tokens || !x_out) return fail(c, LADDER_E_ARG, "null tokens / x_out");
+  if (!c->head_table) return fail(c, LADDER_E_STATE, "the head is not loaded");
+  if (rows <= 0) return fail(c, LADDER_E_ARG, "rows must be positive");
+  if ((long long)rows > (long long)c->cfg.max_batch * c->cfg.max_tokens) return fail(c, LADDER_E_SHAPE, "rows exceed max_batch * max_tokens");
+  HIP_TRY(c, launch_embed_gather(tokens, c->head_table, x_out, rows, c->cfg.hidden, c->vocab, c->bf16, c->main));
+  return LADDER_OK;
+}
+
+int ladder_head(ladder_ctx* c, const float* x, int32_t rows, float* logits_out, int32_t* tokens_out) {
+  if (!c) return LADDER_E_ARG;
+  if (!x || (!logits_out && !tokens_out)) return fail(c, LADDER_E_ARG, "null x, or neither logits_out nor tokens_out");
+  if (!c->head_table) return fail(c, LADDER_E_STATE, "the head is not loaded");
+  if (rows <= 0) return fail(c, LADDER_E_ARG, "rows must be positive");
+  if (rows > c->cfg.max_batch) return fail(c, LADDER_E_SHAPE, "rows exceed max_batch (the head serves one position per sequence)");
+  const ladder_config& g = c->cfg;
+  const int H = g.hidden, V = c->vocab_local;
+  hipStream_t s = c->main;
+  float* logits = logits_out ? logits_out : c->head_logits;
+  HIP_TRY(c, launch_head_norm(x, c->head_fast ? nullptr : c->head_gain, c->head_y, rows, H, g.rms_eps, c->bf16, s));
+  if (!c->head_fast) {
+    HIP_TRY(c, launch_gemm_generic(c->head_y, c->head_w, logits, rows, V, H, V, 0, c->bf16, s));
+  } else if (rows <= 64) {
+    GemvArgs a{};
+    a.x = (const bf16_t*)c->head_y; a.ldx = H; a.wp = c->head_wp; a.M = rows; a.K = H; a.N = V; a.ksplit = 1;
+    a.out = logits; a.out_stride = (size_t)rows * V; a.slot0 = 0; a.epilogue = 0;
+    HIP_TRY(c, launch_gemv(a, s));
+  } else {
+    GemmArgs a{};
+    a.x = (const bf16_t*)c->head_y; a.ldx = H; a.wp = c->head_wp; a.M = rows; a.K = H; a.N = V; a.out = logits; a.epilogue = 0;
+    HIP_TRY(c, launch_gemm_mfma(a, s));
+  }
+  if (tokens_out) HIP_TRY(c, launch_argmax(logits, tokens_out, rows, V, s));
   return LADDER_OK;
 }
 

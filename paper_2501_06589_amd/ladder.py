@@ -52,6 +52,9 @@ EXPORTS = {
     "ladder_profile_read": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
     "ladder_profile_reset": (C.c_int, [C.c_void_p]),
     "ladder_calibration_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
+    "ladder_load_head": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]),
+    "ladder_embed": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
+    "ladder_head": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
 }
 
 _lib = None
@@ -188,6 +191,35 @@ class Ladder:
         self._want("x_out", x_out, max(batch, 1) * self.cfg.hidden, storage=False)
         self._check(self._lib.ladder_decode_step(self._h, _ptr(x_in), _ptr(x_out)))
         return x_out
+
+    # -- generation head
+    def load_head(self, table, final_norm, w_lm):
+        vocab, vocab_local = table.shape[0], w_lm.shape[1]
+        self._want("table", table, vocab * self.cfg.hidden)
+        self._want("final_norm", final_norm, self.cfg.hidden)
+        self._want("w_lm", w_lm, self.cfg.hidden * vocab_local)
+        self._check(self._lib.ladder_load_head(self._h, _ptr(table), _ptr(final_norm), _ptr(w_lm), vocab, vocab_local))
+        self._vocab_local = vocab_local
+
+    def embed(self, tokens):
+        """tokens: int32 device tensor of any shape [...]; returns the embeddings [..., H] in the storage type."""
+        import torch
+        if not tokens.is_cuda or not tokens.is_contiguous() or tokens.dtype != torch.int32:
+            raise ValueError("tokens: need a contiguous int32 device tensor")
+        dt = torch.float32 if self.cfg.dtype == LADDER_FP32 else torch.bfloat16
+        out = torch.empty(tuple(tokens.shape) + (self.cfg.hidden,), dtype=dt, device=tokens.device)
+        self._check(self._lib.ladder_embed(self._h, _ptr(tokens), tokens.numel(), _ptr(out)))
+        return out
+
+    def head(self, x, want_logits=True):
+        """x: f32 device [rows][H]; returns (logits f32 [rows][vocab_local] or None, tokens int32 [rows])."""
+        import torch
+        rows = x.shape[0]
+        self._want("x", x, rows * self.cfg.hidden, storage=False)
+        logits = torch.empty((rows, self._vocab_local), dtype=torch.float32, device=x.device) if want_logits else None
+        toks = torch.empty((rows,), dtype=torch.int32, device=x.device)
+        self._check(self._lib.ladder_head(self._h, _ptr(x), rows, _ptr(logits), _ptr(toks)))
+        return logits, toks
 
     def position(self) -> Tuple[int, int]:
         p, b = C.c_int32(), C.c_int32()
