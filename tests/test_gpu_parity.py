@@ -302,3 +302,27 @@ def test_full_width_70b_r4_prefill_against_oracle(harness):
     w = w.with_(name="70b_r4_prefill_b2_l4", n_layers=4)
     res = harness.run_case(w, gen_device="cuda:0")
     deep_stack_check(res, w.n_layers)
+
+
+def test_seeded_shape_sweep(harness):
+    """A fixed pseudo-random walk over shapes and switches (head size 64 / 128, 1 - 3 kv heads with 1 - 8 q
+    heads each, ragged hidden / intermediate sizes incl. ones that fall back to the plain kernels, batch
+    1 - 16, cache lengths around the attention block and split boundaries, prompts below and above 64 rows,
+    ladder / standard / hybrid wiring, graph replay on or off), each against the oracle."""
+    import random
+    rng = random.Random(1234)
+    base = inputs.WORKLOADS["70b_r8_decode"]
+    for trial in range(12):
+        d = rng.choice([64, 128])
+        nkv = rng.choice([1, 2, 3])
+        g = rng.choice([1, 2, 4, 8])
+        kv = rng.choice([0, 1, 31, 32, 33, 255, 256, 257, 600, 1100])
+        n_layers = rng.randint(1, 4)
+        wiring = rng.choice([ladder.LADDER_WIRING_LADDER, ladder.LADDER_WIRING_LADDER, ladder.LADDER_WIRING_STANDARD])
+        w = base.with_(name=f"sweep{trial}", n_layers=n_layers, hidden=32 * rng.randint(4, 24), n_q_heads=nkv * g,
+                       n_kv_heads=nkv, head_dim=d, inter=16 * rng.randint(5, 40), tp_degree=rng.choice([1, 2, 4, 8]),
+                       n_real_shards=1, batch=rng.randint(1, 16), prefill=0 if kv else rng.choice([1, 5, 40, 64, 65, 130, 300]),
+                       kv_preload=kv, decode_steps=rng.randint(1, 5), peer_pool=rng.choice([1, 2, 3]))
+        nstd = rng.choice([0, 0, 1]) if wiring == ladder.LADDER_WIRING_LADDER and n_layers > 1 else 0
+        res = harness.run_case(w, kv_preload=kv, wiring=wiring, n_standard_layers=nstd, decode_graph=rng.choice([0, 1]))
+        assert max(res.errs) < TOL_BF16, (trial, res.errs)
