@@ -118,6 +118,8 @@ def run_decode(args):
         w = w.with_(n_layers=args.layers)
     if args.batch:
         w = w.with_(batch=args.batch)
+    if args.kv and w.kv_preload:
+        w = w.with_(kv_preload=args.kv)
     dev = "cuda:0"
     prof_steps = 8
     total_steps = args.warmup + args.steps + prof_steps
@@ -287,6 +289,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--mode", choices=["decode", "prefill"], default="decode")
     ap.add_argument("--workload", default=None)
+    ap.add_argument("--kv", type=int, default=0, help="override the preloaded cache length of a decode workload")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (1.2b / 8b are quoted at 1, 4, 16)")
     ap.add_argument("--layers", type=int, default=0, help="debug: truncate the stack (result is then not the metric)")
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers of the oracle's timed sample")

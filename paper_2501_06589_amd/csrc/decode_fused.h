@@ -18,6 +18,10 @@ struct GemvJob {
   float eps;
   const void* wp;
   int M, K, N;
+  // wait_on != null: the job's x operand is produced by the attention job of the SAME launch; the
+  // workgroup starts by waiting (bounded) until *wait_on has reached wait_target, then acquires
+  const unsigned* wait_on;
+  unsigned wait_target;
   int tn;                  // 16-column tiles per workgroup: 1 (0 means 1) or 2
   int group0, n_groups;    // this job's workgroups own the tile groups [group0, group0 + n_groups), tn tiles
                            // each; a projection may be cut over two launches
@@ -56,10 +60,12 @@ struct AttnJob {
   int B, nq, nkv, max_seq;
   int n_splits, split_len; // split s covers positions [s*split_len, (s+1)*split_len); split_len % 64 == 0
   const int* pos_dev;      // position of the new token; positions 0..*pos_dev are visible
+  unsigned* done;          // if non-null: incremented (after a release) by the workgroup that has written the final
+                           // output of its (sequence, kv head); a projection job of the same launch waits on it
 };
 
 #define FUSED_MAX_LDS_BYTES (72 * 1024)
-#define FUSED_MAX_JOBS 3
+#define FUSED_MAX_JOBS 4
 
 struct FusedArgs {
   int n_jobs;              // 1 .. FUSED_MAX_JOBS
@@ -74,5 +80,5 @@ hipError_t launch_fused_decode(const FusedArgs& fa, int d, int g, hipStream_t s,
 hipError_t fused_decode_prepare(int d, int g);   // once per context, before the first launch
 size_t fused_attn_lds_bytes(int d, int g);
 size_t fused_gemv_lds_bytes();
-hipError_t launch_embed(const bf16_t* emb, float* x0, bf16_t* xh0, int n, hipStream_t s, hipEvent_t ev0,
-                        hipEvent_t ev1);
+hipError_t launch_embed(const bf16_t* emb, float* x0, bf16_t* xh0, int n, unsigned* zero_words, int n_zero,
+                        hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);

@@ -27,6 +27,8 @@
 // All sums are taken in a fixed order, so results are bit-reproducible run to run.
 #include <hip/hip_ext.h>
 
+#include <algorithm>
+
 #include "common.h"
 #include "decode_fused.h"
 
@@ -59,7 +61,7 @@ __device__ __forceinline__ void unpack8f(const uint4 v, float f[8]) {
 // set by the workgroup with the most bytes: one tile per workgroup keeps the jobs of a launch even
 // and the number of streaming workgroups high.
 // ------------------------------------------------------------------------------------------------
-template <bool NORMED, int U, int TN>
+template <bool NORMED, int U, int TN, bool COH = false>
 __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
   constexpr int WAVES = FUSED_WAVES;
   const int grp = j.group0 + lb;
@@ -71,6 +73,21 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
   const int per_wave = (KT + WAVES - 1) / WAVES;
   const int kt0 = wave * per_wave;
   const int kt1 = min(KT, kt0 + per_wave);
+
+  if (j.wait_on) {
+    // The x operand comes from the attention job of this launch.  Its workgroups have lower block indices,
+    // so they were dispatched before this one and wait for nothing: the counter always arrives.  The wait is
+    // bounded all the same (about a second), so that the kernel ends whatever happens.
+    if (tid == 0) {
+      for (int spin = 0; spin < (1 << 20); ++spin) {
+        if (__hip_atomic_load(j.wait_on, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= j.wait_target) break;
+        __builtin_amdgcn_s_sleep(16);
+      }
+    }
+    __syncthreads();   // (workgroup-scope ordering; the operand itself is read with device-coherent loads, so no
+                       // cache invalidation is needed: an agent-scope acquire per workgroup would flush the L2
+                       // under the weight streams that run beside)
+  }
 
   f32x4_t acc[TN];
 #pragma unroll
@@ -89,7 +106,14 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
       const int ktc = min(kt + u, kt1 - 1);
 #pragma unroll
       for (int t = 0; t < TN; ++t) wv[t][u] = __builtin_nontemporal_load(wptr + ((size_t)t * KT + ktc) * 64);
-      xv[u] = *reinterpret_cast<const u32x4_t*>(xbp + (size_t)ktc * 32);
+      if (COH) {   // operand written by another workgroup of this launch: device-coherent loads, past L1 and the XCD's L2
+        const unsigned long long* p8 = reinterpret_cast<const unsigned long long*>(xbp + (size_t)ktc * 32);
+        const unsigned long long lo = __hip_atomic_load(p8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long hi = __hip_atomic_load(p8 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        xv[u] = (u32x4_t){(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
+      } else {
+        xv[u] = *reinterpret_cast<const u32x4_t*>(xbp + (size_t)ktc * 32);
+      }
     }
   };
   auto fma = [&](const u32x4_t (&wv)[TN][U], const u32x4_t (&xv)[U], int kt) {
@@ -251,6 +275,17 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
 // The 8 wavefronts take the 32-key blocks of the split round robin, each with its own running
 // softmax and no barrier in the loop; they merge once, through LDS, at the end.
 // ------------------------------------------------------------------------------------------------
+// The workgroup has stored the final attention output of its (sequence, kv head): make it visible to the
+// device and count it, for the projection job of the same launch that consumes it.
+__device__ __forceinline__ void attn_signal_done(const AttnJob& a) {
+  if (!a.done) return;
+  __syncthreads();   // every thread's stores are issued
+  if (threadIdx.x == 0) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    atomicAdd(a.done, 1u);
+  }
+}
+
 template <int D, int G>
 __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag) {
   constexpr int DS = D / 32, DT = D / 16;
@@ -375,7 +410,10 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
       }
     }
   }
-  if (a.n_splits == 1) return;
+  if (a.n_splits == 1) {
+    attn_signal_done(a);
+    return;
+  }
 
   // several splits: the last one to arrive merges them (fixed order)
   const int n_active = min(a.n_splits, (n_pos + a.split_len - 1) / a.split_len);
@@ -421,6 +459,7 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
     }
     a.o[(size_t)bi * a.nq * D + (size_t)kvh * G * D + i] = f32_to_bf16(o / l);
   }
+  attn_signal_done(a);
 }
 
 #ifdef FUSED_TRACE
@@ -460,7 +499,10 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(FusedArg
     attn_job<D, G>(fa.a, lb, smem, &s_flag);
   } else {
     const GemvJob& j = fa.g[job];
-    if (j.tn == 2) {
+    if (j.wait_on) {   // (the plan gives only the un-normed O projection a wait)
+      if (j.tn == 2) gemv_job<false, FUSED_U / 2, 2, true>(j, lb, smem);
+      else gemv_job<false, FUSED_U, 1, true>(j, lb, smem);
+    } else if (j.tn == 2) {
       if (j.normed) gemv_job<true, FUSED_U / 2, 2>(j, lb, smem);
       else gemv_job<false, FUSED_U / 2, 2>(j, lb, smem);
     } else {
@@ -471,20 +513,23 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(FusedArg
 }
 
 // x_0 = embeddings: fp32 for the residual chain, bf16 copy for the projections
+// (also clears the step's arrival counters: a fill kernel, not a memset node, so that a captured step replays)
 __global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ emb, float* __restrict__ x0,
-                                                    bf16_t* __restrict__ xh0, int n) {
+                                                    bf16_t* __restrict__ xh0, int n, unsigned* __restrict__ zero_words,
+                                                    int n_zero) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < n) {
     x0[i] = bf16_to_f32(emb[i]);
     xh0[i] = emb[i];
   }
+  if (i < n_zero) zero_words[i] = 0u;
 }
 
-hipError_t launch_embed(const bf16_t* emb, float* x0, bf16_t* xh0, int n, hipStream_t s, hipEvent_t ev0,
-                        hipEvent_t ev1) {
-  const dim3 grid((n + 255) / 256), block(256);
-  if (ev0 || ev1) hipExtLaunchKernelGGL(embed_kernel, grid, block, 0, s, ev0, ev1, 0, emb, x0, xh0, n);
-  else hipLaunchKernelGGL(embed_kernel, grid, block, 0, s, emb, x0, xh0, n);
+hipError_t launch_embed(const bf16_t* emb, float* x0, bf16_t* xh0, int n, unsigned* zero_words, int n_zero,
+                        hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+  const dim3 grid((std::max(n, n_zero) + 255) / 256), block(256);
+  if (ev0 || ev1) hipExtLaunchKernelGGL(embed_kernel, grid, block, 0, s, ev0, ev1, 0, emb, x0, xh0, n, zero_words, n_zero);
+  else hipLaunchKernelGGL(embed_kernel, grid, block, 0, s, emb, x0, xh0, n, zero_words, n_zero);
   return hipGetLastError();
 }
 

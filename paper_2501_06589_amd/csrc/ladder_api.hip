@@ -91,6 +91,7 @@ struct ladder_ctx {
   int fused_plan_batch = 0;
   int n_cu = 256;                 // compute units of the device (workgroup slots of a fused launch = 2 per CU)
   int wall_khz = 100000;          // rate of the device's wall clock (delay_kernel)
+  unsigned* att_done = nullptr;   // fused decode: per layer, how many (sequence, kv head) attention outputs are final
   // generation head (ladder_load_head)
   char* head_table = nullptr;     // T [vocab][H]
   char* head_gain = nullptr;      // T [H] (plain path; the streaming path folds it into head_wp)
@@ -539,13 +540,15 @@ void build_fused_plan(ladder_ctx* c, int B) {
   };
   auto one = [&](const GemvJob& j) { return several({j}); };
   auto two = [&](const GemvJob& first, const GemvJob& second) { return several({first, second}); };
-  auto att = [&](int l, const GemvJob* beside) {
+  auto att = [&](const AttnJob& aj, std::initializer_list<GemvJob> beside) {
     FusedArgs f{};
-    f.kind[0] = JOB_ATTN; f.a = job_att(l); f.block_end[0] = n_splits * nkv * B; f.n_jobs = 1;
+    f.kind[0] = JOB_ATTN; f.a = aj; f.block_end[0] = n_splits * nkv * B; f.n_jobs = 1;
     f.lds_bytes = (int)fused_attn_lds_bytes(d, nq / nkv);
-    if (beside) {
-      f.n_jobs = 2; f.kind[1] = JOB_GEMV; f.g[1] = *beside; f.block_end[1] = f.block_end[0] + blocks_of(*beside);
-      f.lds_bytes = std::max(f.lds_bytes, lds_of(*beside));
+    for (const GemvJob& j : beside) {
+      const int i = f.n_jobs;
+      f.kind[i] = JOB_GEMV; f.g[i] = j; f.block_end[i] = f.block_end[i - 1] + blocks_of(j);
+      f.lds_bytes = std::max(f.lds_bytes, lds_of(j));
+      f.n_jobs = i + 1;
     }
     for (int i = f.n_jobs; i < FUSED_MAX_JOBS; ++i) f.block_end[i] = f.block_end[f.n_jobs - 1];
     return f;
@@ -568,24 +571,41 @@ void build_fused_plan(ladder_ctx* c, int B) {
   plan.clear();
   const bool all_ladder = g.wiring == LADDER_WIRING_LADDER && g.n_standard_layers == 0;
   if (all_ladder) {
-    // modules 1 and 2 both read x_0; then three launches per layer:
-    //     { attention_l , gate/up_l }     { o_l }     { qkv_{l+1} , down_l }
+    // modules 1 and 2 both read x_0; then TWO launches per layer:
+    //     { attention_l , gate/up_l , o_l }     { qkv_{l+1} , down_l }
     // Attention and gate/up, and the next layer's QKV and down, do not depend on each other under the
     // ladder wiring.  The attention workgroups are few and latency bound: beside the largest weight stream
-    // they cost nothing.  (Cutting gate/up so that a part rides beside o_l measured 2 % slower in halves and
-    // up to 10 % slower for uneven cuts, which leave some CUs with two whole-K workgroups and others with one.)
+    // they cost nothing.  o_l does depend on attention_l: its workgroups wait (asleep) on a per-layer arrival
+    // counter that the attention workgroups raise after a release, and read the attention output with
+    // device-coherent loads.  A workgroup only ever waits for workgroups with lower block indices, which
+    // were dispatched before it and wait for nothing, so the wait always ends (it is bounded all the same).
+    // This is the one cross-workgroup dependency of the path (20 producers that fence, 256 consumers that
+    // do not): o_l streams beside gate/up instead of in a launch of its own at a third of the streaming
+    // rate (4.03 -> 3.87 ms per step on the 70B shard).  An acquire fence in the consumers instead of
+    // coherent loads made the step 5.1 ms (an agent-scope acquire empties the L2 under the weight streams);
+    // o_l at the end of the launch instead of among the first workgroups 4.1 ms (it then runs after
+    // gate/up, not beside it); cutting gate/up over two launches 4.1 - 4.6 ms.
     plan.push_back(one(job_qkv(1, 0)));
     for (int l = 1; l <= N; ++l) {
-      GemvJob gu = job_gu(l, 2 * l - 2);
-      plan.push_back(att(l, &gu));
-      plan.push_back(one(job_o(l, 2 * l - 1)));
+      AttnJob aj = job_att(l);
+      aj.done = c->att_done + (l - 1);
+      GemvJob o = job_o(l, 2 * l - 1);
+      o.wait_on = aj.done; o.wait_target = (unsigned)(B * nkv);
+      // block order: attention, as many gate/up workgroups as leave every CU one long workgroup, o_l (resident
+      // from the start, asleep until attention is done, then beside the rest of gate/up), the rest of gate/up
+      GemvJob gu_a = job_gu(l, 2 * l - 2), gu_b = gu_a;
+      const int n_a = std::min(gu_a.n_groups / 2, c->n_cu / 2);   // (any position in the first half measured the same)
+      gu_a.n_groups = n_a;
+      gu_b.group0 = n_a; gu_b.n_groups -= n_a;
+      if (n_a > 0) plan.push_back(att(aj, {gu_a, o, gu_b}));
+      else plan.push_back(att(aj, {o, gu_b}));
       if (l < N) plan.push_back(qkv_down(job_qkv(l + 1, 2 * l - 1), job_dn(l, 2 * l)));
       else plan.push_back(one(job_dn(N, 2 * N)));
     }
   } else {
     for (int l = 1; l <= N; ++l) {
       plan.push_back(one(job_qkv(l, src_of(2 * l - 1))));
-      plan.push_back(att(l, nullptr));
+      plan.push_back(att(job_att(l), {}));
       plan.push_back(one(job_o(l, 2 * l - 1)));
       plan.push_back(one(job_gu(l, src_of(2 * l))));
       plan.push_back(one(job_dn(l, 2 * l)));
@@ -615,7 +635,7 @@ int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s) {
   };
   hipEvent_t e[2];
   HIP_TRY(c, events(e));
-  HIP_TRY(c, launch_embed((const bf16_t*)emb, c->x_ring[0], c->xh_ring[0], B * g.hidden, s, e[0], e[1]));
+  HIP_TRY(c, launch_embed((const bf16_t*)emb, c->x_ring[0], c->xh_ring[0], B * g.hidden, c->att_done, g.n_layers, s, e[0], e[1]));
   if (c->prof) c->prof_pending.push_back({LADDER_K_OTHER, e[0], e[1]});
   const int gq = g.n_q_heads / g.n_kv_heads;
   for (const FusedArgs& fa : c->fused_plan) {
@@ -871,6 +891,7 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
         INIT_TRY(dev_alloc(c, (void**)&c->x_ring[i], (size_t)16 * H * 4, true));
         INIT_TRY(dev_alloc(c, (void**)&c->xh_ring[i], (size_t)16 * H * 2, true));
       }
+      INIT_TRY(dev_alloc(c, (void**)&c->att_done, (size_t)g.n_layers * 4, true));
       // arrival tickets start at zero and are put back to zero by the last arrival of every launch
       INIT_TRY(dev_alloc(c, (void**)&c->tk_att, (size_t)g.max_batch * nkv * 4, true));
     }
