@@ -5,7 +5,7 @@
 
 mode decode (default): a step = one decode step of the whole block stack (all 2N modules: RMSNorm, QKV,
 rotary + cache append, split-KV attention, O projection, SwiGLU MLP, partial-sum reduce + residual add)
-for one batch, in the fused schedule (242 launches for 80 layers).  Workload 70b_r8_decode: 80 layers of
+for one batch, in the fused schedule (161 launches for 80 layers).  Workload 70b_r8_decode: 80 layers of
 a 70B-shaped TP rank at R = 8 (hidden 8192, 8 q / 1 kv heads, d = 128, intermediate 3584), batch 4,
 synthetic KV cache of 1024 positions, 7 synthetic peer partial sums per module.  All inputs are seeded,
 synthetic and resident in HBM before the timed region.

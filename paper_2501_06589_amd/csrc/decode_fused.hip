@@ -1,16 +1,18 @@
 // Fused decode path of the bf16 storage type (gfx950), batch <= 16, one computed shard.
 //
-// One launch runs up to three independent JOBS side by side (workgroups pick their job from the
-// block index).  Under the ladder wiring module m+1 needs only x_{m-1}, so the MLP projections of
-// layer l and the attention-side work around them have no dependency on each other: putting them
-// into ONE launch keeps HBM streaming while the small, latency-bound attention work runs, with no
-// stream, event or graph edge in between.  A decode step is three launches per layer:
-//     { attention_l , gate/up_l (+ RMSNorm, SwiGLU) }
-//     { o_l (+ residual add) }
+// One launch runs up to four JOBS side by side (workgroups pick their job from the block index).
+// Under the ladder wiring module m+1 needs only x_{m-1}, so the MLP projections of layer l and the
+// attention-side work around them have no dependency on each other: putting them into ONE launch
+// keeps HBM streaming while the small, latency-bound attention work runs, with no stream, event or
+// graph edge in between.  A decode step is two launches per layer:
+//     { attention_l , gate/up_l (+ RMSNorm, SwiGLU) , o_l (+ residual add; waits for attention_l) }
 //     { qkv_{l+1} (+ RMSNorm, rotary, cache append) , down_l (+ residual add) }
-// Everything that used to be a kernel of its own is an epilogue or a prologue here, and none of it
-// needs one workgroup to talk to another (a device-wide release fence per workgroup was measured to
-// cost more than the whole projection):
+// Everything that used to be a kernel of its own is an epilogue or a prologue here.  Workgroups do not
+// talk to each other, with two exceptions that involve a few dozen producers only: the splits of a long
+// attention meet through an arrival ticket, and o_l waits on a counter that the attention workgroups
+// raise (a device-wide release fence per workgroup of a whole projection was measured to cost more
+// than the projection itself, and an acquire per consumer empties the L2 under the weight streams, so
+// the consumers read the attention output with device-coherent loads instead):
 //   * "wait(); residual += out" of Algorithm 1 with the all-reduce written as a sum over rank partial
 //     sums (Eq. 2) is the epilogue of the module's last projection: x_m = x_{m-1} + h_m + sum(peers),
 //     written to a ring of three residual buffers (x_{m-1} is still read by the job that runs beside);

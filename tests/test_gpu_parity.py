@@ -267,7 +267,7 @@ def test_full_width_70b_r8_decode_one_layer_strict(harness):
 
 def test_full_size_70b_r8_decode_all_80_layers_against_oracle(harness):
     """The headline decode workload at full size and depth, in the launch configuration of the default
-    bench run (242 fused launches per step); two decode steps, every output element against the oracle,
+    bench run (161 fused launches per step); two decode steps, every output element against the oracle,
     within the per-module error budget."""
     w = inputs.WORKLOADS["70b_r8_decode"]
     res = harness.run_case(w, decode_steps=2, kv_preload=w.kv_preload, gen_device="cuda:0", max_seq=BENCH_MAX_SEQ)
