@@ -261,7 +261,7 @@ def run_prefill(args):
     flops_per_launch = gemm_flops / (4 * w.n_layers * w.n_real_shards)
     avg_ms = ms_gemm / max(n_gemm, 1)
     achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12 if n_gemm else 0.0
-    roofline = {"bound": "mfma", "kernel": "gemm_mfma_kernel (prefill bf16 MFMA GEMM)", "achieved": achieved,
+    roofline = {"bound": "mfma", "kernel": "gemm_lds_kernel (prefill bf16 MFMA GEMM, 256 x 256 tiles)", "achieved": achieved,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": None, "algorithmic_flops_per_launch": flops_per_launch, "avg_launch_ms": avg_ms,
                 "launches": n_gemm}

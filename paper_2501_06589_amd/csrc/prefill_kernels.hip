@@ -35,6 +35,51 @@ __device__ __forceinline__ f32x4_t mfma16(const uint4 a, const uint4 b, const f3
 #define GEMM_LDS_STRIDE (GEMM_BK + 8)  // bf16 elements per LDS row: 80 bytes, conflict-free 16-byte reads
 #define GEMM_GROUP_M 16
 
+// Epilogue of a wavefront's 64-column x (16 WM)-row accumulator block: row base m0, first weight tile nt0.
+// Output element (m, n) sits in lane (n%16)/4*16 + m%16, register n%4: a lane stores 4 consecutive columns.
+template <int WM>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x4_t (&acc)[4][WM], int m0, int nt0, int NT, int lane) {
+  const int b = lane & 15, q = lane >> 4;
+  if (a.epilogue == 0) {
+#pragma unroll
+    for (int mt = 0; mt < WM; ++mt) {
+      const int m = m0 + mt * 16 + b;
+      if (m >= a.M) continue;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (nt0 + j >= NT) continue;
+        const int n = (nt0 + j) * 16 + 4 * q;
+        *reinterpret_cast<float4*>(a.out + (size_t)m * a.N + n) =
+            make_float4(acc[j][mt][0], acc[j][mt][1], acc[j][mt][2], acc[j][mt][3]);
+      }
+    }
+  } else {
+    // SwiGLU: tile columns 0..7 = gate columns 8nt..8nt+7 (lanes q = 0, 1), columns 8..15 = the matching
+    // up columns (lanes q = 2, 3): lane + 32 holds the up partner of this lane's gate value.
+    const int I = a.N >> 1;
+#pragma unroll
+    for (int mt = 0; mt < WM; ++mt) {
+      const int m = m0 + mt * 16 + b;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float r4[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float g = acc[j][mt][r];
+          const float u = __shfl(acc[j][mt][r], (lane + 32) & 63, 64);
+          r4[r] = g / (1.0f + __expf(-g)) * u;
+        }
+        if (q < 2 && m < a.M && nt0 + j < NT) {
+          uint2 pk;
+          pk.x = (uint32_t)f32_to_bf16(r4[0]) | ((uint32_t)f32_to_bf16(r4[1]) << 16);
+          pk.y = (uint32_t)f32_to_bf16(r4[2]) | ((uint32_t)f32_to_bf16(r4[3]) << 16);
+          *reinterpret_cast<uint2*>(a.act + (size_t)m * I + (nt0 + j) * 8 + 4 * q) = pk;
+        }
+      }
+    }
+  }
+}
+
 template <int WM, int MIN_WAVES>
 __global__ __launch_bounds__(256, MIN_WAVES) void gemm_mfma_kernel(GemmArgs a) {
   constexpr int BM = 16 * WM;
@@ -137,44 +182,7 @@ __global__ __launch_bounds__(256, MIN_WAVES) void gemm_mfma_kernel(GemmArgs a) {
     __syncthreads();
   }
 
-  if (a.epilogue == 0) {
-#pragma unroll
-    for (int mt = 0; mt < WM; ++mt) {
-      const int m = m0 + mt * 16 + b;
-      if (m >= a.M) continue;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (nt0 + j >= NT) continue;
-        const int n = (nt0 + j) * 16 + 4 * q;
-        *reinterpret_cast<float4*>(a.out + (size_t)m * a.N + n) =
-            make_float4(acc[j][mt][0], acc[j][mt][1], acc[j][mt][2], acc[j][mt][3]);
-      }
-    }
-  } else {
-    // SwiGLU: tile columns 0..7 = gate columns 8nt..8nt+7 (lanes q = 0, 1), columns 8..15 = the matching
-    // up columns (lanes q = 2, 3): lane + 32 holds the up partner of this lane's gate value.
-    const int I = a.N >> 1;
-#pragma unroll
-    for (int mt = 0; mt < WM; ++mt) {
-      const int m = m0 + mt * 16 + b;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        float r4[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float g = acc[j][mt][r];
-          const float u = __shfl(acc[j][mt][r], (lane + 32) & 63, 64);
-          r4[r] = g / (1.0f + __expf(-g)) * u;
-        }
-        if (q < 2 && m < a.M && nt0 + j < NT) {
-          uint2 pk;
-          pk.x = (uint32_t)f32_to_bf16(r4[0]) | ((uint32_t)f32_to_bf16(r4[1]) << 16);
-          pk.y = (uint32_t)f32_to_bf16(r4[2]) | ((uint32_t)f32_to_bf16(r4[3]) << 16);
-          *reinterpret_cast<uint2*>(a.act + (size_t)m * I + (nt0 + j) * 8 + 4 * q) = pk;
-        }
-      }
-    }
-  }
+  gemm_epilogue<WM>(a, acc, m0, nt0, NT, lane);
 }
 
 template <int WM, int MIN_WAVES>
@@ -186,8 +194,207 @@ static hipError_t launch_gemm_wm(const GemmArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// Large-M GEMM: 256 x 256 workgroup tile, 8 wavefronts (2 along M x 4 along N, 128 x 64 each), one
+// workgroup per CU.  Both operands travel global memory -> LDS without passing through registers
+// (16-byte direct-to-LDS loads: the 64 lanes of one load fill 1 KiB of LDS in lane order) through a
+// ring of GEMM2_STAGES stages of one k tile (32) each: loads are in flight two to three k tiles ahead
+// of the MFMAs that consume them and cost no registers.  A stage holds 16 activation fragments
+// (16 rows x 32 k, lane (row, k segment) -> slot lane) and 16 packed weight tiles, each exactly the
+// 1 KiB register image of an MFMA operand: every LDS read is one contiguous, conflict-free 1 KiB.
+// One barrier per k tile, in the middle of its MFMAs: after the barrier of k tile kt every wave's loads
+// of stage kt + 1 have landed and every wave has finished reading stage kt - 1, whose buffer the next
+// loads overwrite.  The first fragments of stage kt + 1 are read right after that barrier, sixteen
+// MFMAs before their first use, and a wave's four loads per k tile are spread over its MFMA rows.
+// Rows >= M and weight tiles >= N/16 are clamped on load (they only reach outputs that are not stored).
+// Tile order: the XCD-aware order of gemm_mfma_kernel with groups of GEMM2_GROUP_M row blocks; the 32 CUs
+// of an XCD then work on 4 row blocks x 8 column blocks at a time.  Few row blocks is what matters: an
+// activation row contributes 64 bytes per k tile, half a cache line, so activation panels cost the L2 more
+// requests per byte than the contiguous weight tiles (measured on 32768 x 8192 x 14336: groups of
+// 2 / 4 / 8 / 16 row blocks -> 1263 / 1289 / 1203 / 1086 TFLOP/s).
+// Against gemm_mfma_kernel at 128 x 256 (two workgroups per CU): a third less operand traffic per CU
+// and no register staging; 971 -> 1072, 908 -> 956, 1098 -> 1206, 1158 -> 1289 TFLOP/s on the QKV / O / down /
+// gate-up shapes of the 70B R = 4 shard at 32768 rows.
+// ------------------------------------------------------------------------------------------------
+#ifndef GEMM2_STAGES
+#define GEMM2_STAGES 4
+#endif
+#ifndef GEMM2_GROUP_M
+#define GEMM2_GROUP_M 4
+#endif
+#define GEMM2_STAGE_BYTES 32768
+static_assert(GEMM2_STAGES >= 3 && GEMM2_STAGES * GEMM2_STAGE_BYTES <= 160 * 1024, "stage ring must hold 3 stages and fit the LDS");
+
+#define GEMM2_LDSP(p) ((__attribute__((address_space(3))) void*)(p))
+#define GEMM2_GLBP(p) ((const __attribute__((address_space(1))) void*)(p))
+
+// s_waitcnt vmcnt(N) (at most N of this wave's vector-memory operations still in flight; the other counters
+// are left alone: gfx9 encoding, vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8) and a bare
+// workgroup barrier, without the fence of __syncthreads(), which would wait for ALL outstanding loads.
+// Written with builtins, not inline assembly: after an asm statement the compiler no longer knows which
+// LDS reads are pending and waits for all of them at the next use.
+template <int N>
+__device__ __forceinline__ void gemm2_wait_and_meet() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+__global__ __launch_bounds__(512, 2) void gemm_lds_kernel(GemmArgs a) {
+  constexpr int WM = 8;
+  extern __shared__ __attribute__((aligned(16))) unsigned char g2_lds[];   // GEMM2_STAGES x 32 KiB
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int b = lane & 15, q = lane >> 4;
+  const int wm = wave >> 2, wn = wave & 3;
+  const int KT = a.K >> 5, NT = a.N >> 4;
+  const int tiles_m = (a.M + 255) / 256, tiles_n = (a.N + 255) / 256;
+  const int nblk = gridDim.x, nblk8 = nblk & ~7;   // XCD-aware order, as in gemm_mfma_kernel
+  const int bid = (int)blockIdx.x < nblk8 ? ((int)blockIdx.x & 7) * (nblk8 >> 3) + ((int)blockIdx.x >> 3) : (int)blockIdx.x;
+  const int per_group = GEMM2_GROUP_M * tiles_n;
+  const int group = bid / per_group, in_group = bid % per_group;
+  const int gm = min(GEMM2_GROUP_M, tiles_m - group * GEMM2_GROUP_M);
+  const int m_blk = group * GEMM2_GROUP_M + in_group % gm;
+  const int n_blk = in_group / gm;
+  const int m0 = m_blk * 256;
+  const int nt0 = n_blk * 16;
+
+  // this wave's share of a stage's loads: activation fragments 2 wave, 2 wave + 1 and weight tiles likewise
+  const bf16_t* xsrc[2];
+  const u32x4_t* wsrc[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int f = 2 * wave + i;
+    xsrc[i] = a.x + (size_t)min(m0 + 16 * f + b, a.M - 1) * a.ldx + q * 8;
+    wsrc[i] = reinterpret_cast<const u32x4_t*>(a.wp) + (size_t)min(nt0 + f, NT - 1) * KT * 64 + lane;
+  }
+  // load `part` (0 / 2: activation fragments, 1 / 3: weight tiles) of this wave's share of k tile kt into `stage`
+  auto issue = [&](int stage, int kt, int part) {
+    const int ktc = min(kt, KT - 1);
+    unsigned char* base = g2_lds + stage * GEMM2_STAGE_BYTES + (2 * wave + (part >> 1)) * 1024;
+    if (part & 1)
+      __builtin_amdgcn_global_load_lds(GEMM2_GLBP(wsrc[part >> 1] + (size_t)ktc * 64), GEMM2_LDSP(base + 16384), 16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds(GEMM2_GLBP(xsrc[part >> 1] + (size_t)ktc * 32), GEMM2_LDSP(base), 16, 0, 0);
+  };
+
+  f32x4_t acc[4][WM];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int mt = 0; mt < WM; ++mt) acc[j][mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+
+  // Fragment reads run ahead of the MFMAs that consume them: the 4 weight fragments and the first two
+  // activation fragments of stage kt + 1 are read during the second half of stage kt, the others two row
+  // tiles ahead inside the stage.  The barrier of a k tile sits in the MIDDLE of its MFMAs, so that the wait
+  // in front of it is not followed by a cold start of every wave at once.
+  auto frag_ptr = [&](int stage) { return g2_lds + stage * GEMM2_STAGE_BYTES + lane * 16; };
+  auto xfrag = [&](const unsigned char* base, int mt) { return *reinterpret_cast<const u32x4_t*>(base + (wm * 8 + mt) * 1024); };
+  auto wfrag = [&](const unsigned char* base, int j) { return *reinterpret_cast<const u32x4_t*>(base + 16384 + (wn * 4 + j) * 1024); };
+  auto mfma_row = [&](const u32x4_t (&w)[4], const u32x4_t& f, int mt) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w[j]),
+                                                          __builtin_bit_cast(bf16x8_t, f), acc[j][mt], 0, 0, 0);
+  };
+
+  // prologue: stages 0 .. GEMM2_STAGES - 2, except the second half of the last one (the first k tile issues it)
+#pragma unroll
+  for (int s = 0; s < GEMM2_STAGES - 1; ++s)
+#pragma unroll
+    for (int part = 0; part < (s == GEMM2_STAGES - 2 ? 2 : 4); ++part) issue(s, s, part);
+  gemm2_wait_and_meet<4 * (GEMM2_STAGES - 2) - 2>();   // stage 0 has landed
+  u32x4_t wA[4], wB[4], fA[3], fB[3];
+  {
+    const unsigned char* base = frag_ptr(0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) wA[j] = wfrag(base, j);
+#pragma unroll
+    for (int mt = 0; mt < 3; ++mt) fA[mt] = xfrag(base, mt);
+  }
+  int stage = 0, fill = GEMM2_STAGES - 2;   // `fill`: the stage whose loads are being issued
+  // The four loads of a stage are spread over the MFMAs between two barriers (two after the barrier of k tile
+  // kt, two before the barrier of kt + 1): issued in one burst by all eight waves they fill the address
+  // pipeline, and a wave that cannot issue its load cannot issue the MFMAs behind it either.
+  // One k tile: MFMAs of stage `stage`, whose weight fragments w and first three activation fragments f012 are
+  // already in registers; leaves those of the next stage in (wn, g012).  LDS reads are placed at least eight
+  // MFMAs ahead of the first instruction that waits for them (the compiler waits for ALL pending reads at once).
+  auto step = [&](const u32x4_t (&w)[4], const u32x4_t (&f012)[3], u32x4_t (&wn)[4], u32x4_t (&g012)[3], int kt) {
+    const unsigned char* base = frag_ptr(stage);
+    const int next = stage + 1 == GEMM2_STAGES ? 0 : stage + 1;
+    u32x4_t f[WM];
+    mfma_row(w, f012[0], 0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int mt = 3; mt < WM; ++mt) f[mt] = xfrag(base, mt);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_row(w, f012[1], 1);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(fill, kt + GEMM2_STAGES - 2, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_row(w, f012[2], 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_row(w, f[3], 3);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(fill, kt + GEMM2_STAGES - 2, 3);
+    fill = fill + 1 == GEMM2_STAGES ? 0 : fill + 1;
+    // this wave's loads of stage kt + 1 are complete (those of later stages may be in flight), then all waves
+    // meet: stage kt + 1 is readable, and nobody reads stage kt - 1 any more, whose buffer the next loads fill
+    gemm2_wait_and_meet<4 * (GEMM2_STAGES - 3)>();
+    const unsigned char* nbase = frag_ptr(next);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) wn[j] = wfrag(nbase, j);
+#pragma unroll
+    for (int mt = 0; mt < 3; ++mt) g012[mt] = xfrag(nbase, mt);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_row(w, f[4], 4);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(fill, kt + GEMM2_STAGES - 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_row(w, f[5], 5);
+    mfma_row(w, f[6], 6);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(fill, kt + GEMM2_STAGES - 1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_row(w, f[7], 7);
+    __builtin_amdgcn_sched_barrier(0);
+    stage = next;
+  };
+  for (int kt = 0; kt < KT; kt += 2) {
+    step(wA, fA, wB, fB, kt);
+    if (kt + 1 >= KT) break;
+    step(wB, fB, wA, fA, kt + 1);
+  }
+  // the clamped loads past the last k tile are still in flight into LDS: they must land before the workgroup ends
+  gemm2_wait_and_meet<0>();
+  gemm_epilogue<WM>(a, acc, m0 + wm * 128, nt0 + wn * 4, NT, lane);
+}
+
+static hipError_t launch_gemm_lds(const GemmArgs& a, hipStream_t s) {
+  constexpr size_t lds = (size_t)GEMM2_STAGES * GEMM2_STAGE_BYTES;
+  static bool prepared[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (!prepared[dev]) {   // more than the default 64 KiB of dynamic LDS: asked for once per device
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_lds_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    prepared[dev] = true;
+  }
+  const int tiles_m = (a.M + 255) / 256, tiles_n = (a.N + 255) / 256;
+  hipLaunchKernelGGL(gemm_lds_kernel, dim3(tiles_m * tiles_n), dim3(512), lds, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0 || (a.K & 31) || (a.N & 15) || a.K < 32) return hipErrorInvalidValue;
+#ifndef GEMM_NO_LDS_KERNEL
+  // 256 x 256 tiles, one per CU, when they fill the chip at least once; else the smaller tiles below
+  if ((long)((a.M + 255) / 256) * ((a.N + 255) / 256) >= 256 && a.K >= 32 * GEMM2_STAGES) return launch_gemm_lds(a, s);
+#endif
   if (a.M >= 1024) return launch_gemm_wm<GEMM_WM_LARGE, GEMM_WAVES_LARGE>(a, s);
   if (a.M > 64) return launch_gemm_wm<8, 2>(a, s);   // 128 x 256
   return launch_gemm_wm<4, 2>(a, s);                 //  64 x 256
