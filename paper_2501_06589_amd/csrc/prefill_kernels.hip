@@ -1,6 +1,7 @@
 // Prefill-shape kernels of the bf16 path (gfx950): MFMA GEMM on the packed weight tiles and causal
 // GQA flash attention over the cache, both on v_mfma_f32_16x16x32_bf16.
 #include "common.h"
+#include <type_traits>
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
@@ -197,34 +198,34 @@ static hipError_t launch_gemm_wm(const GemmArgs& a, hipStream_t s) {
 // ------------------------------------------------------------------------------------------------
 // Large-M GEMM: 256 x 256 workgroup tile, 8 wavefronts (2 along M x 4 along N, 128 x 64 each), one
 // workgroup per CU.  Both operands travel global memory -> LDS without passing through registers
-// (16-byte direct-to-LDS loads: the 64 lanes of one load fill 1 KiB of LDS in lane order) through a
-// ring of GEMM2_STAGES stages of one k tile (32) each: loads are in flight two to three k tiles ahead
-// of the MFMAs that consume them and cost no registers.  A stage holds 16 activation fragments
-// (16 rows x 32 k, lane (row, k segment) -> slot lane) and 16 packed weight tiles, each exactly the
-// 1 KiB register image of an MFMA operand: every LDS read is one contiguous, conflict-free 1 KiB.
-// One barrier per k tile, in the middle of its MFMAs: after the barrier of k tile kt every wave's loads
-// of stage kt + 1 have landed and every wave has finished reading stage kt - 1, whose buffer the next
-// loads overwrite.  The first fragments of stage kt + 1 are read right after that barrier, sixteen
-// MFMAs before their first use, and a wave's four loads per k tile are spread over its MFMA rows.
+// (16-byte direct-to-LDS loads: the 64 lanes of one load fill 1 KiB of LDS in lane order), so loads are
+// in flight two to three k tiles ahead of the MFMAs that consume them and cost no registers.
+//   Weights: a ring of 4 stages of one k tile (32): 16 packed tiles of 1 KiB, each the register image of
+//   an MFMA operand (read back as one contiguous 1 KiB).
+//   Activations: a ring of 3 blocks of TWO k tiles (256 rows x 128 bytes): one load covers 8 rows x 64 k,
+//   i.e. whole 128-byte cache lines (a load of 16 rows x 32 k would request every line twice, half a line
+//   per k tile: measured 4 - 7 % slower).  Within a block the 16-byte segments of fragment row b are
+//   stored XOR-swizzled by b / 2 (the lane that fetches segment s of row b sits at position s ^ (b / 2) of
+//   the row's eight lanes), so that the 16 lanes of a fragment read that hold the same k segment hit 16
+//   different bank groups.
+// 160 KiB of LDS in all.  One bare barrier per k tile, in the middle of its MFMAs: after the barrier of k
+// tile kt every wave's loads for k tile kt + 1 have landed and every wave has finished reading k tile
+// kt - 1, whose buffers the next loads overwrite.  The first fragments of k tile kt + 1 are read right
+// after that barrier, sixteen MFMAs before their first use, and a wave's loads are spread over its MFMA
+// rows (issued in one burst by all eight waves they fill the address pipeline, and a wave that cannot
+// issue its load cannot issue the MFMAs behind it either).
 // Rows >= M and weight tiles >= N/16 are clamped on load (they only reach outputs that are not stored).
+// K must be a multiple of 64.
 // Tile order: the XCD-aware order of gemm_mfma_kernel with groups of GEMM2_GROUP_M row blocks; the 32 CUs
-// of an XCD then work on 4 row blocks x 8 column blocks at a time.  Few row blocks is what matters: an
-// activation row contributes 64 bytes per k tile, half a cache line, so activation panels cost the L2 more
-// requests per byte than the contiguous weight tiles (measured on 32768 x 8192 x 14336: groups of
-// 2 / 4 / 8 / 16 row blocks -> 1263 / 1289 / 1203 / 1086 TFLOP/s).
+// of an XCD then work on 4 row blocks x 8 column blocks at a time (groups of 2 / 4 / 8 row blocks:
+// 1309 / 1335 / 1297 TFLOP/s on 32768 x 8192 x 14336).
 // Against gemm_mfma_kernel at 128 x 256 (two workgroups per CU): a third less operand traffic per CU
-// and no register staging; 971 -> 1072, 908 -> 956, 1098 -> 1206, 1158 -> 1289 TFLOP/s on the QKV / O / down /
+// and no register staging; 971 -> 1129, 908 -> 993, 1098 -> 1271, 1158 -> 1338 TFLOP/s on the QKV / O / down /
 // gate-up shapes of the 70B R = 4 shard at 32768 rows.
 // ------------------------------------------------------------------------------------------------
-#ifndef GEMM2_STAGES
-#define GEMM2_STAGES 4
-#endif
 #ifndef GEMM2_GROUP_M
 #define GEMM2_GROUP_M 4
 #endif
-#define GEMM2_STAGE_BYTES 32768
-static_assert(GEMM2_STAGES >= 3 && GEMM2_STAGES * GEMM2_STAGE_BYTES <= 160 * 1024, "stage ring must hold 3 stages and fit the LDS");
-
 #define GEMM2_LDSP(p) ((__attribute__((address_space(3))) void*)(p))
 #define GEMM2_GLBP(p) ((const __attribute__((address_space(1))) void*)(p))
 
@@ -242,14 +243,22 @@ __device__ __forceinline__ void gemm2_wait_and_meet() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
+#define GEMM2_XBLOCK_BYTES 32768
+#define GEMM2_WSTAGE_BYTES 16384
+#define GEMM2_XBLOCKS 3
+#define GEMM2_WSTAGES 4
+#define GEMM2_LDS_BYTES (GEMM2_XBLOCKS * GEMM2_XBLOCK_BYTES + GEMM2_WSTAGES * GEMM2_WSTAGE_BYTES)
+
 __global__ __launch_bounds__(512, 2) void gemm_lds_kernel(GemmArgs a) {
   constexpr int WM = 8;
-  extern __shared__ __attribute__((aligned(16))) unsigned char g2_lds[];   // GEMM2_STAGES x 32 KiB
+  extern __shared__ __attribute__((aligned(16))) unsigned char g2_lds[];
+  unsigned char* const xring = g2_lds;
+  unsigned char* const wring = g2_lds + GEMM2_XBLOCKS * GEMM2_XBLOCK_BYTES;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int b = lane & 15, q = lane >> 4;
   const int wm = wave >> 2, wn = wave & 3;
-  const int KT = a.K >> 5, NT = a.N >> 4;
+  const int KT = a.K >> 5, KB = a.K >> 6, NT = a.N >> 4;
   const int tiles_m = (a.M + 255) / 256, tiles_n = (a.N + 255) / 256;
   const int nblk = gridDim.x, nblk8 = nblk & ~7;   // XCD-aware order, as in gemm_mfma_kernel
   const int bid = (int)blockIdx.x < nblk8 ? ((int)blockIdx.x & 7) * (nblk8 >> 3) + ((int)blockIdx.x >> 3) : (int)blockIdx.x;
@@ -261,23 +270,32 @@ __global__ __launch_bounds__(512, 2) void gemm_lds_kernel(GemmArgs a) {
   const int m0 = m_blk * 256;
   const int nt0 = n_blk * 16;
 
-  // this wave's share of a stage's loads: activation fragments 2 wave, 2 wave + 1 and weight tiles likewise
-  const bf16_t* xsrc[2];
+  // this wave's share of the loads: row groups (8 rows) 4 wave .. 4 wave + 3 of an activation block, weight
+  // tiles 2 wave, 2 wave + 1 of a stage
+  const bf16_t* xsrc[4];
   const u32x4_t* wsrc[2];
+  {
+    const int r = lane >> 3;   // row within the group of 8
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int f = 2 * wave + i;
-    xsrc[i] = a.x + (size_t)min(m0 + 16 * f + b, a.M - 1) * a.ldx + q * 8;
-    wsrc[i] = reinterpret_cast<const u32x4_t*>(a.wp) + (size_t)min(nt0 + f, NT - 1) * KT * 64 + lane;
+    for (int i = 0; i < 4; ++i) {
+      const int g = 4 * wave + i;                  // row group of the tile
+      const int brow = 8 * (g & 1) + r;            // row within its 16-row fragment
+      const int seg = (lane & 7) ^ ((brow >> 1) & 7);
+      xsrc[i] = a.x + (size_t)min(m0 + 8 * g + r, a.M - 1) * a.ldx + seg * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      wsrc[i] = reinterpret_cast<const u32x4_t*>(a.wp) + (size_t)min(nt0 + 2 * wave + i, NT - 1) * KT * 64 + lane;
   }
-  // load `part` (0 / 2: activation fragments, 1 / 3: weight tiles) of this wave's share of k tile kt into `stage`
-  auto issue = [&](int stage, int kt, int part) {
+  auto issue_x = [&](int xbuf, int kb, int i) {   // row group i of this wave, activation block kb (k tiles 2 kb, 2 kb + 1)
+    const int kbc = min(kb, KB - 1);
+    __builtin_amdgcn_global_load_lds(GEMM2_GLBP(xsrc[i] + (size_t)kbc * 64),
+                                     GEMM2_LDSP(xring + xbuf * GEMM2_XBLOCK_BYTES + (4 * wave + i) * 1024), 16, 0, 0);
+  };
+  auto issue_w = [&](int wbuf, int kt, int i) {   // weight tile i of this wave, k tile kt
     const int ktc = min(kt, KT - 1);
-    unsigned char* base = g2_lds + stage * GEMM2_STAGE_BYTES + (2 * wave + (part >> 1)) * 1024;
-    if (part & 1)
-      __builtin_amdgcn_global_load_lds(GEMM2_GLBP(wsrc[part >> 1] + (size_t)ktc * 64), GEMM2_LDSP(base + 16384), 16, 0, 0);
-    else
-      __builtin_amdgcn_global_load_lds(GEMM2_GLBP(xsrc[part >> 1] + (size_t)ktc * 32), GEMM2_LDSP(base), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(GEMM2_GLBP(wsrc[i] + (size_t)ktc * 64),
+                                     GEMM2_LDSP(wring + wbuf * GEMM2_WSTAGE_BYTES + (2 * wave + i) * 1024), 16, 0, 0);
   };
 
   f32x4_t acc[4][WM];
@@ -286,13 +304,11 @@ __global__ __launch_bounds__(512, 2) void gemm_lds_kernel(GemmArgs a) {
 #pragma unroll
     for (int mt = 0; mt < WM; ++mt) acc[j][mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
-  // Fragment reads run ahead of the MFMAs that consume them: the 4 weight fragments and the first two
-  // activation fragments of stage kt + 1 are read during the second half of stage kt, the others two row
-  // tiles ahead inside the stage.  The barrier of a k tile sits in the MIDDLE of its MFMAs, so that the wait
-  // in front of it is not followed by a cold start of every wave at once.
-  auto frag_ptr = [&](int stage) { return g2_lds + stage * GEMM2_STAGE_BYTES + lane * 16; };
-  auto xfrag = [&](const unsigned char* base, int mt) { return *reinterpret_cast<const u32x4_t*>(base + (wm * 8 + mt) * 1024); };
-  auto wfrag = [&](const unsigned char* base, int j) { return *reinterpret_cast<const u32x4_t*>(base + 16384 + (wn * 4 + j) * 1024); };
+  // per-lane read offsets inside an activation block, for the even and the odd k tile of the block
+  const int xoff0 = (b >> 3) * 1024 + ((b & 7) * 8 + ((q) ^ ((b >> 1) & 7))) * 16 + wm * 8 * 2048;
+  const int xoff1 = (b >> 3) * 1024 + ((b & 7) * 8 + ((4 + q) ^ ((b >> 1) & 7))) * 16 + wm * 8 * 2048;
+  auto xfrag = [&](const unsigned char* xb, int mt) { return *reinterpret_cast<const u32x4_t*>(xb + mt * 2048); };
+  auto wfrag = [&](const unsigned char* wb, int j) { return *reinterpret_cast<const u32x4_t*>(wb + (wn * 4 + j) * 1024); };
   auto mfma_row = [&](const u32x4_t (&w)[4], const u32x4_t& f, int mt) {
 #pragma unroll
     for (int j = 0; j < 4; ++j)
@@ -300,72 +316,88 @@ __global__ __launch_bounds__(512, 2) void gemm_lds_kernel(GemmArgs a) {
                                                           __builtin_bit_cast(bf16x8_t, f), acc[j][mt], 0, 0, 0);
   };
 
-  // prologue: stages 0 .. GEMM2_STAGES - 2, except the second half of the last one (the first k tile issues it)
+  // Issue order of a wave, per pair of k tiles (2j, 2j + 1); s = weight stage = k tile, blk = activation block:
+  //   2j   first half : W1(s 2j+2)                       barrier 2j   needs W(2j+1)            -> vmcnt(4)
+  //   2j   second half: W0(s 2j+3) X0 X1(blk j+2)
+  //   2j+1 first half : W1(s 2j+3) X2 X3(blk j+2)        barrier 2j+1 needs W(2j+2), X(j+1)    -> vmcnt(6)
+  //   2j+1 second half: W0(s 2j+4)
+  // prologue in the same order: X(blk 0) W(0) | W0(1) X0 X1(blk 1) | W1(1) X2 X3(blk 1) | W0(2)
 #pragma unroll
-  for (int s = 0; s < GEMM2_STAGES - 1; ++s)
-#pragma unroll
-    for (int part = 0; part < (s == GEMM2_STAGES - 2 ? 2 : 4); ++part) issue(s, s, part);
-  gemm2_wait_and_meet<4 * (GEMM2_STAGES - 2) - 2>();   // stage 0 has landed
+  for (int i = 0; i < 4; ++i) issue_x(0, 0, i);
+  issue_w(0, 0, 0);
+  issue_w(0, 0, 1);
+  issue_w(1, 1, 0);
+  issue_x(1, 1, 0);
+  issue_x(1, 1, 1);
+  issue_w(1, 1, 1);
+  issue_x(1, 1, 2);
+  issue_x(1, 1, 3);
+  issue_w(2, 2, 0);
+  gemm2_wait_and_meet<7>();   // block 0 and stage 0 have landed
   u32x4_t wA[4], wB[4], fA[3], fB[3];
-  {
-    const unsigned char* base = frag_ptr(0);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) wA[j] = wfrag(base, j);
+  for (int j = 0; j < 4; ++j) wA[j] = wfrag(wring + lane * 16, j);
 #pragma unroll
-    for (int mt = 0; mt < 3; ++mt) fA[mt] = xfrag(base, mt);
-  }
-  int stage = 0, fill = GEMM2_STAGES - 2;   // `fill`: the stage whose loads are being issued
-  // The four loads of a stage are spread over the MFMAs between two barriers (two after the barrier of k tile
-  // kt, two before the barrier of kt + 1): issued in one burst by all eight waves they fill the address
-  // pipeline, and a wave that cannot issue its load cannot issue the MFMAs behind it either.
-  // One k tile: MFMAs of stage `stage`, whose weight fragments w and first three activation fragments f012 are
-  // already in registers; leaves those of the next stage in (wn, g012).  LDS reads are placed at least eight
-  // MFMAs ahead of the first instruction that waits for them (the compiler waits for ALL pending reads at once).
-  auto step = [&](const u32x4_t (&w)[4], const u32x4_t (&f012)[3], u32x4_t (&wn)[4], u32x4_t (&g012)[3], int kt) {
-    const unsigned char* base = frag_ptr(stage);
-    const int next = stage + 1 == GEMM2_STAGES ? 0 : stage + 1;
+  for (int mt = 0; mt < 3; ++mt) fA[mt] = xfrag(xring + xoff0, mt);
+
+  int wstage = 0;   // weight stage of the current k tile
+  int xblk = 0;     // activation block of the current pair of k tiles
+  // one k tile; ODD: second tile of its activation block
+  auto step = [&](auto odd_tag, const u32x4_t (&w)[4], const u32x4_t (&f012)[3], u32x4_t (&wn4)[4], u32x4_t (&g012)[3], int kt) {
+    constexpr bool ODD = decltype(odd_tag)::value;
+    const unsigned char* xb = xring + xblk * GEMM2_XBLOCK_BYTES + (ODD ? xoff1 : xoff0);
+    const int wnext = (wstage + 1) & 3, w2 = (wstage + 2) & 3, w3 = (wstage + 3) & 3;
+    const int xnext = xblk + 1 == GEMM2_XBLOCKS ? 0 : xblk + 1;
+    const int xfill = xblk + 2 >= GEMM2_XBLOCKS ? xblk + 2 - GEMM2_XBLOCKS : xblk + 2;
     u32x4_t f[WM];
     mfma_row(w, f012[0], 0);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int mt = 3; mt < WM; ++mt) f[mt] = xfrag(base, mt);
+    for (int mt = 3; mt < WM; ++mt) f[mt] = xfrag(xb, mt);
     __builtin_amdgcn_sched_barrier(0);
     mfma_row(w, f012[1], 1);
     __builtin_amdgcn_sched_barrier(0);
-    issue(fill, kt + GEMM2_STAGES - 2, 2);
+    if (ODD) {
+      issue_w(w2, kt + 2, 1);
+      issue_x(xfill, (kt >> 1) + 2, 2);
+    } else {
+      issue_w(w2, kt + 2, 1);
+    }
     __builtin_amdgcn_sched_barrier(0);
     mfma_row(w, f012[2], 2);
     __builtin_amdgcn_sched_barrier(0);
     mfma_row(w, f[3], 3);
     __builtin_amdgcn_sched_barrier(0);
-    issue(fill, kt + GEMM2_STAGES - 2, 3);
-    fill = fill + 1 == GEMM2_STAGES ? 0 : fill + 1;
-    // this wave's loads of stage kt + 1 are complete (those of later stages may be in flight), then all waves
-    // meet: stage kt + 1 is readable, and nobody reads stage kt - 1 any more, whose buffer the next loads fill
-    gemm2_wait_and_meet<4 * (GEMM2_STAGES - 3)>();
-    const unsigned char* nbase = frag_ptr(next);
+    if (ODD) issue_x(xfill, (kt >> 1) + 2, 3);
+    __builtin_amdgcn_sched_barrier(0);
+    // after the barrier: weight stage kt + 1 (and, behind an odd tile, the next activation block) are readable,
+    // and nobody reads weight stage kt - 1 (behind an even tile: activation block j - 1) any more
+    if (ODD) gemm2_wait_and_meet<6>(); else gemm2_wait_and_meet<4>();
+    const unsigned char* nxb = ODD ? xring + xnext * GEMM2_XBLOCK_BYTES + xoff0 : xring + xblk * GEMM2_XBLOCK_BYTES + xoff1;
+    const unsigned char* nwb = wring + wnext * GEMM2_WSTAGE_BYTES + lane * 16;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) wn[j] = wfrag(nbase, j);
+    for (int j = 0; j < 4; ++j) wn4[j] = wfrag(nwb, j);
 #pragma unroll
-    for (int mt = 0; mt < 3; ++mt) g012[mt] = xfrag(nbase, mt);
+    for (int mt = 0; mt < 3; ++mt) g012[mt] = xfrag(nxb, mt);
     __builtin_amdgcn_sched_barrier(0);
     mfma_row(w, f[4], 4);
     __builtin_amdgcn_sched_barrier(0);
-    issue(fill, kt + GEMM2_STAGES - 1, 0);
+    issue_w(w3, kt + 3, 0);
+    if (!ODD) issue_x(xfill, (kt >> 1) + 2, 0);
     __builtin_amdgcn_sched_barrier(0);
     mfma_row(w, f[5], 5);
     mfma_row(w, f[6], 6);
     __builtin_amdgcn_sched_barrier(0);
-    issue(fill, kt + GEMM2_STAGES - 1, 1);
+    if (!ODD) issue_x(xfill, (kt >> 1) + 2, 1);
     __builtin_amdgcn_sched_barrier(0);
     mfma_row(w, f[7], 7);
     __builtin_amdgcn_sched_barrier(0);
-    stage = next;
+    wstage = wnext;
+    if (ODD) xblk = xnext;
   };
-  for (int kt = 0; kt < KT; kt += 2) {
-    step(wA, fA, wB, fB, kt);
-    if (kt + 1 >= KT) break;
-    step(wB, fB, wA, fA, kt + 1);
+  for (int kt = 0; kt < KT; kt += 2) {   // KT is even
+    step(std::false_type{}, wA, fA, wB, fB, kt);
+    step(std::true_type{}, wB, fB, wA, fA, kt + 1);
   }
   // the clamped loads past the last k tile are still in flight into LDS: they must land before the workgroup ends
   gemm2_wait_and_meet<0>();
@@ -373,19 +405,18 @@ __global__ __launch_bounds__(512, 2) void gemm_lds_kernel(GemmArgs a) {
 }
 
 static hipError_t launch_gemm_lds(const GemmArgs& a, hipStream_t s) {
-  constexpr size_t lds = (size_t)GEMM2_STAGES * GEMM2_STAGE_BYTES;
   static bool prepared[64] = {};
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
   if (!prepared[dev]) {   // more than the default 64 KiB of dynamic LDS: asked for once per device
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_lds_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_lds_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM2_LDS_BYTES);
     if (e != hipSuccess) return e;
     prepared[dev] = true;
   }
   const int tiles_m = (a.M + 255) / 256, tiles_n = (a.N + 255) / 256;
-  hipLaunchKernelGGL(gemm_lds_kernel, dim3(tiles_m * tiles_n), dim3(512), lds, s, a);
+  hipLaunchKernelGGL(gemm_lds_kernel, dim3(tiles_m * tiles_n), dim3(512), GEMM2_LDS_BYTES, s, a);
   return hipGetLastError();
 }
 
@@ -393,7 +424,7 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0 || (a.K & 31) || (a.N & 15) || a.K < 32) return hipErrorInvalidValue;
 #ifndef GEMM_NO_LDS_KERNEL
   // 256 x 256 tiles, one per CU, when they fill the chip at least once; else the smaller tiles below
-  if ((long)((a.M + 255) / 256) * ((a.N + 255) / 256) >= 256 && a.K >= 32 * GEMM2_STAGES) return launch_gemm_lds(a, s);
+  if ((long)((a.M + 255) / 256) * ((a.N + 255) / 256) >= 256 && (a.K & 63) == 0 && a.K >= 256) return launch_gemm_lds(a, s);
 #endif
   if (a.M >= 1024) return launch_gemm_wm<GEMM_WM_LARGE, GEMM_WAVES_LARGE>(a, s);
   if (a.M > 64) return launch_gemm_wm<8, 2>(a, s);   // 128 x 256
