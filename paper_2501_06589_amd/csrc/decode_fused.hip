@@ -279,6 +279,10 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
 // ------------------------------------------------------------------------------------------------
 // The workgroup has stored the final attention output of its (sequence, kv head): make it visible to the
 // device and count it, for the projection job of the same launch that consumes it.
+// (The counter is the word the consumers poll.  That is affordable for these few increments only: an atomic
+// on a cache line that hundreds of workgroups poll takes microseconds, and the workgroup keeps its CU slot
+// until the atomic has completed.  A producer job of many workgroups must count on one line and have the
+// workgroup that completes the count set a flag on another line, which the consumers poll.)
 __device__ __forceinline__ void attn_signal_done(const AttnJob& a) {
   if (!a.done) return;
   __syncthreads();   // every thread's stores are issued
