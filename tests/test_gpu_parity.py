@@ -304,6 +304,19 @@ def test_full_width_70b_r4_prefill_against_oracle(harness):
     deep_stack_check(res, w.n_layers)
 
 
+@pytest.mark.parametrize("hidden,inter,batch", [(1056, 1024, 12), (1024, 1184, 6)])
+def test_bf16_large_tile_gemm_ragged_edges(harness, hidden, inter, batch):
+    """The 256 x 256-tile GEMM serves the calls whose tiles fill the chip; here it gets a ragged last row
+    block (13200 and 6600 rows) and a ragged last column block: hidden 1056 = 4.1 column blocks for the O and
+    down projections (plain epilogue), 2 x 1184 = 9.3 column blocks for gate/up (SwiGLU epilogue).  The
+    projections whose K is not a multiple of 64 or whose grid is small take the other GEMM in the same call."""
+    w = inputs.WORKLOADS["70b_r4_prefill"].with_(name=f"ragged_tiles_{hidden}_{inter}", n_layers=1, hidden=hidden, inter=inter,
+                                                 n_q_heads=8, n_kv_heads=2, head_dim=64, batch=batch, prefill=1100,
+                                                 decode_steps=1)
+    res = harness.run_case(w, gen_device="cuda:0")
+    assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
+
+
 def test_seeded_shape_sweep(harness):
     """A fixed pseudo-random walk over shapes and switches (head size 64 / 128, 1 - 3 kv heads with 1 - 8 q
     heads each, ragged hidden / intermediate sizes incl. ones that fall back to the plain kernels, batch
