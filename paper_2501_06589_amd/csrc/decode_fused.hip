@@ -277,19 +277,40 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
 // The 8 wavefronts take the 32-key blocks of the split round robin, each with its own running
 // softmax and no barrier in the loop; they merge once, through LDS, at the end.
 // ------------------------------------------------------------------------------------------------
-// The workgroup has stored the final attention output of its (sequence, kv head): make it visible to the
-// device and count it, for the projection job of the same launch that consumes it.
+// Device-coherent stores / loads (agent-scope relaxed atomics: written through to memory, read past the caches
+// that are not coherent across the chip) for the few values one workgroup hands to another inside a launch.
+// A producer waits until its coherent stores have completed (s_waitcnt) before it takes a ticket or raises a
+// counter; a consumer reads the data with coherent loads after it has seen the ticket or the counter.  No
+// fence on either side: an agent-scope release writes back, and an acquire invalidates, the whole L2 of the XCD
+// under the weight streams that run beside (1.2 - 2.5 us each on this path).
+__device__ __forceinline__ void st_coherent(uint32_t* p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coherent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_coherent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// stores output element i (bf16) of a row of an even number of elements: lanes i and i ^ 1 pair up for one
+// 32-bit coherent store (all lanes of the wave must call)
+__device__ __forceinline__ void st_coherent_bf16_pair(bf16_t* row, int i, float v) {
+  const uint32_t h = f32_to_bf16(v);
+  const uint32_t other = __shfl_xor(h, 1, 64);
+  if ((i & 1) == 0) st_coherent(reinterpret_cast<uint32_t*>(row + i), h | (other << 16));
+}
+
+// The workgroup has stored the final attention output of its (sequence, kv head) with coherent stores: wait for
+// them and count it, for the projection job of the same launch that consumes it.
 // (The counter is the word the consumers poll.  That is affordable for these few increments only: an atomic
 // on a cache line that hundreds of workgroups poll takes microseconds, and the workgroup keeps its CU slot
 // until the atomic has completed.  A producer job of many workgroups must count on one line and have the
 // workgroup that completes the count set a flag on another line, which the consumers poll.)
 __device__ __forceinline__ void attn_signal_done(const AttnJob& a) {
   if (!a.done) return;
-  __syncthreads();   // every thread's stores are issued
-  if (threadIdx.x == 0) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-    atomicAdd(a.done, 1u);
-  }
+  __builtin_amdgcn_s_waitcnt(0);   // this thread's coherent stores of the output have completed
+  __syncthreads();
+  if (threadIdx.x == 0) atomicAdd(a.done, 1u);
 }
 
 template <int D, int G>
@@ -299,14 +320,31 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int b = lane & 15, q = lane >> 4;
   const int sp = lb % a.n_splits, kvh = (lb / a.n_splits) % a.nkv, bi = lb / (a.n_splits * a.nkv);
-  const int n_pos = *a.pos_dev + 1;
   const int pbeg = sp * a.split_len;
-  if (pbeg >= n_pos) return;  // nothing visible in this split: the workgroup leaves, no ticket taken
-  const int pend = min(n_pos, pbeg + a.split_len);
   const float scale = 1.0f / sqrtf((float)D);
 
   const bf16_t* kc = a.cache_k + ((size_t)bi * a.nkv + kvh) * a.max_seq * D;
   const bf16_t* vc = a.cache_v + ((size_t)bi * a.nkv + kvh) * D * a.max_seq;
+  uint4 kreg[2][DS], vreg[DT];
+  auto load_kv = [&](int kb) {   // keys kb .. kb + 31 (inside the cache's capacity)
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int s = 0; s < DS; ++s)
+        kreg[t][s] = *reinterpret_cast<const uint4*>(kc + (size_t)(kb + 16 * t + b) * D + s * 32 + q * 8);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const bf16_t* vp = vc + (size_t)(dt * 16 + b) * a.max_seq + kb + 4 * q;
+      const uint2 lo = *reinterpret_cast<const uint2*>(vp);
+      const uint2 hi = *reinterpret_cast<const uint2*>(vp + 16);
+      vreg[dt] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    }
+  };
+  // The wave's first key block and the queries are requested before the position is known (one memory round
+  // trip instead of two; a block beyond the new token is masked or never used).
+  const int kb0 = pbeg + 32 * wave;
+  const bool early = kb0 + 32 <= a.max_seq;
+  if (early) load_kv(kb0);
   const uint4 zero4 = make_uint4(0, 0, 0, 0);
   uint4 qreg[DS];
   {
@@ -317,26 +355,15 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
       qreg[s] = b < G ? v : zero4;
     }
   }
+  const int n_pos = *a.pos_dev + 1;
+  if (pbeg >= n_pos) return;  // nothing visible in this split: the workgroup leaves, no ticket taken
+  const int pend = min(n_pos, pbeg + a.split_len);
   f32x4_t oacc[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) oacc[dt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
   float mrun = -INFINITY, lrun = 0.f;
 
-  for (int kb = pbeg + 32 * wave; kb < pend; kb += 32 * FUSED_WAVES) {
-    uint4 kreg[2][DS];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int s = 0; s < DS; ++s)
-        kreg[t][s] = *reinterpret_cast<const uint4*>(kc + (size_t)(kb + 16 * t + b) * D + s * 32 + q * 8);
-    uint4 vreg[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      const bf16_t* vp = vc + (size_t)(dt * 16 + b) * a.max_seq + kb + 4 * q;
-      const uint2 lo = *reinterpret_cast<const uint2*>(vp);
-      const uint2 hi = *reinterpret_cast<const uint2*>(vp + 16);
-      vreg[dt] = make_uint4(lo.x, lo.y, hi.x, hi.y);
-    }
+  auto process = [&](int kb) {   // keys kb .. kb + 31, already in kreg / vreg
     f32x4_t st[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -378,6 +405,14 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
       oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vreg[dt]),
                                                         __builtin_bit_cast(bf16x8_t, pb), oacc[dt], 0, 0, 0);
     }
+  };
+  if (kb0 < pend) {
+    if (!early) load_kv(kb0);
+    process(kb0);
+  }
+  for (int kb = kb0 + 32 * FUSED_WAVES; kb < pend; kb += 32 * FUSED_WAVES) {
+    load_kv(kb);
+    process(kb);
   }
   // per-wave (max, sum, O^T) -> LDS; oacc[dt][r] = O^T[dim = dt*16 + 4q + r][head b]
   lrun += __shfl_xor(lrun, 16, 64);
@@ -407,12 +442,12 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
       o += wo[(w * G + h) * D + dim] * f;
     }
     if (a.n_splits == 1) {
-      a.o[(size_t)bi * a.nq * D + (size_t)(kvh * G + h) * D + dim] = f32_to_bf16(o / l);
+      st_coherent_bf16_pair(a.o + (size_t)bi * a.nq * D + (size_t)kvh * G * D, i, o / l);
     } else {
-      a.part_o[((pbase + sp) * G + h) * D + dim] = o;
+      st_coherent(a.part_o + ((pbase + sp) * G + h) * D + dim, o);
       if (dim == 0) {
-        a.part_ml[((pbase + sp) * G + h) * 2 + 0] = m;
-        a.part_ml[((pbase + sp) * G + h) * 2 + 1] = l;
+        st_coherent(a.part_ml + ((pbase + sp) * G + h) * 2 + 0, m);
+        st_coherent(a.part_ml + ((pbase + sp) * G + h) * 2 + 1, l);
       }
     }
   }
@@ -423,20 +458,19 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
 
   // several splits: the last one to arrive merges them (fixed order)
   const int n_active = min(a.n_splits, (n_pos + a.split_len - 1) / a.split_len);
+  __builtin_amdgcn_s_waitcnt(0);   // this thread's coherent stores of the partial result have completed
   __syncthreads();
   if (tid == 0) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
     const unsigned t = atomicAdd(a.tickets + bi * a.nkv + kvh, 1u);
     *s_flag = t;
     if (t == (unsigned)n_active - 1) a.tickets[bi * a.nkv + kvh] = 0u;  // ready for the next launch
   }
   __syncthreads();
   if (*s_flag != (unsigned)n_active - 1) return;
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-  // After the acquire the other splits' partial results are ordinary memory.  Every thread merges its
-  // own output elements from all splits, eight splits per pass with all of the pass's loads issued
+  // The last arrival reads the other splits' partial results with coherent loads.  Every thread merges its
+  // own output elements from all splits, sixteen splits per pass with all of the pass's loads issued
   // together (one memory round trip per pass), in split order.
-  constexpr int SP = 8;
+  constexpr int SP = 16;
   for (int i = tid; i < G * D; i += FUSED_THREADS) {
     const int h = i / D;
     float m = -INFINITY, l = 0.f, o = 0.f;
@@ -445,9 +479,9 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
 #pragma unroll
       for (int k = 0; k < SP; ++k) {
         const int s = min(s0 + k, n_active - 1);
-        ms[k] = a.part_ml[((pbase + s) * G + h) * 2 + 0];
-        ls[k] = a.part_ml[((pbase + s) * G + h) * 2 + 1];
-        os[k] = a.part_o[(pbase + s) * G * D + i];
+        ms[k] = ld_coherent(a.part_ml + ((pbase + s) * G + h) * 2 + 0);
+        ls[k] = ld_coherent(a.part_ml + ((pbase + s) * G + h) * 2 + 1);
+        os[k] = ld_coherent(a.part_o + (pbase + s) * G * D + i);
       }
       float mnew = m;
 #pragma unroll
@@ -463,7 +497,7 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
       }
       m = mnew;
     }
-    a.o[(size_t)bi * a.nq * D + (size_t)kvh * G * D + i] = f32_to_bf16(o / l);
+    st_coherent_bf16_pair(a.o + (size_t)bi * a.nq * D + (size_t)kvh * G * D, i, o / l);
   }
   attn_signal_done(a);
 }
