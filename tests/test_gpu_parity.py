@@ -235,10 +235,10 @@ def test_fused_decode_other_geometries(harness):
 
 @pytest.mark.parametrize("kv,batch,nq,nkv,d", [(2300, 2, 8, 1, 128), (5000, 3, 4, 2, 64), (9000, 1, 8, 1, 128)])
 def test_fused_decode_long_context_two_level_merge(harness, kv, batch, nq, nkv, d):
-    """Caches of thousands of positions are cut into more than eight attention splits per (sequence, kv head):
-    the splits meet in groups of eight and the groups once more.  2300 positions: 10 splits = a full group and
-    a ragged one; 5000: 20 splits in 3 groups; 9000: 36 splits in 5 groups.  Three steps each, so that the
-    tickets are re-used and the ragged last split grows."""
+    """Caches of thousands of positions are cut into many attention splits per (sequence, kv head), which the
+    last split to arrive merges in passes of sixteen: 2300 positions = 10 splits (one ragged pass), 5000 = 20
+    splits (two passes), 9000 = 36 splits (three passes).  Three steps each, so that the tickets are re-used
+    and the ragged last split grows."""
     w = inputs.WORKLOADS["70b_r8_decode"].with_(name=f"long_ctx_{kv}", n_layers=2, hidden=256, inter=256, n_q_heads=nq,
                                                 n_kv_heads=nkv, head_dim=d, batch=batch, prefill=0, kv_preload=kv,
                                                 decode_steps=3)
