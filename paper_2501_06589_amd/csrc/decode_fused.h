@@ -19,7 +19,8 @@ struct GemvJob {
   const void* wp;
   int M, K, N;
   // wait_on != null: the job's x operand is produced by the attention job of the SAME launch; the
-  // workgroup starts by waiting (bounded) until *wait_on has reached wait_target, then acquires
+  // workgroup starts by waiting (bounded) until *wait_on has reached wait_target, then reads that operand
+  // with device-coherent loads
   const unsigned* wait_on;
   unsigned wait_target;
   int tn;                  // 16-column tiles per workgroup: 1 (0 means 1) or 2
@@ -60,8 +61,9 @@ struct AttnJob {
   int B, nq, nkv, max_seq;
   int n_splits, split_len; // split s covers positions [s*split_len, (s+1)*split_len); split_len % 64 == 0
   const int* pos_dev;      // position of the new token; positions 0..*pos_dev are visible
-  unsigned* done;          // if non-null: incremented (after a release) by the workgroup that has written the final
-                           // output of its (sequence, kv head); a projection job of the same launch waits on it
+  unsigned* done;          // if non-null: incremented by the workgroup that has written the final output of its
+                           // (sequence, kv head), once its device-coherent stores have completed; a projection
+                           // job of the same launch waits on it
 };
 
 #define FUSED_MAX_LDS_BYTES (72 * 1024)

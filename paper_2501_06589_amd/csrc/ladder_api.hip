@@ -576,11 +576,10 @@ void build_fused_plan(ladder_ctx* c, int B) {
     // Attention and gate/up, and the next layer's QKV and down, do not depend on each other under the
     // ladder wiring.  The attention workgroups are few and latency bound: beside the largest weight stream
     // they cost nothing.  o_l does depend on attention_l: its workgroups wait (asleep) on a per-layer arrival
-    // counter that the attention workgroups raise after a release, and read the attention output with
-    // device-coherent loads.  A workgroup only ever waits for workgroups with lower block indices, which
+    // counter that the attention workgroups raise once their device-coherent stores of the output have
+    // completed, and read the attention output with device-coherent loads (no fence on either side).  A workgroup only ever waits for workgroups with lower block indices, which
     // were dispatched before it and wait for nothing, so the wait always ends (it is bounded all the same).
-    // This is the one cross-workgroup dependency of the path (20 producers that fence, 256 consumers that
-    // do not): o_l streams beside gate/up instead of in a launch of its own at a third of the streaming
+    // This is the one dependency between jobs of a launch (20 producers, 256 consumers): o_l streams beside gate/up instead of in a launch of its own at a third of the streaming
     // rate (4.03 -> 3.87 ms per step on the 70B shard).  An acquire fence in the consumers instead of
     // coherent loads made the step 5.1 ms (an agent-scope acquire empties the L2 under the weight streams);
     // o_l at the end of the launch instead of among the first workgroups 4.1 ms (it then runs after
