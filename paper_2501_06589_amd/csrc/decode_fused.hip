@@ -73,9 +73,12 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
   const int b = lane & 15, q = lane >> 4;
   const int nt0 = grp * TN;
   const int KT = j.K >> 5;
-  const int per_wave = (KT + WAVES - 1) / WAVES;
-  const int kt0 = wave * per_wave;
-  const int kt1 = min(KT, kt0 + per_wave);
+  // The wavefronts take groups of U k tiles round robin, so that the workgroup as a whole sweeps its weight range
+  // once, 8 U tiles (32 KiB) at a time: measured 3 % faster over a decode step than a contiguous eighth of the
+  // range per wavefront (DRAM page locality); tile-wise round robin and 2 U tiles per turn were slower.
+  constexpr int KB = WAVES * U, KA = 2 * WAVES * U;   // tile distance to the second register buffer / to the next turn
+  const int kt0 = wave * U;
+  const int kt1 = KT;
 
   if (j.wait_on) {
     // The x operand comes from the attention job of this launch.  Its workgroups have lower block indices,
@@ -169,14 +172,14 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
 
   if (kt0 < kt1) load(wa, xa, kt0);
   if (kt0 < kt1) {
-    for (int kt = kt0; kt < kt1; kt += 2 * U) {
-      load(wb, xb, kt + U);
+    for (int kt = kt0; kt < kt1; kt += KA) {
+      load(wb, xb, kt + KB);
       __builtin_amdgcn_sched_barrier(0);
       fma(wa, xa, kt);
       __builtin_amdgcn_sched_barrier(0);
-      load(wa, xa, kt + 2 * U);
+      load(wa, xa, kt + KA);
       __builtin_amdgcn_sched_barrier(0);
-      fma(wb, xb, kt + U);
+      fma(wb, xb, kt + KB);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
