@@ -41,8 +41,14 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 
 #define FUSED_THREADS 512
 #define FUSED_WAVES 8
+// k tiles per register buffer (two buffers) of a one-tile / a two-tile workgroup: 4 KiB of weights in flight
+// per wavefront.  With the round-robin assignment of k tiles below, 2 beat 4 (3.57 against 3.65 ms per step;
+// 1 gave 4.04, 3 gave 3.74: its turns do not divide the k range)
 #ifndef FUSED_U
-#define FUSED_U 4    // k tiles per register buffer (two buffers): 8 KiB of weights in flight per wavefront
+#define FUSED_U 2
+#endif
+#ifndef FUSED_U2
+#define FUSED_U2 1
 #endif
 #define FUSED_LDS_FLOATS 9216   // attention job: per-wave statistics and outputs
 
@@ -74,7 +80,7 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
   const int nt0 = grp * TN;
   const int KT = j.K >> 5;
   // The wavefronts take groups of U k tiles round robin, so that the workgroup as a whole sweeps its weight range
-  // once, 8 U tiles (32 KiB) at a time: measured 3 % faster over a decode step than a contiguous eighth of the
+  // once, 8 U tiles (16 KiB) at a time: measured 3 % faster over a decode step than a contiguous eighth of the
   // range per wavefront (DRAM page locality); tile-wise round robin and 2 U tiles per turn were slower.
   constexpr int KB = WAVES * U, KA = 2 * WAVES * U;   // tile distance to the second register buffer / to the next turn
   const int kt0 = wave * U;
@@ -544,11 +550,11 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(FusedArg
   } else {
     const GemvJob& j = fa.g[job];
     if (j.wait_on) {   // (the plan gives only the un-normed O projection a wait)
-      if (j.tn == 2) gemv_job<false, FUSED_U / 2, 2, true>(j, lb, smem);
+      if (j.tn == 2) gemv_job<false, FUSED_U2, 2, true>(j, lb, smem);
       else gemv_job<false, FUSED_U, 1, true>(j, lb, smem);
     } else if (j.tn == 2) {
-      if (j.normed) gemv_job<true, FUSED_U / 2, 2>(j, lb, smem);
-      else gemv_job<false, FUSED_U / 2, 2>(j, lb, smem);
+      if (j.normed) gemv_job<true, FUSED_U2, 2>(j, lb, smem);
+      else gemv_job<false, FUSED_U2, 2>(j, lb, smem);
     } else {
       if (j.normed) gemv_job<true, FUSED_U, 1>(j, lb, smem);
       else gemv_job<false, FUSED_U, 1>(j, lb, smem);
