@@ -531,21 +531,23 @@ struct FusedTraceScope {
 };
 #endif
 
+// The first four arguments repeat fa.block_end[0..2] and fa.kind[] (one byte per job): with kernel-argument
+// preloading (the build passes -mllvm -amdgpu-kernarg-preload-count=4) they are in SGPRs when a wave starts, so
+// a workgroup knows its job at once and the load of the job's descriptor is the FIRST memory round trip of the
+// wave, not the second (a cold scalar load costs about 2 us here, and nothing can be requested before it).
+static_assert(FUSED_MAX_JOBS == 4, "the preloaded arguments carry three block boundaries and four kinds");
 template <int D, int G>
-__global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(FusedArgs fa) {
+__global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(int end0, int end1, int end2, unsigned kinds, FusedArgs fa) {
   extern __shared__ float smem[];   // fa.lds_bytes: the largest need of the launch's jobs
   __shared__ unsigned s_flag;
 #ifdef FUSED_TRACE
   FusedTraceScope trace_scope;
 #endif
   int lb = blockIdx.x, job = 0;
-#pragma unroll
-  for (int i = 0; i + 1 < FUSED_MAX_JOBS; ++i)
-    if ((int)blockIdx.x >= fa.block_end[i]) {
-      lb = blockIdx.x - fa.block_end[i];
-      job = i + 1;
-    }
-  if (fa.kind[job] == JOB_ATTN) {
+  if ((int)blockIdx.x >= end0) { lb = blockIdx.x - end0; job = 1; }
+  if ((int)blockIdx.x >= end1) { lb = blockIdx.x - end1; job = 2; }
+  if ((int)blockIdx.x >= end2) { lb = blockIdx.x - end2; job = 3; }
+  if (((kinds >> (8 * job)) & 0xFFu) == (unsigned)JOB_ATTN) {
     attn_job<D, G>(fa.a, lb, smem, &s_flag);
   } else {
     const GemvJob& j = fa.g[job];
@@ -587,12 +589,16 @@ template <int D>
 static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
   const dim3 block(FUSED_THREADS);
   // with events: the dispatch itself carries them, so their distance is the kernel's own run time
+  unsigned kinds = 0;
+  for (int i = 0; i < FUSED_MAX_JOBS; ++i) kinds |= ((unsigned)fa.kind[i] & 0xFFu) << (8 * i);
 #define FUSED_LAUNCH(GQ)                                                                                    \
   do {                                                                                                      \
     if (ev0 || ev1)                                                                                          \
-      hipExtLaunchKernelGGL((fused_decode_kernel<D, GQ>), grid, block, fa.lds_bytes, s, ev0, ev1, 0, fa);    \
+      hipExtLaunchKernelGGL((fused_decode_kernel<D, GQ>), grid, block, fa.lds_bytes, s, ev0, ev1, 0,         \
+                            fa.block_end[0], fa.block_end[1], fa.block_end[2], kinds, fa);                  \
     else                                                                                                    \
-      hipLaunchKernelGGL((fused_decode_kernel<D, GQ>), grid, block, fa.lds_bytes, s, fa);                    \
+      hipLaunchKernelGGL((fused_decode_kernel<D, GQ>), grid, block, fa.lds_bytes, s,                         \
+                         fa.block_end[0], fa.block_end[1], fa.block_end[2], kinds, fa);                     \
   } while (0)
   switch (g) {
     case 1: FUSED_LAUNCH(1); break;
