@@ -481,6 +481,9 @@ void build_fused_plan(ladder_ctx* c, int B) {
     j.cache_k = (bf16_t*)layer(l).cache_k; j.cache_v = (bf16_t*)layer(l).cache_v;
     j.cos_tab = c->cos_tab; j.sin_tab = c->sin_tab; j.pos_dev = c->pos_dev;
     j.nq = nq; j.nkv = nkv; j.d = d; j.max_seq = c->s_cap;
+    // short K range: two tiles per workgroup (8B shape, batch 4: 2.90 -> 2.81 ms per step; 1.2B: 0.86 -> 0.83);
+    // over hidden 8192 one tile is already 256 KiB and two were slower
+    if (H <= 4096 && j.n_groups % 2 == 0) { j.tn = 2; j.n_groups /= 2; }
     return j;
   };
   auto residual = [&](GemvJob& j, int m) {
@@ -507,7 +510,8 @@ void build_fused_plan(ladder_ctx* c, int B) {
     // every workgroup reads the batch's rows of x over its whole K range (from L2): at 13 rows and more that
     // traffic is worth halving with two tiles per workgroup (70B shard, batch 14 / 16: 5.42 -> 5.09 / 5.80 -> 5.31
     // ms per step; batch 12 and less: slower; for QKV and down: slower at every batch)
-    if (B >= 13 && j.n_groups % 2 == 0) { j.tn = 2; j.n_groups /= 2; }
+    // (and when the K range is short, a tile of it is too little work for a workgroup: 1.2B shape 0.89 -> 0.86 ms)
+    if ((B >= 13 || H <= 2048) && j.n_groups % 2 == 0) { j.tn = 2; j.n_groups /= 2; }
     return j;
   };
   auto job_dn = [&](int l, int m) {
