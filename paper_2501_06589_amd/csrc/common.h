@@ -163,6 +163,15 @@ struct GemmArgs {
   float* out;              // epilogue 0: f32 [M][N] (row stride N)
   bf16_t* act;             // epilogue 1: SwiGLU -> bf16 [M][N/2]
   int epilogue;
+  // epilogue 2: the columns are q | k | v heads of d columns each; row m is token m % T of sequence m / T at
+  // position pos0 + m % T: rotary embedding of q and k (adjacent pairs), q -> q_out bf16 [M][nq*d], k and v ->
+  // the cache (k [seq][nkv][max_seq][d], v transposed [seq][nkv][d][max_seq])
+  bf16_t* q_out;
+  bf16_t* cache_k;
+  bf16_t* cache_v;
+  const float* cos_tab;    // [max_seq][d/2]
+  const float* sin_tab;
+  int T, pos0, nq, nkv, d, max_seq;
 };
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s);
 

@@ -263,7 +263,15 @@ int run_module(ladder_ctx* c, int m, int B, int T, int pos0, hipStream_t s, int*
         HIP_TRY(c, timed(c, LADDER_K_GEMV, s, [&] { return launch_gemv(a, s); }));
       } else {
         GemmArgs a{};
-        a.x = (const bf16_t*)yin; a.ldx = H; a.wp = L.pqkv; a.M = rows; a.K = H; a.N = c->nqkv; a.out = c->qkv; a.epilogue = 0;
+        a.x = (const bf16_t*)yin; a.ldx = H; a.wp = L.pqkv; a.M = rows; a.K = H; a.N = c->nqkv;
+        if (!dev_pos) {
+          // rotary embedding and cache append are the GEMM's epilogue (no fp32 q|k|v round trip through memory)
+          a.epilogue = 2; a.q_out = (bf16_t*)c->qbuf; a.cache_k = (bf16_t*)L.cache_k; a.cache_v = (bf16_t*)L.cache_v;
+          a.cos_tab = c->cos_tab; a.sin_tab = c->sin_tab; a.T = T; a.pos0 = pos0; a.nq = nq; a.nkv = nkv; a.d = d; a.max_seq = c->s_cap;
+          qkv_slots = 0;
+        } else {   // (a decode step of more than 64 sequences: the position lives in device memory)
+          a.out = c->qkv; a.epilogue = 0;
+        }
         HIP_TRY(c, timed(c, LADDER_K_GEMM, s, [&] { return launch_gemm_mfma(a, s); }));
       }
       RopeAppendArgs ra{};
@@ -271,7 +279,7 @@ int run_module(ladder_ctx* c, int m, int B, int T, int pos0, hipStream_t s, int*
       ra.q_out = c->qbuf; ra.cache_k = L.cache_k; ra.cache_v = L.cache_v;
       ra.cos_tab = c->cos_tab; ra.sin_tab = c->sin_tab;
       ra.B = B; ra.T = T; ra.pos0 = pos0; ra.nq = nq; ra.nkv = nkv; ra.d = d; ra.max_seq = c->s_cap; ra.pos_dev = dev_pos ? c->pos_dev : nullptr;
-      HIP_TRY(c, timed(c, LADDER_K_ROPE_APPEND, s, [&] { return launch_rope_append(ra, c->bf16, s); }));
+      if (qkv_slots > 0) HIP_TRY(c, timed(c, LADDER_K_ROPE_APPEND, s, [&] { return launch_rope_append(ra, c->bf16, s); }));
       if (!c->fast) {
         AttnGenericArgs aa{c->qbuf, L.cache_k, L.cache_v, c->obuf, B, T, pos0, nq, nkv, d, c->s_cap};
         HIP_TRY(c, timed(c, LADDER_K_GENERIC, s, [&] { return launch_attn_generic(aa, c->bf16, s); }));

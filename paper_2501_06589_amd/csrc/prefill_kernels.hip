@@ -54,6 +54,43 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x4_t (&acc)[
             make_float4(acc[j][mt][0], acc[j][mt][1], acc[j][mt][2], acc[j][mt][3]);
       }
     }
+  } else if (a.epilogue == 2) {
+    // rotary embedding + cache append: a lane's 4 columns are two adjacent pairs of one head
+    const int half = a.d >> 1;
+#pragma unroll
+    for (int mt = 0; mt < WM; ++mt) {
+      const int m = m0 + mt * 16 + b;
+      if (m >= a.M) continue;
+      const int seq = m / a.T, pos = a.pos0 + m % a.T;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (nt0 + j >= NT) continue;
+        const int col = (nt0 + j) * 16 + 4 * q;
+        const int head = col / a.d, dim = col % a.d;
+        float v4[4] = {acc[j][mt][0], acc[j][mt][1], acc[j][mt][2], acc[j][mt][3]};
+        if (head < a.nq + a.nkv) {
+#pragma unroll
+          for (int p = 0; p < 2; ++p) {
+            const float c = a.cos_tab[(size_t)pos * half + (dim >> 1) + p], sn = a.sin_tab[(size_t)pos * half + (dim >> 1) + p];
+            const float e = v4[2 * p], o = v4[2 * p + 1];
+            v4[2 * p] = e * c - o * sn;
+            v4[2 * p + 1] = e * sn + o * c;
+          }
+        }
+        if (head < a.nq + a.nkv) {
+          uint2 pk;
+          pk.x = (uint32_t)f32_to_bf16(v4[0]) | ((uint32_t)f32_to_bf16(v4[1]) << 16);
+          pk.y = (uint32_t)f32_to_bf16(v4[2]) | ((uint32_t)f32_to_bf16(v4[3]) << 16);
+          bf16_t* dst = head < a.nq ? a.q_out + (size_t)m * a.nq * a.d + head * a.d + dim
+                                    : a.cache_k + (((size_t)seq * a.nkv + (head - a.nq)) * a.max_seq + pos) * a.d + dim;
+          *reinterpret_cast<uint2*>(dst) = pk;
+        } else {
+          bf16_t* vt = a.cache_v + (((size_t)seq * a.nkv + (head - a.nq - a.nkv)) * a.d + dim) * a.max_seq + pos;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) vt[(size_t)r * a.max_seq] = f32_to_bf16(v4[r]);
+        }
+      }
+    }
   } else {
     // SwiGLU: tile columns 0..7 = gate columns 8nt..8nt+7 (lanes q = 0, 1), columns 8..15 = the matching
     // up columns (lanes q = 2, 3): lane + 32 holds the up partner of this lane's gate value.
