@@ -519,7 +519,10 @@ void build_fused_plan(ladder_ctx* c, int B) {
     // traffic is worth halving with two tiles per workgroup (70B shard, batch 14 / 16: 5.42 -> 5.09 / 5.80 -> 5.31
     // ms per step; batch 12 and less: slower; for QKV and down: slower at every batch)
     // (and when the K range is short, a tile of it is too little work for a workgroup: 1.2B shape 0.89 -> 0.86 ms)
-    if ((B >= 13 || H <= 2048) && j.n_groups % 2 == 0) { j.tn = 2; j.n_groups /= 2; }
+    // (and when pairs of tiles fit the chip in one round, one workgroup per CU, instead of two rounds of single
+    // tiles: 70B shard at R = 8, batch 4: 3.51 -> 3.41 ms)
+    // (measured: batch 1 - 6 faster, 7 - 12 slower)
+    if ((B >= 13 || H <= 2048 || (j.n_groups / 2 <= c->n_cu && B <= 6)) && j.n_groups % 2 == 0) { j.tn = 2; j.n_groups /= 2; }
     return j;
   };
   auto job_dn = [&](int l, int m) {
