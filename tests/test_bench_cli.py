@@ -1,0 +1,21 @@
+"""Host-side behaviour of bench.py that needs no GPU."""
+import os
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "one GPU" in (res.stdout + res.stderr)
+
+
+def test_profiled_traffic_is_read_from_the_committed_summary():
+    sys.path.insert(0, ROOT)
+    import bench
+    t = bench.read_profiled_traffic("fused_decode", "70b_r8_decode")
+    assert t is not None and 90e6 < t < 140e6, t   # bytes per launch; algorithmic: 107.9e6
+    assert bench.read_profiled_traffic("fused_decode", "no_such_workload") is None
