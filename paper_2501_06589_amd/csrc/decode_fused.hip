@@ -152,18 +152,25 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
   };
   // The epilogue's own operands do not depend on the product: they are requested now, before the
   // weight stream, so their memory latency is hidden behind it instead of trailing the last tile.
+  // (a thread owns output elements tid, tid + 512, ...: one for one or two tiles per workgroup, two for three)
   constexpr int PRE_PEERS = 8;
-  float pre_old = 0.f, pre_cos = 0.f, pre_sin = 0.f;
-  uint16_t pre_peer[PRE_PEERS];
+  constexpr int E_RES = (TN * 256 + FUSED_THREADS - 1) / FUSED_THREADS;   // residual epilogue: elements per thread
+  float pre_old[E_RES], pre_cos = 0.f, pre_sin = 0.f;
+  uint16_t pre_peer[E_RES][PRE_PEERS];
   int pre_pos = 0;
   if (j.epi == EPI_RESIDUAL) {
-    if (tid < TN * 256) {
-      const int t = tid >> 8, row = min((tid >> 4) & 15, j.M - 1), col = (nt0 + t) * 16 + (tid & 15);
-      pre_old = j.x_old[(size_t)row * j.N + col];
-      if (j.n_peers > 0) {
 #pragma unroll
-        for (int p = 0; p < PRE_PEERS; ++p)
-          pre_peer[p] = j.peers[min(p, j.n_peers - 1) * j.peer_stride + (size_t)row * j.N + col];
+    for (int e = 0; e < E_RES; ++e) {
+      const int idx = tid + e * FUSED_THREADS;
+      pre_old[e] = 0.f;
+      if (idx < TN * 256) {
+        const int t = idx >> 8, row = min((idx >> 4) & 15, j.M - 1), col = (nt0 + t) * 16 + (idx & 15);
+        pre_old[e] = j.x_old[(size_t)row * j.N + col];
+        if (j.n_peers > 0) {
+#pragma unroll
+          for (int p = 0; p < PRE_PEERS; ++p)
+            pre_peer[e][p] = j.peers[min(p, j.n_peers - 1) * j.peer_stride + (size_t)row * j.N + col];
+        }
       }
     }
   } else if (j.epi == EPI_QKV_ROPE) {
@@ -231,14 +238,17 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
   }
 
   if (j.epi == EPI_RESIDUAL) {
-    if (tid < TN * 256) {
-      const int t = tid >> 8, row = (tid >> 4) & 15, col16 = tid & 15;
+#pragma unroll
+    for (int e = 0; e < E_RES; ++e) {
+      const int idx = tid + e * FUSED_THREADS;
+      if (idx >= TN * 256) break;
+      const int t = idx >> 8, row = (idx >> 4) & 15, col16 = idx & 15;
       const int col = (nt0 + t) * 16 + col16;
       if (row < j.M) {
-        float v = pre_old + out_of(t, col16, row);
+        float v = pre_old[e] + out_of(t, col16, row);
 #pragma unroll
         for (int p = 0; p < PRE_PEERS; ++p)
-          if (p < j.n_peers) v += bf16_to_f32(pre_peer[p]);
+          if (p < j.n_peers) v += bf16_to_f32(pre_peer[e][p]);
         for (int p = PRE_PEERS; p < j.n_peers; ++p) v += bf16_to_f32(j.peers[p * j.peer_stride + (size_t)row * j.N + col]);
         j.x_new[(size_t)row * j.N + col] = v;
         j.xh_new[(size_t)row * j.N + col] = f32_to_bf16(v);   // what the projections that read x_m multiply
@@ -554,6 +564,8 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(int end0
     if (j.wait_on) {   // (the plan gives only the un-normed O projection a wait)
       if (j.tn == 2) gemv_job<false, FUSED_U2, 2, true>(j, lb, smem);
       else gemv_job<false, FUSED_U, 1, true>(j, lb, smem);
+    } else if (j.tn == 3) {   // (the plan builds three-tile workgroups for un-normed projections only)
+      gemv_job<false, 1, 3>(j, lb, smem);
     } else if (j.tn == 2) {
       if (j.normed) gemv_job<true, FUSED_U2, 2>(j, lb, smem);
       else gemv_job<false, FUSED_U2, 2>(j, lb, smem);
@@ -614,7 +626,7 @@ static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStrea
 // LDS a job needs: the attention job's merge area or the GEMV job's cross-wave sums
 size_t fused_attn_lds_bytes(int d, int g) { return (size_t)(2 * FUSED_WAVES * 16 + FUSED_WAVES * g * d + g * 64) * 4; }
 size_t fused_gemv_lds_bytes() {
-  return (size_t)(FUSED_WAVES * 2 * 16 * 17 + FUSED_WAVES * 16) * 4;   // sized for two-tile workgroups
+  return (size_t)(FUSED_WAVES * 3 * 16 * 17 + FUSED_WAVES * 16) * 4;   // sized for three-tile workgroups
 }
 
 // dynamic LDS above 64 KiB has to be allowed per kernel, once (outside any stream capture)

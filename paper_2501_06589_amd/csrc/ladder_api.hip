@@ -588,7 +588,7 @@ void build_fused_plan(ladder_ctx* c, int B) {
       std::vector<long long> load((size_t)c->n_cu, 0);
       int idx = 0;
       for (const GemvJob& j : jobs)
-        for (int w = 0; w < blocks_of(j) && idx < slots; ++w, ++idx) load[(size_t)(idx % c->n_cu)] += (long long)(j.tn == 2 ? 2 : 1) * j.K * 32;
+        for (int w = 0; w < blocks_of(j) && idx < slots; ++w, ++idx) load[(size_t)(idx % c->n_cu)] += (long long)std::max(1, j.tn) * j.K * 32;
       return *std::max_element(load.begin(), load.end());
     };
     const int over = blocks_of(qkv) + blocks_of(dn) - slots;
@@ -597,6 +597,18 @@ void build_fused_plan(ladder_ctx* c, int B) {
     if (mixed_o) {
       dbl_o.tn = 2; dbl_o.group0 = 0; dbl_o.n_groups = over;                      // tiles [0, 2 * over)
       sgl_o.group0 = 2 * over; sgl_o.n_groups = blocks_of(dn) - 2 * over;         // tiles [2 * over, end)
+    }
+    // Better still where it fits: ONE workgroup per CU, down in workgroups of three and two tiles beside QKV's
+    // (two streaming workgroups that share a CU run below the rate of one: 70B shard 160 x 3 + 16 x 2 tiles + 80
+    // QKV workgroups on 256 CUs: 3.39 -> 3.35 ms per step)
+    const int n_dn = c->n_cu - blocks_of(qkv);
+    if (dn.tn != 2 && blocks_of(dn) % 2 == 0 && n_dn > 0 && 2 * n_dn <= blocks_of(dn) && blocks_of(dn) <= 3 * n_dn) {
+      const int a3 = (blocks_of(dn) - 2 * n_dn) & ~1;      // workgroups of three tiles (even, so that the pairs start on an even tile)
+      const int b2 = (blocks_of(dn) - 3 * a3) / 2;         // workgroups of two tiles
+      GemvJob tri = dn, dbl = dn;
+      tri.tn = 3; tri.group0 = 0; tri.n_groups = a3;                 // tiles [0, 3 a3)
+      dbl.tn = 2; dbl.group0 = 3 * a3 / 2; dbl.n_groups = b2;        // tiles [3 a3, end)
+      if (a3 + b2 + blocks_of(qkv) <= c->n_cu + 1) return several({tri, qkv, dbl});
     }
     if (dn.tn != 2 && n_pairs > 0 && 2 * n_pairs <= blocks_of(dn) && c->n_cu + blocks_of(dn) - 2 * n_pairs <= slots) {
       GemvJob dbl = dn, sgl = dn;
