@@ -41,6 +41,13 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 
 #define FUSED_THREADS 512
 #define FUSED_WAVES 8
+// descriptor byte of a job in the preloaded `kinds` argument of the kernel
+#define FUSED_KIND_MASK 3u          // JOB_NONE / JOB_GEMV / JOB_ATTN
+#define FUSED_KIND_TN_SHIFT 2       // two bits: tiles per workgroup (1, 2, 3)
+#define FUSED_KIND_NORMED 16u       // the job folds RMSNorm in
+#define FUSED_KIND_WAITS 32u        // the job waits for another job of the launch
+#define FUSED_KIND_SLOT_SHIFT 6     // two bits: index of the job's preloaded (weights, K / 32 | group0) pair, 3 = none
+
 // k tiles per register buffer (two buffers) of a one-tile / a two-tile workgroup: 4 KiB of weights in flight
 // per wavefront.  With the round-robin assignment of k tiles below, 2 beat 4 (3.57 against 3.65 ms per step;
 // 1 gave 4.04, 3 gave 3.74: its turns do not divide the k range)
@@ -70,21 +77,41 @@ __device__ __forceinline__ void unpack8f(const uint4 v, float f[8]) {
 // set by the workgroup with the most bytes: one tile per workgroup keeps the jobs of a launch even
 // and the number of streaming workgroups high.
 // ------------------------------------------------------------------------------------------------
+// wp, KT and group0 repeat j.wp, j.K / 32 and j.group0: the kernel hands them over from preloaded kernel
+// arguments where it can, so that the first weight tiles are requested before the job's descriptor (j) has
+// arrived from memory.
 template <bool NORMED, int U, int TN, bool COH = false>
-__device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
+__device__ void gemv_job(const GemvJob& j, const void* wp, int KT, int group0, int lb, float* smem) {
   constexpr int WAVES = FUSED_WAVES;
-  const int grp = j.group0 + lb;
+  const int grp = group0 + lb;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int b = lane & 15, q = lane >> 4;
   const int nt0 = grp * TN;
-  const int KT = j.K >> 5;
   // The wavefronts take groups of U k tiles round robin, so that the workgroup as a whole sweeps its weight range
   // once, 8 U tiles (16 KiB) at a time: measured 3 % faster over a decode step than a contiguous eighth of the
   // range per wavefront (DRAM page locality); tile-wise round robin and 2 U tiles per turn were slower.
   constexpr int KB = WAVES * U, KA = 2 * WAVES * U;   // tile distance to the second register buffer / to the next turn
   const int kt0 = wave * U;
   const int kt1 = KT;
+
+  f32x4_t acc[TN];
+#pragma unroll
+  for (int t = 0; t < TN; ++t) acc[t] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+  float ss = 0.f;  // NORMED: this lane's share of its row's sum of squares
+  const u32x4_t* wptr = reinterpret_cast<const u32x4_t*>(wp) + ((size_t)nt0 * KT) * 64 + lane;
+  u32x4_t wa[TN][U], wb[TN][U], xa[U], xb[U];
+  auto loadw = [&](u32x4_t (&wv)[TN][U], int kt) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int ktc = min(kt + u, kt1 - 1);
+#pragma unroll
+      for (int t = 0; t < TN; ++t) wv[t][u] = __builtin_nontemporal_load(wptr + ((size_t)t * KT + ktc) * 64);
+    }
+  };
+  // the first weight tiles depend on nothing but the (preloaded) arguments: requested before anything else
+  if (kt0 < kt1) loadw(wa, kt0);
+  __builtin_amdgcn_sched_barrier(0);
 
   if (j.wait_on) {
     // The x operand comes from the attention job of this launch.  Its workgroups have lower block indices,
@@ -101,23 +128,15 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
                        // under the weight streams that run beside)
   }
 
-  f32x4_t acc[TN];
-#pragma unroll
-  for (int t = 0; t < TN; ++t) acc[t] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-  float ss = 0.f;  // NORMED: this lane's share of its row's sum of squares
-  const u32x4_t* wptr = reinterpret_cast<const u32x4_t*>(j.wp) + ((size_t)nt0 * KT) * 64 + lane;
   const bool rowok = b < j.M;
   const int rowc = min(b, j.M - 1);
 
   const bf16_t* xbp = j.xb + (size_t)rowc * j.ldx + q * 8;
 
-  u32x4_t wa[TN][U], wb[TN][U], xa[U], xb[U];
-  auto load = [&](u32x4_t (&wv)[TN][U], u32x4_t (&xv)[U], int kt) {
+  auto loadx = [&](u32x4_t (&xv)[U], int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int ktc = min(kt + u, kt1 - 1);
-#pragma unroll
-      for (int t = 0; t < TN; ++t) wv[t][u] = __builtin_nontemporal_load(wptr + ((size_t)t * KT + ktc) * 64);
       if (COH) {   // operand written by another workgroup of this launch: device-coherent loads, past L1 and the XCD's L2
         const unsigned long long* p8 = reinterpret_cast<const unsigned long long*>(xbp + (size_t)ktc * 32);
         const unsigned long long lo = __hip_atomic_load(p8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -127,6 +146,10 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
         xv[u] = *reinterpret_cast<const u32x4_t*>(xbp + (size_t)ktc * 32);
       }
     }
+  };
+  auto load = [&](u32x4_t (&wv)[TN][U], u32x4_t (&xv)[U], int kt) {
+    loadw(wv, kt);
+    loadx(xv, kt);
   };
   auto fma = [&](const u32x4_t (&wv)[TN][U], const u32x4_t (&xv)[U], int kt) {
 #pragma unroll
@@ -183,7 +206,7 @@ __device__ void gemv_job(const GemvJob& j, int lb, float* smem) {
     }
   }
 
-  if (kt0 < kt1) load(wa, xa, kt0);
+  if (kt0 < kt1) loadx(xa, kt0);
   if (kt0 < kt1) {
     for (int kt = kt0; kt < kt1; kt += KA) {
       load(wb, xb, kt + KB);
@@ -541,13 +564,17 @@ struct FusedTraceScope {
 };
 #endif
 
-// The first four arguments repeat fa.block_end[0..2] and fa.kind[] (one byte per job): with kernel-argument
-// preloading (the build passes -mllvm -amdgpu-kernarg-preload-count=4) they are in SGPRs when a wave starts, so
-// a workgroup knows its job at once and the load of the job's descriptor is the FIRST memory round trip of the
-// wave, not the second (a cold scalar load costs about 2 us here, and nothing can be requested before it).
-static_assert(FUSED_MAX_JOBS == 4, "the preloaded arguments carry three block boundaries and four kinds");
+// The leading arguments repeat what a workgroup needs first: the block boundaries of the jobs, one descriptor
+// byte per job (FUSED_KIND_* below) and, for the first three GEMV jobs of the launch, weight pointer, K / 32
+// and first tile group.  With kernel-argument preloading (the build passes -mllvm
+// -amdgpu-kernarg-preload-count=10) they are in SGPRs when a wave starts: a workgroup knows its job and requests
+// its first weight tiles at once, while the job's descriptor is still on its way from memory (a cold scalar
+// load costs 0.7 - 2 us here, and it used to stand in front of every workgroup's first request).
+static_assert(FUSED_MAX_JOBS == 4, "the preloaded arguments carry three block boundaries and four descriptor bytes");
 template <int D, int G>
-__global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(int end0, int end1, int end2, unsigned kinds, FusedArgs fa) {
+__global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(int end0, int end1, int end2, unsigned kinds,
+                                                                       const void* wp0, const void* wp1, const void* wp2,
+                                                                       unsigned geo0, unsigned geo1, unsigned geo2, FusedArgs fa) {
   extern __shared__ float smem[];   // fa.lds_bytes: the largest need of the launch's jobs
   __shared__ unsigned s_flag;
 #ifdef FUSED_TRACE
@@ -557,21 +584,29 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(int end0
   if ((int)blockIdx.x >= end0) { lb = blockIdx.x - end0; job = 1; }
   if ((int)blockIdx.x >= end1) { lb = blockIdx.x - end1; job = 2; }
   if ((int)blockIdx.x >= end2) { lb = blockIdx.x - end2; job = 3; }
-  if (((kinds >> (8 * job)) & 0xFFu) == (unsigned)JOB_ATTN) {
+  const unsigned kb = (kinds >> (8 * job)) & 0xFFu;
+  if ((kb & FUSED_KIND_MASK) == (unsigned)JOB_ATTN) {
     attn_job<D, G>(fa.a, lb, smem, &s_flag);
   } else {
     const GemvJob& j = fa.g[job];
-    if (j.wait_on) {   // (the plan gives only the un-normed O projection a wait)
-      if (j.tn == 2) gemv_job<false, FUSED_U2, 2, true>(j, lb, smem);
-      else gemv_job<false, FUSED_U, 1, true>(j, lb, smem);
-    } else if (j.tn == 3) {   // (the plan builds three-tile workgroups for un-normed projections only)
-      gemv_job<false, 1, 3>(j, lb, smem);
-    } else if (j.tn == 2) {
-      if (j.normed) gemv_job<true, FUSED_U2, 2>(j, lb, smem);
-      else gemv_job<false, FUSED_U2, 2>(j, lb, smem);
+    const unsigned slot = kb >> FUSED_KIND_SLOT_SHIFT;   // which of the three preloaded (wp, geo) pairs, 3: none
+    const void* wp = slot == 0 ? wp0 : slot == 1 ? wp1 : wp2;
+    const unsigned geo = slot == 0 ? geo0 : slot == 1 ? geo1 : geo2;
+    int KT = (int)(geo >> 16), group0 = (int)(geo & 0xFFFFu);
+    if (slot == 3) { wp = j.wp; KT = j.K >> 5; group0 = j.group0; }
+    const unsigned tn = (kb >> FUSED_KIND_TN_SHIFT) & 3u;
+    const bool normed = (kb & FUSED_KIND_NORMED) != 0;
+    if (kb & FUSED_KIND_WAITS) {   // (the plan gives only the un-normed O projection a wait)
+      if (tn == 2) gemv_job<false, FUSED_U2, 2, true>(j, wp, KT, group0, lb, smem);
+      else gemv_job<false, FUSED_U, 1, true>(j, wp, KT, group0, lb, smem);
+    } else if (tn == 3) {   // (the plan builds three-tile workgroups for un-normed projections only)
+      gemv_job<false, 1, 3>(j, wp, KT, group0, lb, smem);
+    } else if (tn == 2) {
+      if (normed) gemv_job<true, FUSED_U2, 2>(j, wp, KT, group0, lb, smem);
+      else gemv_job<false, FUSED_U2, 2>(j, wp, KT, group0, lb, smem);
     } else {
-      if (j.normed) gemv_job<true, FUSED_U, 1>(j, lb, smem);
-      else gemv_job<false, FUSED_U, 1>(j, lb, smem);
+      if (normed) gemv_job<true, FUSED_U, 1>(j, wp, KT, group0, lb, smem);
+      else gemv_job<false, FUSED_U, 1>(j, wp, KT, group0, lb, smem);
     }
   }
 }
@@ -601,16 +636,37 @@ template <int D>
 static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
   const dim3 block(FUSED_THREADS);
   // with events: the dispatch itself carries them, so their distance is the kernel's own run time
-  unsigned kinds = 0;
-  for (int i = 0; i < FUSED_MAX_JOBS; ++i) kinds |= ((unsigned)fa.kind[i] & 0xFFu) << (8 * i);
+  unsigned kinds = 0, geo[3] = {0u, 0u, 0u};
+  const void* wp[3] = {nullptr, nullptr, nullptr};
+  int n_hot = 0;
+  for (int i = 0; i < FUSED_MAX_JOBS; ++i) {
+    unsigned kb = (unsigned)fa.kind[i] & FUSED_KIND_MASK;
+    if (i < fa.n_jobs && fa.kind[i] == JOB_GEMV) {
+      const GemvJob& j = fa.g[i];
+      const int kt = j.K >> 5;
+      unsigned slot = 3;
+      if (n_hot < 3 && kt <= 0xFFFF && j.group0 >= 0 && j.group0 <= 0xFFFF) {
+        slot = (unsigned)n_hot++;
+        wp[slot] = j.wp;
+        geo[slot] = ((unsigned)kt << 16) | (unsigned)j.group0;
+      }
+      kb |= (unsigned)(j.tn >= 2 ? j.tn : 1) << FUSED_KIND_TN_SHIFT;
+      if (j.normed) kb |= FUSED_KIND_NORMED;
+      if (j.wait_on) kb |= FUSED_KIND_WAITS;
+      kb |= slot << FUSED_KIND_SLOT_SHIFT;
+    }
+    kinds |= kb << (8 * i);
+  }
 #define FUSED_LAUNCH(GQ)                                                                                    \
   do {                                                                                                      \
     if (ev0 || ev1)                                                                                          \
       hipExtLaunchKernelGGL((fused_decode_kernel<D, GQ>), grid, block, fa.lds_bytes, s, ev0, ev1, 0,         \
-                            fa.block_end[0], fa.block_end[1], fa.block_end[2], kinds, fa);                  \
+                            fa.block_end[0], fa.block_end[1], fa.block_end[2], kinds, wp[0], wp[1], wp[2],  \
+                            geo[0], geo[1], geo[2], fa);                                                    \
     else                                                                                                    \
       hipLaunchKernelGGL((fused_decode_kernel<D, GQ>), grid, block, fa.lds_bytes, s,                         \
-                         fa.block_end[0], fa.block_end[1], fa.block_end[2], kinds, fa);                     \
+                         fa.block_end[0], fa.block_end[1], fa.block_end[2], kinds, wp[0], wp[1], wp[2],     \
+                         geo[0], geo[1], geo[2], fa);                                                       \
   } while (0)
   switch (g) {
     case 1: FUSED_LAUNCH(1); break;
