@@ -46,7 +46,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 #define FUSED_KIND_TN_SHIFT 2       // two bits: tiles per workgroup (1, 2, 3)
 #define FUSED_KIND_NORMED 16u       // the job folds RMSNorm in
 #define FUSED_KIND_WAITS 32u        // the job waits for another job of the launch
-#define FUSED_KIND_SLOT_SHIFT 6     // two bits: index of the job's preloaded (weights, K / 32 | group0) pair, 3 = none
+#define FUSED_KIND_SLOT_SHIFT 6     // two bits: index of the job's preloaded (weights, operand) pointer pair, 3 = none
 
 // k tiles per register buffer (two buffers) of a one-tile / a two-tile workgroup: 4 KiB of weights in flight
 // per wavefront.  With the round-robin assignment of k tiles below, 2 beat 4 (3.57 against 3.65 ms per step;
@@ -77,11 +77,11 @@ __device__ __forceinline__ void unpack8f(const uint4 v, float f[8]) {
 // set by the workgroup with the most bytes: one tile per workgroup keeps the jobs of a launch even
 // and the number of streaming workgroups high.
 // ------------------------------------------------------------------------------------------------
-// wp, KT and group0 repeat j.wp, j.K / 32 and j.group0: the kernel hands them over from preloaded kernel
-// arguments where it can, so that the first weight tiles are requested before the job's descriptor (j) has
-// arrived from memory.
+// wp, xop, KT, group0 and M repeat j.wp, j.xb, j.K / 32, j.group0 and j.M (the x rows are K elements apart): the
+// kernel hands them over from preloaded kernel arguments where it can, so that the first weight tiles and
+// operand slices are requested before the job's descriptor (j) has arrived from memory.
 template <bool NORMED, int U, int TN, bool COH = false>
-__device__ void gemv_job(const GemvJob& j, const void* wp, int KT, int group0, int lb, float* smem) {
+__device__ void gemv_job(const GemvJob& j, const void* wp, const bf16_t* xop, int KT, int group0, int M, int lb, float* smem) {
   constexpr int WAVES = FUSED_WAVES;
   const int grp = group0 + lb;
   const int tid = threadIdx.x;
@@ -100,6 +100,9 @@ __device__ void gemv_job(const GemvJob& j, const void* wp, int KT, int group0, i
   for (int t = 0; t < TN; ++t) acc[t] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
   float ss = 0.f;  // NORMED: this lane's share of its row's sum of squares
   const u32x4_t* wptr = reinterpret_cast<const u32x4_t*>(wp) + ((size_t)nt0 * KT) * 64 + lane;
+  const bool rowok = b < M;
+  const int rowc = min(b, M - 1);
+  const bf16_t* xbp = xop + (size_t)rowc * (KT * 32) + q * 8;
   u32x4_t wa[TN][U], wb[TN][U], xa[U], xb[U];
   auto loadw = [&](u32x4_t (&wv)[TN][U], int kt) {
 #pragma unroll
@@ -109,30 +112,6 @@ __device__ void gemv_job(const GemvJob& j, const void* wp, int KT, int group0, i
       for (int t = 0; t < TN; ++t) wv[t][u] = __builtin_nontemporal_load(wptr + ((size_t)t * KT + ktc) * 64);
     }
   };
-  // the first weight tiles depend on nothing but the (preloaded) arguments: requested before anything else
-  if (kt0 < kt1) loadw(wa, kt0);
-  __builtin_amdgcn_sched_barrier(0);
-
-  if (j.wait_on) {
-    // The x operand comes from the attention job of this launch.  Its workgroups have lower block indices,
-    // so they were dispatched before this one and wait for nothing: the counter always arrives.  The wait is
-    // bounded all the same (about a second), so that the kernel ends whatever happens.
-    if (tid == 0) {
-      for (int spin = 0; spin < (1 << 20); ++spin) {
-        if (__hip_atomic_load(j.wait_on, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= j.wait_target) break;
-        __builtin_amdgcn_s_sleep(16);
-      }
-    }
-    __syncthreads();   // (workgroup-scope ordering; the operand itself is read with device-coherent loads, so no
-                       // cache invalidation is needed: an agent-scope acquire per workgroup would flush the L2
-                       // under the weight streams that run beside)
-  }
-
-  const bool rowok = b < j.M;
-  const int rowc = min(b, j.M - 1);
-
-  const bf16_t* xbp = j.xb + (size_t)rowc * j.ldx + q * 8;
-
   auto loadx = [&](u32x4_t (&xv)[U], int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -151,6 +130,28 @@ __device__ void gemv_job(const GemvJob& j, const void* wp, int KT, int group0, i
     loadw(wv, kt);
     loadx(xv, kt);
   };
+  // the first tiles depend on nothing but the (preloaded) arguments: requested before anything else; the operand
+  // of a job that waits for its producer only behind the wait
+  if (kt0 < kt1) loadw(wa, kt0);
+  if (!COH && kt0 < kt1) loadx(xa, kt0);
+  __builtin_amdgcn_sched_barrier(0);
+
+  if (j.wait_on) {
+    // The x operand comes from the attention job of this launch.  Its workgroups have lower block indices,
+    // so they were dispatched before this one and wait for nothing: the counter always arrives.  The wait is
+    // bounded all the same (about a second), so that the kernel ends whatever happens.
+    if (tid == 0) {
+      for (int spin = 0; spin < (1 << 20); ++spin) {
+        if (__hip_atomic_load(j.wait_on, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= j.wait_target) break;
+        __builtin_amdgcn_s_sleep(16);
+      }
+    }
+    __syncthreads();   // (workgroup-scope ordering; the operand itself is read with device-coherent loads, so no
+                       // cache invalidation is needed: an agent-scope acquire per workgroup would flush the L2
+                       // under the weight streams that run beside)
+  }
+
+  if (COH && kt0 < kt1) loadx(xa, kt0);
   auto fma = [&](const u32x4_t (&wv)[TN][U], const u32x4_t (&xv)[U], int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -206,7 +207,6 @@ __device__ void gemv_job(const GemvJob& j, const void* wp, int KT, int group0, i
     }
   }
 
-  if (kt0 < kt1) loadx(xa, kt0);
   if (kt0 < kt1) {
     for (int kt = kt0; kt < kt1; kt += KA) {
       load(wb, xb, kt + KB);
@@ -564,22 +564,26 @@ struct FusedTraceScope {
 };
 #endif
 
-// The leading arguments repeat what a workgroup needs first: the block boundaries of the jobs, one descriptor
-// byte per job (FUSED_KIND_* below) and, for the first three GEMV jobs of the launch, weight pointer, K / 32
-// and first tile group.  With kernel-argument preloading (the build passes -mllvm
-// -amdgpu-kernarg-preload-count=10) they are in SGPRs when a wave starts: a workgroup knows its job and requests
-// its first weight tiles at once, while the job's descriptor is still on its way from memory (a cold scalar
-// load costs 0.7 - 2 us here, and it used to stand in front of every workgroup's first request).
+// The leading arguments repeat what a workgroup needs first: two (weights, operand) pointer pairs that cover the
+// GEMV jobs of a launch (jobs that are parts of one projection share theirs), the block boundaries of the jobs
+// and the row count, one descriptor byte per job (FUSED_KIND_* below), and K / 32 and the first tile group of the
+// first three GEMV jobs.  With kernel-argument preloading (the build passes -mllvm
+// -amdgpu-kernarg-preload-count=10; 14 dwords) they are in SGPRs when a wave starts: a workgroup knows its job
+// and requests its first weight tiles and operand slices at once, while the job's descriptor is still on its
+// way from memory (a cold scalar load costs 0.7 - 2 us here, and it used to stand in front of every
+// workgroup's first request).
 static_assert(FUSED_MAX_JOBS == 4, "the preloaded arguments carry three block boundaries and four descriptor bytes");
 template <int D, int G>
-__global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(int end0, int end1, int end2, unsigned kinds,
-                                                                       const void* wp0, const void* wp1, const void* wp2,
-                                                                       unsigned geo0, unsigned geo1, unsigned geo2, FusedArgs fa) {
+__global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(const void* wp_a, const void* wp_b, const bf16_t* x_a,
+                                                                       const bf16_t* x_b, unsigned ends01, unsigned end2_m,
+                                                                       unsigned kinds, unsigned geo0, unsigned geo1,
+                                                                       unsigned geo2, FusedArgs fa) {
   extern __shared__ float smem[];   // fa.lds_bytes: the largest need of the launch's jobs
   __shared__ unsigned s_flag;
 #ifdef FUSED_TRACE
   FusedTraceScope trace_scope;
 #endif
+  const int end0 = (int)(ends01 & 0xFFFFu), end1 = (int)(ends01 >> 16), end2 = (int)(end2_m & 0xFFFFu);
   int lb = blockIdx.x, job = 0;
   if ((int)blockIdx.x >= end0) { lb = blockIdx.x - end0; job = 1; }
   if ((int)blockIdx.x >= end1) { lb = blockIdx.x - end1; job = 2; }
@@ -589,24 +593,26 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(int end0
     attn_job<D, G>(fa.a, lb, smem, &s_flag);
   } else {
     const GemvJob& j = fa.g[job];
-    const unsigned slot = kb >> FUSED_KIND_SLOT_SHIFT;   // which of the three preloaded (wp, geo) pairs, 3: none
-    const void* wp = slot == 0 ? wp0 : slot == 1 ? wp1 : wp2;
-    const unsigned geo = slot == 0 ? geo0 : slot == 1 ? geo1 : geo2;
-    int KT = (int)(geo >> 16), group0 = (int)(geo & 0xFFFFu);
-    if (slot == 3) { wp = j.wp; KT = j.K >> 5; group0 = j.group0; }
+    const unsigned slot = kb >> FUSED_KIND_SLOT_SHIFT;   // which preloaded pointer pair: 0, 1, or 3 = none
+    const int gi = job - ((kinds & FUSED_KIND_MASK) == (unsigned)JOB_ATTN ? 1 : 0);   // index among the GEMV jobs
+    const void* wp = slot == 0 ? wp_a : wp_b;
+    const bf16_t* xop = slot == 0 ? x_a : x_b;
+    const unsigned geo = gi == 0 ? geo0 : gi == 1 ? geo1 : geo2;
+    int KT = (int)(geo >> 16), group0 = (int)(geo & 0xFFFFu), M = (int)(end2_m >> 16);
+    if (slot == 3) { wp = j.wp; xop = j.xb; KT = j.K >> 5; group0 = j.group0; M = j.M; }
     const unsigned tn = (kb >> FUSED_KIND_TN_SHIFT) & 3u;
     const bool normed = (kb & FUSED_KIND_NORMED) != 0;
     if (kb & FUSED_KIND_WAITS) {   // (the plan gives only the un-normed O projection a wait)
-      if (tn == 2) gemv_job<false, FUSED_U2, 2, true>(j, wp, KT, group0, lb, smem);
-      else gemv_job<false, FUSED_U, 1, true>(j, wp, KT, group0, lb, smem);
+      if (tn == 2) gemv_job<false, FUSED_U2, 2, true>(j, wp, xop, KT, group0, M, lb, smem);
+      else gemv_job<false, FUSED_U, 1, true>(j, wp, xop, KT, group0, M, lb, smem);
     } else if (tn == 3) {   // (the plan builds three-tile workgroups for un-normed projections only)
-      gemv_job<false, 1, 3>(j, wp, KT, group0, lb, smem);
+      gemv_job<false, 1, 3>(j, wp, xop, KT, group0, M, lb, smem);
     } else if (tn == 2) {
-      if (normed) gemv_job<true, FUSED_U2, 2>(j, wp, KT, group0, lb, smem);
-      else gemv_job<false, FUSED_U2, 2>(j, wp, KT, group0, lb, smem);
+      if (normed) gemv_job<true, FUSED_U2, 2>(j, wp, xop, KT, group0, M, lb, smem);
+      else gemv_job<false, FUSED_U2, 2>(j, wp, xop, KT, group0, M, lb, smem);
     } else {
-      if (normed) gemv_job<true, FUSED_U, 1>(j, wp, KT, group0, lb, smem);
-      else gemv_job<false, FUSED_U, 1>(j, wp, KT, group0, lb, smem);
+      if (normed) gemv_job<true, FUSED_U, 1>(j, wp, xop, KT, group0, M, lb, smem);
+      else gemv_job<false, FUSED_U, 1>(j, wp, xop, KT, group0, M, lb, smem);
     }
   }
 }
@@ -636,19 +642,31 @@ template <int D>
 static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
   const dim3 block(FUSED_THREADS);
   // with events: the dispatch itself carries them, so their distance is the kernel's own run time
+  // preloaded arguments: a GEMV job is "hot" when it is among the first three, its numbers fit 16 bits and its
+  // (weights, operand) pair is one of the two the launch can carry
   unsigned kinds = 0, geo[3] = {0u, 0u, 0u};
-  const void* wp[3] = {nullptr, nullptr, nullptr};
-  int n_hot = 0;
+  const void* wp[2] = {nullptr, nullptr};
+  const bf16_t* xp[2] = {nullptr, nullptr};
+  int n_pairs = 0, n_gemv = 0, rows = -1;
+  if (fa.block_end[0] > 0xFFFF || fa.block_end[1] > 0xFFFF || fa.block_end[2] > 0xFFFF) return hipErrorInvalidValue;
   for (int i = 0; i < FUSED_MAX_JOBS; ++i) {
     unsigned kb = (unsigned)fa.kind[i] & FUSED_KIND_MASK;
+    if (i < fa.n_jobs && fa.kind[i] == JOB_ATTN && i != 0) return hipErrorInvalidValue;   // (the kernel counts on it)
     if (i < fa.n_jobs && fa.kind[i] == JOB_GEMV) {
       const GemvJob& j = fa.g[i];
-      const int kt = j.K >> 5;
+      if (j.ldx != j.K) return hipErrorInvalidValue;   // (the kernel takes the x rows to be K elements apart)
+      const int kt = j.K >> 5, gi = n_gemv++;
       unsigned slot = 3;
-      if (n_hot < 3 && kt <= 0xFFFF && j.group0 >= 0 && j.group0 <= 0xFFFF) {
-        slot = (unsigned)n_hot++;
-        wp[slot] = j.wp;
-        geo[slot] = ((unsigned)kt << 16) | (unsigned)j.group0;
+      if (gi < 3 && kt <= 0xFFFF && j.group0 >= 0 && j.group0 <= 0xFFFF && j.M >= 1 && j.M <= 0xFFFF &&
+          (rows < 0 || rows == j.M)) {
+        int p = 0;
+        while (p < n_pairs && !(wp[p] == j.wp && xp[p] == j.xb)) ++p;
+        if (p == n_pairs && n_pairs < 2) { wp[p] = j.wp; xp[p] = j.xb; ++n_pairs; }
+        if (p < n_pairs) {
+          slot = (unsigned)p;
+          geo[gi] = ((unsigned)kt << 16) | (unsigned)j.group0;
+          rows = j.M;
+        }
       }
       kb |= (unsigned)(j.tn >= 2 ? j.tn : 1) << FUSED_KIND_TN_SHIFT;
       if (j.normed) kb |= FUSED_KIND_NORMED;
@@ -657,16 +675,16 @@ static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStrea
     }
     kinds |= kb << (8 * i);
   }
+  const unsigned ends01 = (unsigned)fa.block_end[0] | ((unsigned)fa.block_end[1] << 16);
+  const unsigned end2_m = (unsigned)fa.block_end[2] | ((unsigned)(rows < 0 ? 0 : rows) << 16);
 #define FUSED_LAUNCH(GQ)                                                                                    \
   do {                                                                                                      \
     if (ev0 || ev1)                                                                                          \
       hipExtLaunchKernelGGL((fused_decode_kernel<D, GQ>), grid, block, fa.lds_bytes, s, ev0, ev1, 0,         \
-                            fa.block_end[0], fa.block_end[1], fa.block_end[2], kinds, wp[0], wp[1], wp[2],  \
-                            geo[0], geo[1], geo[2], fa);                                                    \
+                            wp[0], wp[1], xp[0], xp[1], ends01, end2_m, kinds, geo[0], geo[1], geo[2], fa);  \
     else                                                                                                    \
       hipLaunchKernelGGL((fused_decode_kernel<D, GQ>), grid, block, fa.lds_bytes, s,                         \
-                         fa.block_end[0], fa.block_end[1], fa.block_end[2], kinds, wp[0], wp[1], wp[2],     \
-                         geo[0], geo[1], geo[2], fa);                                                       \
+                         wp[0], wp[1], xp[0], xp[1], ends01, end2_m, kinds, geo[0], geo[1], geo[2], fa);     \
   } while (0)
   switch (g) {
     case 1: FUSED_LAUNCH(1); break;
