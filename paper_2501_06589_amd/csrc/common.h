@@ -172,8 +172,26 @@ struct GemmArgs {
   const float* cos_tab;    // [max_seq][d/2]
   const float* sin_tab;
   int T, pos0, nq, nkv, d, max_seq;
+  // epilogue 3: the residual update "wait(); residual += out" (Algorithm 1) with the AllReduce written as a sum
+  // over rank partial sums (Eq. 2): x_res[m][n] = x_res[m][n] + product + peers_0[m][n] + peers_1[m][n] + ...
+  // (in this order, in place, row stride N), an optional f32 copy, bf16 copies of the new rows for the modules
+  // that read them, and the rows' sums of squares per column block: ssq_part[block][m], gemm_ssq_parts() blocks
+  float* x_res;
+  float* x_copy;           // or null
+  bf16_t* xh_a;            // bf16 [M][N], or null
+  bf16_t* xh_b;            // or null (only with xh_a)
+  const bf16_t* peers;     // bf16 [n_peers][peer_stride], row stride N; or null
+  int n_peers;
+  size_t peer_stride;      // elements
+  float* ssq_part;         // f32 [gemm_ssq_parts()][M] (at most ceil(N / 64) blocks), or null
+  // every epilogue: if non-null, row m of the product is multiplied by row_scale[m] first (the 1/rms of an
+  // RMSNorm whose gain is folded into the weights: the factor commutes with the product)
+  const float* row_scale;
 };
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s);
+int gemm_ssq_parts(const GemmArgs& a);   // epilogue 3: the number of column blocks that launch_gemm_mfma(a) leaves in ssq_part
+// rs_a[m] (and rs_b[m] if non-null) = 1 / sqrt(sum_p ssq_part[p][m] / H + eps), p < n_part, fixed summation order
+hipError_t launch_row_rms(const float* ssq_part, int n_part, int M, int H, float eps, float* rs_a, float* rs_b, hipStream_t s);
 
 struct AttnPrefillArgs {
   const bf16_t* q;         // [B*T][nq*d] rotated

@@ -74,6 +74,12 @@ struct ladder_ctx {
   // workspaces
   float* x = nullptr;
   char* y[2] = {nullptr, nullptr};
+  // wide calls of the packed-weight path: the residual update is the epilogue of a module's last GEMM, which
+  // leaves un-normed bf16 rows in y[] and the rows' 1/rms in y_rs[]; y_scale[i] is y_rs[i] while y[i] holds
+  // such rows and null while it holds normed ones
+  float* ssq_part = nullptr;
+  float* y_rs[2] = {nullptr, nullptr};
+  const float* y_scale[2] = {nullptr, nullptr};
   float* parts[2] = {nullptr, nullptr};
   size_t parts_cap = 0;  // elements per parity buffer
   float* qkv = nullptr;
@@ -231,10 +237,51 @@ int collect_profile(ladder_ctx* c) {
   return LADDER_OK;
 }
 
+// consumers of x_m: module m+1 if its lag is 1 (m == 0: module 1 always), module m+2 if its lag is 2
+// (m == 0: module 2 always -- modules 1 and 2 both read x_0)
+int consumers_of(const ladder_ctx* c, int m, int out[2]) {
+  int nc = 0;
+  if (m + 1 <= c->n_mod && (m == 0 || lag_of(c, m + 1) == 1)) out[nc++] = m + 1;
+  if (m + 2 <= c->n_mod && ((m == 0 && lag_of(c, 2) == 2) || (m > 0 && lag_of(c, m + 2) == 2))) out[nc++] = m + 2;
+  return nc;
+}
+
+// Wide calls (more than 64 rows) of the packed-weight path with one real shard: the residual update of module m
+// ("wait(); residual += out", Algorithm 1, the AllReduce as a sum over rank partial sums, Eq. 2) is the
+// epilogue of the module's last GEMM instead of a kernel of its own, which saves a round trip of the fp32
+// product through memory.  The epilogue leaves the new rows as bf16 for the modules that read x_m, un-normed:
+// their 1/rms (from the sums of squares the epilogue also leaves) scales the consumer's product instead.
+int fuse_residual(ladder_ctx* c, GemmArgs& a, int m, int rows, float* x_copy, int cons[2]) {
+  const ladder_config& g = c->cfg;
+  a.epilogue = 3; a.x_res = c->x; a.x_copy = x_copy;
+  if (c->peers && c->n_peers > 0) {
+    const size_t set = (size_t)(m % g.peer_pool);
+    a.peers = (const bf16_t*)(c->peers + set * c->n_peers * (size_t)g.peer_rows * g.hidden * c->esz);
+    a.n_peers = c->n_peers; a.peer_stride = (size_t)g.peer_rows * g.hidden;
+  }
+  const int nc = consumers_of(c, m, cons);
+  if (nc > 0) { a.xh_a = (bf16_t*)c->y[cons[0] & 1]; a.ssq_part = c->ssq_part; }
+  if (nc > 1) a.xh_b = (bf16_t*)c->y[cons[1] & 1];
+  (void)rows;
+  return nc;
+}
+
+int finish_residual(ladder_ctx* c, const GemmArgs& a, int rows, int nc, const int cons[2], hipStream_t s) {
+  if (nc == 0) return LADDER_OK;
+  const ladder_config& g = c->cfg;
+  float* ra = c->y_rs[cons[0] & 1];
+  float* rb = nc > 1 ? c->y_rs[cons[1] & 1] : nullptr;
+  HIP_TRY(c, timed(c, LADDER_K_REDUCE_NORM, s, [&] { return launch_row_rms(c->ssq_part, gemm_ssq_parts(a), rows, g.hidden, g.rms_eps, ra, rb, s); }));
+  c->y_scale[cons[0] & 1] = ra;
+  if (nc > 1) c->y_scale[cons[1] & 1] = rb;
+  return LADDER_OK;
+}
+
 // ---------------------------------------------------------------------------------------------
-// one module's compute on the main stream; writes parts[m%2]; returns the number of slots written
+// one module's compute on the main stream; writes parts[m%2] and returns the number of slots written, or (fuse)
+// updates the residual itself and returns -1 slots: then no reduce follows
 // ---------------------------------------------------------------------------------------------
-int run_module(ladder_ctx* c, int m, int B, int T, int pos0, hipStream_t s, int* n_slots) {
+int run_module(ladder_ctx* c, int m, int B, int T, int pos0, hipStream_t s, int* n_slots, bool fuse, float* x_copy) {
   const ladder_config& g = c->cfg;
   const int rows = B * T, H = g.hidden, d = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, I = g.inter;
   const int layer = (m - 1) / 2, par = m & 1;
@@ -263,7 +310,7 @@ int run_module(ladder_ctx* c, int m, int B, int T, int pos0, hipStream_t s, int*
         HIP_TRY(c, timed(c, LADDER_K_GEMV, s, [&] { return launch_gemv(a, s); }));
       } else {
         GemmArgs a{};
-        a.x = (const bf16_t*)yin; a.ldx = H; a.wp = L.pqkv; a.M = rows; a.K = H; a.N = c->nqkv;
+        a.x = (const bf16_t*)yin; a.ldx = H; a.wp = L.pqkv; a.M = rows; a.K = H; a.N = c->nqkv; a.row_scale = c->y_scale[par];
         if (!dev_pos) {
           // rotary embedding and cache append are the GEMM's epilogue (no fp32 q|k|v round trip through memory)
           a.epilogue = 2; a.q_out = (bf16_t*)c->qbuf; a.cache_k = (bf16_t*)L.cache_k; a.cache_v = (bf16_t*)L.cache_v;
@@ -316,7 +363,10 @@ int run_module(ladder_ctx* c, int m, int B, int T, int pos0, hipStream_t s, int*
       } else {
         GemmArgs a{};
         a.x = (const bf16_t*)c->obuf; a.ldx = nqd; a.wp = L.po; a.M = rows; a.K = nqd; a.N = H; a.out = pout + slots * pstride; a.epilogue = 0;
+        int cons[2], nc = 0;
+        if (fuse) nc = fuse_residual(c, a, m, rows, x_copy, cons);
         HIP_TRY(c, timed(c, LADDER_K_GEMM, s, [&] { return launch_gemm_mfma(a, s); }));
+        if (fuse) { const int rc = finish_residual(c, a, rows, nc, cons, s); if (rc) return rc; }
         slots += 1;
       }
     } else {
@@ -340,15 +390,19 @@ int run_module(ladder_ctx* c, int m, int B, int T, int pos0, hipStream_t s, int*
       } else {
         GemmArgs a{};
         a.x = (const bf16_t*)yin; a.ldx = H; a.wp = L.pgu; a.M = rows; a.K = H; a.N = 2 * I; a.act = (bf16_t*)c->act; a.epilogue = 1;
+        a.row_scale = c->y_scale[par];
         HIP_TRY(c, timed(c, LADDER_K_GEMM, s, [&] { return launch_gemm_mfma(a, s); }));
         GemmArgs b{};
         b.x = (const bf16_t*)c->act; b.ldx = I; b.wp = L.pd; b.M = rows; b.K = I; b.N = H; b.out = pout + slots * pstride; b.epilogue = 0;
+        int cons[2], nc = 0;
+        if (fuse) nc = fuse_residual(c, b, m, rows, x_copy, cons);
         HIP_TRY(c, timed(c, LADDER_K_GEMM, s, [&] { return launch_gemm_mfma(b, s); }));
+        if (fuse) { const int rc = finish_residual(c, b, rows, nc, cons, s); if (rc) return rc; }
         slots += 1;
       }
     }
   }
-  *n_slots = slots;
+  *n_slots = fuse ? -1 : slots;
   return LADDER_OK;
 }
 
@@ -377,14 +431,12 @@ int run_reduce(ladder_ctx* c, int m, int rows, int n_slots, const void* emb, flo
       a.n_peers = c->n_peers; a.peer_stride = (size_t)g.peer_rows * g.hidden;
     }
   }
-  // consumers of x_m: module m+1 if its lag is 1 (m == 0: module 1 always), module m+2 if its lag is 2
-  // (m == 0: module 2 always -- modules 1 and 2 both read x_0)
-  int consumers[2], nc = 0;
-  if (m + 1 <= c->n_mod && (m == 0 || lag_of(c, m + 1) == 1)) consumers[nc++] = m + 1;
-  if (m + 2 <= c->n_mod && ((m == 0 && lag_of(c, 2) == 2) || (m > 0 && lag_of(c, m + 2) == 2))) consumers[nc++] = m + 2;
+  int consumers[2];
+  const int nc = consumers_of(c, m, consumers);
   for (int i = 0; i < nc; ++i) {
     const int cm = consumers[i], layer = (cm - 1) / 2;
     void* out = c->y[cm & 1];
+    c->y_scale[cm & 1] = nullptr;   // normed rows
     // packed-weight path: the gain lives in the consumer's weights
     const void* gain = c->fast ? nullptr : ((cm & 1) ? (const void*)c->gain_attn[layer] : (const void*)c->gain_mlp[layer]);
     if (i == 0) { a.out_a = out; a.gain_a = gain; }
@@ -421,6 +473,9 @@ int forward_body(ladder_ctx* c, const void* x_in, int B, int T, int pos0, void* 
   hipStream_t s0 = c->s_attn;
   auto module_stream = [&](int m) { return (overlap && (m & 1) == 0) ? c->s_mlp : s0; };
   auto reduce_stream = [&](int m) { return m == 0 ? s0 : (overlap ? module_stream(m) : (side ? c->side : s0)); };
+  // (the skinny kernels have no such epilogue, several real shards would each add to the residual, and the
+  // emulated collective latency wants the reduce as a step of its own)
+  const bool fuse = c->fast && rows > 64 && c->cfg.n_real_shards == 1 && c->cfg.reduce_delay_us == 0;
   int rc = run_reduce(c, 0, rows, 0, x_in, c->n_mod == 0 ? (float*)x_out : nullptr, s0);
   if (rc) return rc;
   if (overlap && c->n_mod >= 2) {  // fork: the MLP stream starts once x_0 and its normed copies exist
@@ -433,8 +488,9 @@ int forward_body(ladder_ctx* c, const void* x_in, int B, int T, int pos0, void* 
     const int src = m - lag_of(c, m);
     if (src >= 1 && reduce_stream(src) != sm) HIP_TRY(c, hipStreamWaitEvent(sm, c->ev_red[src & 1], 0));
     int n_slots = 0;
-    rc = run_module(c, m, B, T, pos0, sm, &n_slots);
+    rc = run_module(c, m, B, T, pos0, sm, &n_slots, fuse, m == c->n_mod ? (float*)x_out : nullptr);
     if (rc) return rc;
+    if (n_slots < 0) continue;   // the module has updated the residual itself (wide calls run on one stream)
     if (rs != sm) {
       HIP_TRY(c, hipEventRecord(c->ev_mod[m & 1], sm));
       HIP_TRY(c, hipStreamWaitEvent(rs, c->ev_mod[m & 1], 0));
@@ -931,6 +987,8 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
   INIT_TRY(dev_alloc(c, (void**)&c->act, rows * I * esz, false));
   if (!c->fast) INIT_TRY(dev_alloc(c, (void**)&c->gu, rows * 2 * I * 4, false));
   if (c->fast) {
+    INIT_TRY(dev_alloc(c, (void**)&c->ssq_part, (size_t)((H + 63) / 64) * rows * 4, false));
+    for (int i = 0; i < 2; ++i) INIT_TRY(dev_alloc(c, (void**)&c->y_rs[i], rows * 4, false));
     const size_t chunks = (size_t)(c->s_cap / 32);
     const size_t gq = nq / nkv;
     INIT_TRY(dev_alloc(c, (void**)&c->att_o, (size_t)g.max_batch * nkv * chunks * gq * d * 4, false));

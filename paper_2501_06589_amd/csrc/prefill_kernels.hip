@@ -41,17 +41,82 @@ __device__ __forceinline__ f32x4_t mfma16(const uint4 a, const uint4 b, const f3
 template <int WM>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x4_t (&acc)[4][WM], int m0, int nt0, int NT, int lane) {
   const int b = lane & 15, q = lane >> 4;
+  // row scale (1.0 where there is none: the multiplication is exact then), applied where an accumulator is read
+  auto scale_of = [&](int mt) { return a.row_scale ? a.row_scale[min(m0 + mt * 16 + b, a.M - 1)] : 1.0f; };
   if (a.epilogue == 0) {
 #pragma unroll
     for (int mt = 0; mt < WM; ++mt) {
       const int m = m0 + mt * 16 + b;
+      const float rs = scale_of(mt);
       if (m >= a.M) continue;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         if (nt0 + j >= NT) continue;
         const int n = (nt0 + j) * 16 + 4 * q;
         *reinterpret_cast<float4*>(a.out + (size_t)m * a.N + n) =
-            make_float4(acc[j][mt][0], acc[j][mt][1], acc[j][mt][2], acc[j][mt][3]);
+            make_float4(acc[j][mt][0] * rs, acc[j][mt][1] * rs, acc[j][mt][2] * rs, acc[j][mt][3] * rs);
+      }
+    }
+  } else if (a.epilogue == 3) {
+    // residual update; the summation order per element is fixed: old value, product, peers 0, 1, ...
+    // The operands (old values, the first three peers) of two column tiles are requested at once.
+    constexpr int PB = 3, JB = 2, JG = 4 / JB, STEPS = WM * JG;
+    struct Operands { float4 xo[JB]; uint2 pk[JB][PB]; };
+    Operands o;
+    auto row_of = [&](int mt) { return (size_t)min(m0 + mt * 16 + b, a.M - 1) * a.N; };
+    auto request = [&](Operands& o, int st) {
+      const size_t row = row_of(st / JG);
+#pragma unroll
+      for (int jj = 0; jj < JB; ++jj) {
+        const size_t off = row + min(nt0 + (st % JG) * JB + jj, NT - 1) * 16 + 4 * q;
+        o.xo[jj] = *reinterpret_cast<const float4*>(a.x_res + off);
+#pragma unroll
+        for (int p = 0; p < PB; ++p)
+          if (p < a.n_peers) o.pk[jj][p] = *reinterpret_cast<const uint2*>(a.peers + p * a.peer_stride + off);
+      }
+    };
+    auto add_peer = [&](float (&v4)[4], const uint2 pk) {
+      v4[0] += __uint_as_float(pk.x << 16);
+      v4[1] += __uint_as_float(pk.x & 0xFFFF0000u);
+      v4[2] += __uint_as_float(pk.y << 16);
+      v4[3] += __uint_as_float(pk.y & 0xFFFF0000u);
+    };
+    float ss = 0.f;
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+      request(o, st);
+      const int mt = st / JG;
+      const int m = m0 + mt * 16 + b;
+      const bool ok = m < a.M;
+      const size_t row = row_of(mt);
+#pragma unroll
+      for (int jj = 0; jj < JB; ++jj) {
+        const int j = (st % JG) * JB + jj;
+        if (nt0 + j >= NT) continue;   // (uniform over the wavefront)
+        const size_t off = row + (nt0 + j) * 16 + 4 * q;
+        float v4[4] = {o.xo[jj].x + acc[j][mt][0], o.xo[jj].y + acc[j][mt][1], o.xo[jj].z + acc[j][mt][2], o.xo[jj].w + acc[j][mt][3]};
+#pragma unroll
+        for (int p = 0; p < PB; ++p)
+          if (p < a.n_peers) add_peer(v4, o.pk[jj][p]);
+        for (int p = PB; p < a.n_peers; ++p) add_peer(v4, *reinterpret_cast<const uint2*>(a.peers + p * a.peer_stride + off));
+        if (ok) {
+          *reinterpret_cast<float4*>(a.x_res + off) = make_float4(v4[0], v4[1], v4[2], v4[3]);
+          if (a.x_copy) *reinterpret_cast<float4*>(a.x_copy + off) = make_float4(v4[0], v4[1], v4[2], v4[3]);
+          if (a.xh_a) {
+            uint2 pk;
+            pk.x = (uint32_t)f32_to_bf16(v4[0]) | ((uint32_t)f32_to_bf16(v4[1]) << 16);
+            pk.y = (uint32_t)f32_to_bf16(v4[2]) | ((uint32_t)f32_to_bf16(v4[3]) << 16);
+            *reinterpret_cast<uint2*>(a.xh_a + off) = pk;
+            if (a.xh_b) *reinterpret_cast<uint2*>(a.xh_b + off) = pk;
+          }
+        }
+        ss += v4[0] * v4[0] + v4[1] * v4[1] + v4[2] * v4[2] + v4[3] * v4[3];
+      }
+      if (st % JG == JG - 1) {   // the row block is complete: its rows' sums of squares over this wavefront's 64 columns
+        ss += __shfl_xor(ss, 16, 64);
+        ss += __shfl_xor(ss, 32, 64);
+        if (a.ssq_part && q == 0 && ok && nt0 < NT) a.ssq_part[(size_t)(nt0 >> 2) * a.M + m] = ss;
+        ss = 0.f;
       }
     }
   } else if (a.epilogue == 2) {
@@ -60,6 +125,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x4_t (&acc)[
 #pragma unroll
     for (int mt = 0; mt < WM; ++mt) {
       const int m = m0 + mt * 16 + b;
+      const float rs = scale_of(mt);
       if (m >= a.M) continue;
       const int seq = m / a.T, pos = a.pos0 + m % a.T;
 #pragma unroll
@@ -67,7 +133,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x4_t (&acc)[
         if (nt0 + j >= NT) continue;
         const int col = (nt0 + j) * 16 + 4 * q;
         const int head = col / a.d, dim = col % a.d;
-        float v4[4] = {acc[j][mt][0], acc[j][mt][1], acc[j][mt][2], acc[j][mt][3]};
+        float v4[4] = {acc[j][mt][0] * rs, acc[j][mt][1] * rs, acc[j][mt][2] * rs, acc[j][mt][3] * rs};
         if (head < a.nq + a.nkv) {
 #pragma unroll
           for (int p = 0; p < 2; ++p) {
@@ -98,13 +164,14 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x4_t (&acc)[
 #pragma unroll
     for (int mt = 0; mt < WM; ++mt) {
       const int m = m0 + mt * 16 + b;
+      const float rs = scale_of(mt);   // (lane + 32 holds the same row)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         float r4[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float g = acc[j][mt][r];
-          const float u = __shfl(acc[j][mt][r], (lane + 32) & 63, 64);
+          const float g = acc[j][mt][r] * rs;
+          const float u = __shfl(g, (lane + 32) & 63, 64);
           r4[r] = g / (1.0f + __expf(-g)) * u;
         }
         if (q < 2 && m < a.M && nt0 + j < NT) {
@@ -223,6 +290,23 @@ __global__ __launch_bounds__(256, MIN_WAVES) void gemm_mfma_kernel(GemmArgs a) {
   gemm_epilogue<WM>(a, acc, m0, nt0, NT, lane);
 }
 
+__global__ __launch_bounds__(256) void row_rms_kernel(const float* __restrict__ part, int n_part, int M, float h, float eps,
+                                                      float* __restrict__ rs_a, float* __restrict__ rs_b) {
+  const int m = blockIdx.x * 256 + threadIdx.x;
+  if (m >= M) return;
+  float tot = 0.f;
+  for (int p = 0; p < n_part; ++p) tot += part[(size_t)p * M + m];
+  const float rs = 1.0f / sqrtf(tot / h + eps);
+  rs_a[m] = rs;
+  if (rs_b) rs_b[m] = rs;
+}
+
+hipError_t launch_row_rms(const float* ssq_part, int n_part, int M, int H, float eps, float* rs_a, float* rs_b, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  hipLaunchKernelGGL(row_rms_kernel, dim3((M + 255) / 256), dim3(256), 0, s, ssq_part, n_part, M, (float)H, eps, rs_a, rs_b);
+  return hipGetLastError();
+}
+
 template <int WM, int MIN_WAVES>
 static hipError_t launch_gemm_wm(const GemmArgs& a, hipStream_t s) {
   constexpr int BM = 16 * WM;
@@ -285,6 +369,105 @@ __device__ __forceinline__ void gemm2_wait_and_meet() {
 #define GEMM2_XBLOCKS 3
 #define GEMM2_WSTAGES 4
 #define GEMM2_LDS_BYTES (GEMM2_XBLOCKS * GEMM2_XBLOCK_BYTES + GEMM2_WSTAGES * GEMM2_WSTAGE_BYTES)
+
+// Epilogue 3 of the 256 x 256 tile (see GemmArgs), with whole rows per memory instruction.  In the accumulator
+// layout a wavefront's load or store touches 16 rows, 64 (fp32) or 32 (bf16) bytes of each; this epilogue
+// moves 16 bytes per element through memory (the old row, three peers, the new row twice), and in that shape it
+// cost as much as the separate reduce kernel it replaces.  So the tile passes through LDS (free once the
+// workgroup is past its last k tile), 64 rows at a time: the wavefronts write their accumulator blocks, meet,
+// and read back one row of 256 columns per half-wavefront, eight columns per lane, so that every access to
+// memory is a whole row segment of 1 KiB (fp32) or 512 bytes (bf16), 16 bytes per lane and instruction.  The rows' sums of squares are left per 256-column
+// block: ssq_part[n_blk][m].  The summation order per element is fixed: old value, product, peers 0, 1, ...
+#define GEMM2_EPI_STRIDE 260   // floats per staged row: 256 + 4, so that the 16 rows of a write spread over the banks
+static_assert(64 * GEMM2_EPI_STRIDE * 4 <= GEMM2_LDS_BYTES, "staging area");
+__device__ __forceinline__ void gemm2_residual_epilogue(const GemmArgs& a, f32x4_t (&acc)[4][8], unsigned char* lds, int m0,
+                                                        int n_blk, int wave, int lane) {
+  float* stage = reinterpret_cast<float*>(lds);
+  const int b = lane & 15, q = lane >> 4;
+  const int wm = wave >> 2, wn = wave & 3;
+  const int half = lane >> 5, l32 = lane & 31;
+  const int n = n_blk * 256 + 8 * l32;       // on the way back: a half-wavefront per row, eight columns per lane
+  const bool col_ok = n < a.N;               // (N is a multiple of 16)
+  const int nc = col_ok ? n : 0;
+  constexpr int PB = 3, RB = 2;              // peers and row pairs requested at once
+#pragma unroll
+  for (int pass = 0; pass < 4; ++pass) {     // row blocks mt = 2 pass, 2 pass + 1 of both halves of the tile
+    if (pass > 0) __syncthreads();           // the previous pass has been read
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        *reinterpret_cast<f32x4_t*>(stage + (wm * 32 + h * 16 + b) * GEMM2_EPI_STRIDE + wn * 64 + j * 16 + 4 * q) = acc[j][2 * pass + h];
+    __syncthreads();
+    // wavefront w takes the staged row pairs (2 w, 2 w + 1), (2 w + 16, 2 w + 17), ..., RB of them at a time
+#pragma unroll
+    for (int g = 0; g < 4 / RB; ++g) {
+      float4 xo[RB][2];
+      uint4 pk[RB][PB];
+      size_t off[RB];
+      bool ok[RB];
+      int mrow[RB];
+#pragma unroll
+      for (int r = 0; r < RB; ++r) {
+        const int lr = 2 * wave + 16 * (g * RB + r) + half;              // staged row: half lr / 32, row lr % 32 of the pass
+        mrow[r] = m0 + (lr >> 5) * 128 + pass * 32 + (lr & 31);
+        ok[r] = col_ok && mrow[r] < a.M;
+        off[r] = (size_t)min(mrow[r], a.M - 1) * a.N + nc;
+        xo[r][0] = *reinterpret_cast<const float4*>(a.x_res + off[r]);
+        xo[r][1] = *reinterpret_cast<const float4*>(a.x_res + off[r] + 4);
+#pragma unroll
+        for (int p = 0; p < PB; ++p)
+          if (p < a.n_peers) pk[r][p] = *reinterpret_cast<const uint4*>(a.peers + p * a.peer_stride + off[r]);
+      }
+#pragma unroll
+      for (int r = 0; r < RB; ++r) {
+        const int lr = 2 * wave + 16 * (g * RB + r) + half;
+        const float4 p0 = *reinterpret_cast<const float4*>(stage + lr * GEMM2_EPI_STRIDE + 8 * l32);
+        const float4 p1 = *reinterpret_cast<const float4*>(stage + lr * GEMM2_EPI_STRIDE + 8 * l32 + 4);
+        float v8[8] = {xo[r][0].x + p0.x, xo[r][0].y + p0.y, xo[r][0].z + p0.z, xo[r][0].w + p0.w,
+                       xo[r][1].x + p1.x, xo[r][1].y + p1.y, xo[r][1].z + p1.z, xo[r][1].w + p1.w};
+        auto add_peer = [&](const uint4 u) {
+          const uint32_t w4[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v8[2 * e] += __uint_as_float(w4[e] << 16);
+            v8[2 * e + 1] += __uint_as_float(w4[e] & 0xFFFF0000u);
+          }
+        };
+#pragma unroll
+        for (int p = 0; p < PB; ++p)
+          if (p < a.n_peers) add_peer(pk[r][p]);
+        for (int p = PB; p < a.n_peers; ++p) add_peer(*reinterpret_cast<const uint4*>(a.peers + p * a.peer_stride + off[r]));
+        if (ok[r]) {
+          *reinterpret_cast<float4*>(a.x_res + off[r]) = make_float4(v8[0], v8[1], v8[2], v8[3]);
+          *reinterpret_cast<float4*>(a.x_res + off[r] + 4) = make_float4(v8[4], v8[5], v8[6], v8[7]);
+          if (a.x_copy) {
+            *reinterpret_cast<float4*>(a.x_copy + off[r]) = make_float4(v8[0], v8[1], v8[2], v8[3]);
+            *reinterpret_cast<float4*>(a.x_copy + off[r] + 4) = make_float4(v8[4], v8[5], v8[6], v8[7]);
+          }
+          if (a.xh_a) {
+            uint4 u;
+            u.x = (uint32_t)f32_to_bf16(v8[0]) | ((uint32_t)f32_to_bf16(v8[1]) << 16);
+            u.y = (uint32_t)f32_to_bf16(v8[2]) | ((uint32_t)f32_to_bf16(v8[3]) << 16);
+            u.z = (uint32_t)f32_to_bf16(v8[4]) | ((uint32_t)f32_to_bf16(v8[5]) << 16);
+            u.w = (uint32_t)f32_to_bf16(v8[6]) | ((uint32_t)f32_to_bf16(v8[7]) << 16);
+            *reinterpret_cast<uint4*>(a.xh_a + off[r]) = u;
+            if (a.xh_b) *reinterpret_cast<uint4*>(a.xh_b + off[r]) = u;
+          }
+        }
+        if (a.ssq_part) {   // (uniform)
+          float ss = 0.f;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) ss += v8[e] * v8[e];
+          if (!ok[r]) ss = 0.f;
+#pragma unroll
+          for (int o = 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);   // over the half-wavefront of the row
+          if (l32 == 0 && mrow[r] < a.M) a.ssq_part[(size_t)n_blk * a.M + mrow[r]] = ss;
+        }
+      }
+    }
+  }
+}
 
 __global__ __launch_bounds__(512, 2) void gemm_lds_kernel(GemmArgs a) {
   constexpr int WM = 8;
@@ -438,7 +621,8 @@ __global__ __launch_bounds__(512, 2) void gemm_lds_kernel(GemmArgs a) {
   }
   // the clamped loads past the last k tile are still in flight into LDS: they must land before the workgroup ends
   gemm2_wait_and_meet<0>();
-  gemm_epilogue<WM>(a, acc, m0 + wm * 128, nt0 + wn * 4, NT, lane);
+  if (a.epilogue == 3) gemm2_residual_epilogue(a, acc, g2_lds, m0, n_blk, wave, lane);
+  else gemm_epilogue<WM>(a, acc, m0 + wm * 128, nt0 + wn * 4, NT, lane);
 }
 
 static hipError_t launch_gemm_lds(const GemmArgs& a, hipStream_t s) {
@@ -457,12 +641,20 @@ static hipError_t launch_gemm_lds(const GemmArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+static bool gemm_takes_lds_kernel(const GemmArgs& a) {
+#ifndef GEMM_NO_LDS_KERNEL
+  // 256 x 256 tiles, one per CU, when they fill the chip at least once; else the smaller tiles
+  return (long)((a.M + 255) / 256) * ((a.N + 255) / 256) >= 256 && (a.K & 63) == 0 && a.K >= 256;
+#else
+  return false;
+#endif
+}
+
+int gemm_ssq_parts(const GemmArgs& a) { return gemm_takes_lds_kernel(a) ? (a.N + 255) / 256 : (a.N + 63) / 64; }
+
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0 || (a.K & 31) || (a.N & 15) || a.K < 32) return hipErrorInvalidValue;
-#ifndef GEMM_NO_LDS_KERNEL
-  // 256 x 256 tiles, one per CU, when they fill the chip at least once; else the smaller tiles below
-  if ((long)((a.M + 255) / 256) * ((a.N + 255) / 256) >= 256 && (a.K & 63) == 0 && a.K >= 256) return launch_gemm_lds(a, s);
-#endif
+  if (gemm_takes_lds_kernel(a)) return launch_gemm_lds(a, s);
   if (a.M >= 1024) return launch_gemm_wm<GEMM_WM_LARGE, GEMM_WAVES_LARGE>(a, s);
   if (a.M > 64) return launch_gemm_wm<8, 2>(a, s);   // 128 x 256
   return launch_gemm_wm<4, 2>(a, s);                 //  64 x 256

@@ -330,6 +330,30 @@ def test_bf16_large_tile_gemm_ragged_edges(harness, hidden, inter, batch):
     assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
 
 
+@pytest.mark.parametrize("wiring,nstd", [(ladder.LADDER_WIRING_LADDER, 0), (ladder.LADDER_WIRING_STANDARD, 0),
+                                         (ladder.LADDER_WIRING_LADDER, 1)])
+def test_bf16_wide_prefill_residual_epilogue_all_wirings(harness, wiring, nstd):
+    """Calls of more than 64 rows update the residual in the epilogue of each module's last GEMM (old rows +
+    product + peers, bf16 rows for the consumers, whose products are scaled by the rows' 1/rms).  Seven peers
+    (more than the epilogue requests at once), 150 ragged rows on the small-tile GEMM, and every wiring: in
+    the hybrid stack the last standard module's output has two consumers."""
+    w = inputs.WORKLOADS["70b_r8_decode"].with_(name=f"wide_residual_{wiring}_{nstd}", n_layers=3, hidden=512, inter=448,
+                                                batch=3, prefill=50, decode_steps=1)
+    res = harness.run_case(w, wiring=wiring, n_standard_layers=nstd)
+    assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
+
+
+def test_bf16_large_tile_residual_epilogue_hybrid(harness):
+    """The 256 x 256-tile GEMM's residual epilogue (staged through LDS, whole rows per memory instruction) with a
+    ragged last row block and a ragged last column block (hidden 1056), in a hybrid stack (one standard layer, two
+    ladder layers: two consumers at the boundary) with seven peers."""
+    w = inputs.WORKLOADS["70b_r8_decode"].with_(name="large_tile_residual_hybrid", n_layers=3, hidden=1056, inter=1024,
+                                                n_q_heads=8, n_kv_heads=2, head_dim=64, batch=12, prefill=1100,
+                                                decode_steps=1)
+    res = harness.run_case(w, gen_device="cuda:0", wiring=ladder.LADDER_WIRING_LADDER, n_standard_layers=1)
+    assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
+
+
 def test_seeded_shape_sweep(harness):
     """A fixed pseudo-random walk over shapes and switches (head size 64 / 128, 1 - 3 kv heads with 1 - 8 q
     heads each, ragged hidden / intermediate sizes incl. ones that fall back to the plain kernels, batch
