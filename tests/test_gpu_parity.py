@@ -341,6 +341,9 @@ def test_bf16_wide_prefill_residual_epilogue_all_wirings(harness, wiring, nstd):
                                                 batch=3, prefill=50, decode_steps=1)
     res = harness.run_case(w, wiring=wiring, n_standard_layers=nstd)
     assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
+    # the whole model on one rank: no peers to add
+    res = harness.run_case(w.with_(name=w.name + "_r1", tp_degree=1, n_real_shards=1), wiring=wiring, n_standard_layers=nstd)
+    assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
 
 
 def test_bf16_large_tile_residual_epilogue_hybrid(harness):
@@ -351,6 +354,9 @@ def test_bf16_large_tile_residual_epilogue_hybrid(harness):
                                                 n_q_heads=8, n_kv_heads=2, head_dim=64, batch=12, prefill=1100,
                                                 decode_steps=1)
     res = harness.run_case(w, gen_device="cuda:0", wiring=ladder.LADDER_WIRING_LADDER, n_standard_layers=1)
+    assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
+    # two peers (fewer than the epilogue requests at once), ladder wiring
+    res = harness.run_case(w.with_(name="large_tile_residual_r3", tp_degree=3, n_layers=2), gen_device="cuda:0")
     assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
 
 
