@@ -120,6 +120,8 @@ def run_decode(args):
         w = w.with_(batch=args.batch)
     if args.kv and w.kv_preload:
         w = w.with_(kv_preload=args.kv)
+    if args.no_peers:
+        w = w.with_(tp_degree=w.n_real_shards)
     dev = "cuda:0"
     prof_steps = 8
     total_steps = args.warmup + args.steps + prof_steps
@@ -127,7 +129,8 @@ def run_decode(args):
     ctx = build_context(w, dev, total_steps, w.batch * max(w.prefill, 1), max_tokens=max(w.prefill, 1),
                         decode_graph=1 if args.graph else 0, overlap_modules=0 if args.no_overlap else 1,
                         decode_fused=0 if args.no_fused else 1, reduce_delay_us=args.reduce_delay_us,
-                        wiring=ladder.LADDER_WIRING_STANDARD if args.wiring == "standard" else ladder.LADDER_WIRING_LADDER)
+                        wiring={"ladder": ladder.LADDER_WIRING_LADDER, "standard": ladder.LADDER_WIRING_STANDARD,
+                                "parallel": ladder.LADDER_WIRING_PARALLEL}[args.wiring])
     if w.kv_preload:
         for i in range(w.n_layers):
             for r in range(w.n_real_shards):
@@ -296,8 +299,11 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--graph", action="store_true", help="replay decode steps from a captured HIP graph instead of eager launches")
     ap.add_argument("--no-overlap", action="store_true", help="one compute stream instead of attention / MLP streams")
-    ap.add_argument("--wiring", choices=["ladder", "standard"], default="ladder",
+    ap.add_argument("--wiring", choices=["ladder", "standard", "parallel"], default="ladder",
                     help="residual wiring of the stack (the metric is quoted on ladder; standard is the paper's Eq. 1 baseline)")
+    ap.add_argument("--no-peers", action="store_true",
+                    help="no synthetic peer partial sums: with the standard wiring and no emulated latency this is the "
+                         "communication-free upper bound of the paper's comparison (result is then not the metric)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="before the steps, run 4 plain copy kernels of 1 GiB (read 1 GiB, write 1 GiB each): "
                          "the known-size dispatches that scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters")

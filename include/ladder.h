@@ -45,7 +45,7 @@ extern "C" {
 typedef struct ladder_ctx ladder_ctx; /* opaque, owned by the library */
 
 enum { LADDER_FP32 = 0, LADDER_BF16 = 1 };
-enum { LADDER_WIRING_LADDER = 0, LADDER_WIRING_STANDARD = 1 };
+enum { LADDER_WIRING_LADDER = 0, LADDER_WIRING_STANDARD = 1, LADDER_WIRING_PARALLEL = 2 };
 enum { LADDER_PATH_AUTO = 0, LADDER_PATH_GENERIC = 1 };
 
 enum {
@@ -72,7 +72,11 @@ typedef struct {
   int32_t max_tokens;     /* largest T of a prefill call (workspaces hold max_batch*max_tokens rows) */
   int32_t dtype;          /* LADDER_FP32 | LADDER_BF16: storage type T of weights, inputs, KV cache, peers */
   int32_t wiring;         /* LADDER_WIRING_LADDER: module m reads x_{m-2} (Eq. 2);
-                             LADDER_WIRING_STANDARD: module m reads x_{m-1} (Eq. 1) */
+                             LADDER_WIRING_STANDARD: module m reads x_{m-1} (Eq. 1);
+                             LADDER_WIRING_PARALLEL: the parallel attention / MLP block that section "Faster
+                             Inference with Ladder Residual" compares with: both modules of a layer read the
+                             layer's input (attention x_{m-1}, MLP x_{m-2}); one reduce per layer where the
+                             reduce is a step of its own (n_standard_layers must be 0) */
   int32_t n_standard_layers; /* hybrid: with wiring LADDER, the first n_standard_layers layers still use
                                 the standard wiring (the paper's hybrid keeps ladder for the upper layers) */
   int32_t reduce_on_side_stream; /* 1: reduce + residual add overlap the next module on a side stream;

@@ -237,11 +237,16 @@ def all_reduce(m: int, parts: Sequence[np.ndarray], peers: Optional[np.ndarray],
 
 def _lags(n_modules: int, wiring) -> List[int]:
     """Input index of module m is m - lag[m]: 2 = ladder (Eq. 2), 1 = standard (Eq. 1).
-    `wiring` is "ladder", "standard" or a sequence of per-module lags (hybrid)."""
+    `wiring` is "ladder", "standard", "parallel" or a sequence of per-module lags (hybrid).
+    "parallel" is the parallel attention / MLP block that section "Faster Inference with Ladder Residual"
+    compares with: both modules of a layer read the layer's input and both outputs are added to it, i.e. the
+    attention module reads x_{m-1} and the MLP module x_{m-2}."""
     if wiring == "ladder":
         return [2] * n_modules
     if wiring == "standard":
         return [1] * n_modules
+    if wiring == "parallel":
+        return [1 if m % 2 == 1 else 2 for m in range(1, n_modules + 1)]
     lag = list(wiring)
     assert len(lag) == n_modules and all(v in (1, 2) for v in lag)
     return lag

@@ -182,6 +182,7 @@ hipError_t timed(ladder_ctx* c, int cls, hipStream_t s, F&& f) {
 
 int lag_of(const ladder_ctx* c, int m) {  // module m reads x_{m - lag}
   if (c->cfg.wiring == LADDER_WIRING_STANDARD) return 1;
+  if (c->cfg.wiring == LADDER_WIRING_PARALLEL) return (m & 1) ? 1 : 2;   // both modules of a layer read the layer's input
   return (m - 1) / 2 < c->cfg.n_standard_layers ? 1 : 2;
 }
 
@@ -194,10 +195,11 @@ int check_config(const ladder_config* g, std::string& why) {
     return LADDER_E_ARG;
   }
   if (g->dtype != LADDER_FP32 && g->dtype != LADDER_BF16) { why = "unknown dtype"; return LADDER_E_ARG; }
-  if (g->wiring != LADDER_WIRING_LADDER && g->wiring != LADDER_WIRING_STANDARD) { why = "unknown wiring"; return LADDER_E_ARG; }
+  if (g->wiring != LADDER_WIRING_LADDER && g->wiring != LADDER_WIRING_STANDARD && g->wiring != LADDER_WIRING_PARALLEL) { why = "unknown wiring"; return LADDER_E_ARG; }
   if (g->kernel_path != LADDER_PATH_AUTO && g->kernel_path != LADDER_PATH_GENERIC) { why = "unknown kernel_path"; return LADDER_E_ARG; }
   if (!(g->rms_eps > 0.f) || !(g->rope_theta > 0.f)) { why = "rms_eps and rope_theta must be positive"; return LADDER_E_ARG; }
   if (g->n_standard_layers < 0 || g->n_standard_layers > g->n_layers) { why = "n_standard_layers out of range"; return LADDER_E_SHAPE; }
+  if (g->wiring == LADDER_WIRING_PARALLEL && g->n_standard_layers != 0) { why = "n_standard_layers must be 0 with the parallel wiring"; return LADDER_E_SHAPE; }
   if (g->hidden % 8) { why = "hidden must be a multiple of 8"; return LADDER_E_SHAPE; }
   if (g->n_q_heads % g->n_kv_heads) { why = "n_q_heads must be a multiple of n_kv_heads"; return LADDER_E_SHAPE; }
   if (g->head_dim % 2 || g->head_dim > 256) { why = "head_dim must be even and <= 256"; return LADDER_E_SHAPE; }
@@ -443,7 +445,10 @@ int run_reduce(ladder_ctx* c, int m, int rows, int n_slots, const void* emb, flo
     else { a.out_b = out; a.gain_b = gain; }
   }
   a.x_out = x_out;
-  if (m > 0 && g.reduce_delay_us > 0) {   // the emulated collective takes this long before its result is there
+  // (the parallel block sums the partial sums of both modules of a layer before its one collective: the
+  // attention module's reduce stands for the local addition, the MLP module's for the collective)
+  const bool local_only = g.wiring == LADDER_WIRING_PARALLEL && (m & 1);
+  if (m > 0 && g.reduce_delay_us > 0 && !local_only) {   // the emulated collective takes this long before its result is there
     const unsigned long long ticks = (unsigned long long)g.reduce_delay_us * (unsigned long long)c->wall_khz / 1000ull;
     HIP_TRY(c, timed(c, LADDER_K_OTHER, s, [&] {
       hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(64), 0, s, ticks);
@@ -550,18 +555,20 @@ void build_fused_plan(ladder_ctx* c, int B) {
     if (H <= 4096 && j.n_groups % 2 == 0) { j.tn = 2; j.n_groups /= 2; }
     return j;
   };
-  auto residual = [&](GemvJob& j, int m) {
+  // the job adds the output (and peers) of module m to ring slot at - 1 and leaves the sum in slot at (at = m
+  // unless the two modules of a layer are added in the other order)
+  auto residual = [&](GemvJob& j, int m, int at) {
     j.N = H; j.n_groups = H / 16; j.epi = EPI_RESIDUAL;
-    j.x_old = c->x_ring[(m - 1) % 3]; j.x_new = c->x_ring[m % 3]; j.xh_new = c->xh_ring[m % 3];
+    j.x_old = c->x_ring[(at - 1) % 3]; j.x_new = c->x_ring[at % 3]; j.xh_new = c->xh_ring[at % 3];
     if (c->peers && c->n_peers > 0) {
       j.peers = (const bf16_t*)c->peers + (size_t)(m % g.peer_pool) * c->n_peers * (size_t)g.peer_rows * H;
       j.n_peers = c->n_peers; j.peer_stride = (size_t)g.peer_rows * H;
     }
   };
-  auto job_o = [&](int l, int m) {
+  auto job_o = [&](int l, int m, int at = -1) {
     GemvJob j{};
     j.xb = (const bf16_t*)c->obuf; j.ldx = nqd; j.wp = layer(l).po; j.M = B; j.K = nqd;
-    residual(j, m);
+    residual(j, m, at < 0 ? m : at);
     // its K range is short: two tiles per workgroup halve the number of (latency-bound) workgroups
     if (j.n_groups % 2 == 0) { j.tn = 2; j.n_groups /= 2; }
     return j;
@@ -581,10 +588,10 @@ void build_fused_plan(ladder_ctx* c, int B) {
     if ((B >= 13 || H <= 2048 || (j.n_groups / 2 <= c->n_cu && B <= 6)) && j.n_groups % 2 == 0) { j.tn = 2; j.n_groups /= 2; }
     return j;
   };
-  auto job_dn = [&](int l, int m) {
+  auto job_dn = [&](int l, int m, int at = -1) {
     GemvJob j{};
     j.xb = (const bf16_t*)c->act; j.ldx = I; j.wp = layer(l).pd; j.M = B; j.K = I;
-    residual(j, m);
+    residual(j, m, at < 0 ? m : at);
     return j;
   };
   auto job_att = [&](int l) {
@@ -712,6 +719,16 @@ void build_fused_plan(ladder_ctx* c, int B) {
       else plan.push_back(att(aj, {o, gu_b}));
       if (l < N) plan.push_back(qkv_down(job_qkv(l + 1, 2 * l - 1), job_dn(l, 2 * l)));
       else plan.push_back(one(job_dn(N, 2 * N)));
+    }
+  } else if (g.wiring == LADDER_WIRING_PARALLEL) {
+    // both modules of layer l read x_{2l-2}: THREE launches per layer,
+    //     { gate/up_l , qkv_l }     { attention_l , down_l }     { o_l }
+    // with the two outputs added in the order MLP, attention (the sum is the same up to rounding): down_l does
+    // not wait for attention that way, and o_l, which does, is the short one.
+    for (int l = 1; l <= N; ++l) {
+      plan.push_back(two(job_gu(l, 2 * l - 2), job_qkv(l, 2 * l - 2)));
+      plan.push_back(att(job_att(l), {job_dn(l, 2 * l, 2 * l - 1)}));
+      plan.push_back(one(job_o(l, 2 * l - 1, 2 * l)));
     }
   } else {
     for (int l = 1; l <= N; ++l) {

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libladder.so")
 
 LADDER_FP32, LADDER_BF16 = 0, 1
-LADDER_WIRING_LADDER, LADDER_WIRING_STANDARD = 0, 1
+LADDER_WIRING_LADDER, LADDER_WIRING_STANDARD, LADDER_WIRING_PARALLEL = 0, 1, 2
 LADDER_PATH_AUTO, LADDER_PATH_GENERIC = 0, 1
 LADDER_OK, LADDER_E_ARG, LADDER_E_SHAPE, LADDER_E_STATE, LADDER_E_OVERFLOW, LADDER_E_HIP = 0, -1, -2, -3, -4, -5
 (LADDER_K_REDUCE_NORM, LADDER_K_GEMV, LADDER_K_GEMM, LADDER_K_ROPE_APPEND, LADDER_K_ATTN_DECODE,

@@ -46,6 +46,8 @@ def make_tensors(w: inputs.Workload, device="cpu"):
 def oracle_lag(w: inputs.Workload, wiring: int, n_standard_layers: int):
     if wiring == ladder.LADDER_WIRING_STANDARD:
         return "standard"
+    if wiring == ladder.LADDER_WIRING_PARALLEL:
+        return "parallel"
     if n_standard_layers == 0:
         return "ladder"
     return [1 if (m - 1) // 2 < n_standard_layers else 2 for m in range(1, 2 * w.n_layers + 1)]

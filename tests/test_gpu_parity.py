@@ -34,7 +34,8 @@ def test_tiny_fp32_full(harness):
     assert len(res.errs) == 9 and max(res.errs) < TOL_FP32, res.errs
 
 
-@pytest.mark.parametrize("wiring,nstd", [(ladder.LADDER_WIRING_STANDARD, 0), (ladder.LADDER_WIRING_LADDER, 1)])
+@pytest.mark.parametrize("wiring,nstd", [(ladder.LADDER_WIRING_STANDARD, 0), (ladder.LADDER_WIRING_LADDER, 1),
+                                         (ladder.LADDER_WIRING_PARALLEL, 0)])
 def test_tiny_fp32_standard_and_hybrid_wiring(harness, wiring, nstd):
     res = harness.run_case(TINY.with_(n_layers=3), decode_steps=2, wiring=wiring, n_standard_layers=nstd)
     assert max(res.errs) < TOL_FP32, res.errs
@@ -197,6 +198,13 @@ def test_emulated_reduce_latency_changes_time_not_results(harness):
         ctx.free()
         return dt
     assert decode_ms(300) - decode_ms(0) > 0.8 * 6 * 0.3
+    # the parallel block has one collective per layer: per-operation schedule (bf16 streaming kernels, two
+    # module streams) against the oracle, with and without the wait
+    res = harness.run_case(w, wiring=ladder.LADDER_WIRING_PARALLEL, decode_fused=0)
+    assert max(res.errs) < TOL_BF16, res.errs
+    late = harness.run_case(w, gpu_only=True, wiring=ladder.LADDER_WIRING_PARALLEL, reduce_delay_us=300)
+    for x, y in zip(res.gpu, late.gpu):
+        assert np.array_equal(x, y)
 
 
 # ---- fused decode launches ----------------------------------------------------------------------
@@ -205,9 +213,10 @@ R8_SMALL = inputs.WORKLOADS["70b_r8_decode"].with_(name="r8_small", n_layers=3, 
 
 
 @pytest.mark.parametrize("wiring,nstd", [(ladder.LADDER_WIRING_LADDER, 0), (ladder.LADDER_WIRING_STANDARD, 0),
-                                         (ladder.LADDER_WIRING_LADDER, 2)])
+                                         (ladder.LADDER_WIRING_LADDER, 2), (ladder.LADDER_WIRING_PARALLEL, 0)])
 def test_fused_decode_matches_oracle(harness, wiring, nstd):
-    """Fused launches (ladder: paired jobs; standard / hybrid: one job per launch) against the oracle,
+    """Fused launches (ladder: paired jobs; standard / hybrid: one job per launch; parallel block: three launches
+    per layer, the MLP output added before the attention output) against the oracle,
     with synthetic peers, preloaded cache, decode crossing a 32-position chunk boundary (125 -> 131)."""
     res = harness.run_case(R8_SMALL, kv_preload=125 if nstd else 700, wiring=wiring, n_standard_layers=nstd, decode_fused=1)
     assert len(res.errs) == 6 and max(res.errs) < TOL_BF16, res.errs
@@ -331,7 +340,7 @@ def test_bf16_large_tile_gemm_ragged_edges(harness, hidden, inter, batch):
 
 
 @pytest.mark.parametrize("wiring,nstd", [(ladder.LADDER_WIRING_LADDER, 0), (ladder.LADDER_WIRING_STANDARD, 0),
-                                         (ladder.LADDER_WIRING_LADDER, 1)])
+                                         (ladder.LADDER_WIRING_LADDER, 1), (ladder.LADDER_WIRING_PARALLEL, 0)])
 def test_bf16_wide_prefill_residual_epilogue_all_wirings(harness, wiring, nstd):
     """Calls of more than 64 rows update the residual in the epilogue of each module's last GEMM (old rows +
     product + peers, bf16 rows for the consumers, whose products are scaled by the rows' 1/rms).  Seven peers

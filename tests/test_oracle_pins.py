@@ -203,6 +203,10 @@ def test_two_layer_ladder_and_standard_against_torch_modules():
     # hybrid: layer 1 standard, layer 2 ladder -> h3 reads x1, h4 reads x2 of the standard prefix
     y3 = s2 + A(1, s1); y4 = y3 + M(1, s2)
     assert np.max(np.abs(lo.forward_eq2(emb, layers, cfg, wiring=[1, 1, 2, 2]) - y4)) < 1e-11
+    # parallel attention / MLP block: layer output = layer input + A(layer input) + M(layer input)
+    p2 = x0 + A(0, x0) + M(0, x0); p4 = p2 + A(1, p2) + M(1, p2)
+    assert np.max(np.abs(lo.forward_eq2(emb, layers, cfg, wiring="parallel") - p4)) < 1e-11
+    assert np.max(np.abs(p4 - s4)) > 1e-3 and np.max(np.abs(p4 - x4)) > 1e-3
 
 
 def test_shard_sum_equals_unsharded():
