@@ -88,7 +88,8 @@ def cpu_baseline_decode(w, device, n_layers_sample, kv_len):
     cfg = from_torch.config_from_workload(ws)
     layers = [from_torch.layer_from_tensors([{k: v.cpu() for k, v in inputs.layer_weights(ws, i, r, device).items()}
                                              for r in range(ws.n_real_shards)]) for i in range(n_layers_sample)]
-    state = lo.State.empty(cfg, ws.n_real_shards, ws.batch, kv_len + 4)
+    n_steps = 20   # about 10 s of CPU work on the box's 16 host cores
+    state = lo.State.empty(cfg, ws.n_real_shards, ws.batch, kv_len + n_steps + 1)
     for i in range(n_layers_sample):
         for r in range(ws.n_real_shards):
             k, v = inputs.kv_cache(ws, i, r, ws.batch, kv_len, device)
@@ -97,7 +98,6 @@ def cpu_baseline_decode(w, device, n_layers_sample, kv_len):
     peers = inputs.peer_partials(ws, ws.batch, device)
     opeers = from_torch.to_f64(peers) if peers is not None else None
     e = from_torch.to_f64(inputs.embeddings(ws, ws.batch, 1, inputs.SEED_DECODE0, device))
-    n_steps = 3
     t0 = time.perf_counter()
     for i in range(n_steps):
         if i:
