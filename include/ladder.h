@@ -102,7 +102,8 @@ typedef struct {
   int32_t reduce_delay_us; /* emulated all-reduce latency (Fig. 2 / Table 2 of the paper vary the interconnect):
                               > 0 puts a timed wait of that many microseconds in front of every partial-sum
                               reduce, on the stream the reduce runs on.  Per-operation schedules only: a
-                              non-zero value switches the fused decode schedule off.  0 .. 10000; same results. */
+                              non-zero value switches the fused decode schedule off.  0 .. 10000; same results.
+                              (LADDER_WIRING_PARALLEL: one wait per layer, in front of the MLP module's reduce.) */
   float rms_eps;          /* RMSNorm epsilon (inside the square root) */
   float rope_theta;       /* rotary base; pair (2j,2j+1) turns by pos * theta^(-2j/d) */
 } ladder_config;

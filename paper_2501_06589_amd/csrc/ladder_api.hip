@@ -7,13 +7,16 @@
 // writes its partial sums into parts[m%2].  "AsyncAllReduce(m)" = reduce_norm: it waits for the event
 // recorded after module m, folds the partial sums (computed shards, split-K slots, synthetic peers)
 // into the fp32 residual x in place (x_m = x_{m-1} + sum), and emits the RMS-normed input of the
-// module(s) that read x_m: module m+2 with the ladder wiring, module m+1 with the standard wiring.
+// module(s) that read x_m: module m+2 with the ladder wiring, module m+1 with the standard wiring (the
+// parallel attention / MLP block: both modules of a layer read the layer's input, lag_of()).
 // The event recorded after it is the handle; module m+lag waits on it.  For calls of at most 64 rows
 // the two module kinds may run on two streams (or the reduces on a side stream), so that with the
-// ladder wiring reduce(m) overlaps module m+1; larger calls run in order on one stream.
+// ladder wiring reduce(m) overlaps module m+1; larger calls run in order on one stream, and with the
+// packed weights and one computed shard their reduce is the epilogue of the module's last GEMM
+// (fuse_residual).
 //
 // Fused decode schedule (build_fused_plan / fused_body: bf16, batch <= 16, one computed shard).  A
-// decode step is a fixed list of launches of one kernel, each holding up to two independent jobs
+// decode step is a fixed list of launches of one kernel, each holding up to four independent jobs
 // (under the ladder wiring the MLP projections of layer l and the attention side of layer l+1);
 // reduce, residual add, RMSNorm, rotary and cache append are epilogues of the projections.
 #include <math.h>
