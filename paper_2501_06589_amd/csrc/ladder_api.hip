@@ -256,7 +256,7 @@ int consumers_of(const ladder_ctx* c, int m, int out[2]) {
 // epilogue of the module's last GEMM instead of a kernel of its own, which saves a round trip of the fp32
 // product through memory.  The epilogue leaves the new rows as bf16 for the modules that read x_m, un-normed:
 // their 1/rms (from the sums of squares the epilogue also leaves) scales the consumer's product instead.
-int fuse_residual(ladder_ctx* c, GemmArgs& a, int m, int rows, float* x_copy, int cons[2]) {
+int fuse_residual(ladder_ctx* c, GemmArgs& a, int m, float* x_copy, int cons[2]) {
   const ladder_config& g = c->cfg;
   a.epilogue = 3; a.x_res = c->x; a.x_copy = x_copy;
   if (c->peers && c->n_peers > 0) {
@@ -267,7 +267,6 @@ int fuse_residual(ladder_ctx* c, GemmArgs& a, int m, int rows, float* x_copy, in
   const int nc = consumers_of(c, m, cons);
   if (nc > 0) { a.xh_a = (bf16_t*)c->y[cons[0] & 1]; a.ssq_part = c->ssq_part; }
   if (nc > 1) a.xh_b = (bf16_t*)c->y[cons[1] & 1];
-  (void)rows;
   return nc;
 }
 
@@ -369,7 +368,7 @@ int run_module(ladder_ctx* c, int m, int B, int T, int pos0, hipStream_t s, int*
         GemmArgs a{};
         a.x = (const bf16_t*)c->obuf; a.ldx = nqd; a.wp = L.po; a.M = rows; a.K = nqd; a.N = H; a.out = pout + slots * pstride; a.epilogue = 0;
         int cons[2], nc = 0;
-        if (fuse) nc = fuse_residual(c, a, m, rows, x_copy, cons);
+        if (fuse) nc = fuse_residual(c, a, m, x_copy, cons);
         HIP_TRY(c, timed(c, LADDER_K_GEMM, s, [&] { return launch_gemm_mfma(a, s); }));
         if (fuse) { const int rc = finish_residual(c, a, rows, nc, cons, s); if (rc) return rc; }
         slots += 1;
@@ -400,7 +399,7 @@ int run_module(ladder_ctx* c, int m, int B, int T, int pos0, hipStream_t s, int*
         GemmArgs b{};
         b.x = (const bf16_t*)c->act; b.ldx = I; b.wp = L.pd; b.M = rows; b.K = I; b.N = H; b.out = pout + slots * pstride; b.epilogue = 0;
         int cons[2], nc = 0;
-        if (fuse) nc = fuse_residual(c, b, m, rows, x_copy, cons);
+        if (fuse) nc = fuse_residual(c, b, m, x_copy, cons);
         HIP_TRY(c, timed(c, LADDER_K_GEMM, s, [&] { return launch_gemm_mfma(b, s); }));
         if (fuse) { const int rc = finish_residual(c, b, rows, nc, cons, s); if (rc) return rc; }
         slots += 1;

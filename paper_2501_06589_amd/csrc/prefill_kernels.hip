@@ -654,6 +654,13 @@ int gemm_ssq_parts(const GemmArgs& a) { return gemm_takes_lds_kernel(a) ? (a.N +
 
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0 || (a.K & 31) || (a.N & 15) || a.K < 32) return hipErrorInvalidValue;
+  // operands of the chosen epilogue
+  if (a.epilogue < 0 || a.epilogue > 3) return hipErrorInvalidValue;
+  if (a.epilogue == 0 && !a.out) return hipErrorInvalidValue;
+  if (a.epilogue == 1 && !a.act) return hipErrorInvalidValue;
+  if (a.epilogue == 2 && (!a.q_out || !a.cache_k || !a.cache_v || !a.cos_tab || !a.sin_tab || a.T <= 0 || a.d <= 0)) return hipErrorInvalidValue;
+  if (a.epilogue == 3 && (!a.x_res || a.n_peers < 0 || (a.n_peers > 0 && !a.peers) || (a.xh_b && !a.xh_a) || (a.ssq_part && !a.xh_a)))
+    return hipErrorInvalidValue;
   if (gemm_takes_lds_kernel(a)) return launch_gemm_lds(a, s);
   if (a.M >= 1024) return launch_gemm_wm<GEMM_WM_LARGE, GEMM_WAVES_LARGE>(a, s);
   if (a.M > 64) return launch_gemm_wm<8, 2>(a, s);   // 128 x 256
