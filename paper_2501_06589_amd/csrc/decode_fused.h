@@ -23,7 +23,8 @@ struct GemvJob {
   // with device-coherent loads
   const unsigned* wait_on;
   unsigned wait_target;
-  int tn;                  // 16-column tiles per workgroup: 1 (0 means 1), 2, or 3 (un-normed jobs without a wait)
+  int tn;                  // 16-column tiles per workgroup: 1 (0 means 1), 2, 3 (un-normed jobs without a wait)
+                           // or 4 (normed jobs without a wait, un-normed jobs with one)
   int group0, n_groups;    // this job's workgroups own the tile groups [group0, group0 + n_groups), tn tiles
                            // each; a projection may be cut over two launches
   int epi;

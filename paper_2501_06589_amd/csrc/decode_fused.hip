@@ -33,6 +33,7 @@
 #include <algorithm>
 
 #include "common.h"
+#include <cstddef>
 #include "decode_fused.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
@@ -43,7 +44,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 #define FUSED_WAVES 8
 // descriptor byte of a job in the preloaded `kinds` argument of the kernel
 #define FUSED_KIND_MASK 3u          // JOB_NONE / JOB_GEMV / JOB_ATTN
-#define FUSED_KIND_TN_SHIFT 2       // two bits: tiles per workgroup (1, 2, 3)
+#define FUSED_KIND_TN_SHIFT 2       // two bits: tiles per workgroup - 1 (1 .. 4 tiles)
 #define FUSED_KIND_NORMED 16u       // the job folds RMSNorm in
 #define FUSED_KIND_WAITS 32u        // the job waits for another job of the launch
 #define FUSED_KIND_SLOT_SHIFT 6     // two bits: index of the job's preloaded (weights, operand) pointer pair, 3 = none
@@ -81,7 +82,7 @@ __device__ __forceinline__ void unpack8f(const uint4 v, float f[8]) {
 // kernel hands them over from preloaded kernel arguments where it can, so that the first weight tiles and
 // operand slices are requested before the job's descriptor (j) has arrived from memory.
 template <bool NORMED, int U, int TN, bool COH = false>
-__device__ void gemv_job(const GemvJob& j, const void* wp, const bf16_t* xop, int KT, int group0, int M, int lb, float* smem) {
+__device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const bf16_t* xop, int KT, int group0, int M, int lb, float* smem) {
   constexpr int WAVES = FUSED_WAVES;
   const int grp = group0 + lb;
   const int tid = threadIdx.x;
@@ -592,7 +593,15 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(const vo
   if ((kb & FUSED_KIND_MASK) == (unsigned)JOB_ATTN) {
     attn_job<D, G>(fa.a, lb, smem, &s_flag);
   } else {
-    const GemvJob& j = fa.g[job];
+    // The job's descriptor is read in place from the kernel-argument segment (uniform index -> scalar loads).
+    // Indexing the by-value argument itself makes the compiler, beyond some amount of code that uses it, keep a
+    // copy of all of it in private memory (a kilobyte of scratch stores at the head of every wavefront).  The
+    // leading arguments are four pointers and six 32-bit words, after which the block follows with no padding.
+    constexpr size_t kLeadingArgBytes = 4 * sizeof(void*) + 6 * sizeof(unsigned);
+    static_assert(kLeadingArgBytes % alignof(FusedArgs) == 0, "FusedArgs directly behind the leading arguments");
+    typedef __attribute__((address_space(4))) const char* kernarg_ptr_t;
+    const kernarg_ptr_t ka = (kernarg_ptr_t)__builtin_amdgcn_kernarg_segment_ptr();
+    const GemvJob& j = *(const GemvJob*)(ka + kLeadingArgBytes + offsetof(FusedArgs, g) + (size_t)job * sizeof(GemvJob));
     const unsigned slot = kb >> FUSED_KIND_SLOT_SHIFT;   // which preloaded pointer pair: 0, 1, or 3 = none
     const int gi = job - ((kinds & FUSED_KIND_MASK) == (unsigned)JOB_ATTN ? 1 : 0);   // index among the GEMV jobs
     const void* wp = slot == 0 ? wp_a : wp_b;
@@ -600,11 +609,14 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(const vo
     const unsigned geo = gi == 0 ? geo0 : gi == 1 ? geo1 : geo2;
     int KT = (int)(geo >> 16), group0 = (int)(geo & 0xFFFFu), M = (int)(end2_m >> 16);
     if (slot == 3) { wp = j.wp; xop = j.xb; KT = j.K >> 5; group0 = j.group0; M = j.M; }
-    const unsigned tn = (kb >> FUSED_KIND_TN_SHIFT) & 3u;
+    const unsigned tn = ((kb >> FUSED_KIND_TN_SHIFT) & 3u) + 1u;
     const bool normed = (kb & FUSED_KIND_NORMED) != 0;
     if (kb & FUSED_KIND_WAITS) {   // (the plan gives only the un-normed O projection a wait)
-      if (tn == 2) gemv_job<false, FUSED_U2, 2, true>(j, wp, xop, KT, group0, M, lb, smem);
+      if (tn == 4) gemv_job<false, 1, 4, true>(j, wp, xop, KT, group0, M, lb, smem);
+      else if (tn == 2) gemv_job<false, FUSED_U2, 2, true>(j, wp, xop, KT, group0, M, lb, smem);
       else gemv_job<false, FUSED_U, 1, true>(j, wp, xop, KT, group0, M, lb, smem);
+    } else if (tn == 4) {   // (the plan builds four-tile workgroups for normed projections only: gate/up at 13 rows and more)
+      gemv_job<true, 1, 4>(j, wp, xop, KT, group0, M, lb, smem);
     } else if (tn == 3) {   // (the plan builds three-tile workgroups for un-normed projections only)
       gemv_job<false, 1, 3>(j, wp, xop, KT, group0, M, lb, smem);
     } else if (tn == 2) {
@@ -668,7 +680,11 @@ static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStrea
           rows = j.M;
         }
       }
-      kb |= (unsigned)(j.tn >= 2 ? j.tn : 1) << FUSED_KIND_TN_SHIFT;
+      // tiles per workgroup the kernel has code for: 1 and 2 for every job, 3 without norm and wait, 4 with norm
+      // and without wait or without norm and with a wait
+      const int tn = j.tn >= 2 ? j.tn : 1;
+      if (tn > 4 || (tn == 3 && (j.normed || j.wait_on)) || (tn == 4 && ((j.normed != 0) == (j.wait_on != nullptr)))) return hipErrorInvalidValue;
+      kb |= (unsigned)(tn - 1) << FUSED_KIND_TN_SHIFT;
       if (j.normed) kb |= FUSED_KIND_NORMED;
       if (j.wait_on) kb |= FUSED_KIND_WAITS;
       kb |= slot << FUSED_KIND_SLOT_SHIFT;
@@ -700,7 +716,7 @@ static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStrea
 // LDS a job needs: the attention job's merge area or the GEMV job's cross-wave sums
 size_t fused_attn_lds_bytes(int d, int g) { return (size_t)(2 * FUSED_WAVES * 16 + FUSED_WAVES * g * d + g * 64) * 4; }
 size_t fused_gemv_lds_bytes() {
-  return (size_t)(FUSED_WAVES * 3 * 16 * 17 + FUSED_WAVES * 16) * 4;   // sized for three-tile workgroups
+  return (size_t)(FUSED_WAVES * 4 * 16 * 17 + FUSED_WAVES * 16) * 4;   // sized for four-tile workgroups
 }
 
 // dynamic LDS above 64 KiB has to be allowed per kernel, once (outside any stream capture)

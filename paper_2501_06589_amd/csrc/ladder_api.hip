@@ -588,6 +588,11 @@ void build_fused_plan(ladder_ctx* c, int B) {
     // tiles: 70B shard at R = 8, batch 4: 3.51 -> 3.41 ms)
     // (measured: batch 1 - 6 faster, 7 - 12 slower)
     if ((B >= 13 || H <= 2048 || (j.n_groups / 2 <= c->n_cu && B <= 6)) && j.n_groups % 2 == 0) { j.tn = 2; j.n_groups /= 2; }
+#ifndef FUSED_NO_GU4
+    // (13 rows and more, and enough tiles that quadruples still give most CUs a workgroup: four tiles per
+    // workgroup halve the operand traffic once more)
+    if (B >= 13 && j.tn == 2 && j.n_groups % 2 == 0 && 4 * (j.n_groups / 2) >= 3 * c->n_cu) { j.tn = 4; j.n_groups /= 2; }
+#endif
     return j;
   };
   auto job_dn = [&](int l, int m, int at = -1) {
@@ -714,6 +719,15 @@ void build_fused_plan(ladder_ctx* c, int B) {
       // block order: attention, as many gate/up workgroups as leave every CU one long workgroup, o_l (resident
       // from the start, asleep until attention is done, then beside the rest of gate/up), the rest of gate/up
       GemvJob gu_a = job_gu(l, 2 * l - 2), gu_b = gu_a;
+#ifndef FUSED_NO_O4
+      // every workgroup of the launch should be resident from the start (two per CU): workgroups beyond that wait
+      // for a slot, and the last in block order are long gate/up workgroups.  Where attention, gate/up and o_l
+      // make more than that (large batches: attention has a workgroup per sequence and split), o_l takes four
+      // tiles per workgroup, if its K range is long enough for that to pay (measured: 8B shape at batch 16
+      // 4.06 -> 3.86 ms per step, 70B R = 4 shard at batch 16 8.89 -> 8.61; with the R = 8 shard's K range of
+      // 1024, batch 8 and 16, it cost 1 - 2 %).
+      if (n_splits * nkv * B + blocks_of(gu_a) + blocks_of(o) > 2 * c->n_cu && nqd >= 2048 && o.tn == 2 && o.n_groups % 2 == 0) { o.tn = 4; o.n_groups /= 2; }
+#endif
       const int n_a = std::min(gu_a.n_groups / 2, c->n_cu / 2);   // (any position in the first half measured the same)
       gu_a.n_groups = n_a;
       gu_b.group0 = n_a; gu_b.n_groups -= n_a;

@@ -222,6 +222,13 @@ def test_fused_decode_matches_oracle(harness, wiring, nstd):
     assert len(res.errs) == 6 and max(res.errs) < TOL_BF16, res.errs
 
 
+def test_fused_decode_four_tile_gate_up_at_large_batch(harness):
+    """13 rows and more with enough gate/up tiles (here 768 on 256 CUs): four tiles per workgroup."""
+    w = R8_SMALL.with_(name="r8_small_gu4", inter=6144, batch=14, decode_steps=3)
+    res = harness.run_case(w, kv_preload=100, decode_fused=1)
+    assert len(res.errs) == 3 and max(res.errs) < TOL_BF16, res.errs
+
+
 def test_fused_decode_graph_and_eager_bit_identical_and_reproducible(harness):
     a = harness.run_case(R8_SMALL, kv_preload=125, gpu_only=True, decode_fused=1, decode_graph=0)
     b = harness.run_case(R8_SMALL, kv_preload=125, gpu_only=True, decode_fused=1, decode_graph=1)
