@@ -573,6 +573,17 @@ struct FusedTraceScope {
 // and requests its first weight tiles and operand slices at once, while the job's descriptor is still on its
 // way from memory (a cold scalar load costs 0.7 - 2 us here, and it used to stand in front of every
 // workgroup's first request).
+// The kernel's parameter list as a struct: kernel arguments are laid out in the argument segment like the members
+// of a C struct, so offsetof() of the last member is where the by-value FusedArgs block starts.  Keep it in step
+// with the parameter list of fused_decode_kernel.
+struct FusedKernelParams {
+  const void* wp_a;
+  const void* wp_b;
+  const bf16_t* x_a;
+  const bf16_t* x_b;
+  unsigned ends01, end2_m, kinds, geo0, geo1, geo2;
+  FusedArgs fa;
+};
 static_assert(FUSED_MAX_JOBS == 4, "the preloaded arguments carry three block boundaries and four descriptor bytes");
 template <int D, int G>
 __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(const void* wp_a, const void* wp_b, const bf16_t* x_a,
@@ -596,12 +607,10 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(const vo
     // The job's descriptor is read in place from the kernel-argument segment (uniform index -> scalar loads).
     // Indexing the by-value argument itself makes the compiler, beyond some amount of code that uses it, keep a
     // copy of all of it in private memory (a kilobyte of scratch stores at the head of every wavefront).  The
-    // leading arguments are four pointers and six 32-bit words, after which the block follows with no padding.
-    constexpr size_t kLeadingArgBytes = 4 * sizeof(void*) + 6 * sizeof(unsigned);
-    static_assert(kLeadingArgBytes % alignof(FusedArgs) == 0, "FusedArgs directly behind the leading arguments");
+    // block's offset in the segment is that of the last member of FusedKernelParams.
     typedef __attribute__((address_space(4))) const char* kernarg_ptr_t;
     const kernarg_ptr_t ka = (kernarg_ptr_t)__builtin_amdgcn_kernarg_segment_ptr();
-    const GemvJob& j = *(const GemvJob*)(ka + kLeadingArgBytes + offsetof(FusedArgs, g) + (size_t)job * sizeof(GemvJob));
+    const GemvJob& j = *(const GemvJob*)(ka + offsetof(FusedKernelParams, fa) + offsetof(FusedArgs, g) + (size_t)job * sizeof(GemvJob));
     const unsigned slot = kb >> FUSED_KIND_SLOT_SHIFT;   // which preloaded pointer pair: 0, 1, or 3 = none
     const int gi = job - ((kinds & FUSED_KIND_MASK) == (unsigned)JOB_ATTN ? 1 : 0);   // index among the GEMV jobs
     const void* wp = slot == 0 ? wp_a : wp_b;
