@@ -99,6 +99,18 @@ def m_lags_three(n, wiring):
     return [3 if v == 2 else v for v in base]
 
 
+def m_lags_parallel_as_ladder(n_modules, wiring):
+    """The parallel attention / MLP block wired like the ladder."""
+    return _orig["_lags"](n_modules, "ladder" if wiring == "parallel" else wiring)
+
+
+def m_lags_parallel_swapped(n_modules, wiring):
+    """Attention reads the stale stream and the MLP the fresh one instead of the other way round."""
+    if wiring == "parallel":
+        return [2 if m % 2 == 1 else 1 for m in range(1, n_modules + 1)]
+    return _orig["_lags"](n_modules, wiring)
+
+
 def m_round_truncate(a):
     m, e = np.frexp(np.asarray(a, dtype=np.float64))
     return np.ldexp(np.trunc(m * 256.0) / 256.0, e)
@@ -111,7 +123,7 @@ MUTANTS = {
     "causal_gqa_attention": [m_attn_no_scale, m_attn_not_causal, m_attn_head_map],
     "mlp_partial": [m_mlp_swapped],
     "all_reduce": [m_allreduce_drop_peer, m_allreduce_pool_shift, m_allreduce_first_only],
-    "_lags": [m_lags_three],
+    "_lags": [m_lags_three, m_lags_parallel_as_ladder, m_lags_parallel_swapped],
     "round_bf16": [m_round_truncate],
 }
 _orig = {k: getattr(lo, k) for k in MUTANTS}
