@@ -362,6 +362,18 @@ def test_bf16_wide_prefill_residual_epilogue_all_wirings(harness, wiring, nstd):
     assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
 
 
+def test_bf16_decode_of_more_than_64_sequences(harness):
+    """A decode step of 80 sequences is a wide call (80 rows): the projections take the GEMM kernels, the position
+    comes from device memory (rotary + append as a kernel of its own), attention the split-KV decode kernels,
+    and the residual update is the GEMM epilogue; after a synthetic cache and after a prefill."""
+    w = inputs.WORKLOADS["70b_r8_decode"].with_(name="decode_b80", n_layers=2, hidden=256, inter=352, n_q_heads=4,
+                                                n_kv_heads=2, head_dim=64, batch=80, decode_steps=2)
+    res = harness.run_case(w, kv_preload=40)
+    assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
+    res = harness.run_case(w.with_(name="decode_b80_prefill", prefill=3), wiring=ladder.LADDER_WIRING_STANDARD)
+    assert len(res.errs) == 3 and max(res.errs) < TOL_BF16, res.errs
+
+
 def test_bf16_large_tile_residual_epilogue_hybrid(harness):
     """The 256 x 256-tile GEMM's residual epilogue (staged through LDS, whole rows per memory instruction) with a
     ragged last row block and a ragged last column block (hidden 1056), in a hybrid stack (one standard layer, two
