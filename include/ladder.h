@@ -200,6 +200,24 @@ int ladder_embed(ladder_ctx* ctx, const int32_t* tokens, int32_t rows, void* x_o
  * Enqueued on the caller's stream.  Errors: LADDER_E_ARG, LADDER_E_STATE (head not loaded), LADDER_E_SHAPE. */
 int ladder_head(ladder_ctx* ctx, const float* x, int32_t rows, float* logits_out, int32_t* tokens_out);
 
+/* ladder_head for callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): the same final RMSNorm + output projection + greedy arg max, with the normed rows and
+ * the logits -- which ladder_head keeps in buffers the context allocated -- in a fixed static device array
+ * of the library instead (LADDER_HEAD_STATIC_MAX_ROWS x (LADDER_HEAD_STATIC_MAX_HIDDEN +
+ * LADDER_HEAD_STATIC_MAX_VOCAB) x 4 bytes = 2.5 MiB per GPU, held until the process ends).  The call
+ * allocates and frees nothing, on the host side of the runtime or the device.
+ *   x           device f32 [rows][H]
+ *   tokens_out  device int32 [rows]   (the same tokens as ladder_head gives)
+ * Every call on a GPU shares that GPU's array (whatever the context): calls that overlap on one GPU --
+ * different streams, or different host threads -- race; calls ordered on one stream do not.  Nothing in the
+ * array has to start at zero: a call overwrites all it reads.
+ * Errors: as ladder_head; LADDER_E_SHAPE also when rows, hidden or vocab_local exceed the limits below;
+ * LADDER_E_STATE when the current device is not the context's. */
+#define LADDER_HEAD_STATIC_MAX_ROWS 16
+#define LADDER_HEAD_STATIC_MAX_HIDDEN 8192
+#define LADDER_HEAD_STATIC_MAX_VOCAB 32768
+int ladder_head_static(ladder_ctx* ctx, const float* x, int32_t rows, int32_t* tokens_out);
+
 /* ---- helpers ---------------------------------------------------------------------------- */
 
 /* Text of the last error of this context (or of the last failed ladder_init when ctx is NULL).

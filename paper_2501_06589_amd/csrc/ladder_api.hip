@@ -36,6 +36,30 @@ namespace {
 
 std::string g_init_error;
 
+// Scratch of ladder_head_static, the entry point for callers that cannot allocate: normed rows in the storage
+// type, then the logits.  One copy per GPU, held until the process ends; its device address is looked up
+// once per device (resolve_static_scratch), and host code only ever uses that looked-up pointer.
+#define HEAD_STATIC_Y_BYTES ((size_t)LADDER_HEAD_STATIC_MAX_ROWS * LADDER_HEAD_STATIC_MAX_HIDDEN * 4)
+#define HEAD_STATIC_LOGIT_BYTES ((size_t)LADDER_HEAD_STATIC_MAX_ROWS * LADDER_HEAD_STATIC_MAX_VOCAB * 4)
+static __device__ __align__(256) unsigned char scratch[HEAD_STATIC_Y_BYTES + HEAD_STATIC_LOGIT_BYTES];
+#define STATIC_SCRATCH_MAX_DEVICES 64
+void* g_scratch_ptr[STATIC_SCRATCH_MAX_DEVICES] = {};
+
+// device address of this GPU's copy of `scratch` (dev must be the current device); null + error on failure
+hipError_t resolve_static_scratch(int dev, void** out) {
+  *out = nullptr;
+  if (dev < 0 || dev >= STATIC_SCRATCH_MAX_DEVICES) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 struct ProfRec {
   int cls;
   hipEvent_t start, stop;
@@ -111,6 +135,8 @@ struct ladder_ctx {
   int vocab = 0, vocab_local = 0;
   bool head_fast = false;
   const char* fused_plan_peers = nullptr;
+  int device = 0;                 // the device the context lives on
+  void* static_scratch = nullptr; // this device's copy of the file-scope scratch array (ladder_head_static)
   int pos = 0, batch = 0;
   std::string err;
   // profiling
@@ -923,7 +949,9 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
   {
     int dev_id = 0, khz = 0;
     INIT_HIP(hipGetDevice(&dev_id));
+    c->device = dev_id;
     if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev_id) == hipSuccess && khz > 0) c->wall_khz = khz;
+    INIT_HIP(resolve_static_scratch(dev_id, &c->static_scratch));
   }
   INIT_HIP(hipStreamCreateWithFlags(&c->s_attn, hipStreamNonBlocking));
   INIT_HIP(hipStreamCreateWithFlags(&c->s_mlp, hipStreamNonBlocking));
@@ -1262,31 +1290,51 @@ int ladder_embed(ladder_ctx* c, const int32_t* tokens, int32_t rows, void* x_out
   return LADDER_OK;
 }
 
+// final norm -> output projection -> (arg max) with the normed rows in y and the logits in `logits`
+static int head_body(ladder_ctx* c, const float* x, int rows, char* y, float* logits, int32_t* tokens_out) {
+  const ladder_config& g = c->cfg;
+  const int H = g.hidden, V = c->vocab_local;
+  hipStream_t s = c->main;
+  HIP_TRY(c, launch_head_norm(x, c->head_fast ? nullptr : c->head_gain, y, rows, H, g.rms_eps, c->bf16, s));
+  if (!c->head_fast) {
+    HIP_TRY(c, launch_gemm_generic(y, c->head_w, logits, rows, V, H, V, 0, c->bf16, s));
+  } else if (rows <= 64) {
+    GemvArgs a{};
+    a.x = (const bf16_t*)y; a.ldx = H; a.wp = c->head_wp; a.M = rows; a.K = H; a.N = V; a.ksplit = 1;
+    a.out = logits; a.out_stride = (size_t)rows * V; a.slot0 = 0; a.epilogue = 0;
+    HIP_TRY(c, launch_gemv(a, s));
+  } else {
+    GemmArgs a{};
+    a.x = (const bf16_t*)y; a.ldx = H; a.wp = c->head_wp; a.M = rows; a.K = H; a.N = V; a.out = logits; a.epilogue = 0;
+    HIP_TRY(c, launch_gemm_mfma(a, s));
+  }
+  if (tokens_out) HIP_TRY(c, launch_argmax(logits, tokens_out, rows, V, s));
+  return LADDER_OK;
+}
+
 int ladder_head(ladder_ctx* c, const float* x, int32_t rows, float* logits_out, int32_t* tokens_out) {
   if (!c) return LADDER_E_ARG;
   if (!x || (!logits_out && !tokens_out)) return fail(c, LADDER_E_ARG, "null x, or neither logits_out nor tokens_out");
   if (!c->head_table) return fail(c, LADDER_E_STATE, "the head is not loaded");
   if (rows <= 0) return fail(c, LADDER_E_ARG, "rows must be positive");
   if (rows > c->cfg.max_batch) return fail(c, LADDER_E_SHAPE, "rows exceed max_batch (the head serves one position per sequence)");
-  const ladder_config& g = c->cfg;
-  const int H = g.hidden, V = c->vocab_local;
-  hipStream_t s = c->main;
-  float* logits = logits_out ? logits_out : c->head_logits;
-  HIP_TRY(c, launch_head_norm(x, c->head_fast ? nullptr : c->head_gain, c->head_y, rows, H, g.rms_eps, c->bf16, s));
-  if (!c->head_fast) {
-    HIP_TRY(c, launch_gemm_generic(c->head_y, c->head_w, logits, rows, V, H, V, 0, c->bf16, s));
-  } else if (rows <= 64) {
-    GemvArgs a{};
-    a.x = (const bf16_t*)c->head_y; a.ldx = H; a.wp = c->head_wp; a.M = rows; a.K = H; a.N = V; a.ksplit = 1;
-    a.out = logits; a.out_stride = (size_t)rows * V; a.slot0 = 0; a.epilogue = 0;
-    HIP_TRY(c, launch_gemv(a, s));
-  } else {
-    GemmArgs a{};
-    a.x = (const bf16_t*)c->head_y; a.ldx = H; a.wp = c->head_wp; a.M = rows; a.K = H; a.N = V; a.out = logits; a.epilogue = 0;
-    HIP_TRY(c, launch_gemm_mfma(a, s));
-  }
-  if (tokens_out) HIP_TRY(c, launch_argmax(logits, tokens_out, rows, V, s));
-  return LADDER_OK;
+  return head_body(c, x, rows, c->head_y, logits_out ? logits_out : c->head_logits, tokens_out);
+}
+
+int ladder_head_static(ladder_ctx* c, const float* x, int32_t rows, int32_t* tokens_out) {
+  if (!c) return LADDER_E_ARG;
+  if (!x || !tokens_out) return fail(c, LADDER_E_ARG, "null x / tokens_out");
+  if (!c->head_table) return fail(c, LADDER_E_STATE, "the head is not loaded");
+  if (rows <= 0) return fail(c, LADDER_E_ARG, "rows must be positive");
+  if (rows > c->cfg.max_batch) return fail(c, LADDER_E_SHAPE, "rows exceed max_batch (the head serves one position per sequence)");
+  if (rows > LADDER_HEAD_STATIC_MAX_ROWS || c->cfg.hidden > LADDER_HEAD_STATIC_MAX_HIDDEN || c->vocab_local > LADDER_HEAD_STATIC_MAX_VOCAB)
+    return fail(c, LADDER_E_SHAPE, "ladder_head_static: rows, hidden or vocab_local beyond the LADDER_HEAD_STATIC_MAX_* limits of the static scratch");
+  int dev = -1;
+  HIP_TRY(c, hipGetDevice(&dev));
+  if (dev != c->device || !c->static_scratch) return fail(c, LADDER_E_STATE, "ladder_head_static: the context's device is not the current device");
+  char* y = (char*)c->static_scratch;                                   // the looked-up device address, never the array's name
+  float* logits = (float*)((char*)c->static_scratch + HEAD_STATIC_Y_BYTES);
+  return head_body(c, x, rows, y, logits, tokens_out);
 }
 
 int ladder_calibration_copy(ladder_ctx* c, void* dst, const void* src, size_t bytes) {

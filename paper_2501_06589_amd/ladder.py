@@ -55,6 +55,7 @@ EXPORTS = {
     "ladder_load_head": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]),
     "ladder_embed": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "ladder_head": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
+    "ladder_head_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
 }
 
 _lib = None
@@ -220,6 +221,16 @@ class Ladder:
         toks = torch.empty((rows,), dtype=torch.int32, device=x.device)
         self._check(self._lib.ladder_head(self._h, _ptr(x), rows, _ptr(logits), _ptr(toks)))
         return logits, toks
+
+    def head_static(self, x, tokens_out):
+        """ladder_head_static: greedy tokens into the caller's int32 device tensor [rows]; allocates nothing."""
+        import torch
+        rows = x.shape[0]
+        self._want("x", x, rows * self.cfg.hidden, storage=False)
+        if not tokens_out.is_cuda or not tokens_out.is_contiguous() or tokens_out.dtype != torch.int32 or tokens_out.numel() != rows:
+            raise ValueError("tokens_out: need a contiguous int32 device tensor of `rows` elements")
+        self._check(self._lib.ladder_head_static(self._h, _ptr(x), rows, _ptr(tokens_out)))
+        return tokens_out
 
     def position(self) -> Tuple[int, int]:
         p, b = C.c_int32(), C.c_int32()
