@@ -123,29 +123,36 @@ typedef struct {
   const void* w_down;    /* T [I][H] */
 } ladder_layer_weights;
 
-/* Creates a context: validates the configuration, allocates the repacked-weight store, the KV
- * cache, workspaces, the side stream and events on the current device.
+/* Creates a context for the block stack that Algorithm 1 / Eq. 2 define (N layers of an attention module and
+ * an MLP module around one residual stream, section "Ladder Residual"; module shapes per "Llama-3's model
+ * architecture", section "Setup"; this rank's shard per section "Tensor Parallelism Background"): validates
+ * the configuration, allocates the repacked-weight store, the KV cache, workspaces, the internal streams and
+ * events (the handles of Algorithm 1's AsyncAllReduce) on the current device.
  *   cfg        host pointer.
  *   hip_stream the caller's hipStream_t (NULL = the null stream); all work is ordered on it.
  *   out        receives the context.
  * Errors: LADDER_E_ARG, LADDER_E_SHAPE, LADDER_E_HIP (then *out is NULL). */
 int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out);
 
-/* Copies / repacks one shard of one layer into the context (enqueued on the caller's stream).
- * layer in [0, N), shard in [0, n_real_shards).  Every (layer, shard) must be loaded before the
- * first forward call (else LADDER_E_STATE there).  All nine pointers are read for every shard: on
- * the bf16 streaming path the two norm gains are multiplied into the rows of the packed QKV and
- * gate/up weights (RMSNorm's gain commutes into the following projection), once, in fp32, before the
- * rounding to bf16. */
+/* Copies / repacks one shard of one layer into the context (enqueued on the caller's stream): the
+ * weights of AttentionNorm, Attention, MLPNorm and MLP of Algorithm 1, split as section "Tensor Parallelism
+ * Background" says.  layer in [0, N), shard in [0, n_real_shards).  Every (layer, shard) must be loaded
+ * before the first forward call (else LADDER_E_STATE there).  The two gains are taken from shard 0's call
+ * (they are replicated across ranks) and may be NULL for the other shards.  Repacking only re-orders: the
+ * library keeps the weights' bits as given. */
 int ladder_load_layer(ladder_ctx* ctx, int32_t layer, int32_t shard, const ladder_layer_weights* w);
 
-/* Synthetic partial sums of the ranks that are not computed: device T
+/* The other ranks' terms of the AllReduce of Eq. 2 (x_m = AllReduce(h_m(x_{m-2})) + x_{m-1}) on one GPU:
+ * synthetic partial sums of the ranks that are not computed: device T
  * [peer_pool][R - n_real_shards][peer_rows][H], caller-owned, NOT copied: it must stay valid and
  * unchanged while forward calls use it.  Row b*T + t of a set is added for token t of sequence b.
- * NULL switches the peers off.  LADDER_E_SHAPE if the configuration has no peers. */
+ * NULL switches the peers off.  A change takes effect at the next forward call (a captured decode step is
+ * captured again).  LADDER_E_SHAPE if the configuration has no peers. */
 int ladder_set_peer_partials(ladder_ctx* ctx, const void* peers);
 
-/* Fills the KV cache of (layer, shard) with caller-made content instead of a prefill:
+/* The cache that the attention modules of Algorithm 1 read at decode (section "Setup": generation after a
+ * prompt of 1024 tokens), without running the prompt: fills the KV cache of (layer, shard) with caller-made
+ * content instead of a prefill:
  * k, v device T [B][nkv][S][d] (k already rotated).  Sets the context position to S once every
  * (layer, shard) has been given the same B and S.  LADDER_E_SHAPE / LADDER_E_OVERFLOW on misfit. */
 int ladder_load_kv(ladder_ctx* ctx, int32_t layer, int32_t shard, const void* k, const void* v,
@@ -160,14 +167,19 @@ int ladder_load_kv(ladder_ctx* ctx, int32_t layer, int32_t shard, const void* k,
  * LADDER_E_OVERFLOW (T > max_seq), LADDER_E_STATE (a layer is not loaded), LADDER_E_HIP. */
 int ladder_prefill(ladder_ctx* ctx, const void* x_in, int32_t B, int32_t T, void* x_out);
 
-/* One decode step: one new embedding per sequence at the current position (the batch size is the
- * one of the preceding prefill / load_kv); appends to the cache; position += 1.
+/* One decode step = modules 1..2N of Eq. 2 / Algorithm 1 (or Eq. 1 per the wiring) on one new token per
+ * sequence (section "Inference Implementation": token-by-token generation after the prefill): one new
+ * embedding per sequence at the current position (the batch size is the one of the preceding prefill /
+ * load_kv); appends to the cache; position += 1.
  *   x_in   device T   [B][H]
  *   x_out  device f32 [B][H]
- * Errors: LADDER_E_STATE (no prefill / load_kv yet), LADDER_E_OVERFLOW (cache full), others as above. */
+ * Errors: LADDER_E_STATE (no prefill / load_kv yet), LADDER_E_OVERFLOW (cache full), others as above;
+ * LADDER_E_HIP also when a kernel of an EARLIER step gave up its bounded in-launch wait (that step's output
+ * is then invalid; the failing call itself does nothing and clears the condition). */
 int ladder_decode_step(ladder_ctx* ctx, const void* x_in, void* x_out);
 
-/* Releases everything the context owns (synchronises its streams first).  NULL is a no-op. */
+/* Ends the block stack of ladder_init: releases everything the context owns (synchronises its streams
+ * first).  NULL is a no-op. */
 void ladder_free(ladder_ctx* ctx);
 
 /* ---- generation head (Llama-3 architecture around the block stack; the paper's engine is a prefill
@@ -175,7 +187,7 @@ void ladder_free(ladder_ctx* ctx);
  *
  * ladder_load_head copies the token-embedding table, and copies / repacks this rank's slice of the
  * output projection (split along the vocabulary, the rule of section "Tensor Parallelism Background"
- * for a first matmul; on the bf16 streaming path the final norm's gain is folded into its rows):
+ * for a first matmul):
  *   table       device T [vocab][H]
  *   final_norm  device T [H]             gain of the RMSNorm in front of the output projection
  *   w_lm        device T [H][vocab_local]
@@ -185,7 +197,9 @@ int ladder_load_head(ladder_ctx* ctx, const void* table, const void* final_norm,
                      int32_t vocab_local);
 
 /* Token embedding: x_out[r][:] = table[tokens[r]][:].
- *   tokens  device int32 [rows]  (ids outside [0, vocab) are clamped into the table)
+ *   tokens  device int32 [rows]  (an id outside [0, vocab) reads row 0 or vocab - 1 instead, so that no
+ *                                access leaves the table, and is REPORTED: the next ladder_embed, ladder_prefill
+ *                                or ladder_decode_step of this context fails with LADDER_E_ARG and does nothing)
  *   x_out   device T [rows][H]   rows <= max_batch * max_tokens; ready to be x_in of ladder_prefill
  *                                ([B][T][H], rows = B*T) or ladder_decode_step ([B][H]).
  * Enqueued on the caller's stream.  Errors: LADDER_E_ARG, LADDER_E_STATE (head not loaded), LADDER_E_SHAPE. */
@@ -220,16 +234,31 @@ int ladder_head_static(ladder_ctx* ctx, const float* x, int32_t rows, int32_t* t
 
 /* ---- helpers ---------------------------------------------------------------------------- */
 
-/* Text of the last error of this context (or of the last failed ladder_init when ctx is NULL).
+/* Text of the last error of this context (or of the last failed ladder_init / sizing call when ctx is NULL).
  * The pointer stays valid until the next failing call. */
 const char* ladder_last_error(const ladder_ctx* ctx);
 
-/* Current number of cached positions per sequence and current batch size (0 before any
- * prefill / load_kv).  LADDER_E_ARG on NULL. */
+/* Where the context stands in the prefill-then-decode run (section "Setup"): current number of cached
+ * positions per sequence and current batch size (0 before any prefill / load_kv).  LADDER_E_ARG on NULL. */
 int ladder_position(const ladder_ctx* ctx, int32_t* pos, int32_t* batch);
 
-/* Device bytes the context holds (weights store + KV cache + workspaces). */
+/* Device bytes the context holds (weights store + KV cache + workspaces + generation head, if loaded). */
 size_t ladder_device_bytes(const ladder_ctx* ctx);
+
+/* Sizing before any allocation (host only, no GPU needed, callable before ladder_init): the device bytes that
+ * ladder_init(cfg) allocates apart from the weight store -- KV cache, rotary tables, norm gains, residual
+ * stream, partial-sum and activation buffers of Algorithm 1's modules -- and the bytes of the weight store
+ * itself.  Their sum is ladder_device_bytes of a fresh context.  0 if the configuration is rejected (the
+ * text is in ladder_last_error(NULL)). */
+size_t ladder_workspace_bytes(const ladder_config* cfg);
+size_t ladder_weight_bytes(const ladder_config* cfg);
+
+/* Test hook for the one in-launch wait of the fused decode schedule (the output projection of a layer waits,
+ * inside the launch, for that layer's attention workgroups; the wait is bounded): max_polls polls instead of
+ * 2^20, and target_bias added to the count it waits for.  With a bias no count can reach, the wait gives up:
+ * the waiting workgroups store nothing, every kernel still ends normally, and the NEXT ladder_decode_step /
+ * ladder_prefill returns LADDER_E_HIP.  (1 << 20, 0) restores normal operation.  Errors: LADDER_E_ARG. */
+int ladder_set_wait_limit(ladder_ctx* ctx, int32_t max_polls, int32_t target_bias);
 
 /* Per-kernel timing for measurement.  With profiling on, every kernel launch is bracketed by HIP
  * events on the stream it is launched on; ladder_profile_read synchronises, folds the events

@@ -52,7 +52,7 @@ struct ReduceNormArgs {
   int n_peers;
   size_t peer_stride;      // elements
   void* out_a;             // T or null
-  const void* gain_a;      // T, or null = no gain (it has been folded into the consumer's weights)
+  const void* gain_a;      // T, or null = no gain
   void* out_b;
   const void* gain_b;
   float* x_out;            // f32 or null
@@ -117,10 +117,8 @@ static inline size_t packed_tiles_bytes(int K, int N) {
 // Repack src (bf16 [K][N], row stride N) into dst tiles at column-tile offset: column n of src becomes
 // packed column map(n).  mode 0: n -> col0 + n.  mode 1 (gate) / 2 (up): SwiGLU interleave,
 // n -> 16*(n/8) + (n%8) + (mode==2 ? 8 : 0), so each 16-wide tile holds 8 gate and the 8 matching up columns.
-// row_gain (bf16 [K], may be null): W[k][n] is multiplied by row_gain[k] before packing -- the RMSNorm
-// gain of the activations this projection reads, folded into the weights.
-hipError_t launch_repack_tiles(const bf16_t* src, void* dst, int K, int N, int N_total, int col0, int mode,
-                               const bf16_t* row_gain, hipStream_t s);
+// The values are copied bit for bit.
+hipError_t launch_repack_tiles(const bf16_t* src, void* dst, int K, int N, int N_total, int col0, int mode, hipStream_t s);
 
 struct GemvArgs {
   const bf16_t* x;         // bf16 [M][ldx]
@@ -174,18 +172,21 @@ struct GemmArgs {
   int T, pos0, nq, nkv, d, max_seq;
   // epilogue 3: the residual update "wait(); residual += out" (Algorithm 1) with the AllReduce written as a sum
   // over rank partial sums (Eq. 2): x_res[m][n] = x_res[m][n] + product + peers_0[m][n] + peers_1[m][n] + ...
-  // (in this order, in place, row stride N), an optional f32 copy, bf16 copies of the new rows for the modules
-  // that read them, and the rows' sums of squares per column block: ssq_part[block][m], gemm_ssq_parts() blocks
+  // (in this order, in place, row stride N), an optional f32 copy, for each module that reads the new rows a bf16
+  // copy of them times the gain of that module's RMSNorm (the product in fp32, one rounding), and the rows' sums
+  // of squares per column block: ssq_part[block][m], gemm_ssq_parts() blocks
   float* x_res;
   float* x_copy;           // or null
   bf16_t* xh_a;            // bf16 [M][N], or null
+  const bf16_t* gain_a;    // bf16 [N] (with xh_a)
   bf16_t* xh_b;            // or null (only with xh_a)
+  const bf16_t* gain_b;    // bf16 [N] (with xh_b)
   const bf16_t* peers;     // bf16 [n_peers][peer_stride], row stride N; or null
   int n_peers;
   size_t peer_stride;      // elements
   float* ssq_part;         // f32 [gemm_ssq_parts()][M] (at most ceil(N / 64) blocks), or null
   // every epilogue: if non-null, row m of the product is multiplied by row_scale[m] first (the 1/rms of an
-  // RMSNorm whose gain is folded into the weights: the factor commutes with the product)
+  // RMSNorm whose gain the producer of x has already applied: the factor commutes with the product)
   const float* row_scale;
 };
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s);

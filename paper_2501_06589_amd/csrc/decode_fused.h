@@ -6,39 +6,59 @@
 enum { JOB_NONE = 0, JOB_GEMV = 1, JOB_ATTN = 2 };
 enum { EPI_SWIGLU = 1, EPI_RESIDUAL = 2, EPI_QKV_ROPE = 3 };
 
+// Operands of the matrix core on this path are SPLIT: a value v travels as two bf16 numbers, high = bf16(v) and
+// low = bf16(v - high), so that high + low carries 16 significant bits and the products with the (bf16) weights
+// lose nothing that an fp32 operand would keep.  A split matrix is stored as bf16 [32][width]: rows 0..15 the
+// high parts of rows 0..15, rows 16..31 the low parts (FUSED_LOW_ROW).  Up to 8 rows, high and low parts share
+// ONE 16-column MFMA operand (columns 0..7 high, 8..15 low: the columns that a small batch leaves empty) and the
+// two halves of the result are added afterwards; from 9 rows on they are two operands and two MFMAs into the
+// same accumulator.  Decode is bound by the weight stream: the matrix core has the time.
+#define FUSED_LOW_ROW 16
+
 // One skinny GEMM  out[m][n] = sum_k x[m][k] W[k][n], M <= 16, on packed weight tiles; a workgroup
-// owns 32 columns and the whole K range.
+// owns tn adjacent 16-column tiles and the whole K range.
 struct GemvJob {
-  // x operand: a bf16 matrix.  normed != 0: it is the bf16 copy of the residual stream and this
-  // projection applies RMSNorm: the gain is already folded into the weight rows, and the rows' 1/rms,
-  // computed from the same operand loads, scales the output (the factor commutes with the product)
+  // x operand: a split bf16 matrix [32][K] (see above).  normed != 0: it is the residual stream times the gain of
+  // this module's RMSNorm (both applied in fp32 by the job that wrote the stream, before the split), and this
+  // projection scales its output rows by 1/rms (the factor commutes with the product), the rows' sums of squares
+  // coming from ssq: f32 [K/16][16], one value per 16-column tile of the stream and row, summed in a fixed order
   const bf16_t* xb;
   int ldx;
   int normed;
   float eps;
+  const float* ssq;
   const void* wp;
   int M, K, N;
   // wait_on != null: the job's x operand is produced by the attention job of the SAME launch; the
-  // workgroup starts by waiting (bounded) until *wait_on has reached wait_target, then reads that operand
-  // with device-coherent loads
+  // workgroup starts by waiting (bounded: wait_spins polls) until *wait_on has reached wait_target, then reads
+  // that operand with device-coherent loads.  If the wait gives up, the workgroup stores nothing and raises
+  // *err_word (host-visible memory), which the next call of the library reports.
   const unsigned* wait_on;
   unsigned wait_target;
-  int tn;                  // 16-column tiles per workgroup: 1 (0 means 1), 2, 3 (un-normed jobs without a wait)
-                           // or 4 (normed jobs without a wait, un-normed jobs with one)
+  int wait_spins;
+  unsigned* err_word;
+  int tn;                  // 16-column tiles per workgroup: 1 (0 means 1), 2, 4, or 3 (jobs without a wait)
   int group0, n_groups;    // this job's workgroups own the tile groups [group0, group0 + n_groups), tn tiles
                            // each; a projection may be cut over two launches
   int epi;
-  // EPI_SWIGLU: act[m][N/2] bf16
+  // EPI_SWIGLU: act split bf16 [32][N/2]
   bf16_t* act;
-  // EPI_RESIDUAL: x_new = x_old + out + sum_p peers[p]   ("wait(); residual += out" with the
-  // all-reduce written as a sum over rank partial sums)
+  // EPI_RESIDUAL: x_new = x_old + out + sum_p peers[p]   (the residual update of Algorithm 1 with the
+  // all-reduce written as a sum over rank partial sums, Eq. 2); for each of the (at most two) modules that read
+  // x_new: its operand xop = split(x_new * gain of that module's RMSNorm), gain in the storage type [N];
+  // and the sums of squares of x_new per 16-column tile and row, ssq_new f32 [N/16][16]
   const float* x_old;
   float* x_new;
-  bf16_t* xh_new;          // bf16 copy of x_new
+  bf16_t* xop_a;
+  const bf16_t* gain_a;
+  bf16_t* xop_b;
+  const bf16_t* gain_b;
+  float* ssq_new;
   const bf16_t* peers;
   int n_peers;
   size_t peer_stride;
-  // EPI_QKV_ROPE: rotary on q and k (adjacent pairs), q -> q_out, k and v appended at *pos_dev
+  // EPI_QKV_ROPE: rotary on q and k (adjacent pairs), q -> q_out (split bf16 [32][nq*d]), k and v rounded to the
+  // cache's storage type and appended at *pos_dev
   bf16_t* q_out;
   bf16_t* cache_k;
   bf16_t* cache_v;
@@ -49,15 +69,16 @@ struct GemvJob {
 };
 
 // Decode attention over the cache.  One workgroup per (split, kv head, sequence) walks its share of
-// the positions in passes of 64 with a running softmax; with one split (the usual case) the result
-// is final, with several the last split to arrive (ticket) merges them.
+// the positions in blocks of 32 with a running softmax; with one split the result is final, with several
+// the last split to arrive (ticket) merges them.  Queries, probabilities and the output are split operands:
+// the nq/nkv <= 8 heads of a kv head sit in operand columns 0..7 (high parts) and 8..15 (low parts).
 struct AttnJob {
-  const bf16_t* q;         // [B][nq*d] rotated
+  const bf16_t* q;         // split [32][nq*d] rotated
   const bf16_t* cache_k;   // [B_cap][nkv][max_seq][d]
   const bf16_t* cache_v;   // [B_cap][nkv][d][max_seq]
   float* part_o;           // [B][nkv][n_splits][g][d]   (n_splits > 1 only)
   float* part_ml;          // [B][nkv][n_splits][g][2]
-  bf16_t* o;               // [B][nq*d]
+  bf16_t* o;               // split [32][nq*d]
   unsigned* tickets;       // [B][nkv]
   int B, nq, nkv, max_seq;
   int n_splits, split_len; // split s covers positions [s*split_len, (s+1)*split_len); split_len % 64 == 0
@@ -83,5 +104,19 @@ hipError_t launch_fused_decode(const FusedArgs& fa, int d, int g, hipStream_t s,
 hipError_t fused_decode_prepare(int d, int g);   // once per context, before the first launch
 size_t fused_attn_lds_bytes(int d, int g);
 size_t fused_gemv_lds_bytes();
-hipError_t launch_embed(const bf16_t* emb, float* x0, bf16_t* xh0, int n, unsigned* zero_words, int n_zero,
-                        hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+// x_0 = the embeddings (emb: bf16 [rows][H]): fp32 rows for the residual chain, the split operands of the (at most
+// two) modules that read x_0 (each times that module's gain), the sums of squares per tile and row; also clears
+// n_zero words at zero_words (the step's arrival counters).
+struct EmbedArgs {
+  const bf16_t* emb;
+  float* x0;
+  bf16_t* xop_a;
+  const bf16_t* gain_a;
+  bf16_t* xop_b;
+  const bf16_t* gain_b;
+  float* ssq;              // [H/16][16]
+  int rows, H;
+  unsigned* zero_words;
+  int n_zero;
+};
+hipError_t launch_embed(const EmbedArgs& a, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);

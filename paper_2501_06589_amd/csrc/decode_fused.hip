@@ -14,19 +14,21 @@
 // XCD's whole L2 under the weight streams: 1.2 - 2.5 us each where measured, and a release per workgroup of
 // a whole projection cost more than the projection itself): the producer writes with device-coherent stores,
 // waits for them, then takes the ticket or raises the counter; the consumer reads with device-coherent loads:
-//   * "wait(); residual += out" of Algorithm 1 with the all-reduce written as a sum over rank partial
+//   * the residual update of Algorithm 1 with the all-reduce written as a sum over rank partial
 //     sums (Eq. 2) is the epilogue of the module's last projection: x_m = x_{m-1} + h_m + sum(peers),
 //     written to a ring of three residual buffers (x_{m-1} is still read by the job that runs beside);
-//   * RMSNorm: the gain is folded into the rows of the following projection's weights when they are
-//     packed; a workgroup of that projection owns the whole K range, so it sees every element of the
-//     rows it multiplies: it feeds the bf16 copy of x to the matrix core, accumulates the rows' sums of
-//     squares from the same loads, and scales its outputs by 1/rms at the end (the factor commutes with
-//     the product);
+//   * RMSNorm: that same epilogue multiplies the new rows by the gain of the module that will read them (in
+//     fp32) and leaves them as the split matrix-core operand of that module, together with the rows' sums of
+//     squares per 16-column tile; the reading projection adds those up and scales its outputs by 1/rms at the
+//     end (the factor commutes with the product);
 //   * rotary embedding + KV append: epilogue of the QKV projection;
 //   * attention: one workgroup per (sequence, kv head); its 8 wavefronts share out the visible
 //     positions, each with a running softmax on the matrix cores, and merge through LDS, so nothing is
 //     left to combine across workgroups; only when the cache is long enough to be split do the splits
 //     meet through an arrival ticket.
+// Precision: the weights and the cache are bf16 (storage); every operand this path itself produces for the
+// matrix core (stream rows, q, softmax weights, attention output, SwiGLU output) is SPLIT into a high and a
+// low bf16 part (see decode_fused.h), so nothing is rounded to 8 bits between the modules; sums are fp32.
 // All sums are taken in a fixed order, so results are bit-reproducible run to run.
 #include <hip/hip_ext.h>
 
@@ -45,19 +47,14 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 // descriptor byte of a job in the preloaded `kinds` argument of the kernel
 #define FUSED_KIND_MASK 3u          // JOB_NONE / JOB_GEMV / JOB_ATTN
 #define FUSED_KIND_TN_SHIFT 2       // two bits: tiles per workgroup - 1 (1 .. 4 tiles)
-#define FUSED_KIND_NORMED 16u       // the job folds RMSNorm in
 #define FUSED_KIND_WAITS 32u        // the job waits for another job of the launch
 #define FUSED_KIND_SLOT_SHIFT 6     // two bits: index of the job's preloaded (weights, operand) pointer pair, 3 = none
 
 // k tiles per register buffer (two buffers) of a one-tile / a two-tile workgroup: 4 KiB of weights in flight
 // per wavefront.  With the round-robin assignment of k tiles below, 2 beat 4 (3.57 against 3.65 ms per step;
 // 1 gave 4.04, 3 gave 3.74: its turns do not divide the k range)
-#ifndef FUSED_U
 #define FUSED_U 2
-#endif
-#ifndef FUSED_U2
 #define FUSED_U2 1
-#endif
 #define FUSED_LDS_FLOATS 9216   // attention job: per-wave statistics and outputs
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -71,6 +68,18 @@ __device__ __forceinline__ void unpack8f(const uint4 v, float f[8]) {
   f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xFFFF0000u);
 }
 
+// v as two bf16 numbers: hi = bf16(v), lo = bf16(v - hi); hi + lo carries 16 significant bits of v
+__device__ __forceinline__ void split_bf16(float v, uint32_t& hi, uint32_t& lo) {
+  hi = f32_to_bf16(v);
+  lo = f32_to_bf16(v - __uint_as_float(hi << 16));
+}
+
+// the value that lane ^ 8 holds (DPP rotation by 8 within each row of 16 lanes): joins the two halves of a split
+// operand's result, whose high parts sit in operand columns 0..7 and low parts in columns 8..15
+__device__ __forceinline__ float other_half(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128 /* row_ror:8 */, 0xF, 0xF, false));
+}
+
 // ------------------------------------------------------------------------------------------------
 // skinny GEMM job: see gemv_mfma_kernel for the streaming scheme (same tiles, same pipeline).
 // A workgroup owns TN adjacent 16-column tiles and the whole K range; U k-tiles per register buffer.
@@ -81,9 +90,13 @@ __device__ __forceinline__ void unpack8f(const uint4 v, float f[8]) {
 // wp, xop, KT, group0 and M repeat j.wp, j.xb, j.K / 32, j.group0 and j.M (the x rows are K elements apart): the
 // kernel hands them over from preloaded kernel arguments where it can, so that the first weight tiles and
 // operand slices are requested before the job's descriptor (j) has arrived from memory.
-template <bool NORMED, int U, int TN, bool COH = false>
-__device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const bf16_t* xop, int KT, int group0, int M, int lb, float* smem) {
+// WIDE = more than 8 rows: the high and the low parts of the operand are two MFMA operands (rows 0..15 each);
+// else one: lanes 0..7 of a row of 16 carry the high parts of rows 0..7, lanes 8..15 their low parts.
+template <int U, int TN, bool COH, bool WIDE>
+__device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const bf16_t* xop, int KT, int group0, int M, int lb,
+                                         float* smem, unsigned* s_flag) {
   constexpr int WAVES = FUSED_WAVES;
+  constexpr int XP = WIDE ? 2 : 1;   // operand registers per k tile
   const int grp = group0 + lb;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -99,12 +112,15 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
   f32x4_t acc[TN];
 #pragma unroll
   for (int t = 0; t < TN; ++t) acc[t] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-  float ss = 0.f;  // NORMED: this lane's share of its row's sum of squares
   const u32x4_t* wptr = reinterpret_cast<const u32x4_t*>(wp) + ((size_t)nt0 * KT) * 64 + lane;
-  const bool rowok = b < M;
-  const int rowc = min(b, M - 1);
+  // operand row of this lane: WIDE: row b of the high parts (the low parts sit FUSED_LOW_ROW rows further);
+  // else row b % 8 of the high (b < 8) or of the low parts
+  const int brow = WIDE ? b : (b & 7);
+  const bool rowok = brow < M;
+  const int rowc = min(brow, M - 1) + ((!WIDE && (b & 8)) ? FUSED_LOW_ROW : 0);
   const bf16_t* xbp = xop + (size_t)rowc * (KT * 32) + q * 8;
-  u32x4_t wa[TN][U], wb[TN][U], xa[U], xb[U];
+  const size_t low_off = (size_t)FUSED_LOW_ROW * (KT * 32);
+  u32x4_t wa[TN][U], wb[TN][U], xa[U][XP], xb[U][XP];
   auto loadw = [&](u32x4_t (&wv)[TN][U], int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -113,21 +129,25 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
       for (int t = 0; t < TN; ++t) wv[t][u] = __builtin_nontemporal_load(wptr + ((size_t)t * KT + ktc) * 64);
     }
   };
-  auto loadx = [&](u32x4_t (&xv)[U], int kt) {
+  auto loadx = [&](u32x4_t (&xv)[U][XP], int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int ktc = min(kt + u, kt1 - 1);
-      if (COH) {   // operand written by another workgroup of this launch: device-coherent loads, past L1 and the XCD's L2
-        const unsigned long long* p8 = reinterpret_cast<const unsigned long long*>(xbp + (size_t)ktc * 32);
-        const unsigned long long lo = __hip_atomic_load(p8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned long long hi = __hip_atomic_load(p8 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        xv[u] = (u32x4_t){(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
-      } else {
-        xv[u] = *reinterpret_cast<const u32x4_t*>(xbp + (size_t)ktc * 32);
+#pragma unroll
+      for (int h = 0; h < XP; ++h) {
+        const bf16_t* src = xbp + (size_t)ktc * 32 + (h ? low_off : 0);
+        if (COH) {   // operand written by another workgroup of this launch: device-coherent loads, past L1 and the XCD's L2
+          const unsigned long long* p8 = reinterpret_cast<const unsigned long long*>(src);
+          const unsigned long long lo = __hip_atomic_load(p8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const unsigned long long hi = __hip_atomic_load(p8 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          xv[u][h] = (u32x4_t){(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
+        } else {
+          xv[u][h] = *reinterpret_cast<const u32x4_t*>(src);
+        }
       }
     }
   };
-  auto load = [&](u32x4_t (&wv)[TN][U], u32x4_t (&xv)[U], int kt) {
+  auto load = [&](u32x4_t (&wv)[TN][U], u32x4_t (&xv)[U][XP], int kt) {
     loadw(wv, kt);
     loadx(xv, kt);
   };
@@ -140,39 +160,36 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
   if (j.wait_on) {
     // The x operand comes from the attention job of this launch.  Its workgroups have lower block indices,
     // so they were dispatched before this one and wait for nothing: the counter always arrives.  The wait is
-    // bounded all the same (about a second), so that the kernel ends whatever happens.
+    // bounded all the same, so that the kernel ends whatever happens; a workgroup whose wait gives up stores
+    // nothing and raises the error word, which the host reads at the library's next call.
     if (tid == 0) {
-      for (int spin = 0; spin < (1 << 20); ++spin) {
-        if (__hip_atomic_load(j.wait_on, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= j.wait_target) break;
+      unsigned arrived = 0u;
+      for (int spin = 0; spin < j.wait_spins; ++spin) {
+        if (__hip_atomic_load(j.wait_on, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= j.wait_target) { arrived = 1u; break; }
         __builtin_amdgcn_s_sleep(16);
       }
+      *s_flag = arrived;
+      if (!arrived && j.err_word) __hip_atomic_store(j.err_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
     __syncthreads();   // (workgroup-scope ordering; the operand itself is read with device-coherent loads, so no
                        // cache invalidation is needed: an agent-scope acquire per workgroup would flush the L2
                        // under the weight streams that run beside)
+    if (*s_flag == 0u) return;
   }
 
   if (COH && kt0 < kt1) loadx(xa, kt0);
-  auto fma = [&](const u32x4_t (&wv)[TN][U], const u32x4_t (&xv)[U], int kt) {
+  auto fma = [&](const u32x4_t (&wv)[TN][U], const u32x4_t (&xv)[U][XP], int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool ok = rowok && (kt + u < kt1);
-      u32x4_t xz = xv[u];
-      if (NORMED) {  // the operand is the bf16 copy of the residual stream: its squares give the row's rms
-        float s8 = 0.f;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float lo = __uint_as_float(xz[e] << 16), hi = __uint_as_float(xz[e] & 0xFFFF0000u);
-          s8 = fmaf(lo, lo, s8);
-          s8 = fmaf(hi, hi, s8);
-        }
-        ss += ok ? s8 : 0.f;
+      for (int h = 0; h < XP; ++h) {
+        const u32x4_t xz = ok ? xv[u][h] : (u32x4_t){0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int t = 0; t < TN; ++t)
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wv[t][u]),
+                                                          __builtin_bit_cast(bf16x8_t, xz), acc[t], 0, 0, 0);
       }
-      if (!ok) xz = (u32x4_t){0u, 0u, 0u, 0u};
-#pragma unroll
-      for (int t = 0; t < TN; ++t)
-        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wv[t][u]),
-                                                        __builtin_bit_cast(bf16x8_t, xz), acc[t], 0, 0, 0);
     }
   };
   // The epilogue's own operands do not depend on the product: they are requested now, before the
@@ -181,16 +198,29 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
   constexpr int PRE_PEERS = 8;
   constexpr int E_RES = (TN * 256 + FUSED_THREADS - 1) / FUSED_THREADS;   // residual epilogue: elements per thread
   float pre_old[E_RES], pre_cos = 0.f, pre_sin = 0.f;
-  uint16_t pre_peer[E_RES][PRE_PEERS];
+  uint16_t pre_peer[E_RES][PRE_PEERS], pre_ga[E_RES], pre_gb[E_RES];
   int pre_pos = 0;
+  // normed: this thread's share of the rows' sums of squares, tile tid of the stream, four rows per register quad
+  float4 pre_ss[4];
+  const int n_st = KT * 2;   // 16-column tiles of the stream the operand was made from
+  if (j.normed) {
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      pre_ss[rq] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (rq * 4 < M) pre_ss[rq] = *reinterpret_cast<const float4*>(j.ssq + (size_t)min(tid, n_st - 1) * 16 + rq * 4);
+    }
+  }
   if (j.epi == EPI_RESIDUAL) {
 #pragma unroll
     for (int e = 0; e < E_RES; ++e) {
       const int idx = tid + e * FUSED_THREADS;
       pre_old[e] = 0.f;
+      pre_ga[e] = pre_gb[e] = 0x3F80;   // 1.0
       if (idx < TN * 256) {
         const int t = idx >> 8, row = min((idx >> 4) & 15, j.M - 1), col = (nt0 + t) * 16 + (idx & 15);
         pre_old[e] = j.x_old[(size_t)row * j.N + col];
+        if (j.xop_a) pre_ga[e] = j.gain_a[col];
+        if (j.xop_b) pre_gb[e] = j.gain_b[col];
         if (j.n_peers > 0) {
 #pragma unroll
           for (int p = 0; p < PRE_PEERS; ++p)
@@ -221,27 +251,43 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
     }
   }
 
-  // cross-wave sums through LDS: red[wave][tile][col in tile][row], ssq[wave][row]
+  // cross-wave sums through LDS: red[wave][tile][col in tile][operand column], ssq[wave][row]
   float* red = smem;                            // WAVES * TN * 16 * 17 floats
   float* ssq = smem + WAVES * TN * 16 * 17;     // WAVES * 16 floats
 #pragma unroll
   for (int t = 0; t < TN; ++t)
 #pragma unroll
     for (int r = 0; r < 4; ++r) red[((wave * TN + t) * 16 + 4 * q + r) * 17 + b] = acc[t][r];
-  if (NORMED) {
-    ss += __shfl_xor(ss, 16, 64);
-    ss += __shfl_xor(ss, 32, 64);
-    if (q == 0) ssq[wave * 16 + b] = ss;
+  if (j.normed) {
+    // the rows' sums of squares: this thread's tile (and, for streams of more than 512 tiles, the tiles beyond),
+    // then the wavefront, then (below) the eight wavefronts, always in this order
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      if (rq * 4 >= M) break;
+      float4 v = tid < n_st ? pre_ss[rq] : make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int tile = tid + FUSED_THREADS; tile < n_st; tile += FUSED_THREADS) {
+        const float4 t4 = *reinterpret_cast<const float4*>(j.ssq + (size_t)tile * 16 + rq * 4);
+        v.x += t4.x; v.y += t4.y; v.z += t4.z; v.w += t4.w;
+      }
+      v.x = wave_sum(v.x); v.y = wave_sum(v.y); v.z = wave_sum(v.z); v.w = wave_sum(v.w);
+      if (lane == 0) {
+        float* dst = ssq + wave * 16 + rq * 4;
+        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+      }
+    }
   }
   __syncthreads();
-  auto out_of = [&](int t, int col16, int row16) {  // finished output element: wave sums, then 1/rms of the row
+  auto out_of = [&](int t, int col16, int row) {  // finished output element: wave sums (high + low half), then 1/rms of the row
     float v = 0.f;
 #pragma unroll
-    for (int w = 0; w < WAVES; ++w) v += red[((w * TN + t) * 16 + col16) * 17 + row16];
-    if (NORMED) {
+    for (int w = 0; w < WAVES; ++w) {
+      const float* r = red + ((w * TN + t) * 16 + col16) * 17;
+      v += WIDE ? r[row] : r[row] + r[row + 8];
+    }
+    if (j.normed) {
       float s = 0.f;
 #pragma unroll
-      for (int w = 0; w < WAVES; ++w) s += ssq[w * 16 + row16];
+      for (int w = 0; w < WAVES; ++w) s += ssq[w * 16 + row];
       v *= 1.0f / sqrtf(s / (float)j.K + j.eps);
     }
     return v;
@@ -255,7 +301,10 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
       const int col = (nt0 + t) * 8 + c8;
       if (row < j.M && col < I) {
         const float g = out_of(t, c8, row), u = out_of(t, c8 + 8, row);
-        j.act[(size_t)row * I + col] = f32_to_bf16(g / (1.0f + __expf(-g)) * u);
+        uint32_t hi, lo;
+        split_bf16(g / (1.0f + __expf(-g)) * u, hi, lo);
+        j.act[(size_t)row * I + col] = (bf16_t)hi;
+        j.act[(size_t)(FUSED_LOW_ROW + row) * I + col] = (bf16_t)lo;
       }
     }
     return;
@@ -265,18 +314,38 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
 #pragma unroll
     for (int e = 0; e < E_RES; ++e) {
       const int idx = tid + e * FUSED_THREADS;
-      if (idx >= TN * 256) break;
+      if (idx >= TN * 256) break;   // (uniform over a wavefront: TN * 256 is a multiple of 64)
       const int t = idx >> 8, row = (idx >> 4) & 15, col16 = idx & 15;
       const int col = (nt0 + t) * 16 + col16;
+      float v = 0.f;
       if (row < j.M) {
-        float v = pre_old[e] + out_of(t, col16, row);
+        v = pre_old[e] + out_of(t, col16, row);
 #pragma unroll
         for (int p = 0; p < PRE_PEERS; ++p)
           if (p < j.n_peers) v += bf16_to_f32(pre_peer[e][p]);
         for (int p = PRE_PEERS; p < j.n_peers; ++p) v += bf16_to_f32(j.peers[p * j.peer_stride + (size_t)row * j.N + col]);
         j.x_new[(size_t)row * j.N + col] = v;
-        j.xh_new[(size_t)row * j.N + col] = f32_to_bf16(v);   // what the projections that read x_m multiply
+        // what the modules that read x_m multiply: x_m times their norm's gain, split
+        if (j.xop_a) {
+          uint32_t hi, lo;
+          split_bf16(v * bf16_to_f32(pre_ga[e]), hi, lo);
+          j.xop_a[(size_t)row * j.N + col] = (bf16_t)hi;
+          j.xop_a[(size_t)(FUSED_LOW_ROW + row) * j.N + col] = (bf16_t)lo;
+        }
+        if (j.xop_b) {
+          uint32_t hi, lo;
+          split_bf16(v * bf16_to_f32(pre_gb[e]), hi, lo);
+          j.xop_b[(size_t)row * j.N + col] = (bf16_t)hi;
+          j.xop_b[(size_t)(FUSED_LOW_ROW + row) * j.N + col] = (bf16_t)lo;
+        }
       }
+      // the row's sum of squares over this tile's 16 columns (the 16 lanes that share t and row)
+      float s = v * v;
+      s += __shfl_xor(s, 1, 64);
+      s += __shfl_xor(s, 2, 64);
+      s += __shfl_xor(s, 4, 64);
+      s += __shfl_xor(s, 8, 64);
+      if (col16 == 0 && row < j.M && j.ssq_new) j.ssq_new[(size_t)(nt0 + t) * 16 + row] = s;
     }
     return;
   }
@@ -297,7 +366,12 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
         o = ro;
       }
       if (head < j.nq) {
-        *reinterpret_cast<uint32_t*>(j.q_out + (size_t)row * j.nq * j.d + col) = pack_bf16(e, o);
+        uint32_t eh, el, oh, ol;
+        split_bf16(e, eh, el);
+        split_bf16(o, oh, ol);
+        const size_t at = (size_t)row * j.nq * j.d + col;
+        *reinterpret_cast<uint32_t*>(j.q_out + at) = eh | (oh << 16);
+        *reinterpret_cast<uint32_t*>(j.q_out + (size_t)FUSED_LOW_ROW * j.nq * j.d + at) = el | (ol << 16);
       } else if (head < j.nq + j.nkv) {
         const int kvh = head - j.nq;
         *reinterpret_cast<uint32_t*>(j.cache_k + (((size_t)row * j.nkv + kvh) * j.max_seq + pos) * j.d + 2 * jj) =
@@ -318,6 +392,9 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
 //                                 B = Q^T (the G heads of this kv head as columns, rest zero);
 //   O^T[dim][head] = V^T P^T      A = V^T tile (16 dims x 32 keys, from the transposed V cache),
 //                                 B = the lane's own 8 probabilities of the 32-key block.
+// Q and P are split operands: operand column h < 8 carries the high part of head h's row, column 8 + h its
+// low part (at most 8 q heads share a kv head), so the two halves of S^T and of O^T are added across lanes
+// b and b ^ 8; the cache rows (K, V) are bf16 as stored.
 // The 8 wavefronts take the 32-key blocks of the split round robin, each with its own running
 // softmax and no barrier in the loop; they merge once, through LDS, at the end.
 // ------------------------------------------------------------------------------------------------
@@ -336,12 +413,16 @@ __device__ __forceinline__ void st_coherent(float* p, float v) {
 __device__ __forceinline__ float ld_coherent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// stores output element i (bf16) of a row of an even number of elements: lanes i and i ^ 1 pair up for one
-// 32-bit coherent store (all lanes of the wave must call)
-__device__ __forceinline__ void st_coherent_bf16_pair(bf16_t* row, int i, float v) {
-  const uint32_t h = f32_to_bf16(v);
-  const uint32_t other = __shfl_xor(h, 1, 64);
-  if ((i & 1) == 0) st_coherent(reinterpret_cast<uint32_t*>(row + i), h | (other << 16));
+// stores output element i of a row of an even number of elements as a split value (high part in row_hi, low
+// part in row_lo): lanes i and i ^ 1 pair up for one 32-bit coherent store each (all lanes of the wave must call)
+__device__ __forceinline__ void st_coherent_split_pair(bf16_t* row_hi, bf16_t* row_lo, int i, float v) {
+  uint32_t h, l;
+  split_bf16(v, h, l);
+  const uint32_t oh = __shfl_xor(h, 1, 64), ol = __shfl_xor(l, 1, 64);
+  if ((i & 1) == 0) {
+    st_coherent(reinterpret_cast<uint32_t*>(row_hi + i), h | (oh << 16));
+    st_coherent(reinterpret_cast<uint32_t*>(row_lo + i), l | (ol << 16));
+  }
 }
 
 // The workgroup has stored the final attention output of its (sequence, kv head) with coherent stores: wait for
@@ -358,11 +439,10 @@ __device__ __forceinline__ void attn_signal_done(const AttnJob& a) {
 }
 
 template <int D, int G>
-__device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag) {
+__device__ __forceinline__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag) {
   constexpr int DS = D / 32, DT = D / 16;
-  const int tid = threadIdx.x;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-  const int b = lane & 15, q = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int b = threadIdx.x & 15, q = (threadIdx.x & 63) >> 4;   // (valid up to the end of the key loop: see below)
   const int sp = lb % a.n_splits, kvh = (lb / a.n_splits) % a.nkv, bi = lb / (a.n_splits * a.nkv);
   const int pbeg = sp * a.split_len;
   const float scale = 1.0f / sqrtf((float)D);
@@ -390,13 +470,16 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
   const bool early = kb0 + 32 <= a.max_seq;
   if (early) load_kv(kb0);
   const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  static_assert(G <= 8, "high and low parts of the heads of a kv head share one 16-column operand");
+  const int hsel = b & 7;             // head of this lane's operand column
+  const bool low = (b & 8) != 0;      // its column carries the low parts
   uint4 qreg[DS];
   {
-    const bf16_t* qg = a.q + (size_t)bi * a.nq * D + (size_t)(kvh * G + min(b, G - 1)) * D;
+    const bf16_t* qg = a.q + ((size_t)((low ? FUSED_LOW_ROW : 0) + bi) * a.nq + kvh * G + min(hsel, G - 1)) * D;
 #pragma unroll
     for (int s = 0; s < DS; ++s) {
       const uint4 v = *reinterpret_cast<const uint4*>(qg + s * 32 + q * 8);
-      qreg[s] = b < G ? v : zero4;
+      qreg[s] = hsel < G ? v : zero4;
     }
   }
   const int n_pos = *a.pos_dev + 1;
@@ -423,7 +506,8 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int key = kb + 16 * t + 4 * q + r;
-        const float v = key < pend ? st[t][r] * scale : -INFINITY;   // positions past the new token: masked
+        const float sc = st[t][r] + other_half(st[t][r]);             // q = high + low part: both halves now hold the score
+        const float v = key < pend ? sc * scale : -INFINITY;          // positions past the new token: masked
         sv[t * 4 + r] = v;
         mloc = fmaxf(mloc, v);
       }
@@ -439,9 +523,16 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
     }
     lrun = lrun * corr + psum;
     mrun = mnew;
+    uint32_t pe[8];   // this column's part of the probabilities: high parts in columns 0..7, low parts in 8..15
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      uint32_t h, l;
+      split_bf16(pv[e], h, l);
+      pe[e] = low ? l : h;
+    }
     uint4 pb;
-    pb.x = pack_bf16(pv[0], pv[1]); pb.y = pack_bf16(pv[2], pv[3]);
-    pb.z = pack_bf16(pv[4], pv[5]); pb.w = pack_bf16(pv[6], pv[7]);
+    pb.x = pe[0] | (pe[1] << 16); pb.y = pe[2] | (pe[3] << 16);
+    pb.z = pe[4] | (pe[5] << 16); pb.w = pe[6] | (pe[7] << 16);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
 #pragma unroll
@@ -461,19 +552,30 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
   // per-wave (max, sum, O^T) -> LDS; oacc[dt][r] = O^T[dim = dt*16 + 4q + r][head b]
   lrun += __shfl_xor(lrun, 16, 64);
   lrun += __shfl_xor(lrun, 32, 64);
+  // (the lane's coordinates are taken afresh from the hardware here, so that the ones above need not stay in
+  // registers across the key loop, where every register is wanted for rows in flight)
+  const int lane_m = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+  const int tid_m = wave * 64 + lane_m;
   float* wm = smem;                          // [WAVES][16]
   float* wl = wm + FUSED_WAVES * 16;         // [WAVES][16]
   float* wo = wl + FUSED_WAVES * 16;         // [WAVES][G][D]
-  if (q == 0) { wm[wave * 16 + b] = mrun; wl[wave * 16 + b] = lrun; }
-  if (b < G) {
+  const int b2 = lane_m & 15, q2 = lane_m >> 4;
+  if (q2 == 0) { wm[wave * 16 + b2] = mrun; wl[wave * 16 + b2] = lrun; }
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) oacc[dt][r] += other_half(oacc[dt][r]);   // P = high + low part
+  if (b2 < G) {
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) wo[(wave * G + b) * D + dt * 16 + 4 * q + r] = oacc[dt][r];
+      for (int r = 0; r < 4; ++r) wo[(wave * G + b2) * D + dt * 16 + 4 * q2 + r] = oacc[dt][r];
   }
   __syncthreads();
   const size_t pbase = ((size_t)bi * a.nkv + kvh) * a.n_splits;
-  for (int i = tid; i < G * D; i += FUSED_THREADS) {
+  bf16_t* const o_hi = a.o + ((size_t)bi * a.nq + kvh * G) * D;
+  bf16_t* const o_lo = a.o + ((size_t)(FUSED_LOW_ROW + bi) * a.nq + kvh * G) * D;
+  for (int i = tid_m; i < G * D; i += FUSED_THREADS) {
     const int h = i / D, dim = i % D;
     float m = -INFINITY;
 #pragma unroll
@@ -486,7 +588,7 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
       o += wo[(w * G + h) * D + dim] * f;
     }
     if (a.n_splits == 1) {
-      st_coherent_bf16_pair(a.o + (size_t)bi * a.nq * D + (size_t)kvh * G * D, i, o / l);
+      st_coherent_split_pair(o_hi, o_lo, i, o / l);
     } else {
       st_coherent(a.part_o + ((pbase + sp) * G + h) * D + dim, o);
       if (dim == 0) {
@@ -504,7 +606,7 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
   const int n_active = min(a.n_splits, (n_pos + a.split_len - 1) / a.split_len);
   __builtin_amdgcn_s_waitcnt(0);   // this thread's coherent stores of the partial result have completed
   __syncthreads();
-  if (tid == 0) {
+  if (tid_m == 0) {
     const unsigned t = atomicAdd(a.tickets + bi * a.nkv + kvh, 1u);
     *s_flag = t;
     if (t == (unsigned)n_active - 1) a.tickets[bi * a.nkv + kvh] = 0u;  // ready for the next launch
@@ -515,7 +617,7 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
   // own output elements from all splits, sixteen splits per pass with all of the pass's loads issued
   // together (one memory round trip per pass), in split order.
   constexpr int SP = 16;
-  for (int i = tid; i < G * D; i += FUSED_THREADS) {
+  for (int i = tid_m; i < G * D; i += FUSED_THREADS) {
     const int h = i / D;
     float m = -INFINITY, l = 0.f, o = 0.f;
     for (int s0 = 0; s0 < n_active; s0 += SP) {
@@ -541,29 +643,11 @@ __device__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag
       }
       m = mnew;
     }
-    st_coherent_bf16_pair(a.o + (size_t)bi * a.nq * D + (size_t)kvh * G * D, i, o / l);
+    st_coherent_split_pair(o_hi, o_lo, i, o / l);
   }
   attn_signal_done(a);
 }
 
-#ifdef FUSED_TRACE
-// development builds only: per-workgroup start / end time (100 MHz counter) and hardware placement
-__device__ unsigned long long* g_fused_trace;
-struct FusedTraceScope {
-  unsigned long long t0;
-  __device__ FusedTraceScope() : t0(wall_clock64()) {}
-  __device__ ~FusedTraceScope() {
-    if (threadIdx.x == 0 && g_fused_trace) {
-      unsigned hw, xcc;
-      asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
-      asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-      g_fused_trace[blockIdx.x * 4 + 0] = t0;
-      g_fused_trace[blockIdx.x * 4 + 1] = wall_clock64();
-      g_fused_trace[blockIdx.x * 4 + 2] = ((unsigned long long)xcc << 32) | hw;
-    }
-  }
-};
-#endif
 
 // The leading arguments repeat what a workgroup needs first: two (weights, operand) pointer pairs that cover the
 // GEMV jobs of a launch (jobs that are parts of one projection share theirs), the block boundaries of the jobs
@@ -592,24 +676,22 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(const vo
                                                                        unsigned geo2, FusedArgs fa) {
   extern __shared__ float smem[];   // fa.lds_bytes: the largest need of the launch's jobs
   __shared__ unsigned s_flag;
-#ifdef FUSED_TRACE
-  FusedTraceScope trace_scope;
-#endif
   const int end0 = (int)(ends01 & 0xFFFFu), end1 = (int)(ends01 >> 16), end2 = (int)(end2_m & 0xFFFFu);
   int lb = blockIdx.x, job = 0;
   if ((int)blockIdx.x >= end0) { lb = blockIdx.x - end0; job = 1; }
   if ((int)blockIdx.x >= end1) { lb = blockIdx.x - end1; job = 2; }
   if ((int)blockIdx.x >= end2) { lb = blockIdx.x - end2; job = 3; }
   const unsigned kb = (kinds >> (8 * job)) & 0xFFu;
+  // The jobs' descriptors are read in place from the kernel-argument segment (uniform index -> scalar loads).
+  // Touching the by-value argument itself makes the compiler, beyond some amount of code that uses it, keep a
+  // copy of all of it in private memory (a kilobyte of scratch stores at the head of every wavefront).  The
+  // block's offset in the segment is that of the last member of FusedKernelParams.
+  typedef __attribute__((address_space(4))) const char* kernarg_ptr_t;
+  const kernarg_ptr_t ka = (kernarg_ptr_t)__builtin_amdgcn_kernarg_segment_ptr();
   if ((kb & FUSED_KIND_MASK) == (unsigned)JOB_ATTN) {
-    attn_job<D, G>(fa.a, lb, smem, &s_flag);
+    const AttnJob& aj = *(const AttnJob*)(ka + offsetof(FusedKernelParams, fa) + offsetof(FusedArgs, a));
+    attn_job<D, G>(aj, lb, smem, &s_flag);
   } else {
-    // The job's descriptor is read in place from the kernel-argument segment (uniform index -> scalar loads).
-    // Indexing the by-value argument itself makes the compiler, beyond some amount of code that uses it, keep a
-    // copy of all of it in private memory (a kilobyte of scratch stores at the head of every wavefront).  The
-    // block's offset in the segment is that of the last member of FusedKernelParams.
-    typedef __attribute__((address_space(4))) const char* kernarg_ptr_t;
-    const kernarg_ptr_t ka = (kernarg_ptr_t)__builtin_amdgcn_kernarg_segment_ptr();
     const GemvJob& j = *(const GemvJob*)(ka + offsetof(FusedKernelParams, fa) + offsetof(FusedArgs, g) + (size_t)job * sizeof(GemvJob));
     const unsigned slot = kb >> FUSED_KIND_SLOT_SHIFT;   // which preloaded pointer pair: 0, 1, or 3 = none
     const int gi = job - ((kinds & FUSED_KIND_MASK) == (unsigned)JOB_ATTN ? 1 : 0);   // index among the GEMV jobs
@@ -619,43 +701,68 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(const vo
     int KT = (int)(geo >> 16), group0 = (int)(geo & 0xFFFFu), M = (int)(end2_m >> 16);
     if (slot == 3) { wp = j.wp; xop = j.xb; KT = j.K >> 5; group0 = j.group0; M = j.M; }
     const unsigned tn = ((kb >> FUSED_KIND_TN_SHIFT) & 3u) + 1u;
-    const bool normed = (kb & FUSED_KIND_NORMED) != 0;
-    if (kb & FUSED_KIND_WAITS) {   // (the plan gives only the un-normed O projection a wait)
-      if (tn == 4) gemv_job<false, 1, 4, true>(j, wp, xop, KT, group0, M, lb, smem);
-      else if (tn == 2) gemv_job<false, FUSED_U2, 2, true>(j, wp, xop, KT, group0, M, lb, smem);
-      else gemv_job<false, FUSED_U, 1, true>(j, wp, xop, KT, group0, M, lb, smem);
-    } else if (tn == 4) {   // (the plan builds four-tile workgroups for normed projections only: gate/up at 13 rows and more)
-      gemv_job<true, 1, 4>(j, wp, xop, KT, group0, M, lb, smem);
-    } else if (tn == 3) {   // (the plan builds three-tile workgroups for un-normed projections only)
-      gemv_job<false, 1, 3>(j, wp, xop, KT, group0, M, lb, smem);
+    // more than 8 rows: high and low operand parts are two MFMA operands (else they share one)
+#define FUSED_GEMV(U_, TN_, COH_)                                                              \
+  do {                                                                                         \
+    if (M > 8) gemv_job<U_, TN_, COH_, true>(j, wp, xop, KT, group0, M, lb, smem, &s_flag);    \
+    else gemv_job<U_, TN_, COH_, false>(j, wp, xop, KT, group0, M, lb, smem, &s_flag);         \
+  } while (0)
+    if (kb & FUSED_KIND_WAITS) {
+      if (tn == 4) FUSED_GEMV(1, 4, true);
+      else if (tn == 2) FUSED_GEMV(FUSED_U2, 2, true);
+      else FUSED_GEMV(FUSED_U, 1, true);
+    } else if (tn == 4) {
+      FUSED_GEMV(1, 4, false);
+    } else if (tn == 3) {
+      FUSED_GEMV(1, 3, false);
     } else if (tn == 2) {
-      if (normed) gemv_job<true, FUSED_U2, 2>(j, wp, xop, KT, group0, M, lb, smem);
-      else gemv_job<false, FUSED_U2, 2>(j, wp, xop, KT, group0, M, lb, smem);
+      FUSED_GEMV(FUSED_U2, 2, false);
     } else {
-      if (normed) gemv_job<true, FUSED_U, 1>(j, wp, xop, KT, group0, M, lb, smem);
-      else gemv_job<false, FUSED_U, 1>(j, wp, xop, KT, group0, M, lb, smem);
+      FUSED_GEMV(FUSED_U, 1, false);
+    }
+#undef FUSED_GEMV
+  }
+}
+
+// x_0 = embeddings: fp32 for the residual chain, split operands (times the readers' gains) for the projections,
+// sums of squares per 16-column tile and row (a tile = 16 adjacent threads: H is a multiple of 16)
+// (also clears the step's arrival counters: a fill kernel, not a memset node, so that a captured step replays)
+__global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a) {
+  const int i = blockIdx.x * 256 + threadIdx.x, n = a.rows * a.H;
+  const bool ok = i < n;
+  const int ic = min(i, n - 1);
+  const int row = ic / a.H, col = ic % a.H;
+  const float v = bf16_to_f32(a.emb[ic]);
+  if (ok) {
+    a.x0[ic] = v;
+    if (a.xop_a) {
+      uint32_t hi, lo;
+      split_bf16(v * bf16_to_f32(a.gain_a[col]), hi, lo);
+      a.xop_a[ic] = (bf16_t)hi;
+      a.xop_a[(size_t)FUSED_LOW_ROW * a.H + ic] = (bf16_t)lo;
+    }
+    if (a.xop_b) {
+      uint32_t hi, lo;
+      split_bf16(v * bf16_to_f32(a.gain_b[col]), hi, lo);
+      a.xop_b[ic] = (bf16_t)hi;
+      a.xop_b[(size_t)FUSED_LOW_ROW * a.H + ic] = (bf16_t)lo;
     }
   }
+  float s = ok ? v * v : 0.f;
+  s += __shfl_xor(s, 1, 64);
+  s += __shfl_xor(s, 2, 64);
+  s += __shfl_xor(s, 4, 64);
+  s += __shfl_xor(s, 8, 64);
+  if (ok && (col & 15) == 0) a.ssq[(size_t)(col >> 4) * 16 + row] = s;
+  if (i < a.n_zero) a.zero_words[i] = 0u;
 }
 
-// x_0 = embeddings: fp32 for the residual chain, bf16 copy for the projections
-// (also clears the step's arrival counters: a fill kernel, not a memset node, so that a captured step replays)
-__global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ emb, float* __restrict__ x0,
-                                                    bf16_t* __restrict__ xh0, int n, unsigned* __restrict__ zero_words,
-                                                    int n_zero) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < n) {
-    x0[i] = bf16_to_f32(emb[i]);
-    xh0[i] = emb[i];
-  }
-  if (i < n_zero) zero_words[i] = 0u;
-}
-
-hipError_t launch_embed(const bf16_t* emb, float* x0, bf16_t* xh0, int n, unsigned* zero_words, int n_zero,
-                        hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
-  const dim3 grid((std::max(n, n_zero) + 255) / 256), block(256);
-  if (ev0 || ev1) hipExtLaunchKernelGGL(embed_kernel, grid, block, 0, s, ev0, ev1, 0, emb, x0, xh0, n, zero_words, n_zero);
-  else hipLaunchKernelGGL(embed_kernel, grid, block, 0, s, emb, x0, xh0, n, zero_words, n_zero);
+hipError_t launch_embed(const EmbedArgs& a, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+  if (a.rows <= 0 || a.rows > 16 || a.H <= 0 || (a.H & 15) || !a.emb || !a.x0 || !a.ssq) return hipErrorInvalidValue;
+  if ((a.xop_a && !a.gain_a) || (a.xop_b && !a.gain_b)) return hipErrorInvalidValue;
+  const dim3 grid((std::max(a.rows * a.H, a.n_zero) + 255) / 256), block(256);
+  if (ev0 || ev1) hipExtLaunchKernelGGL(embed_kernel, grid, block, 0, s, ev0, ev1, 0, a);
+  else hipLaunchKernelGGL(embed_kernel, grid, block, 0, s, a);
   return hipGetLastError();
 }
 
@@ -689,12 +796,15 @@ static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStrea
           rows = j.M;
         }
       }
-      // tiles per workgroup the kernel has code for: 1 and 2 for every job, 3 without norm and wait, 4 with norm
-      // and without wait or without norm and with a wait
+      // tiles per workgroup the kernel has code for: 1, 2 and 4 for every job, 3 for jobs without a wait
       const int tn = j.tn >= 2 ? j.tn : 1;
-      if (tn > 4 || (tn == 3 && (j.normed || j.wait_on)) || (tn == 4 && ((j.normed != 0) == (j.wait_on != nullptr)))) return hipErrorInvalidValue;
+      if (tn > 4 || (tn == 3 && j.wait_on)) return hipErrorInvalidValue;
+      // what the kernel takes for granted about the operands
+      if (j.M < 1 || j.M > 16 || (j.K & 31) || (j.N & 15)) return hipErrorInvalidValue;
+      if (j.normed && !j.ssq) return hipErrorInvalidValue;
+      if (j.wait_on && j.wait_spins <= 0) return hipErrorInvalidValue;
+      if (j.epi == EPI_RESIDUAL && ((j.xop_a && !j.gain_a) || (j.xop_b && !j.gain_b) || !j.x_old || !j.x_new)) return hipErrorInvalidValue;
       kb |= (unsigned)(tn - 1) << FUSED_KIND_TN_SHIFT;
-      if (j.normed) kb |= FUSED_KIND_NORMED;
       if (j.wait_on) kb |= FUSED_KIND_WAITS;
       kb |= slot << FUSED_KIND_SLOT_SHIFT;
     }

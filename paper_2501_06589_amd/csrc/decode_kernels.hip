@@ -9,7 +9,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 // Repack: one thread per (tile, lane); writes the lane's 8 consecutive k of its packed column.
 // ------------------------------------------------------------------------------------------------
 __global__ void repack_tiles_kernel(const bf16_t* __restrict__ src, uint4* __restrict__ dst, int K, int N,
-                                    int N_total, int col0, int mode, const bf16_t* __restrict__ row_gain) {
+                                    int N_total, int col0, int mode) {
   const int KT = (K + 31) / 32, NT = (N_total + 15) / 16;
   const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= (long long)NT * KT * 64) return;
@@ -30,23 +30,17 @@ __global__ void repack_tiles_kernel(const bf16_t* __restrict__ src, uint4* __res
   uint32_t w[4];
   for (int e = 0; e < 4; ++e) {
     const int ka = k0 + 2 * e, kb = ka + 1;
-    uint32_t lo = ka < K ? src[(size_t)ka * N + n_src] : 0;
-    uint32_t hi = kb < K ? src[(size_t)kb * N + n_src] : 0;
-    if (row_gain) {  // fold the RMSNorm gain of input row k into the weight (one extra bf16 rounding)
-      if (ka < K) lo = f32_to_bf16(bf16_to_f32((bf16_t)lo) * bf16_to_f32(row_gain[ka]));
-      if (kb < K) hi = f32_to_bf16(bf16_to_f32((bf16_t)hi) * bf16_to_f32(row_gain[kb]));
-    }
+    const uint32_t lo = ka < K ? src[(size_t)ka * N + n_src] : 0;
+    const uint32_t hi = kb < K ? src[(size_t)kb * N + n_src] : 0;
     w[e] = lo | (hi << 16);
   }
   dst[gid] = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-hipError_t launch_repack_tiles(const bf16_t* src, void* dst, int K, int N, int N_total, int col0, int mode,
-                               const bf16_t* row_gain, hipStream_t s) {
+hipError_t launch_repack_tiles(const bf16_t* src, void* dst, int K, int N, int N_total, int col0, int mode, hipStream_t s) {
   const long long total = (long long)((N_total + 15) / 16) * ((K + 31) / 32) * 64;
   const unsigned blocks = (unsigned)((total + 255) / 256);
-  hipLaunchKernelGGL(repack_tiles_kernel, dim3(blocks), dim3(256), 0, s, src, (uint4*)dst, K, N, N_total, col0,
-                     mode, row_gain);
+  hipLaunchKernelGGL(repack_tiles_kernel, dim3(blocks), dim3(256), 0, s, src, (uint4*)dst, K, N, N_total, col0, mode);
   return hipGetLastError();
 }
 

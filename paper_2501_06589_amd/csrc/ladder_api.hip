@@ -1,5 +1,5 @@
 // Host side of the C-ABI: configuration checks, memory plan, weight loading (repack into matrix-core
-// tiles, norm gains folded in), and the schedules of the Ladder-Residual forward (Algorithm 1 / Eq. 2).
+// tiles), and the schedules of the Ladder-Residual forward (Algorithm 1 / Eq. 2).
 //
 // All work runs on the context's own streams; the caller's stream is fenced in and out with events.
 //
@@ -91,8 +91,11 @@ struct ladder_ctx {
   char* emb_stage = nullptr;    // T [max_batch][H]: decode input staged for the captured graph
   hipGraphExec_t graph_exec = nullptr;
   int graph_batch = 0;
+  bool graph_stale = false;     // the captured step no longer matches the context (peers changed)
   std::vector<void*> allocs;
   size_t dev_bytes = 0;
+  size_t weight_bytes = 0;      // of dev_bytes: the weight store
+  bool dry = false;             // sizing pass: the memory plan is walked, no HIP call is made
   std::vector<LayerStore> store;  // [layer * n_real + shard]
   std::vector<char*> gain_attn, gain_mlp;  // per layer, T [H]
   std::vector<char> gains_loaded;
@@ -118,7 +121,16 @@ struct ladder_ctx {
   // the launch list of one step
   bool fused = false;
   float* x_ring[3] = {nullptr, nullptr, nullptr};
-  bf16_t* xh_ring[3] = {nullptr, nullptr, nullptr};   // bf16 copies: the operand of the projections
+  // what the projections multiply: x_m times the gain of the reading module's RMSNorm, as a split bf16 matrix
+  // [32][H] (decode_fused.h); slot [m % 3][reader & 1] (a stream has at most one odd = attention and one even =
+  // MLP reader); and the rows' sums of squares per 16-column tile, [H/16][16]
+  bf16_t* xop_ring[3][2] = {{nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}};
+  float* ssq_ring[3] = {nullptr, nullptr, nullptr};
+  bf16_t *f_q = nullptr, *f_o = nullptr, *f_act = nullptr;   // split q, attention output, SwiGLU output: [32][width]
+  unsigned* err_word = nullptr;   // host-visible word that a kernel raises when its bounded in-launch wait gives up
+  unsigned* err_word_dev = nullptr;   // its device address
+  int wait_spins = 1 << 20;       // polls of that wait (about a second); a test shortens it
+  unsigned wait_bias = 0;         // added to the wait's target (0 in normal operation; a test makes it unreachable)
   unsigned* tk_att = nullptr;     // arrival tickets of split attention, [max_batch][nkv]
   std::vector<FusedArgs> fused_plan;
   int fused_plan_batch = 0;
@@ -127,7 +139,7 @@ struct ladder_ctx {
   unsigned* att_done = nullptr;   // fused decode: per layer, how many (sequence, kv head) attention outputs are final
   // generation head (ladder_load_head)
   char* head_table = nullptr;     // T [vocab][H]
-  char* head_gain = nullptr;      // T [H] (plain path; the streaming path folds it into head_wp)
+  char* head_gain = nullptr;      // T [H]
   char* head_w = nullptr;         // plain path: T [H][vocab_local]
   char* head_wp = nullptr;        // streaming path: packed tiles
   char* head_y = nullptr;         // T [max_batch][H] normed rows
@@ -179,6 +191,10 @@ int fail(ladder_ctx* c, int code, const std::string& msg) {
 int dev_alloc(ladder_ctx* c, void** p, size_t bytes, bool zero) {
   *p = nullptr;
   if (bytes == 0) bytes = 16;
+  if (c->dry) {   // sizing pass (ladder_workspace_bytes): nothing is allocated
+    c->dev_bytes += bytes;
+    return LADDER_OK;
+  }
   HIP_TRY(c, hipMalloc(p, bytes));
   c->allocs.push_back(*p);
   c->dev_bytes += bytes;
@@ -280,8 +296,9 @@ int consumers_of(const ladder_ctx* c, int m, int out[2]) {
 // Wide calls (more than 64 rows) of the packed-weight path with one real shard: the residual update of module m
 // ("wait(); residual += out", Algorithm 1, the AllReduce as a sum over rank partial sums, Eq. 2) is the
 // epilogue of the module's last GEMM instead of a kernel of its own, which saves a round trip of the fp32
-// product through memory.  The epilogue leaves the new rows as bf16 for the modules that read x_m, un-normed:
-// their 1/rms (from the sums of squares the epilogue also leaves) scales the consumer's product instead.
+// product through memory.  The epilogue leaves the new rows, times the reading module's gain, as bf16 for the
+// modules that read x_m; their 1/rms (from the sums of squares the epilogue also leaves) scales the consumer's
+// product instead (the factor commutes with the product).
 int fuse_residual(ladder_ctx* c, GemmArgs& a, int m, float* x_copy, int cons[2]) {
   const ladder_config& g = c->cfg;
   a.epilogue = 3; a.x_res = c->x; a.x_copy = x_copy;
@@ -291,8 +308,9 @@ int fuse_residual(ladder_ctx* c, GemmArgs& a, int m, float* x_copy, int cons[2])
     a.n_peers = c->n_peers; a.peer_stride = (size_t)g.peer_rows * g.hidden;
   }
   const int nc = consumers_of(c, m, cons);
-  if (nc > 0) { a.xh_a = (bf16_t*)c->y[cons[0] & 1]; a.ssq_part = c->ssq_part; }
-  if (nc > 1) a.xh_b = (bf16_t*)c->y[cons[1] & 1];
+  auto gain_of = [&](int cm) { return (const bf16_t*)((cm & 1) ? c->gain_attn[(cm - 1) / 2] : c->gain_mlp[(cm - 1) / 2]); };
+  if (nc > 0) { a.xh_a = (bf16_t*)c->y[cons[0] & 1]; a.gain_a = gain_of(cons[0]); a.ssq_part = c->ssq_part; }
+  if (nc > 1) { a.xh_b = (bf16_t*)c->y[cons[1] & 1]; a.gain_b = gain_of(cons[1]); }
   return nc;
 }
 
@@ -467,8 +485,7 @@ int run_reduce(ladder_ctx* c, int m, int rows, int n_slots, const void* emb, flo
     const int cm = consumers[i], layer = (cm - 1) / 2;
     void* out = c->y[cm & 1];
     c->y_scale[cm & 1] = nullptr;   // normed rows
-    // packed-weight path: the gain lives in the consumer's weights
-    const void* gain = c->fast ? nullptr : ((cm & 1) ? (const void*)c->gain_attn[layer] : (const void*)c->gain_mlp[layer]);
+    const void* gain = (cm & 1) ? (const void*)c->gain_attn[layer] : (const void*)c->gain_mlp[layer];
     if (i == 0) { a.out_a = out; a.gain_a = gain; }
     else { a.out_b = out; a.gain_b = gain; }
   }
@@ -571,10 +588,10 @@ void build_fused_plan(ladder_ctx* c, int B) {
 
   auto job_qkv = [&](int l, int src) {
     GemvJob j{};
-    j.xb = c->xh_ring[src % 3]; j.ldx = H; j.normed = 1; j.eps = g.rms_eps;
+    j.xb = c->xop_ring[src % 3][1]; j.ldx = H; j.normed = 1; j.eps = g.rms_eps; j.ssq = c->ssq_ring[src % 3];
     j.wp = layer(l).pqkv; j.M = B; j.K = H; j.N = c->nqkv;
     j.n_groups = c->nqkv / 16; j.epi = EPI_QKV_ROPE;
-    j.q_out = (bf16_t*)c->qbuf;
+    j.q_out = c->f_q;
     j.cache_k = (bf16_t*)layer(l).cache_k; j.cache_v = (bf16_t*)layer(l).cache_v;
     j.cos_tab = c->cos_tab; j.sin_tab = c->sin_tab; j.pos_dev = c->pos_dev;
     j.nq = nq; j.nkv = nkv; j.d = d; j.max_seq = c->s_cap;
@@ -587,7 +604,17 @@ void build_fused_plan(ladder_ctx* c, int B) {
   // unless the two modules of a layer are added in the other order)
   auto residual = [&](GemvJob& j, int m, int at) {
     j.N = H; j.n_groups = H / 16; j.epi = EPI_RESIDUAL;
-    j.x_old = c->x_ring[(at - 1) % 3]; j.x_new = c->x_ring[at % 3]; j.xh_new = c->xh_ring[at % 3];
+    j.x_old = c->x_ring[(at - 1) % 3]; j.x_new = c->x_ring[at % 3];
+    // the modules that read what this job leaves in slot `at` (x_at; under the parallel wiring the odd slots hold
+    // an intermediate sum that nobody reads): each gets its operand, the new rows times its norm's gain
+    int cons[2];
+    const int nc = consumers_of(c, at, cons);
+    for (int i = 0; i < nc; ++i) {
+      const int cm = cons[i], cl = (cm - 1) / 2;
+      if (cm & 1) { j.xop_a = c->xop_ring[at % 3][1]; j.gain_a = (const bf16_t*)c->gain_attn[cl]; }
+      else { j.xop_b = c->xop_ring[at % 3][0]; j.gain_b = (const bf16_t*)c->gain_mlp[cl]; }
+    }
+    if (nc > 0) j.ssq_new = c->ssq_ring[at % 3];
     if (c->peers && c->n_peers > 0) {
       j.peers = (const bf16_t*)c->peers + (size_t)(m % g.peer_pool) * c->n_peers * (size_t)g.peer_rows * H;
       j.n_peers = c->n_peers; j.peer_stride = (size_t)g.peer_rows * H;
@@ -595,7 +622,7 @@ void build_fused_plan(ladder_ctx* c, int B) {
   };
   auto job_o = [&](int l, int m, int at = -1) {
     GemvJob j{};
-    j.xb = (const bf16_t*)c->obuf; j.ldx = nqd; j.wp = layer(l).po; j.M = B; j.K = nqd;
+    j.xb = c->f_o; j.ldx = nqd; j.wp = layer(l).po; j.M = B; j.K = nqd;
     residual(j, m, at < 0 ? m : at);
     // its K range is short: two tiles per workgroup halve the number of (latency-bound) workgroups
     if (j.n_groups % 2 == 0) { j.tn = 2; j.n_groups /= 2; }
@@ -603,9 +630,9 @@ void build_fused_plan(ladder_ctx* c, int B) {
   };
   auto job_gu = [&](int l, int src) {
     GemvJob j{};
-    j.xb = c->xh_ring[src % 3]; j.ldx = H; j.normed = 1; j.eps = g.rms_eps;
+    j.xb = c->xop_ring[src % 3][0]; j.ldx = H; j.normed = 1; j.eps = g.rms_eps; j.ssq = c->ssq_ring[src % 3];
     j.wp = layer(l).pgu; j.M = B; j.K = H; j.N = 2 * I;
-    j.n_groups = 2 * I / 16; j.epi = EPI_SWIGLU; j.act = (bf16_t*)c->act;
+    j.n_groups = 2 * I / 16; j.epi = EPI_SWIGLU; j.act = c->f_act;
     // every workgroup reads the batch's rows of x over its whole K range (from L2): at 13 rows and more that
     // traffic is worth halving with two tiles per workgroup (70B shard, batch 14 / 16: 5.42 -> 5.09 / 5.80 -> 5.31
     // ms per step; batch 12 and less: slower; for QKV and down: slower at every batch)
@@ -614,23 +641,21 @@ void build_fused_plan(ladder_ctx* c, int B) {
     // tiles: 70B shard at R = 8, batch 4: 3.51 -> 3.41 ms)
     // (measured: batch 1 - 6 faster, 7 - 12 slower)
     if ((B >= 13 || H <= 2048 || (j.n_groups / 2 <= c->n_cu && B <= 6)) && j.n_groups % 2 == 0) { j.tn = 2; j.n_groups /= 2; }
-#ifndef FUSED_NO_GU4
     // (13 rows and more, and enough tiles that quadruples still give most CUs a workgroup: four tiles per
     // workgroup halve the operand traffic once more)
     if (B >= 13 && j.tn == 2 && j.n_groups % 2 == 0 && 4 * (j.n_groups / 2) >= 3 * c->n_cu) { j.tn = 4; j.n_groups /= 2; }
-#endif
     return j;
   };
   auto job_dn = [&](int l, int m, int at = -1) {
     GemvJob j{};
-    j.xb = (const bf16_t*)c->act; j.ldx = I; j.wp = layer(l).pd; j.M = B; j.K = I;
+    j.xb = c->f_act; j.ldx = I; j.wp = layer(l).pd; j.M = B; j.K = I;
     residual(j, m, at < 0 ? m : at);
     return j;
   };
   auto job_att = [&](int l) {
     AttnJob a{};
-    a.q = (const bf16_t*)c->qbuf; a.cache_k = (const bf16_t*)layer(l).cache_k; a.cache_v = (const bf16_t*)layer(l).cache_v;
-    a.part_o = c->att_o; a.part_ml = c->att_ml; a.o = (bf16_t*)c->obuf; a.tickets = c->tk_att;
+    a.q = c->f_q; a.cache_k = (const bf16_t*)layer(l).cache_k; a.cache_v = (const bf16_t*)layer(l).cache_v;
+    a.part_o = c->att_o; a.part_ml = c->att_ml; a.o = c->f_o; a.tickets = c->tk_att;
     a.B = B; a.nq = nq; a.nkv = nkv; a.max_seq = c->s_cap; a.n_splits = n_splits; a.split_len = split_len;
     a.pos_dev = c->pos_dev;
     return a;
@@ -741,11 +766,10 @@ void build_fused_plan(ladder_ctx* c, int B) {
       AttnJob aj = job_att(l);
       aj.done = c->att_done + (l - 1);
       GemvJob o = job_o(l, 2 * l - 1);
-      o.wait_on = aj.done; o.wait_target = (unsigned)(B * nkv);
+      o.wait_on = aj.done; o.wait_target = (unsigned)(B * nkv) + c->wait_bias; o.wait_spins = c->wait_spins; o.err_word = c->err_word_dev;
       // block order: attention, as many gate/up workgroups as leave every CU one long workgroup, o_l (resident
       // from the start, asleep until attention is done, then beside the rest of gate/up), the rest of gate/up
       GemvJob gu_a = job_gu(l, 2 * l - 2), gu_b = gu_a;
-#ifndef FUSED_NO_O4
       // every workgroup of the launch should be resident from the start (two per CU): workgroups beyond that wait
       // for a slot, and the last in block order are long gate/up workgroups.  Where attention, gate/up and o_l
       // make more than that (large batches: attention has a workgroup per sequence and split), o_l takes four
@@ -753,7 +777,6 @@ void build_fused_plan(ladder_ctx* c, int B) {
       // 4.06 -> 3.86 ms per step, 70B R = 4 shard at batch 16 8.89 -> 8.61; with the R = 8 shard's K range of
       // 1024, batch 8 and 16, it cost 1 - 2 %).
       if (n_splits * nkv * B + blocks_of(gu_a) + blocks_of(o) > 2 * c->n_cu && nqd >= 2048 && o.tn == 2 && o.n_groups % 2 == 0) { o.tn = 4; o.n_groups /= 2; }
-#endif
       const int n_a = std::min(gu_a.n_groups / 2, c->n_cu / 2);   // (any position in the first half measured the same)
       gu_a.n_groups = n_a;
       gu_b.group0 = n_a; gu_b.n_groups -= n_a;
@@ -805,7 +828,20 @@ int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s) {
   };
   hipEvent_t e[2];
   HIP_TRY(c, events(e));
-  HIP_TRY(c, launch_embed((const bf16_t*)emb, c->x_ring[0], c->xh_ring[0], B * g.hidden, c->att_done, g.n_layers, s, e[0], e[1]));
+  {
+    // x_0 and the operands of the modules that read it (module 1, and module 2 where its lag is 2)
+    EmbedArgs ea{};
+    ea.emb = (const bf16_t*)emb; ea.x0 = c->x_ring[0]; ea.ssq = c->ssq_ring[0]; ea.rows = B; ea.H = g.hidden;
+    ea.zero_words = c->att_done; ea.n_zero = g.n_layers;
+    int cons[2];
+    const int nc = consumers_of(c, 0, cons);
+    for (int i = 0; i < nc; ++i) {
+      const int cm = cons[i], cl = (cm - 1) / 2;
+      if (cm & 1) { ea.xop_a = c->xop_ring[0][1]; ea.gain_a = (const bf16_t*)c->gain_attn[cl]; }
+      else { ea.xop_b = c->xop_ring[0][0]; ea.gain_b = (const bf16_t*)c->gain_mlp[cl]; }
+    }
+    HIP_TRY(c, launch_embed(ea, s, e[0], e[1]));
+  }
   if (c->prof) c->prof_pending.push_back({LADDER_K_OTHER, e[0], e[1]});
   const int gq = g.n_q_heads / g.n_kv_heads;
   for (const FusedArgs& fa : c->fused_plan) {
@@ -838,11 +874,13 @@ int forward(ladder_ctx* c, const void* x_in, int B, int T, int pos0, void* x_out
 // one decode step replayed from a captured graph: stage the input, launch, copy the result out
 int decode_graph_step(ladder_ctx* c, const void* x_in, void* x_out) {
   const int B = c->batch, H = c->cfg.hidden;
-  if (!c->graph_exec || c->graph_batch != B) {
+  if (!c->graph_exec || c->graph_batch != B || c->graph_stale) {
     if (c->graph_exec) {
+      HIP_TRY(c, hipStreamSynchronize(c->s_attn));   // (a replay may still be running)
       HIP_TRY(c, hipGraphExecDestroy(c->graph_exec));
       c->graph_exec = nullptr;
     }
+    c->graph_stale = false;
     hipGraph_t graph = nullptr;
     DBG("capture: begin (batch %d)", B);
     HIP_TRY(c, hipStreamBeginCapture(c->s_attn, hipStreamCaptureModeThreadLocal));
@@ -894,6 +932,16 @@ int decode_fused_step(ladder_ctx* c, const void* x_in, void* x_out) {
   return fence_out(c);
 }
 
+// A kernel of an earlier call has raised the error word (its bounded in-launch wait gave up, so that call's
+// output is not valid): reported once, by the next forward call, which does nothing else.
+int check_device_error(ladder_ctx* c) {
+  if (c->err_word && *(volatile unsigned*)c->err_word != 0u) {
+    *(volatile unsigned*)c->err_word = 0u;
+    return fail(c, LADDER_E_HIP, "a kernel of an earlier decode step gave up its bounded in-launch wait (attention -> output projection): that step's output is invalid");
+  }
+  return LADDER_OK;
+}
+
 int all_loaded(ladder_ctx* c) {
   for (auto& L : c->store)
     if (!L.loaded) return fail(c, LADDER_E_STATE, "a (layer, shard) has not been given to ladder_load_layer");
@@ -907,13 +955,16 @@ int all_loaded(ladder_ctx* c) {
 // =================================================================================================
 extern "C" {
 
-int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
+// ladder_init, or (dry) the same walk through the memory plan without a single HIP call: then *out receives a
+// context that owns nothing but its byte counts
+static int init_impl(const ladder_config* cfg, void* hip_stream, ladder_ctx** out, bool dry) {
   if (out) *out = nullptr;
   if (!cfg || !out) return fail(nullptr, LADDER_E_ARG, "null argument");
   std::string why;
   int rc = check_config(cfg, why);
   if (rc) return fail(nullptr, rc, why);
   ladder_ctx* c = new ladder_ctx();
+  c->dry = dry;
   c->cfg = *cfg;
   const ladder_config& g = c->cfg;
   c->bf16 = g.dtype == LADDER_BF16;
@@ -928,7 +979,8 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
 
   auto bail = [&](int code) {
     std::string msg = c->err;
-    ladder_free(c);
+    if (c->dry) delete c;
+    else ladder_free(c);
     g_init_error = msg;
     return code;
   };
@@ -939,6 +991,7 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
   } while (0)
 #define INIT_HIP(expr)                                                                       \
   do {                                                                                       \
+    if (c->dry) break;                                                                       \
     hipError_t e_ = (expr);                                                                  \
     if (e_ != hipSuccess) {                                                                  \
       c->err = std::string(#expr) + ": " + hipGetErrorString(e_);                            \
@@ -950,7 +1003,7 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
     int dev_id = 0, khz = 0;
     INIT_HIP(hipGetDevice(&dev_id));
     c->device = dev_id;
-    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev_id) == hipSuccess && khz > 0) c->wall_khz = khz;
+    if (!c->dry && hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev_id) == hipSuccess && khz > 0) c->wall_khz = khz;
     INIT_HIP(resolve_static_scratch(dev_id, &c->static_scratch));
   }
   INIT_HIP(hipStreamCreateWithFlags(&c->s_attn, hipStreamNonBlocking));
@@ -981,6 +1034,7 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
   }
   char* wbase = nullptr;
   INIT_TRY(dev_alloc(c, (void**)&wbase, per_shard * c->store.size(), false));
+  c->weight_bytes = c->dev_bytes;
   char* gbase = nullptr;
   INIT_TRY(dev_alloc(c, (void**)&gbase, (size_t)g.n_layers * 2 * H * esz, false));
   // KV cache: K rows [B][nkv][s_cap][d]; V transposed [B][nkv][d][s_cap]; zero-filled so that no
@@ -1016,7 +1070,7 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
   {
     const int half = d / 2;
     std::vector<float> ct((size_t)c->s_cap * half), st((size_t)c->s_cap * half);
-    for (int j = 0; j < half; ++j) {
+    for (int j = 0; j < half && !c->dry; ++j) {
       const double inv_freq = pow((double)g.rope_theta, -2.0 * j / (double)d);
       for (int p = 0; p < c->s_cap; ++p) {
         const double ang = (double)p * inv_freq;
@@ -1063,8 +1117,17 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
       if (n_cu > 0) c->n_cu = n_cu;
       for (int i = 0; i < 3; ++i) {
         INIT_TRY(dev_alloc(c, (void**)&c->x_ring[i], (size_t)16 * H * 4, true));
-        INIT_TRY(dev_alloc(c, (void**)&c->xh_ring[i], (size_t)16 * H * 2, true));
+        for (int k = 0; k < 2; ++k) INIT_TRY(dev_alloc(c, (void**)&c->xop_ring[i][k], (size_t)32 * H * 2, true));
+        INIT_TRY(dev_alloc(c, (void**)&c->ssq_ring[i], (size_t)(H / 16) * 16 * 4, true));
       }
+      INIT_TRY(dev_alloc(c, (void**)&c->f_q, (size_t)32 * nq * d * 2, true));
+      INIT_TRY(dev_alloc(c, (void**)&c->f_o, (size_t)32 * nq * d * 2, true));
+      INIT_TRY(dev_alloc(c, (void**)&c->f_act, (size_t)32 * I * 2, true));
+      // the word a kernel raises when its bounded wait gives up: host memory that the device can write, so that
+      // the host can look at it at the start of every call without synchronising anything
+      INIT_HIP(hipHostMalloc((void**)&c->err_word, 64, hipHostMallocMapped));
+      if (c->err_word) *c->err_word = 0u;
+      INIT_HIP(hipHostGetDevicePointer((void**)&c->err_word_dev, c->err_word, 0));
       INIT_TRY(dev_alloc(c, (void**)&c->att_done, (size_t)g.n_layers * 4, true));
       // arrival tickets start at zero and are put back to zero by the last arrival of every launch
       INIT_TRY(dev_alloc(c, (void**)&c->tk_att, (size_t)g.max_batch * nkv * 4, true));
@@ -1073,6 +1136,34 @@ int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) {
 #undef INIT_TRY
 #undef INIT_HIP
   *out = c;
+  return LADDER_OK;
+}
+
+int ladder_init(const ladder_config* cfg, void* hip_stream, ladder_ctx** out) { return init_impl(cfg, hip_stream, out, false); }
+
+size_t ladder_workspace_bytes(const ladder_config* cfg) {
+  ladder_ctx* c = nullptr;
+  if (init_impl(cfg, nullptr, &c, true) != LADDER_OK || !c) return 0;
+  const size_t bytes = c->dev_bytes - c->weight_bytes;
+  delete c;
+  return bytes;
+}
+
+size_t ladder_weight_bytes(const ladder_config* cfg) {
+  ladder_ctx* c = nullptr;
+  if (init_impl(cfg, nullptr, &c, true) != LADDER_OK || !c) return 0;
+  const size_t bytes = c->weight_bytes;
+  delete c;
+  return bytes;
+}
+
+int ladder_set_wait_limit(ladder_ctx* c, int32_t max_polls, int32_t target_bias) {
+  if (!c) return LADDER_E_ARG;
+  if (max_polls < 1 || max_polls > (1 << 24) || target_bias < 0) return fail(c, LADDER_E_ARG, "max_polls must be in 1 .. 2^24, target_bias >= 0");
+  c->wait_spins = max_polls;
+  c->wait_bias = (unsigned)target_bias;
+  c->fused_plan.clear();     // the launch list carries both: it is built again at the next step
+  c->graph_stale = true;
   return LADDER_OK;
 }
 
@@ -1094,17 +1185,14 @@ int ladder_load_layer(ladder_ctx* c, int32_t layer, int32_t shard, const ladder_
     c->gains_loaded[layer] = 1;
   }
   if (c->fast) {
-    // the RMSNorm gains are folded into the rows of the projections that read the normed stream
-    // (every shard's call must therefore carry the gains; they are replicated across ranks)
-    if (!w->attn_norm || !w->mlp_norm) return fail(c, LADDER_E_ARG, "null gain pointer");
-    const bf16_t *ga = (const bf16_t*)w->attn_norm, *gm = (const bf16_t*)w->mlp_norm;
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wq, L.pqkv, H, nq * d, c->nqkv, 0, 0, ga, s));
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wk, L.pqkv, H, nkv * d, c->nqkv, nq * d, 0, ga, s));
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wv, L.pqkv, H, nkv * d, c->nqkv, (nq + nkv) * d, 0, ga, s));
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wo, L.po, nq * d, H, H, 0, 0, nullptr, s));
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_gate, L.pgu, H, I, 2 * I, 0, 1, gm, s));
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_up, L.pgu, H, I, 2 * I, 0, 2, gm, s));
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_down, L.pd, I, H, H, 0, 0, nullptr, s));
+    // a pure re-ordering: the packed tiles hold the stored bf16 values bit for bit
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wq, L.pqkv, H, nq * d, c->nqkv, 0, 0, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wk, L.pqkv, H, nkv * d, c->nqkv, nq * d, 0, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wv, L.pqkv, H, nkv * d, c->nqkv, (nq + nkv) * d, 0, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->wo, L.po, nq * d, H, H, 0, 0, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_gate, L.pgu, H, I, 2 * I, 0, 1, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_up, L.pgu, H, I, 2 * I, 0, 2, s));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w->w_down, L.pd, I, H, H, 0, 0, s));
   } else {
     HIP_TRY(c, hipMemcpyAsync(L.wq, w->wq, (size_t)H * nq * d * esz, hipMemcpyDeviceToDevice, s));
     HIP_TRY(c, hipMemcpyAsync(L.wk, w->wk, (size_t)H * nkv * d * esz, hipMemcpyDeviceToDevice, s));
@@ -1121,6 +1209,9 @@ int ladder_load_layer(ladder_ctx* c, int32_t layer, int32_t shard, const ladder_
 int ladder_set_peer_partials(ladder_ctx* c, const void* peers) {
   if (!c) return LADDER_E_ARG;
   if (peers && c->n_peers == 0) return fail(c, LADDER_E_SHAPE, "this configuration has no synthetic peers");
+  // a captured decode step carries the peers' addresses in its kernel arguments: it is captured again at the
+  // next step (decode_graph_step) when they change
+  if ((const char*)peers != c->peers) c->graph_stale = true;
   c->peers = (const char*)peers;
   return LADDER_OK;
 }
@@ -1157,7 +1248,9 @@ int ladder_prefill(ladder_ctx* c, const void* x_in, int32_t B, int32_t T, void* 
   if (T > g.max_seq) return fail(c, LADDER_E_OVERFLOW, "T exceeds max_seq");
   if (T > g.max_tokens) return fail(c, LADDER_E_SHAPE, "T exceeds max_tokens");
   if (c->peers && B * T > g.peer_rows) return fail(c, LADDER_E_SHAPE, "B*T exceeds peer_rows");
-  int rc = all_loaded(c);
+  int rc = check_device_error(c);
+  if (rc) return rc;
+  rc = all_loaded(c);
   if (rc) return rc;
   rc = forward(c, x_in, B, T, 0, x_out);
   if (rc) return rc;
@@ -1175,7 +1268,9 @@ int ladder_decode_step(ladder_ctx* c, const void* x_in, void* x_out) {
   if (c->batch <= 0 || c->pos <= 0) return fail(c, LADDER_E_STATE, "decode before prefill / load_kv");
   if (c->pos + 1 > c->cfg.max_seq) return fail(c, LADDER_E_OVERFLOW, "KV cache is full");
   if (c->peers && c->batch > c->cfg.peer_rows) return fail(c, LADDER_E_SHAPE, "batch exceeds peer_rows");
-  int rc = all_loaded(c);
+  int rc = check_device_error(c);
+  if (rc) return rc;
+  rc = all_loaded(c);
   if (rc) return rc;
   if (c->fast && c->cfg.decode_graph && !c->prof) {
     rc = decode_graph_step(c, x_in, x_out);
@@ -1216,6 +1311,7 @@ void ladder_free(ladder_ctx* c) {
     if (c->ev_red[i]) (void)hipEventDestroy(c->ev_red[i]);
   }
   for (void* p : c->allocs) (void)hipFree(p);
+  if (c->err_word) (void)hipHostFree(c->err_word);
   delete c;
 }
 
@@ -1265,15 +1361,14 @@ int ladder_load_head(ladder_ctx* c, const void* table, const void* final_norm, c
   if ((rc = dev_alloc(c, (void**)&c->head_logits, (size_t)g.max_batch * vocab_local * 4, false))) return rc;
   HIP_TRY(c, hipMemcpyAsync(c->head_table, table, (size_t)vocab * H * esz, hipMemcpyDeviceToDevice, c->main));
   c->head_fast = c->fast && vocab_local % 16 == 0;
-  if (c->head_fast) {   // packed tiles with the final norm's gain folded into the rows, as for the block projections
+  if ((rc = dev_alloc(c, (void**)&c->head_gain, (size_t)H * esz, false))) return rc;
+  HIP_TRY(c, hipMemcpyAsync(c->head_gain, final_norm, (size_t)H * esz, hipMemcpyDeviceToDevice, c->main));
+  if (c->head_fast) {   // packed tiles, as for the block projections
     if ((rc = dev_alloc(c, (void**)&c->head_wp, (size_t)H * vocab_local * 2, false))) return rc;
-    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w_lm, c->head_wp, H, vocab_local, vocab_local, 0, 0,
-                                   (const bf16_t*)final_norm, c->main));
+    HIP_TRY(c, launch_repack_tiles((const bf16_t*)w_lm, c->head_wp, H, vocab_local, vocab_local, 0, 0, c->main));
   } else {
     if ((rc = dev_alloc(c, (void**)&c->head_w, (size_t)H * vocab_local * esz, false))) return rc;
-    if ((rc = dev_alloc(c, (void**)&c->head_gain, (size_t)H * esz, false))) return rc;
     HIP_TRY(c, hipMemcpyAsync(c->head_w, w_lm, (size_t)H * vocab_local * esz, hipMemcpyDeviceToDevice, c->main));
-    HIP_TRY(c, hipMemcpyAsync(c->head_gain, final_norm, (size_t)H * esz, hipMemcpyDeviceToDevice, c->main));
   }
   c->vocab = vocab;
   c->vocab_local = vocab_local;
@@ -1295,7 +1390,7 @@ static int head_body(ladder_ctx* c, const float* x, int rows, char* y, float* lo
   const ladder_config& g = c->cfg;
   const int H = g.hidden, V = c->vocab_local;
   hipStream_t s = c->main;
-  HIP_TRY(c, launch_head_norm(x, c->head_fast ? nullptr : c->head_gain, y, rows, H, g.rms_eps, c->bf16, s));
+  HIP_TRY(c, launch_head_norm(x, c->head_gain, y, rows, H, g.rms_eps, c->bf16, s));
   if (!c->head_fast) {
     HIP_TRY(c, launch_gemm_generic(y, c->head_w, logits, rows, V, H, V, 0, c->bf16, s));
   } else if (rows <= 64) {

@@ -13,6 +13,13 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 #define GEMM_WAVES_LARGE 2
 #endif
 
+__device__ __forceinline__ void unpack8(const uint4 v, float (&f)[8]) {
+  f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+  f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+  f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+  f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+}
+
 __device__ __forceinline__ f32x4_t mfma16(const uint4 a, const uint4 b, const f32x4_t c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
                                                  0, 0, 0);
@@ -102,13 +109,18 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x4_t (&acc)[
         if (ok) {
           *reinterpret_cast<float4*>(a.x_res + off) = make_float4(v4[0], v4[1], v4[2], v4[3]);
           if (a.x_copy) *reinterpret_cast<float4*>(a.x_copy + off) = make_float4(v4[0], v4[1], v4[2], v4[3]);
-          if (a.xh_a) {
+          // the rows as the modules that read them want them: times their norm's gain (fp32 product, one rounding)
+          auto store_gained = [&](bf16_t* dst, const bf16_t* gain) {
+            const uint2 gk = *reinterpret_cast<const uint2*>(gain + (nt0 + j) * 16 + 4 * q);
+            const float g4[4] = {__uint_as_float(gk.x << 16), __uint_as_float(gk.x & 0xFFFF0000u),
+                                 __uint_as_float(gk.y << 16), __uint_as_float(gk.y & 0xFFFF0000u)};
             uint2 pk;
-            pk.x = (uint32_t)f32_to_bf16(v4[0]) | ((uint32_t)f32_to_bf16(v4[1]) << 16);
-            pk.y = (uint32_t)f32_to_bf16(v4[2]) | ((uint32_t)f32_to_bf16(v4[3]) << 16);
-            *reinterpret_cast<uint2*>(a.xh_a + off) = pk;
-            if (a.xh_b) *reinterpret_cast<uint2*>(a.xh_b + off) = pk;
-          }
+            pk.x = (uint32_t)f32_to_bf16(v4[0] * g4[0]) | ((uint32_t)f32_to_bf16(v4[1] * g4[1]) << 16);
+            pk.y = (uint32_t)f32_to_bf16(v4[2] * g4[2]) | ((uint32_t)f32_to_bf16(v4[3] * g4[3]) << 16);
+            *reinterpret_cast<uint2*>(dst + off) = pk;
+          };
+          if (a.xh_a) store_gained(a.xh_a, a.gain_a);
+          if (a.xh_b) store_gained(a.xh_b, a.gain_b);
         }
         ss += v4[0] * v4[0] + v4[1] * v4[1] + v4[2] * v4[2] + v4[3] * v4[3];
       }
@@ -390,6 +402,14 @@ __device__ __forceinline__ void gemm2_residual_epilogue(const GemmArgs& a, f32x4
   const bool col_ok = n < a.N;               // (N is a multiple of 16)
   const int nc = col_ok ? n : 0;
   constexpr int PB = 3, RB = 2;              // peers and row pairs requested at once
+  // the gains of the modules that read the new rows, for this lane's eight columns (the same for every row)
+  float ga8[8], gb8[8];
+  {
+    const uint4 za = a.xh_a ? *reinterpret_cast<const uint4*>(a.gain_a + nc) : make_uint4(0, 0, 0, 0);
+    const uint4 zb = a.xh_b ? *reinterpret_cast<const uint4*>(a.gain_b + nc) : make_uint4(0, 0, 0, 0);
+    unpack8(za, ga8);
+    unpack8(zb, gb8);
+  }
 #pragma unroll
   for (int pass = 0; pass < 4; ++pass) {     // row blocks mt = 2 pass, 2 pass + 1 of both halves of the tile
     if (pass > 0) __syncthreads();           // the previous pass has been read
@@ -445,15 +465,17 @@ __device__ __forceinline__ void gemm2_residual_epilogue(const GemmArgs& a, f32x4
             *reinterpret_cast<float4*>(a.x_copy + off[r]) = make_float4(v8[0], v8[1], v8[2], v8[3]);
             *reinterpret_cast<float4*>(a.x_copy + off[r] + 4) = make_float4(v8[4], v8[5], v8[6], v8[7]);
           }
-          if (a.xh_a) {
+          // the rows as the modules that read them want them: times their norm's gain (fp32 product, one rounding)
+          auto store_gained = [&](bf16_t* dst, const float (&g8)[8]) {
             uint4 u;
-            u.x = (uint32_t)f32_to_bf16(v8[0]) | ((uint32_t)f32_to_bf16(v8[1]) << 16);
-            u.y = (uint32_t)f32_to_bf16(v8[2]) | ((uint32_t)f32_to_bf16(v8[3]) << 16);
-            u.z = (uint32_t)f32_to_bf16(v8[4]) | ((uint32_t)f32_to_bf16(v8[5]) << 16);
-            u.w = (uint32_t)f32_to_bf16(v8[6]) | ((uint32_t)f32_to_bf16(v8[7]) << 16);
-            *reinterpret_cast<uint4*>(a.xh_a + off[r]) = u;
-            if (a.xh_b) *reinterpret_cast<uint4*>(a.xh_b + off[r]) = u;
-          }
+            u.x = (uint32_t)f32_to_bf16(v8[0] * g8[0]) | ((uint32_t)f32_to_bf16(v8[1] * g8[1]) << 16);
+            u.y = (uint32_t)f32_to_bf16(v8[2] * g8[2]) | ((uint32_t)f32_to_bf16(v8[3] * g8[3]) << 16);
+            u.z = (uint32_t)f32_to_bf16(v8[4] * g8[4]) | ((uint32_t)f32_to_bf16(v8[5] * g8[5]) << 16);
+            u.w = (uint32_t)f32_to_bf16(v8[6] * g8[6]) | ((uint32_t)f32_to_bf16(v8[7] * g8[7]) << 16);
+            *reinterpret_cast<uint4*>(dst + off[r]) = u;
+          };
+          if (a.xh_a) store_gained(a.xh_a, ga8);
+          if (a.xh_b) store_gained(a.xh_b, gb8);
         }
         if (a.ssq_part) {   // (uniform)
           float ss = 0.f;
@@ -659,7 +681,8 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
   if (a.epilogue == 0 && !a.out) return hipErrorInvalidValue;
   if (a.epilogue == 1 && !a.act) return hipErrorInvalidValue;
   if (a.epilogue == 2 && (!a.q_out || !a.cache_k || !a.cache_v || !a.cos_tab || !a.sin_tab || a.T <= 0 || a.d <= 0)) return hipErrorInvalidValue;
-  if (a.epilogue == 3 && (!a.x_res || a.n_peers < 0 || (a.n_peers > 0 && !a.peers) || (a.xh_b && !a.xh_a) || (a.ssq_part && !a.xh_a)))
+  if (a.epilogue == 3 && (!a.x_res || a.n_peers < 0 || (a.n_peers > 0 && !a.peers) || (a.xh_b && !a.xh_a) || (a.ssq_part && !a.xh_a) ||
+                          (a.xh_a && !a.gain_a) || (a.xh_b && !a.gain_b)))
     return hipErrorInvalidValue;
   if (gemm_takes_lds_kernel(a)) return launch_gemm_lds(a, s);
 #ifndef GEMM_NO_SMALL_TILE_RULE

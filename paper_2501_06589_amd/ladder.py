@@ -48,6 +48,9 @@ EXPORTS = {
     "ladder_last_error": (C.c_char_p, [C.c_void_p]),
     "ladder_position": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "ladder_device_bytes": (C.c_size_t, [C.c_void_p]),
+    "ladder_workspace_bytes": (C.c_size_t, [C.POINTER(ladder_config)]),
+    "ladder_weight_bytes": (C.c_size_t, [C.POINTER(ladder_config)]),
+    "ladder_set_wait_limit": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
     "ladder_profile_enable": (C.c_int, [C.c_void_p, C.c_int32]),
     "ladder_profile_read": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
     "ladder_profile_reset": (C.c_int, [C.c_void_p]),
@@ -74,6 +77,16 @@ def lib() -> C.CDLL:
             fn.restype, fn.argtypes = res, args
         _lib = handle
     return _lib
+
+
+def workspace_bytes(cfg: ladder_config) -> int:
+    """Device bytes ladder_init(cfg) allocates apart from the weight store (host only)."""
+    return int(lib().ladder_workspace_bytes(C.byref(cfg)))
+
+
+def weight_bytes(cfg: ladder_config) -> int:
+    """Device bytes of the weight store of ladder_init(cfg) (host only)."""
+    return int(lib().ladder_weight_bytes(C.byref(cfg)))
 
 
 class LadderError(RuntimeError):
@@ -239,6 +252,9 @@ class Ladder:
 
     def device_bytes(self) -> int:
         return int(self._lib.ladder_device_bytes(self._h))
+
+    def set_wait_limit(self, max_polls: int, target_bias: int):
+        self._check(self._lib.ladder_set_wait_limit(self._h, max_polls, target_bias))
 
     def profile_enable(self, on: bool):
         self._check(self._lib.ladder_profile_enable(self._h, 1 if on else 0))

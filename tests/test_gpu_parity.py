@@ -294,14 +294,13 @@ def test_full_width_70b_r8_decode_one_layer_strict(harness):
     assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
 
 
-def test_full_size_70b_r8_decode_all_80_layers_against_oracle(harness):
+def test_full_size_70b_r8_decode_all_80_layers_strict(harness):
     """The headline decode workload at full size and depth, in the launch configuration of the default
-    bench run (161 fused launches per step); two decode steps, every output element against the oracle,
-    within the per-module error budget."""
+    bench run (161 fused launches per step); two decode steps, every output element against the oracle at
+    the stated tolerance: max |gpu - oracle| <= 2e-2 RMS over all 80 layers."""
     w = inputs.WORKLOADS["70b_r8_decode"]
     res = harness.run_case(w, decode_steps=2, kv_preload=w.kv_preload, gen_device="cuda:0", max_seq=BENCH_MAX_SEQ)
-    assert len(res.errs) == 2
-    deep_stack_check(res, w.n_layers)
+    assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
 
 
 def test_full_size_70b_r8_decode_schedules_agree(harness):
