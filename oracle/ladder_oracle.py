@@ -279,25 +279,25 @@ def forward_eq2(emb: np.ndarray, layers: Sequence[Layer], cfg: OracleConfig,
 
 def forward_alg1(emb: np.ndarray, layers: Sequence[Layer], cfg: OracleConfig,
                  state: Optional[State] = None, peers: Optional[np.ndarray] = None) -> np.ndarray:
-    """Variable-passing form of Algorithm 1 (ladder wiring only): the layer function
-    receives and returns (residual, attn_out, mlp_out); the handles' wait() is the
-    point where the reduced value is read.  Initial module outputs are zero and the
-    two outstanding outputs are added after the last layer."""
-    residual = np.asarray(emb, dtype=F64).copy()
-    attn_out = np.zeros_like(residual)
-    mlp_out = np.zeros_like(residual)
+    """Variable-passing form (the shape of Algorithm 1; ladder wiring only).  Where `forward_eq2` keeps the
+    whole history x_0 .. x_m and indexes it, this form carries what a layer hands to the next one: the stream as
+    far as it has been completed, and the module outputs that have been computed but not yet added to it (at
+    most two: the paper's attention and MLP outputs in flight).  A module's output is added only when the module
+    after next needs the stream, which is where the asynchronous reduction of Algorithm 1 has to have finished.
+    Before the first module nothing is outstanding (zero outputs), and after the last one the two outstanding
+    outputs are added, oldest first."""
+    stream = np.asarray(emb, dtype=F64).copy()     # x_{m-2} when module m starts (x_0 for modules 1 and 2)
+    outstanding: List[np.ndarray] = []             # outputs of modules m-2 and m-1, oldest first
     s0 = state.pos if state is not None else 0
-    for li in range(cfg.n_layers):
-        m_attn, m_mlp = 2 * li + 1, 2 * li + 2
-        # attn_work.wait(); residual += attn_out
-        residual = residual + attn_out
-        attn_out = all_reduce(m_attn, module_partials(m_attn, residual, layers, cfg, state, s0), peers, cfg)
-        # mlp_work.wait(); residual += mlp_out
-        residual = residual + mlp_out
-        mlp_out = all_reduce(m_mlp, module_partials(m_mlp, residual, layers, cfg, state, s0), peers, cfg)
+    for m in range(1, 2 * cfg.n_layers + 1):
+        if len(outstanding) == 2:                  # module m reads x_{m-2} = x_{m-3} + h_{m-2}
+            stream = stream + outstanding.pop(0)
+        outstanding.append(all_reduce(m, module_partials(m, stream, layers, cfg, state, s0), peers, cfg))
     if state is not None:
-        state.pos = s0 + residual.shape[1]
-    return residual + attn_out + mlp_out
+        state.pos = s0 + stream.shape[1]
+    for h in outstanding:
+        stream = stream + h
+    return stream
 
 
 # ---------------------------------------------------------------------------

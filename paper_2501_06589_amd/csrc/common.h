@@ -170,7 +170,7 @@ struct GemmArgs {
   const float* cos_tab;    // [max_seq][d/2]
   const float* sin_tab;
   int T, pos0, nq, nkv, d, max_seq;
-  // epilogue 3: the residual update "wait(); residual += out" (Algorithm 1) with the AllReduce written as a sum
+  // epilogue 3: the residual update of Algorithm 1 (a module's reduced output joins the stream) with the AllReduce written as a sum
   // over rank partial sums (Eq. 2): x_res[m][n] = x_res[m][n] + product + peers_0[m][n] + peers_1[m][n] + ...
   // (in this order, in place, row stride N), an optional f32 copy, for each module that reads the new rows a bf16
   // copy of them times the gain of that module's RMSNorm (the product in fp32, one rounding), and the rows' sums

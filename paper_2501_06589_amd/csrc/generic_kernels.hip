@@ -26,7 +26,7 @@ template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, const floa
 }
 
 // ------------------------------------------------------------------------------------------------
-// Reduce + residual add + RMSNorm: the local image of "wait(); residual += out; Norm(residual)"
+// Reduce + residual add + RMSNorm: the local image of the residual update and the norm that follows it
 // (Algorithm 1) with the AllReduce written as a sum over rank partial sums (Eq. 2).
 // One workgroup per row; the summation order is fixed: x, parts 0.., peers 0.. .
 // ------------------------------------------------------------------------------------------------

@@ -294,7 +294,7 @@ int consumers_of(const ladder_ctx* c, int m, int out[2]) {
 }
 
 // Wide calls (more than 64 rows) of the packed-weight path with one real shard: the residual update of module m
-// ("wait(); residual += out", Algorithm 1, the AllReduce as a sum over rank partial sums, Eq. 2) is the
+// (Algorithm 1: the module's reduced output joins the stream; the AllReduce as a sum over rank partial sums, Eq. 2) is the
 // epilogue of the module's last GEMM instead of a kernel of its own, which saves a round trip of the fp32
 // product through memory.  The epilogue leaves the new rows, times the reading module's gain, as bf16 for the
 // modules that read x_m; their 1/rms (from the sums of squares the epilogue also leaves) scales the consumer's
