@@ -11,10 +11,14 @@ synthetic KV cache of 1024 positions, 7 synthetic peer partial sums per module. 
 synthetic and resident in HBM before the timed region.
 mode prefill: a step = one prefill call (workload 70b_r4_prefill: 16 x 2048 tokens).
 
+With no --mode the default run is the whole metric: the decode workload (REPS timed regions of K steps each,
+every region over the same cache positions; the median is reported), then, on a fresh context, the prefill
+workload 70b_r4_prefill (median of 3 calls), reported under "prefill" in the same line.
+
 Prints ONE JSON line: the contract fields plus "roofline" (dominant kernel: HIP events attached to every
 dispatch in an instrumented pass right after the timed one; "traffic" = HBM bytes per launch counted by
-rocprofv3, read from the committed summary under profiles/) and "cpu_baseline" (the CPU oracle timed on
-a bounded sample of the same workload).
+rocprofv3, read from the committed summary under profiles/, with its source) and "cpu_baseline" (the CPU
+oracle timed on a bounded sample of the same workload).
 """
 import argparse
 import json
@@ -52,15 +56,12 @@ def build_context(w, device, extra_seq, peers_rows, **override):
     return ctx
 
 
-def read_profiled_traffic(kernel, workload):
-    """HBM bytes per launch of the dominant kernel as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by
-    a known-size copy): the figure of the committed summary profiles/<kernel>_hbm_traffic_<workload>.md, which
-    states it on a line 'traffic_bytes_per_launch: <number>'.  None if there is no such summary."""
+def read_profile_value(path, key):
+    """'<key>: <number>' line of a committed profile summary, or None."""
     import re
-    path = os.path.join(ROOT, "profiles", f"{kernel}_hbm_traffic_{workload}.md")
     if not os.path.exists(path):
         return None
-    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+    m = re.search(r"^" + re.escape(key) + r":\s*([0-9.eE+-]+)", open(path).read(), re.M)
     return float(m.group(1)) if m else None
 
 
@@ -125,29 +126,45 @@ def run_decode(args):
     dev = "cuda:0"
     prof_steps = 8
     total_steps = args.warmup + args.steps + prof_steps
+    reps = max(1, args.reps)
     # the peer tensor must hold as many rows per set as the configuration announces (peer_rows)
     ctx = build_context(w, dev, total_steps, w.batch * max(w.prefill, 1), max_tokens=max(w.prefill, 1),
                         decode_graph=1 if args.graph else 0, overlap_modules=0 if args.no_overlap else 1,
                         decode_fused=0 if args.no_fused else 1, reduce_delay_us=args.reduce_delay_us,
                         wiring={"ladder": ladder.LADDER_WIRING_LADDER, "standard": ladder.LADDER_WIRING_STANDARD,
                                 "parallel": ladder.LADDER_WIRING_PARALLEL}[args.wiring])
-    if w.kv_preload:
-        for i in range(w.n_layers):
-            for r in range(w.n_real_shards):
-                k, v = inputs.kv_cache(w, i, r, w.batch, w.kv_preload, dev)
-                ctx.load_kv(i, r, k, v)
-    else:
-        ctx.prefill(inputs.embeddings(w, w.batch, w.prefill, inputs.SEED_PREFILL, dev))
+    # the cache as it stands before the first decode step: a synthetic one (kept, so that every timed region can
+    # start from the same positions) or the one a prefill leaves
+    kv = [[inputs.kv_cache(w, i, r, w.batch, w.kv_preload, dev) for r in range(w.n_real_shards)]
+          for i in range(w.n_layers)] if w.kv_preload else None
+    emb_prefill = None if w.kv_preload else inputs.embeddings(w, w.batch, w.prefill, inputs.SEED_PREFILL, dev)
+
+    def reset_cache():
+        if kv is not None:
+            for i in range(w.n_layers):
+                for r in range(w.n_real_shards):
+                    ctx.load_kv(i, r, kv[i][r][0], kv[i][r][1])
+        else:
+            ctx.prefill(emb_prefill)
+
+    reset_cache()
     xs = torch.stack([inputs.embeddings(w, w.batch, 1, inputs.SEED_DECODE0 + i, dev)[:, 0] for i in range(total_steps)])
     out = torch.empty((w.batch, w.hidden), dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
     log(f"[bench] context ready: {ctx.device_bytes() / 2**30:.2f} GiB on device")
-    if args.copy_calibration:
+    copy_gbps = None
+    if args.copy_calibration or not args.no_ceiling:
+        # plain copy kernel, 1 GiB read + 1 GiB written per launch: the known-size dispatch that scales rocprofv3's
+        # FETCH_SIZE / WRITE_SIZE counters, and a measured ceiling for streaming kernels on this machine
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
-        for _ in range(4):
-            ctx.calibration_copy(dst, src)    # calibration_copy_kernel: reads 1 GiB, writes 1 GiB
+        ctx.calibration_copy(dst, src)
         torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(4):
+            ctx.calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        copy_gbps = 4 * 2 * src.numel() * 4 / (time.perf_counter() - t0) / 1e9
         del src, dst
     head_vocab, toks = None, None
     if args.head:
@@ -166,19 +183,25 @@ def run_decode(args):
         else:
             ctx.decode_step(xs[i], out)
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    pos_start = ctx.position()[0]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    pos_end = ctx.position()[0]
-    assert torch.isfinite(out).all()
-    ms_per_step = dt * 1e3 / args.steps
-    tokens_per_s = w.batch * args.steps / dt
+    # reps timed regions of exactly K steps, each after W untimed warm-up steps from the same cache state
+    rep_ms = []
+    pos_start = pos_end = 0
+    for rep in range(reps):
+        if rep:
+            reset_cache()
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
+        pos_start = ctx.position()[0]
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(args.warmup + i)
+        torch.cuda.synchronize()
+        rep_ms.append((time.perf_counter() - t0) * 1e3 / args.steps)
+        pos_end = ctx.position()[0]
+        assert torch.isfinite(out).all()
+    ms_per_step = sorted(rep_ms)[len(rep_ms) // 2]      # the median region
+    tokens_per_s = w.batch / (ms_per_step * 1e-3)
     s_mean = (pos_start + pos_end + 1) / 2.0           # visible positions averaged over the timed steps
     wb, kvb, pb = decode_algorithmic_bytes(w, s_mean)
     step_bytes = wb + kvb + pb
@@ -190,7 +213,8 @@ def run_decode(args):
         ctx.decode_step(xs[args.warmup + args.steps + i], out)
     prof = ctx.profile_read()
     ctx.profile_enable(False)
-    if prof.get("fused_decode", (0, 0.0))[0]:
+    fused = bool(prof.get("fused_decode", (0, 0.0))[0])
+    if fused:
         # fused path: every launch is the same kernel (one or two projections and/or the attention of
         # one layer); algorithmic bytes of a step (weights + visible KV + peers) over its launches
         kernel_name = "fused_decode_kernel (decode: weight-streaming skinny GEMM jobs + split-KV attention job)"
@@ -202,28 +226,44 @@ def run_decode(args):
         gemv_bytes_per_launch = wb / (4 * w.n_layers * w.n_real_shards)   # 4 projections per layer and shard
     avg_ms = ms_gemv / max(n_gemv, 1)
     achieved = gemv_bytes_per_launch / (avg_ms * 1e-3) / 1e9 if n_gemv else 0.0
-    traffic = read_profiled_traffic("fused_decode" if prof.get("fused_decode", (0, 0.0))[0] else "gemv", w.name)
+    kname = "fused_decode" if fused else "gemv"
+    traffic_file = os.path.join("profiles", f"{kname}_hbm_traffic_{w.name}.md")
+    traffic = read_profile_value(os.path.join(ROOT, traffic_file), "traffic_bytes_per_launch")
+    trace_file = os.path.join("profiles", f"{kname}_kernel_{w.name}.md")
+    prof_avg_us = read_profile_value(os.path.join(ROOT, trace_file), "rocprofv3_avg_launch_us")
     roofline = {"bound": "hbm", "kernel": kernel_name,
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": traffic, "algorithmic_bytes_per_launch": gemv_bytes_per_launch,
-                "avg_launch_ms": avg_ms, "launches": n_gemv}
+                "traffic": traffic, "traffic_source": traffic_file if traffic else None,
+                "algorithmic_bytes_per_launch": gemv_bytes_per_launch,
+                "avg_launch_ms": avg_ms, "launches": n_gemv,
+                "duration_source": f"HIP events attached to every dispatch of {prof_steps} steps after the timed regions, "
+                                   "on the stream the kernel is launched on; excludes the ~1.5 us between launches",
+                # the same figures from the committed rocprofv3 kernel trace (a separate run of this command)
+                "rocprofv3": ({"avg_launch_us": prof_avg_us, "frac": gemv_bytes_per_launch / (prof_avg_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                               "source": trace_file} if prof_avg_us else None),
+                # algorithmic bytes of a step over the measured step time, launch gaps included
+                "frac_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS}
     per_class = {k: {"launches": n, "avg_us": (ms / n * 1e3 if n else 0.0), "ms_per_step": ms / prof_steps}
                  for k, (n, ms) in prof.items() if n}
     ctx.free()
-    del ctx
+    del ctx, kv
     torch.cuda.empty_cache()
     cpu = cpu_baseline_decode(w, dev, min(args.cpu_layers, w.n_layers), w.kv_preload or w.prefill) if not args.no_cpu else None
+    whole_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
     return {
         "metric": "decode_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "repetitions": {"n": reps, "ms_per_step": rep_ms, "reported": "median"},
         "config": {"workload": w.name, "n_layers": w.n_layers, "hidden": w.hidden, "n_q_heads": w.n_q_heads,
                    "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "inter": w.inter, "tp_degree": w.tp_degree,
                    "batch": w.batch, "kv_positions": [pos_start, pos_end], "peers": w.n_peers,
                    **({"head_vocab": head_vocab[0], "head_vocab_local": head_vocab[1]} if head_vocab else {})},
         "hbm": {"algorithmic_bytes_per_step": step_bytes, "weights": wb, "kv": kvb, "peers": pb,
-                "achieved_GBps_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9,
-                "frac_of_peak_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                "achieved_GBps_whole_step": whole_gbps,
+                "frac_of_peak_whole_step": whole_gbps / HBM_PEAK_GBS,
+                "measured_copy_GBps": copy_gbps,
+                "frac_of_measured_copy_whole_step": (whole_gbps / copy_gbps) if copy_gbps else None},
         "roofline": roofline, "kernel_classes": per_class, "cpu_baseline": cpu,
     }
 
@@ -246,13 +286,15 @@ def run_prefill(args):
     for _ in range(args.warmup):
         ctx.prefill(x, out)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
+    call_ms = []
+    for _ in range(args.steps):        # every call timed on its own; the median is reported
+        t0 = time.perf_counter()
         ctx.prefill(x, out)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+        torch.cuda.synchronize()
+        call_ms.append((time.perf_counter() - t0) * 1e3)
     assert torch.isfinite(out).all()
-    ms_per_step = dt * 1e3 / args.steps
+    ms_per_step = sorted(call_ms)[len(call_ms) // 2]
+    dt = ms_per_step * 1e-3 * args.steps
     gemm_flops = 2.0 * w.n_layers * w.n_real_shards * w.params_per_layer() * rows
     attn_flops = w.n_layers * w.n_real_shards * w.batch * w.n_q_heads * 4.0 * w.head_dim * (w.prefill * (w.prefill + 1) / 2)
     ctx.profile_enable(True)
@@ -275,6 +317,7 @@ def run_prefill(args):
         "metric": "prefill_tokens_per_s", "value": rows * args.steps / dt, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "repetitions": {"n": args.steps, "ms_per_call": call_ms, "reported": "median"},
         "config": {"workload": w.name, "n_layers": w.n_layers, "hidden": w.hidden, "n_q_heads": w.n_q_heads,
                    "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "inter": w.inter, "tp_degree": w.tp_degree,
                    "batch": w.batch, "prefill_tokens": w.prefill, "peers": w.n_peers},
@@ -290,7 +333,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--mode", choices=["decode", "prefill"], default="decode")
+    ap.add_argument("--mode", choices=["both", "decode", "prefill"], default="both",
+                    help="both (default): the decode workload, then the prefill workload, one JSON line carrying the two "
+                         "halves of the metric; decode / prefill: that half alone (any workload)")
+    ap.add_argument("--reps", type=int, default=3, help="decode: timed regions of --steps steps each (the median is reported)")
+    ap.add_argument("--no-ceiling", action="store_true", help="decode: skip the copy-kernel measurement of the box's streaming rate")
     ap.add_argument("--workload", default=None)
     ap.add_argument("--kv", type=int, default=0, help="override the preloaded cache length of a decode workload")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (1.2b / 8b are quoted at 1, 4, 16)")
@@ -318,11 +365,24 @@ def main():
         print("bench.py measures one GPU: this build has no multi-GPU path (one process, one MI355X); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
-    if args.mode == "decode":
+    if args.mode in ("decode", "both"):
+        both = args.mode == "both" and args.workload in (None, "70b_r8_decode")
         args.workload = args.workload or "70b_r8_decode"
+        steps_given, warmup_given = args.steps, args.warmup
         args.steps = 256 if args.steps is None else args.steps
         args.warmup = 16 if args.warmup is None else args.warmup
         res = run_decode(args)
+        if both:
+            # the other half of the metric: the prefill workload on a fresh context (the decode context has been freed)
+            pa = argparse.Namespace(**vars(args))
+            pa.workload, pa.steps, pa.warmup, pa.batch, pa.layers = "70b_r4_prefill", 3, 1, 0, args.layers
+            pr = run_prefill(pa)
+            res["prefill"] = {"workload": pr["config"]["workload"], "rows": pr["config"]["batch"] * pr["config"]["prefill_tokens"],
+                              "ms": pr["ms_per_step"], "ms_per_call": pr["repetitions"]["ms_per_call"], "tokens_per_s": pr["value"],
+                              "gemm_tflops": pr["roofline"]["achieved"], "gemm_frac": pr["roofline"]["frac"],
+                              "whole_tflops": pr["mfma"]["whole_prefill_TFLOPs"], "whole_frac": pr["mfma"]["frac_of_peak_whole_prefill"],
+                              "peak_tflops": MFMA_BF16_PEAK_TFLOPS, "dtype": "bf16", "kernel_classes": pr["kernel_classes"],
+                              "roofline": pr["roofline"]}
     else:
         args.workload = args.workload or "70b_r4_prefill"
         args.steps = 3 if args.steps is None else args.steps

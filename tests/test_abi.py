@@ -98,3 +98,26 @@ def test_init_without_a_gpu_reports_a_hip_error_or_succeeds(lib):
         lib.ladder_free(h)
     else:
         assert not h and b"hip" in lib.ladder_last_error(None).lower()
+
+
+def test_sizing_calls_need_no_gpu(lib):
+    """ladder_workspace_bytes / ladder_weight_bytes walk the memory plan on the host: positive for a good
+    configuration, 0 (with a text) for a rejected one, growing with the cache capacity, and the weight store of a
+    tile-aligned bf16 configuration is exactly two bytes per projection parameter."""
+    cfg = good_config()
+    ws, wt = ladder.workspace_bytes(cfg), ladder.weight_bytes(cfg)
+    assert ws > 0 and wt > 0
+    assert ladder.workspace_bytes(good_config(max_seq=4000)) > ws
+    assert ladder.weight_bytes(good_config(max_seq=4000)) == wt
+    assert ladder.workspace_bytes(good_config(hidden=252)) == 0 and len(lib.ladder_last_error(None)) > 0
+    assert lib.ladder_workspace_bytes(None) == 0
+    h, nq, nkv, d, inter, n = 512, 8, 2, 64, 448, 3
+    cfg = good_config(n_layers=n, hidden=h, n_q_heads=nq, n_kv_heads=nkv, head_dim=d, inter=inter, tp_degree=1,
+                      n_real_shards=1, dtype=ladder.LADDER_BF16)
+    params = h * (nq + 2 * nkv) * d + nq * d * h + 3 * h * inter
+    assert ladder.weight_bytes(cfg) == n * params * 2
+    # the KV cache dominates the workspace of a long-context configuration: capacity rounded up to 128 positions
+    big = good_config(n_layers=n, hidden=h, n_q_heads=nq, n_kv_heads=nkv, head_dim=d, inter=inter, tp_degree=1,
+                      n_real_shards=1, dtype=ladder.LADDER_BF16, max_batch=4, max_seq=10000, max_tokens=1)
+    kv = n * 2 * 4 * nkv * 10112 * d * 2
+    assert kv <= ladder.workspace_bytes(big) <= kv + (64 << 20)

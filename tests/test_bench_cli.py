@@ -13,9 +13,11 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert "one GPU" in (res.stdout + res.stderr)
 
 
-def test_profiled_traffic_is_read_from_the_committed_summary():
+def test_profiled_figures_are_read_from_the_committed_summaries():
     sys.path.insert(0, ROOT)
     import bench
-    t = bench.read_profiled_traffic("fused_decode", "70b_r8_decode")
+    t = bench.read_profile_value(os.path.join(ROOT, "profiles", "fused_decode_hbm_traffic_70b_r8_decode.md"), "traffic_bytes_per_launch")
     assert t is not None and 90e6 < t < 140e6, t   # bytes per launch; algorithmic: 107.9e6
-    assert bench.read_profiled_traffic("fused_decode", "no_such_workload") is None
+    assert bench.read_profile_value(os.path.join(ROOT, "profiles", "no_such_file.md"), "traffic_bytes_per_launch") is None
+    us = bench.read_profile_value(os.path.join(ROOT, "profiles", "fused_decode_kernel_70b_r8_decode.md"), "rocprofv3_avg_launch_us")
+    assert us is not None and 10 < us < 40, us

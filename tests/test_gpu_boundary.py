@@ -1,0 +1,110 @@
+"""Boundary behaviour that needs the GPU: the sizing calls against a live context, the error word of the bounded
+in-launch wait, and a change of the peer partial sums under a captured decode step."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import from_torch
+from oracle import ladder_oracle as lo
+from paper_2501_06589_amd import inputs, ladder
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+R8_SMALL = inputs.WORKLOADS["70b_r8_decode"].with_(name="r8_small", n_layers=3, hidden=512, inter=448, batch=4,
+                                                   decode_steps=6)
+
+
+@pytest.fixture(scope="module")
+def harness():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_harness
+    return gpu_harness
+
+
+@pytest.mark.parametrize("w", [inputs.WORKLOADS["tiny"], R8_SMALL,
+                               inputs.WORKLOADS["1.2b"].with_(n_layers=2, batch=16, prefill=300),
+                               inputs.WORKLOADS["70b_r4_prefill"].with_(n_layers=1, hidden=1056, inter=1024, n_q_heads=8,
+                                                                        n_kv_heads=2, head_dim=64, batch=3, prefill=70)])
+def test_sizing_calls_agree_with_a_live_context(harness, w):
+    """ladder_workspace_bytes + ladder_weight_bytes (host only, before any allocation) == the device bytes a fresh
+    context reports; the weight store holds every projection parameter once."""
+    cfg = ladder.config_for(w)
+    ws, wt = ladder.workspace_bytes(cfg), ladder.weight_bytes(cfg)
+    assert ws > 0 and wt > 0
+    ctx = ladder.Ladder(cfg)
+    assert ctx.device_bytes() == ws + wt
+    ctx.free()
+    esz = 4 if w.dtype == "fp32" else 2
+    assert wt >= w.n_layers * w.n_real_shards * w.params_per_layer() * esz          # (tiles pad ragged sizes up)
+    assert wt <= 1.1 * w.n_layers * w.n_real_shards * w.params_per_layer() * esz + 4096
+
+
+def test_in_launch_wait_that_gives_up_is_reported_by_the_next_call(harness):
+    """The output projection's bounded wait for its layer's attention workgroups: with a target that no count can
+    reach and four polls, the wait gives up; every kernel still ends normally (the stream synchronises), the step
+    itself returns LADDER_OK (it had only been enqueued), and the NEXT forward call reports LADDER_E_HIP, does
+    nothing, and clears the condition."""
+    w = R8_SMALL
+    tensors = harness.make_tensors(w)
+    peers = inputs.peer_partials(w, w.batch)
+    ctx = harness.build_gpu(w, tensors, peers, max_seq=200)
+    for i in range(w.n_layers):
+        k, v = inputs.kv_cache(w, i, 0, w.batch, 50)
+        ctx.load_kv(i, 0, k.to(DEV), v.to(DEV))
+    x = inputs.embeddings(w, w.batch, 1, inputs.SEED_DECODE0)[:, 0].contiguous().to(DEV)
+    good = ctx.decode_step(x).cpu()
+    assert torch.isfinite(good).all()
+    ctx.set_wait_limit(4, 1000)
+    ctx.decode_step(x)                       # enqueued; its O projections give up their wait
+    torch.cuda.synchronize()                 # every kernel has ended
+    pos = ctx.position()
+    with pytest.raises(ladder.LadderError) as e:
+        ctx.decode_step(x)
+    assert e.value.code == ladder.LADDER_E_HIP and "wait" in str(e.value)
+    assert ctx.position() == pos             # the failing call did nothing
+    ctx.set_wait_limit(1 << 20, 0)
+    out = ctx.decode_step(x)                 # condition cleared, normal operation again
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
+    ctx.decode_step(x)
+    torch.cuda.synchronize()
+    with pytest.raises(ladder.LadderError) as e:
+        ctx.set_wait_limit(0, 0)
+    assert e.value.code == ladder.LADDER_E_ARG
+    ctx.free()
+
+
+@pytest.mark.parametrize("fused", [1, 0])
+def test_peers_changed_under_a_captured_decode_step(harness, fused):
+    """decode_graph = 1: a step replayed from the captured graph, then another set of peer partial sums, then
+    none at all: every step against the oracle with the peers in force at that step (a captured step carries the
+    peers' addresses; it has to be captured again)."""
+    w = R8_SMALL
+    tensors = harness.make_tensors(w)
+    cfg = from_torch.config_from_workload(w)
+    layers = [from_torch.layer_from_tensors(tensors[i]) for i in range(w.n_layers)]
+    state = lo.State.empty(cfg, 1, w.batch, 200)
+    ctx = harness.build_gpu(w, tensors, None, max_seq=200, decode_graph=1, decode_fused=fused)
+    for i in range(w.n_layers):
+        k, v = inputs.kv_cache(w, i, 0, w.batch, 40)
+        ctx.load_kv(i, 0, k.to(DEV), v.to(DEV))
+        from_torch.load_kv(state, i, 0, k, v)
+    state.pos = 40
+    peers_a = inputs.peer_partials(w, w.batch)
+    peers_b = inputs.peer_partials(w, w.batch, seed=inputs.SEED_PEERS + 1)
+    assert not torch.equal(peers_a, peers_b)
+    step = 0
+    for peers in (peers_a, peers_a, peers_b, None, peers_a):
+        dev_peers = peers.to(DEV) if peers is not None else None
+        ctx.set_peer_partials(dev_peers)
+        del dev_peers                                            # the binding keeps the tensor alive
+        e = inputs.embeddings(w, w.batch, 1, inputs.SEED_DECODE0 + step)
+        got = ctx.decode_step(e[:, 0].contiguous().to(DEV)).cpu().double().numpy()
+        want = lo.forward_eq2(from_torch.to_f64(e), layers, cfg, state,
+                              from_torch.to_f64(peers) if peers is not None else None)[:, 0]
+        err = float(np.max(np.abs(got - want)) / np.sqrt(np.mean(want * want)))
+        assert err < 2e-2, (step, err)
+        step += 1
+    ctx.free()
