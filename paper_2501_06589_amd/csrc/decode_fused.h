@@ -8,17 +8,37 @@ enum { EPI_SWIGLU = 1, EPI_RESIDUAL = 2, EPI_QKV_ROPE = 3 };
 
 // Operands of the matrix core on this path are SPLIT: a value v travels as two bf16 numbers, high = bf16(v) and
 // low = bf16(v - high), so that high + low carries 16 significant bits and the products with the (bf16) weights
-// lose nothing that an fp32 operand would keep.  A split matrix is stored as bf16 [32][width]: rows 0..15 the
-// high parts of rows 0..15, rows 16..31 the low parts (FUSED_LOW_ROW).  Up to 8 rows, high and low parts share
-// ONE 16-column MFMA operand (columns 0..7 high, 8..15 low: the columns that a small batch leaves empty) and the
-// two halves of the result are added afterwards; from 9 rows on they are two operands and two MFMAs into the
-// same accumulator.  Decode is bound by the weight stream: the matrix core has the time.
+// lose nothing that an fp32 operand would keep.  Up to 8 rows, high and low parts share ONE 16-column MFMA
+// operand (the columns that a small batch leaves empty) and the two halves of the result are added afterwards;
+// from 9 rows on they are two operands and two MFMAs into the same accumulator.  Decode is bound by the
+// weight stream: the matrix core has the time.
+//
+// Layout of a split operand matrix of M rows (M = the batch of the step) and K columns, in the order the matrix
+// core reads it: the K range is cut into k tiles of 32; a k tile holds S row slots, S = fused_slots(M) = 8, 16
+// or 32: slots 0 .. S/2-1 the high parts of rows 0 .., slots S/2 .. S-1 their low parts; a slot's 32 values
+// are stored as four groups of 8 (16 bytes: one lane's share of the MFMA operand), group-major:
+//     element (row r, part p, column k)  at  (k / 32) * S * 32 + (((k % 32) / 8) * S + r + p * S/2) * 8 + k % 8
+// A wavefront's load of a k tile is then S * 64 contiguous bytes (512 bytes for a batch of 4) instead of 16 bytes
+// from each of 2 M rows that lie K elements apart.  Every such matrix is allocated for S = 32 (K * 64 bytes).
+// The queries of the attention job are the exception: a split matrix in plain rows, bf16 [32][nq * d], rows
+// 0..15 the high parts, rows 16..31 (FUSED_LOW_ROW) the low parts.
 #define FUSED_LOW_ROW 16
+#if defined(__HIPCC__)
+#define FUSED_HD __host__ __device__
+#else
+#define FUSED_HD
+#endif
+static inline FUSED_HD int fused_slots(int M) { return M <= 4 ? 8 : (M <= 8 ? 16 : 32); }
+// element offset of (row, column) of the HIGH part in a split operand matrix with S slots; the low part sits
+// (S / 2) * 8 elements further
+static inline FUSED_HD size_t fused_xop_offset(int S, int row, int col) {
+  return (size_t)(col >> 5) * (size_t)(S * 32) + (size_t)(((((col & 31) >> 3) * S) + row) << 3) + (size_t)(col & 7);
+}
 
 // One skinny GEMM  out[m][n] = sum_k x[m][k] W[k][n], M <= 16, on packed weight tiles; a workgroup
 // owns tn adjacent 16-column tiles and the whole K range.
 struct GemvJob {
-  // x operand: a split bf16 matrix [32][K] (see above).  normed != 0: it is the residual stream times the gain of
+  // x operand: a split bf16 matrix of M rows and K columns (see above).  normed != 0: it is the residual stream times the gain of
   // this module's RMSNorm (both applied in fp32 by the job that wrote the stream, before the split), and this
   // projection scales its output rows by 1/rms (the factor commutes with the product), the rows' sums of squares
   // coming from ssq: f32 [K/16][16], one value per 16-column tile of the stream and row, summed in a fixed order
@@ -41,11 +61,11 @@ struct GemvJob {
   int group0, n_groups;    // this job's workgroups own the tile groups [group0, group0 + n_groups), tn tiles
                            // each; a projection may be cut over two launches
   int epi;
-  // EPI_SWIGLU: act split bf16 [32][N/2]
+  // EPI_SWIGLU: act = split operand matrix of M rows and N/2 columns
   bf16_t* act;
   // EPI_RESIDUAL: x_new = x_old + out + sum_p peers[p]   (the residual update of Algorithm 1 with the
   // all-reduce written as a sum over rank partial sums, Eq. 2); for each of the (at most two) modules that read
-  // x_new: its operand xop = split(x_new * gain of that module's RMSNorm), gain in the storage type [N];
+  // x_new: its operand xop = split(x_new * gain of that module's RMSNorm) (M rows, N columns), gain in the storage type [N];
   // and the sums of squares of x_new per 16-column tile and row, ssq_new f32 [N/16][16]
   const float* x_old;
   float* x_new;
@@ -78,7 +98,7 @@ struct AttnJob {
   const bf16_t* cache_v;   // [B_cap][nkv][d][max_seq]
   float* part_o;           // [B][nkv][n_splits][g][d]   (n_splits > 1 only)
   float* part_ml;          // [B][nkv][n_splits][g][2]
-  bf16_t* o;               // split [32][nq*d]
+  bf16_t* o;               // split operand matrix of B rows and nq*d columns (the output projection's operand)
   unsigned* tickets;       // [B][nkv]
   int B, nq, nkv, max_seq;
   int n_splits, split_len; // split s covers positions [s*split_len, (s+1)*split_len); split_len % 64 == 0
@@ -104,8 +124,9 @@ hipError_t launch_fused_decode(const FusedArgs& fa, int d, int g, hipStream_t s,
 hipError_t fused_decode_prepare(int d, int g);   // once per context, before the first launch
 size_t fused_attn_lds_bytes(int d, int g);
 size_t fused_gemv_lds_bytes();
-// x_0 = the embeddings (emb: bf16 [rows][H]): fp32 rows for the residual chain, the split operands of the (at most
-// two) modules that read x_0 (each times that module's gain), the sums of squares per tile and row; also clears
+// x_0 = the embeddings (emb: bf16 [rows][H]): fp32 rows for the residual chain, the split operand matrices (rows
+// rows, H columns) of the (at most two) modules that read x_0 (each times that module's gain), the sums of
+// squares per tile and row; also clears
 // n_zero words at zero_words (the step's arrival counters).
 struct EmbedArgs {
   const bf16_t* emb;

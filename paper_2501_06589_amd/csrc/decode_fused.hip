@@ -92,6 +92,8 @@ __device__ __forceinline__ float other_half(float v) {
 // operand slices are requested before the job's descriptor (j) has arrived from memory.
 // WIDE = more than 8 rows: the high and the low parts of the operand are two MFMA operands (rows 0..15 each);
 // else one: lanes 0..7 of a row of 16 carry the high parts of rows 0..7, lanes 8..15 their low parts.
+// Operand columns beyond the rows in use hold whatever their slots hold (finite): a column of the operand only
+// reaches its own column of the result, which nobody reads.
 template <int U, int TN, bool COH, bool WIDE>
 __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const bf16_t* xop, int KT, int group0, int M, int lb,
                                          float* smem, unsigned* s_flag) {
@@ -113,13 +115,14 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
 #pragma unroll
   for (int t = 0; t < TN; ++t) acc[t] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
   const u32x4_t* wptr = reinterpret_cast<const u32x4_t*>(wp) + ((size_t)nt0 * KT) * 64 + lane;
-  // operand row of this lane: WIDE: row b of the high parts (the low parts sit FUSED_LOW_ROW rows further);
-  // else row b % 8 of the high (b < 8) or of the low parts
-  const int brow = WIDE ? b : (b & 7);
-  const bool rowok = brow < M;
-  const int rowc = min(brow, M - 1) + ((!WIDE && (b & 8)) ? FUSED_LOW_ROW : 0);
-  const bf16_t* xbp = xop + (size_t)rowc * (KT * 32) + q * 8;
-  const size_t low_off = (size_t)FUSED_LOW_ROW * (KT * 32);
+  // operand slot of this lane (decode_fused.h): WIDE: slot b = row b of the high parts, the low parts 16 slots
+  // further; up to 8 rows: slots 0..7 high, 8..15 low = lane b as it stands; up to 4 rows the k tile has 8 slots,
+  // 0..3 high, 4..7 low, and the lanes in between repeat them
+  const int S = WIDE ? 32 : (M <= 4 ? 8 : 16);
+  const int slot = (!WIDE && M <= 4) ? ((b & 3) | ((b & 8) >> 1)) : b;
+  const int tile_stride = S * 32;                      // elements per k tile
+  const bf16_t* xbp = xop + (q * S + slot) * 8;
+  constexpr int low_off = 16 * 8;                      // WIDE: the low parts' slots
   u32x4_t wa[TN][U], wb[TN][U], xa[U][XP], xb[U][XP];
   auto loadw = [&](u32x4_t (&wv)[TN][U], int kt) {
 #pragma unroll
@@ -135,7 +138,7 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
       const int ktc = min(kt + u, kt1 - 1);
 #pragma unroll
       for (int h = 0; h < XP; ++h) {
-        const bf16_t* src = xbp + (size_t)ktc * 32 + (h ? low_off : 0);
+        const bf16_t* src = xbp + (size_t)ktc * tile_stride + (h ? low_off : 0);
         if (COH) {   // operand written by another workgroup of this launch: device-coherent loads, past L1 and the XCD's L2
           const unsigned long long* p8 = reinterpret_cast<const unsigned long long*>(src);
           const unsigned long long lo = __hip_atomic_load(p8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -181,7 +184,7 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
   auto fma = [&](const u32x4_t (&wv)[TN][U], const u32x4_t (&xv)[U][XP], int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const bool ok = rowok && (kt + u < kt1);
+      const bool ok = kt + u < kt1;
 #pragma unroll
       for (int h = 0; h < XP; ++h) {
         const u32x4_t xz = ok ? xv[u][h] : (u32x4_t){0u, 0u, 0u, 0u};
@@ -303,8 +306,9 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
         const float g = out_of(t, c8, row), u = out_of(t, c8 + 8, row);
         uint32_t hi, lo;
         split_bf16(g / (1.0f + __expf(-g)) * u, hi, lo);
-        j.act[(size_t)row * I + col] = (bf16_t)hi;
-        j.act[(size_t)(FUSED_LOW_ROW + row) * I + col] = (bf16_t)lo;
+        const size_t at = fused_xop_offset(S, row, col);
+        j.act[at] = (bf16_t)hi;
+        j.act[at + (S / 2) * 8] = (bf16_t)lo;
       }
     }
     return;
@@ -326,17 +330,18 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
         for (int p = PRE_PEERS; p < j.n_peers; ++p) v += bf16_to_f32(j.peers[p * j.peer_stride + (size_t)row * j.N + col]);
         j.x_new[(size_t)row * j.N + col] = v;
         // what the modules that read x_m multiply: x_m times their norm's gain, split
+        const size_t at = fused_xop_offset(S, row, col);
         if (j.xop_a) {
           uint32_t hi, lo;
           split_bf16(v * bf16_to_f32(pre_ga[e]), hi, lo);
-          j.xop_a[(size_t)row * j.N + col] = (bf16_t)hi;
-          j.xop_a[(size_t)(FUSED_LOW_ROW + row) * j.N + col] = (bf16_t)lo;
+          j.xop_a[at] = (bf16_t)hi;
+          j.xop_a[at + (S / 2) * 8] = (bf16_t)lo;
         }
         if (j.xop_b) {
           uint32_t hi, lo;
           split_bf16(v * bf16_to_f32(pre_gb[e]), hi, lo);
-          j.xop_b[(size_t)row * j.N + col] = (bf16_t)hi;
-          j.xop_b[(size_t)(FUSED_LOW_ROW + row) * j.N + col] = (bf16_t)lo;
+          j.xop_b[at] = (bf16_t)hi;
+          j.xop_b[at + (S / 2) * 8] = (bf16_t)lo;
         }
       }
       // the row's sum of squares over this tile's 16 columns (the 16 lanes that share t and row)
@@ -413,15 +418,16 @@ __device__ __forceinline__ void st_coherent(float* p, float v) {
 __device__ __forceinline__ float ld_coherent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// stores output element i of a row of an even number of elements as a split value (high part in row_hi, low
-// part in row_lo): lanes i and i ^ 1 pair up for one 32-bit coherent store each (all lanes of the wave must call)
-__device__ __forceinline__ void st_coherent_split_pair(bf16_t* row_hi, bf16_t* row_lo, int i, float v) {
+// stores a split value whose high part belongs at hi_at and whose low part at lo_at, for an element with an even
+// index i whose neighbour i ^ 1 lies right behind it: lanes i and i ^ 1 pair up for one 32-bit coherent store
+// each (all lanes of the wave must call)
+__device__ __forceinline__ void st_coherent_split_pair(bf16_t* hi_at, bf16_t* lo_at, int i, float v) {
   uint32_t h, l;
   split_bf16(v, h, l);
   const uint32_t oh = __shfl_xor(h, 1, 64), ol = __shfl_xor(l, 1, 64);
   if ((i & 1) == 0) {
-    st_coherent(reinterpret_cast<uint32_t*>(row_hi + i), h | (oh << 16));
-    st_coherent(reinterpret_cast<uint32_t*>(row_lo + i), l | (ol << 16));
+    st_coherent(reinterpret_cast<uint32_t*>(hi_at), h | (oh << 16));
+    st_coherent(reinterpret_cast<uint32_t*>(lo_at), l | (ol << 16));
   }
 }
 
@@ -573,8 +579,9 @@ __device__ __forceinline__ void attn_job(const AttnJob& a, int lb, float* smem, 
   }
   __syncthreads();
   const size_t pbase = ((size_t)bi * a.nkv + kvh) * a.n_splits;
-  bf16_t* const o_hi = a.o + ((size_t)bi * a.nq + kvh * G) * D;
-  bf16_t* const o_lo = a.o + ((size_t)(FUSED_LOW_ROW + bi) * a.nq + kvh * G) * D;
+  // the output is the output projection's operand: a split operand matrix of B rows, column = head * D + dim
+  const int So = fused_slots(a.B);
+  const int ocol0 = kvh * G * D;
   for (int i = tid_m; i < G * D; i += FUSED_THREADS) {
     const int h = i / D, dim = i % D;
     float m = -INFINITY;
@@ -588,7 +595,10 @@ __device__ __forceinline__ void attn_job(const AttnJob& a, int lb, float* smem, 
       o += wo[(w * G + h) * D + dim] * f;
     }
     if (a.n_splits == 1) {
-      st_coherent_split_pair(o_hi, o_lo, i, o / l);
+      {
+        bf16_t* const at = a.o + fused_xop_offset(So, bi, ocol0 + i);
+        st_coherent_split_pair(at, at + (So / 2) * 8, i, o / l);
+      }
     } else {
       st_coherent(a.part_o + ((pbase + sp) * G + h) * D + dim, o);
       if (dim == 0) {
@@ -643,7 +653,10 @@ __device__ __forceinline__ void attn_job(const AttnJob& a, int lb, float* smem, 
       }
       m = mnew;
     }
-    st_coherent_split_pair(o_hi, o_lo, i, o / l);
+    {
+        bf16_t* const at = a.o + fused_xop_offset(So, bi, ocol0 + i);
+        st_coherent_split_pair(at, at + (So / 2) * 8, i, o / l);
+      }
   }
   attn_signal_done(a);
 }
@@ -735,17 +748,19 @@ __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a) {
   const float v = bf16_to_f32(a.emb[ic]);
   if (ok) {
     a.x0[ic] = v;
+    const int S = fused_slots(a.rows);
+    const size_t at = fused_xop_offset(S, row, col);
     if (a.xop_a) {
       uint32_t hi, lo;
       split_bf16(v * bf16_to_f32(a.gain_a[col]), hi, lo);
-      a.xop_a[ic] = (bf16_t)hi;
-      a.xop_a[(size_t)FUSED_LOW_ROW * a.H + ic] = (bf16_t)lo;
+      a.xop_a[at] = (bf16_t)hi;
+      a.xop_a[at + (S / 2) * 8] = (bf16_t)lo;
     }
     if (a.xop_b) {
       uint32_t hi, lo;
       split_bf16(v * bf16_to_f32(a.gain_b[col]), hi, lo);
-      a.xop_b[ic] = (bf16_t)hi;
-      a.xop_b[(size_t)FUSED_LOW_ROW * a.H + ic] = (bf16_t)lo;
+      a.xop_b[at] = (bf16_t)hi;
+      a.xop_b[at + (S / 2) * 8] = (bf16_t)lo;
     }
   }
   float s = ok ? v * v : 0.f;
