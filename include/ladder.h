@@ -94,16 +94,21 @@ typedef struct {
   int32_t decode_graph;   /* 1: a decode step of the bf16 streaming path is captured once into a HIP graph
                              and replayed (the position lives in device memory and is advanced by the
                              graph itself); 0: eager launches.  Same results. */
-  int32_t decode_fused;   /* 1: decode steps of the bf16 streaming path (batch <= 16, one computed shard,
-                             max_seq <= 65536) use the fused launches: independent projections / attention
-                             of neighbouring modules share one launch; residual add, partial-sum reduce,
-                             RMSNorm, rotary, cache append and SwiGLU are epilogues / prologues;
+  int32_t decode_fused;   /* 1 or 2: decode steps of the bf16 streaming path (batch <= 16, one computed shard,
+                             max_seq <= 65536) use the fused launches: residual add, partial-sum reduce,
+                             RMSNorm, rotary, cache append and SwiGLU are epilogues / prologues of the
+                             projections.  1: the independent projections / attention of neighbouring modules
+                             share one launch where the wiring leaves them independent (ladder: two launches per
+                             layer; parallel block: three); 2: one job per launch whatever the wiring (five per
+                             layer), which leaves every collective a whole module to hide behind;
                              0: one kernel per operation */
-  int32_t reduce_delay_us; /* emulated all-reduce latency (Fig. 2 / Table 2 of the paper vary the interconnect):
-                              > 0 puts a timed wait of that many microseconds in front of every partial-sum
-                              reduce, on the stream the reduce runs on.  Per-operation schedules only: a
-                              non-zero value switches the fused decode schedule off.  0 .. 10000; same results.
-                              (LADDER_WIRING_PARALLEL: one wait per layer, in front of the MLP module's reduce.) */
+  int32_t reduce_delay_us; /* emulated all-reduce latency (Fig. 2 / Table 2 of the paper vary the interconnect), 0 .. 10000.
+                              Fused decode schedule: the collective that completes x_m starts when the launch
+                              holding module m's residual update ends, lasts this many microseconds on a side
+                              stream, and the launches whose projections read x_m wait for it; the arithmetic
+                              is unchanged (same bits).  One kernel per operation: a timed wait of that length in
+                              front of every partial-sum reduce, on the stream the reduce runs on.
+                              (LADDER_WIRING_PARALLEL: one collective per layer.) */
   float rms_eps;          /* RMSNorm epsilon (inside the square root) */
   float rope_theta;       /* rotary base; pair (2j,2j+1) turns by pos * theta^(-2j/d) */
 } ladder_config;

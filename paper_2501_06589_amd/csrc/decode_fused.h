@@ -47,6 +47,8 @@ struct GemvJob {
   int normed;
   float eps;
   const float* ssq;
+  int reads_stream;        // host-side note: normed jobs read the stream x_m with this m (the kernel does not use it)
+  int completes_stream;    // host-side note: a residual job after which the stream x_m is complete (a collective ends there): that m; else 0
   const void* wp;
   int M, K, N;
   // wait_on != null: the job's x operand is produced by the attention job of the SAME launch; the

@@ -133,6 +133,12 @@ struct ladder_ctx {
   unsigned wait_bias = 0;         // added to the wait's target (0 in normal operation; a test makes it unreachable)
   unsigned* tk_att = nullptr;     // arrival tickets of split attention, [max_batch][nkv]
   std::vector<FusedArgs> fused_plan;
+  // per launch of the plan: the emulated collectives (reduce_delay_us) that have to be complete before it (those
+  // that complete the streams its normed projections read) and the one that starts when it ends (the launch holds
+  // the residual update that completes stream x_id); 0 = none.  Ids are stream indices m of x_m.
+  struct FusedSync { int wait[2]; int signal; };
+  std::vector<FusedSync> fused_sync;
+  hipEvent_t ev_coll_start[4] = {nullptr, nullptr, nullptr, nullptr}, ev_coll_done[4] = {nullptr, nullptr, nullptr, nullptr};
   int fused_plan_batch = 0;
   int n_cu = 256;                 // compute units of the device (workgroup slots of a fused launch = 2 per CU)
   int wall_khz = 100000;          // rate of the device's wall clock (delay_kernel)
@@ -251,7 +257,7 @@ int check_config(const ladder_config* g, std::string& why) {
   if (g->n_real_shards > g->tp_degree) { why = "n_real_shards exceeds tp_degree"; return LADDER_E_SHAPE; }
   if (g->max_tokens > g->max_seq) { why = "max_tokens exceeds max_seq"; return LADDER_E_SHAPE; }
   if ((g->decode_graph != 0 && g->decode_graph != 1) || (g->overlap_modules != 0 && g->overlap_modules != 1)) { why = "decode_graph / overlap_modules must be 0 or 1"; return LADDER_E_ARG; }
-  if (g->decode_fused != 0 && g->decode_fused != 1) { why = "decode_fused must be 0 or 1"; return LADDER_E_ARG; }
+  if (g->decode_fused < 0 || g->decode_fused > 2) { why = "decode_fused must be 0, 1 or 2"; return LADDER_E_ARG; }
   if (g->reduce_delay_us < 0 || g->reduce_delay_us > 10000) { why = "reduce_delay_us must be in 0 .. 10000"; return LADDER_E_ARG; }
   if (g->peer_pool < 0 || g->peer_rows < 0) { why = "peer_pool / peer_rows negative"; return LADDER_E_ARG; }
   if (g->tp_degree > g->n_real_shards && g->peer_pool > 0 && g->peer_rows <= 0) { why = "peer_rows must be positive when peers are used"; return LADDER_E_SHAPE; }
@@ -568,7 +574,7 @@ __global__ void inc_pos_kernel(int* p) { *p += 1; }
 // ---------------------------------------------------------------------------------------------
 bool fused_usable(const ladder_ctx* c) {
   const ladder_config& g = c->cfg;
-  return c->fast && g.decode_fused != 0 && g.reduce_delay_us == 0 && g.n_real_shards == 1 && g.max_batch <= 16 && g.max_seq <= 65536 &&
+  return c->fast && g.decode_fused != 0 && g.n_real_shards == 1 && g.max_batch <= 16 && g.max_seq <= 65536 &&
          g.hidden % 32 == 0;
 }
 
@@ -589,6 +595,7 @@ void build_fused_plan(ladder_ctx* c, int B) {
   auto job_qkv = [&](int l, int src) {
     GemvJob j{};
     j.xb = c->xop_ring[src % 3][1]; j.ldx = H; j.normed = 1; j.eps = g.rms_eps; j.ssq = c->ssq_ring[src % 3];
+    j.reads_stream = src;
     j.wp = layer(l).pqkv; j.M = B; j.K = H; j.N = c->nqkv;
     j.n_groups = c->nqkv / 16; j.epi = EPI_QKV_ROPE;
     j.q_out = c->f_q;
@@ -615,6 +622,9 @@ void build_fused_plan(ladder_ctx* c, int B) {
       else { j.xop_b = c->xop_ring[at % 3][0]; j.gain_b = (const bf16_t*)c->gain_mlp[cl]; }
     }
     if (nc > 0) j.ssq_new = c->ssq_ring[at % 3];
+    // a collective ends every module (x_at is then complete); the parallel block has one per layer, after the
+    // second of its two local additions (the odd slots hold the intermediate sum)
+    if (g.wiring != LADDER_WIRING_PARALLEL || (at & 1) == 0) j.completes_stream = at;
     if (c->peers && c->n_peers > 0) {
       j.peers = (const bf16_t*)c->peers + (size_t)(m % g.peer_pool) * c->n_peers * (size_t)g.peer_rows * H;
       j.n_peers = c->n_peers; j.peer_stride = (size_t)g.peer_rows * H;
@@ -631,6 +641,7 @@ void build_fused_plan(ladder_ctx* c, int B) {
   auto job_gu = [&](int l, int src) {
     GemvJob j{};
     j.xb = c->xop_ring[src % 3][0]; j.ldx = H; j.normed = 1; j.eps = g.rms_eps; j.ssq = c->ssq_ring[src % 3];
+    j.reads_stream = src;
     j.wp = layer(l).pgu; j.M = B; j.K = H; j.N = 2 * I;
     j.n_groups = 2 * I / 16; j.epi = EPI_SWIGLU; j.act = c->f_act;
     // every workgroup reads the batch's rows of x over its whole K range (from L2): at 13 rows and more that
@@ -747,7 +758,8 @@ void build_fused_plan(ladder_ctx* c, int B) {
   std::vector<FusedArgs>& plan = c->fused_plan;
   plan.clear();
   const bool all_ladder = g.wiring == LADDER_WIRING_LADDER && g.n_standard_layers == 0;
-  if (all_ladder) {
+  const bool paired = g.decode_fused == 1;   // (2: one job per launch whatever the wiring)
+  if (all_ladder && paired) {
     // modules 1 and 2 both read x_0; then TWO launches per layer:
     //     { attention_l , gate/up_l , o_l }     { qkv_{l+1} , down_l }
     // Attention and gate/up, and the next layer's QKV and down, do not depend on each other under the
@@ -785,7 +797,7 @@ void build_fused_plan(ladder_ctx* c, int B) {
       if (l < N) plan.push_back(qkv_down(job_qkv(l + 1, 2 * l - 1), job_dn(l, 2 * l)));
       else plan.push_back(one(job_dn(N, 2 * N)));
     }
-  } else if (g.wiring == LADDER_WIRING_PARALLEL) {
+  } else if (g.wiring == LADDER_WIRING_PARALLEL && paired) {
     // both modules of layer l read x_{2l-2}: THREE launches per layer,
     //     { gate/up_l , qkv_l }     { attention_l , down_l }     { o_l }
     // with the two outputs added in the order MLP, attention (the sum is the same up to rounding): down_l does
@@ -802,6 +814,17 @@ void build_fused_plan(ladder_ctx* c, int B) {
       plan.push_back(one(job_o(l, 2 * l - 1)));
       plan.push_back(one(job_gu(l, src_of(2 * l))));
       plan.push_back(one(job_dn(l, 2 * l)));
+    }
+  }
+  // the emulated collectives around each launch (fused_body)
+  c->fused_sync.assign(plan.size(), ladder_ctx::FusedSync{{0, 0}, 0});
+  for (size_t i = 0; i < plan.size(); ++i) {
+    ladder_ctx::FusedSync& sy = c->fused_sync[i];
+    for (int k = 0; k < plan[i].n_jobs; ++k) {
+      if (plan[i].kind[k] != JOB_GEMV) continue;
+      const GemvJob& j = plan[i].g[k];
+      if (j.normed && j.reads_stream > 0 && sy.wait[0] != j.reads_stream && sy.wait[1] != j.reads_stream) sy.wait[sy.wait[0] ? 1 : 0] = j.reads_stream;
+      if (j.epi == EPI_RESIDUAL && j.completes_stream > 0) sy.signal = std::max(sy.signal, j.completes_stream);
     }
   }
   c->fused_plan_batch = B;
@@ -844,11 +867,36 @@ int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s) {
   }
   if (c->prof) c->prof_pending.push_back({LADDER_K_OTHER, e[0], e[1]});
   const int gq = g.n_q_heads / g.n_kv_heads;
-  for (const FusedArgs& fa : c->fused_plan) {
+  // Emulated collective latency (reduce_delay_us): the collective that completes stream x_id starts when the
+  // launch holding that residual update ends, takes its time on the side stream (one wavefront polling the wall
+  // clock), and every launch whose projections read x_id waits for it.  The arithmetic stays where it is (the
+  // partial sums of the other ranks are local memory here): what is emulated is WHEN the reduced stream may be
+  // read, so a schedule hides the latency exactly where it has independent launches to run meanwhile.
+  const bool late = g.reduce_delay_us > 0;
+  const unsigned long long ticks = (unsigned long long)g.reduce_delay_us * (unsigned long long)c->wall_khz / 1000ull;
+  int last_signal = 0;
+  for (size_t i = 0; i < c->fused_plan.size(); ++i) {
+    const FusedArgs& fa = c->fused_plan[i];
+    const ladder_ctx::FusedSync& sy = c->fused_sync[i];
+    if (late)
+      for (int k = 0; k < 2; ++k)
+        if (sy.wait[k] > 0) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_coll_done[sy.wait[k] & 3], 0));
     HIP_TRY(c, events(e));
     HIP_TRY(c, launch_fused_decode(fa, g.head_dim, gq, s, e[0], e[1]));
     if (c->prof) c->prof_pending.push_back({LADDER_K_FUSED_DECODE, e[0], e[1]});
+    if (late && sy.signal > 0) {
+      const int k = sy.signal & 3;
+      HIP_TRY(c, hipEventRecord(c->ev_coll_start[k], s));
+      HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_coll_start[k], 0));
+      HIP_TRY(c, timed(c, LADDER_K_OTHER, c->side, [&] {
+        hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(64), 0, c->side, ticks);
+        return hipGetLastError();
+      }));
+      HIP_TRY(c, hipEventRecord(c->ev_coll_done[k], c->side));
+      last_signal = sy.signal;
+    }
   }
+  if (late && last_signal > 0) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_coll_done[last_signal & 3], 0));   // x_2N is complete
   return LADDER_OK;
 }
 
@@ -1015,6 +1063,10 @@ static int init_impl(const ladder_config* cfg, void* hip_stream, ladder_ctx** ou
   for (int i = 0; i < 2; ++i) {
     INIT_HIP(hipEventCreateWithFlags(&c->ev_mod[i], hipEventDisableTiming));
     INIT_HIP(hipEventCreateWithFlags(&c->ev_red[i], hipEventDisableTiming));
+  }
+  for (int i = 0; i < 4; ++i) {
+    INIT_HIP(hipEventCreateWithFlags(&c->ev_coll_start[i], hipEventDisableTiming));
+    INIT_HIP(hipEventCreateWithFlags(&c->ev_coll_done[i], hipEventDisableTiming));
   }
   const int H = g.hidden, d = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, I = g.inter;
   const size_t esz = c->esz;
@@ -1272,7 +1324,8 @@ int ladder_decode_step(ladder_ctx* c, const void* x_in, void* x_out) {
   if (rc) return rc;
   rc = all_loaded(c);
   if (rc) return rc;
-  if (c->fast && c->cfg.decode_graph && !c->prof) {
+  // (a captured step holds at most two streams; the emulated collectives of the fused schedule use a third)
+  if (c->fast && c->cfg.decode_graph && !c->prof && !(c->fused && c->cfg.reduce_delay_us > 0)) {
     rc = decode_graph_step(c, x_in, x_out);
     if (rc) return rc;
   } else if (c->fused) {
@@ -1309,6 +1362,10 @@ void ladder_free(ladder_ctx* c) {
   for (int i = 0; i < 2; ++i) {
     if (c->ev_mod[i]) (void)hipEventDestroy(c->ev_mod[i]);
     if (c->ev_red[i]) (void)hipEventDestroy(c->ev_red[i]);
+  }
+  for (int i = 0; i < 4; ++i) {
+    if (c->ev_coll_start[i]) (void)hipEventDestroy(c->ev_coll_start[i]);
+    if (c->ev_coll_done[i]) (void)hipEventDestroy(c->ev_coll_done[i]);
   }
   for (void* p : c->allocs) (void)hipFree(p);
   if (c->err_word) (void)hipHostFree(c->err_word);

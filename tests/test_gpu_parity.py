@@ -176,35 +176,72 @@ def test_graph_decode_after_prefill_matches_oracle(harness):
 
 
 def test_emulated_reduce_latency_changes_time_not_results(harness):
-    """A timed wait in front of every reduce (the stand-in for a collective's latency): same bits, and under
-    the standard wiring, where nothing can overlap it, a call lasts at least 2N waits longer."""
-    import time
+    """One kernel per operation: a timed wait in front of every reduce (the stand-in for a collective's latency)
+    changes no bit, and the waits are really there: with profiling on, the timed-wait kernels of a decode step
+    (kernel class "other") number one per collective and last at least the configured time each."""
     w = SMALL_BF16.with_(name="small_bf16_delay", n_layers=3, decode_steps=2)
     ref = harness.run_case(w, gpu_only=True, decode_fused=0)
-    got = harness.run_case(w, gpu_only=True, decode_fused=1, reduce_delay_us=300)   # the delay selects the per-operation schedule
+    got = harness.run_case(w, gpu_only=True, decode_fused=0, reduce_delay_us=300)
     for x, y in zip(ref.gpu, got.gpu):
         assert np.array_equal(x, y)
-    tensors = harness.make_tensors(w)
-    def decode_ms(delay):
-        ctx = harness.build_gpu(w, tensors, None, wiring=ladder.LADDER_WIRING_STANDARD, reduce_delay_us=delay)
-        ctx.prefill(inputs.embeddings(w, w.batch, w.prefill, inputs.SEED_PREFILL).to("cuda:0"))
-        x = inputs.embeddings(w, w.batch, 1, inputs.SEED_DECODE0)[:, 0].contiguous().to("cuda:0")
+    # (two computed shards take the per-operation schedule whatever decode_fused says; one shard takes the fused
+    # launches, which have one more "other" kernel: the embedding copy)
+    for wk, fused, n_other in ((w, 0, 0), (w.with_(tp_degree=1, n_real_shards=1), 2, 1)):
+        tensors = harness.make_tensors(wk)
+        ctx = harness.build_gpu(wk, tensors, None, wiring=ladder.LADDER_WIRING_STANDARD, reduce_delay_us=300, decode_fused=fused)
+        ctx.prefill(inputs.embeddings(wk, wk.batch, wk.prefill, inputs.SEED_PREFILL).to("cuda:0"))
+        x = inputs.embeddings(wk, wk.batch, 1, inputs.SEED_DECODE0)[:, 0].contiguous().to("cuda:0")
         ctx.decode_step(x)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
+        ctx.profile_enable(True)
+        ctx.profile_reset()
         ctx.decode_step(x)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) * 1e3
+        prof = ctx.profile_read()
+        ctx.profile_enable(False)
         ctx.free()
-        return dt
-    assert decode_ms(300) - decode_ms(0) > 0.8 * 6 * 0.3
+        launches, ms = prof["other"]
+        assert launches == 2 * w.n_layers + n_other, prof
+        assert ms >= 0.9 * 2 * w.n_layers * 0.3, prof
     # the parallel block has one collective per layer: per-operation schedule (bf16 streaming kernels, two
     # module streams) against the oracle, with and without the wait
     res = harness.run_case(w, wiring=ladder.LADDER_WIRING_PARALLEL, decode_fused=0)
     assert max(res.errs) < TOL_BF16, res.errs
-    late = harness.run_case(w, gpu_only=True, wiring=ladder.LADDER_WIRING_PARALLEL, reduce_delay_us=300)
+    late = harness.run_case(w, gpu_only=True, wiring=ladder.LADDER_WIRING_PARALLEL, reduce_delay_us=300, decode_fused=0)
     for x, y in zip(res.gpu, late.gpu):
         assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("wiring,nstd", [(ladder.LADDER_WIRING_LADDER, 0), (ladder.LADDER_WIRING_STANDARD, 0),
+                                         (ladder.LADDER_WIRING_LADDER, 1), (ladder.LADDER_WIRING_PARALLEL, 0)])
+def test_emulated_latency_on_the_fused_schedule(harness, wiring, nstd):
+    """The fused decode schedule with emulated collectives (side stream, events): same bits as without them, for
+    both launch lists (paired jobs, one job per launch) and every wiring; the one-job-per-launch list against the
+    oracle; and the collectives of a step are all there (one per module; one per layer for the parallel block)."""
+    w = inputs.WORKLOADS["70b_r8_decode"].with_(name="r8_small_late", n_layers=3, hidden=512, inter=448, batch=4, decode_steps=3)
+    kw = dict(kv_preload=90, wiring=wiring, n_standard_layers=nstd)
+    ref = harness.run_case(w, decode_fused=2, **kw)
+    assert len(ref.errs) == 3 and max(ref.errs) < TOL_BF16, ref.errs
+    for plan in (1, 2):
+        base = harness.run_case(w, gpu_only=True, decode_fused=plan, **kw)
+        late = harness.run_case(w, gpu_only=True, decode_fused=plan, reduce_delay_us=200, **kw)
+        for x, y, z in zip(base.gpu, late.gpu, ref.gpu):
+            assert np.array_equal(x, y)
+            assert np.max(np.abs(x - z)) <= 1e-3 * np.sqrt(np.mean(z * z))      # (the two launch lists sum in different orders)
+    tensors = harness.make_tensors(w)
+    peers = inputs.peer_partials(w, w.batch)
+    ctx = harness.build_gpu(w, tensors, peers, max_seq=200, reduce_delay_us=200, decode_fused=1, **{k: v for k, v in kw.items() if k != "kv_preload"})
+    for i in range(w.n_layers):
+        k, v = inputs.kv_cache(w, i, 0, w.batch, 90)
+        ctx.load_kv(i, 0, k.to("cuda:0"), v.to("cuda:0"))
+    x = inputs.embeddings(w, w.batch, 1, inputs.SEED_DECODE0)[:, 0].contiguous().to("cuda:0")
+    ctx.decode_step(x)
+    ctx.profile_enable(True)
+    ctx.profile_reset()
+    ctx.decode_step(x)
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    ctx.free()
+    n_coll = w.n_layers if wiring == ladder.LADDER_WIRING_PARALLEL else 2 * w.n_layers
+    assert prof["other"][0] == n_coll + 1 and prof["other"][1] >= 0.9 * n_coll * 0.2, prof
 
 
 # ---- fused decode launches ----------------------------------------------------------------------
