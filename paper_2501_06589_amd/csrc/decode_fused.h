@@ -59,6 +59,13 @@ struct GemvJob {
   unsigned wait_target;
   int wait_spins;
   unsigned* err_word;
+  // Emulated collective latency (both null / 0 in normal operation).  t_ready: the job reads a stream whose
+  // collective ends delay_ticks (wall clock) after the time stored there by an earlier launch; its workgroups
+  // hold back until then (bounded).  t_done: every workgroup of this (residual) job leaves the time it ended there
+  // (atomic maximum), which is when the collective of the stream it completes starts.
+  const unsigned long long* t_ready;
+  unsigned long long delay_ticks;
+  unsigned long long* t_done;
   int tn;                  // 16-column tiles per workgroup: 1 (0 means 1), 2, 4, or 3 (jobs without a wait)
   int group0, n_groups;    // this job's workgroups own the tile groups [group0, group0 + n_groups), tn tiles
                            // each; a projection may be cut over two launches

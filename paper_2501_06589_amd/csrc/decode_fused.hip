@@ -180,6 +180,19 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
     if (*s_flag == 0u) return;
   }
 
+  if (j.t_ready) {
+    // emulated collective: the stream this job reads counts as reduced delay_ticks after the time its producer
+    // left; a wait on the clock alone (it ends whatever other workgroups do), bounded all the same
+    if (tid == 0) {
+      const unsigned long long t1 = *j.t_ready + j.delay_ticks;
+      for (int spin = 0; spin < (1 << 20); ++spin) {
+        if (wall_clock64() >= t1) break;
+        __builtin_amdgcn_s_sleep(8);
+      }
+    }
+    __syncthreads();
+  }
+
   if (COH && kt0 < kt1) loadx(xa, kt0);
   auto fma = [&](const u32x4_t (&wv)[TN][U], const u32x4_t (&xv)[U][XP], int kt) {
 #pragma unroll
@@ -352,6 +365,7 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
       s += __shfl_xor(s, 8, 64);
       if (col16 == 0 && row < j.M && j.ssq_new) j.ssq_new[(size_t)(nt0 + t) * 16 + row] = s;
     }
+    if (j.t_done && tid == 0) atomicMax(j.t_done, (unsigned long long)wall_clock64());   // (emulated collectives only)
     return;
   }
 

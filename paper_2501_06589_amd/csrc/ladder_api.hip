@@ -133,12 +133,9 @@ struct ladder_ctx {
   unsigned wait_bias = 0;         // added to the wait's target (0 in normal operation; a test makes it unreachable)
   unsigned* tk_att = nullptr;     // arrival tickets of split attention, [max_batch][nkv]
   std::vector<FusedArgs> fused_plan;
-  // per launch of the plan: the emulated collectives (reduce_delay_us) that have to be complete before it (those
-  // that complete the streams its normed projections read) and the one that starts when it ends (the launch holds
-  // the residual update that completes stream x_id); 0 = none.  Ids are stream indices m of x_m.
-  struct FusedSync { int wait[2]; int signal; };
-  std::vector<FusedSync> fused_sync;
-  hipEvent_t ev_coll_start[4] = {nullptr, nullptr, nullptr, nullptr}, ev_coll_done[4] = {nullptr, nullptr, nullptr, nullptr};
+  // emulated collectives (reduce_delay_us) of the fused schedule: t_done[m] = wall-clock time at which the last
+  // workgroup of the residual update that completes stream x_m ended (0 .. 2N)
+  unsigned long long* t_done = nullptr;
   int fused_plan_batch = 0;
   int n_cu = 256;                 // compute units of the device (workgroup slots of a fused launch = 2 per CU)
   int wall_khz = 100000;          // rate of the device's wall clock (delay_kernel)
@@ -469,6 +466,16 @@ __global__ __launch_bounds__(64) void delay_kernel(unsigned long long ticks) {
   const unsigned long long t0 = wall_clock64();
   for (int i = 0; i < (1 << 20); ++i) {
     if (wall_clock64() - t0 >= ticks) break;
+    __builtin_amdgcn_s_sleep(8);
+  }
+}
+
+// Same, until `ticks` after the time *t0 (left by an earlier kernel of the stream): the end of an emulated
+// collective whose start another kernel has recorded.
+__global__ __launch_bounds__(64) void wait_until_kernel(const unsigned long long* t0, unsigned long long ticks) {
+  const unsigned long long t1 = *t0 + ticks;
+  for (int i = 0; i < (1 << 20); ++i) {
+    if (wall_clock64() >= t1) break;
     __builtin_amdgcn_s_sleep(8);
   }
 }
@@ -816,16 +823,21 @@ void build_fused_plan(ladder_ctx* c, int B) {
       plan.push_back(one(job_dn(l, 2 * l)));
     }
   }
-  // the emulated collectives around each launch (fused_body)
-  c->fused_sync.assign(plan.size(), ladder_ctx::FusedSync{{0, 0}, 0});
-  for (size_t i = 0; i < plan.size(); ++i) {
-    ladder_ctx::FusedSync& sy = c->fused_sync[i];
-    for (int k = 0; k < plan[i].n_jobs; ++k) {
-      if (plan[i].kind[k] != JOB_GEMV) continue;
-      const GemvJob& j = plan[i].g[k];
-      if (j.normed && j.reads_stream > 0 && sy.wait[0] != j.reads_stream && sy.wait[1] != j.reads_stream) sy.wait[sy.wait[0] ? 1 : 0] = j.reads_stream;
-      if (j.epi == EPI_RESIDUAL && j.completes_stream > 0) sy.signal = std::max(sy.signal, j.completes_stream);
-    }
+  // Emulated collective latency (reduce_delay_us): the collective that completes stream x_m starts when the last
+  // workgroup of module m's residual update ends (those workgroups leave the wall-clock time in t_done[m]) and
+  // lasts the configured time; a projection that reads x_m holds its workgroups back until then (they have
+  // requested their first weight tiles already), while the other jobs of its launch run.  The arithmetic stays
+  // where it is (the other ranks' partial sums are local memory here): what is emulated is WHEN a reduced stream
+  // may be read, so a schedule hides the latency exactly where it has independent work to run meanwhile.
+  if (g.reduce_delay_us > 0) {
+    const unsigned long long ticks = (unsigned long long)g.reduce_delay_us * (unsigned long long)c->wall_khz / 1000ull;
+    for (FusedArgs& fa : plan)
+      for (int k = 0; k < fa.n_jobs; ++k) {
+        if (fa.kind[k] != JOB_GEMV) continue;
+        GemvJob& j = fa.g[k];
+        if (j.normed && j.reads_stream > 0) { j.t_ready = c->t_done + j.reads_stream; j.delay_ticks = ticks; }
+        if (j.epi == EPI_RESIDUAL && j.completes_stream > 0) j.t_done = c->t_done + j.completes_stream;
+      }
   }
   c->fused_plan_batch = B;
   c->fused_plan_peers = c->peers;
@@ -867,36 +879,18 @@ int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s) {
   }
   if (c->prof) c->prof_pending.push_back({LADDER_K_OTHER, e[0], e[1]});
   const int gq = g.n_q_heads / g.n_kv_heads;
-  // Emulated collective latency (reduce_delay_us): the collective that completes stream x_id starts when the
-  // launch holding that residual update ends, takes its time on the side stream (one wavefront polling the wall
-  // clock), and every launch whose projections read x_id waits for it.  The arithmetic stays where it is (the
-  // partial sums of the other ranks are local memory here): what is emulated is WHEN the reduced stream may be
-  // read, so a schedule hides the latency exactly where it has independent launches to run meanwhile.
-  const bool late = g.reduce_delay_us > 0;
-  const unsigned long long ticks = (unsigned long long)g.reduce_delay_us * (unsigned long long)c->wall_khz / 1000ull;
-  int last_signal = 0;
-  for (size_t i = 0; i < c->fused_plan.size(); ++i) {
-    const FusedArgs& fa = c->fused_plan[i];
-    const ladder_ctx::FusedSync& sy = c->fused_sync[i];
-    if (late)
-      for (int k = 0; k < 2; ++k)
-        if (sy.wait[k] > 0) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_coll_done[sy.wait[k] & 3], 0));
+  for (const FusedArgs& fa : c->fused_plan) {
     HIP_TRY(c, events(e));
     HIP_TRY(c, launch_fused_decode(fa, g.head_dim, gq, s, e[0], e[1]));
     if (c->prof) c->prof_pending.push_back({LADDER_K_FUSED_DECODE, e[0], e[1]});
-    if (late && sy.signal > 0) {
-      const int k = sy.signal & 3;
-      HIP_TRY(c, hipEventRecord(c->ev_coll_start[k], s));
-      HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_coll_start[k], 0));
-      HIP_TRY(c, timed(c, LADDER_K_OTHER, c->side, [&] {
-        hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(64), 0, c->side, ticks);
-        return hipGetLastError();
-      }));
-      HIP_TRY(c, hipEventRecord(c->ev_coll_done[k], c->side));
-      last_signal = sy.signal;
-    }
   }
-  if (late && last_signal > 0) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_coll_done[last_signal & 3], 0));   // x_2N is complete
+  if (g.reduce_delay_us > 0) {   // x_2N is complete when the last module's emulated collective is
+    const unsigned long long ticks = (unsigned long long)g.reduce_delay_us * (unsigned long long)c->wall_khz / 1000ull;
+    HIP_TRY(c, timed(c, LADDER_K_OTHER, s, [&] {
+      hipLaunchKernelGGL(wait_until_kernel, dim3(1), dim3(64), 0, s, (const unsigned long long*)(c->t_done + c->n_mod), ticks);
+      return hipGetLastError();
+    }));
+  }
   return LADDER_OK;
 }
 
@@ -1064,10 +1058,6 @@ static int init_impl(const ladder_config* cfg, void* hip_stream, ladder_ctx** ou
     INIT_HIP(hipEventCreateWithFlags(&c->ev_mod[i], hipEventDisableTiming));
     INIT_HIP(hipEventCreateWithFlags(&c->ev_red[i], hipEventDisableTiming));
   }
-  for (int i = 0; i < 4; ++i) {
-    INIT_HIP(hipEventCreateWithFlags(&c->ev_coll_start[i], hipEventDisableTiming));
-    INIT_HIP(hipEventCreateWithFlags(&c->ev_coll_done[i], hipEventDisableTiming));
-  }
   const int H = g.hidden, d = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, I = g.inter;
   const size_t esz = c->esz;
   c->store.resize((size_t)g.n_layers * g.n_real_shards);
@@ -1180,6 +1170,7 @@ static int init_impl(const ladder_config* cfg, void* hip_stream, ladder_ctx** ou
       INIT_HIP(hipHostMalloc((void**)&c->err_word, 64, hipHostMallocMapped));
       if (c->err_word) *c->err_word = 0u;
       INIT_HIP(hipHostGetDevicePointer((void**)&c->err_word_dev, c->err_word, 0));
+      INIT_TRY(dev_alloc(c, (void**)&c->t_done, (size_t)(c->n_mod + 1) * 8, true));
       INIT_TRY(dev_alloc(c, (void**)&c->att_done, (size_t)g.n_layers * 4, true));
       // arrival tickets start at zero and are put back to zero by the last arrival of every launch
       INIT_TRY(dev_alloc(c, (void**)&c->tk_att, (size_t)g.max_batch * nkv * 4, true));
@@ -1324,8 +1315,7 @@ int ladder_decode_step(ladder_ctx* c, const void* x_in, void* x_out) {
   if (rc) return rc;
   rc = all_loaded(c);
   if (rc) return rc;
-  // (a captured step holds at most two streams; the emulated collectives of the fused schedule use a third)
-  if (c->fast && c->cfg.decode_graph && !c->prof && !(c->fused && c->cfg.reduce_delay_us > 0)) {
+  if (c->fast && c->cfg.decode_graph && !c->prof) {
     rc = decode_graph_step(c, x_in, x_out);
     if (rc) return rc;
   } else if (c->fused) {
@@ -1362,10 +1352,6 @@ void ladder_free(ladder_ctx* c) {
   for (int i = 0; i < 2; ++i) {
     if (c->ev_mod[i]) (void)hipEventDestroy(c->ev_mod[i]);
     if (c->ev_red[i]) (void)hipEventDestroy(c->ev_red[i]);
-  }
-  for (int i = 0; i < 4; ++i) {
-    if (c->ev_coll_start[i]) (void)hipEventDestroy(c->ev_coll_start[i]);
-    if (c->ev_coll_done[i]) (void)hipEventDestroy(c->ev_coll_done[i]);
   }
   for (void* p : c->allocs) (void)hipFree(p);
   if (c->err_word) (void)hipHostFree(c->err_word);
