@@ -203,8 +203,9 @@ int ladder_load_head(ladder_ctx* ctx, const void* table, const void* final_norm,
 
 /* Token embedding: x_out[r][:] = table[tokens[r]][:].
  *   tokens  device int32 [rows]  (an id outside [0, vocab) reads row 0 or vocab - 1 instead, so that no
- *                                access leaves the table, and is REPORTED: the next ladder_embed, ladder_prefill
- *                                or ladder_decode_step of this context fails with LADDER_E_ARG and does nothing)
+ *                                access leaves the table, and is REPORTED: once the kernel has run, the next
+ *                                ladder_embed, ladder_prefill or ladder_decode_step of this context fails with
+ *                                LADDER_E_ARG, does nothing else, and clears the condition)
  *   x_out   device T [rows][H]   rows <= max_batch * max_tokens; ready to be x_in of ladder_prefill
  *                                ([B][T][H], rows = B*T) or ladder_decode_step ([B][H]).
  * Enqueued on the caller's stream.  Errors: LADDER_E_ARG, LADDER_E_STATE (head not loaded), LADDER_E_SHAPE. */

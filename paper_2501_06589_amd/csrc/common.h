@@ -97,10 +97,11 @@ hipError_t launch_attn_generic(const AttnGenericArgs& a, bool is_bf16, hipStream
 hipError_t launch_swiglu(const float* gu, void* act, int M, int I, bool is_bf16, hipStream_t s);
 
 // ---- generation head ----------------------------------------------------------------------------
-// x_out[r][:] = table[tokens[r]][:]  (T [rows][H]); ids outside [0, vocab) are clamped into the table
+// x_out[r][:] = table[tokens[r]][:]  (T [rows][H]); an id outside [0, vocab) reads the nearest valid row and sets
+// *bad_id (host-visible memory, may be null) to 1
 hipError_t launch_embed_gather(const int* tokens, const void* table, void* x_out, int rows, int H, int vocab,
-                               bool is_bf16, hipStream_t s);
-// y[r][:] = x[r][:] / sqrt(mean(x[r]^2) + eps) * gain   (gain may be null: folded into the projection); y: T
+                               unsigned* bad_id, bool is_bf16, hipStream_t s);
+// y[r][:] = x[r][:] / sqrt(mean(x[r]^2) + eps) * gain   (gain may be null = 1); y: T
 hipError_t launch_head_norm(const float* x, const void* gain, void* y, int rows, int H, float eps, bool is_bf16,
                             hipStream_t s);
 // tokens_out[r] = index of the largest of logits[r][0..V), the lowest index among equal maxima

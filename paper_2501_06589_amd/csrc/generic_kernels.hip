@@ -321,17 +321,19 @@ hipError_t launch_load_kv(const void* k, const void* v, void* cache_k, void* cac
 // ------------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void embed_gather_kernel(const int* __restrict__ tokens, const T* __restrict__ table,
-                                                           T* __restrict__ out, int H, int vocab) {
+                                                           T* __restrict__ out, int H, int vocab, unsigned* bad_id) {
   const int r = blockIdx.x;
-  const int tok = min(max(tokens[r], 0), vocab - 1);
+  const int raw = tokens[r];
+  const int tok = min(max(raw, 0), vocab - 1);   // no access leaves the table; an id outside it is reported
+  if (raw != tok && bad_id && threadIdx.x == 0) __hip_atomic_store(bad_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   for (int i = threadIdx.x; i < H; i += 256) out[(size_t)r * H + i] = table[(size_t)tok * H + i];
 }
 
 hipError_t launch_embed_gather(const int* tokens, const void* table, void* x_out, int rows, int H, int vocab,
-                               bool is_bf16, hipStream_t s) {
+                               unsigned* bad_id, bool is_bf16, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
-  if (is_bf16) hipLaunchKernelGGL(embed_gather_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, tokens, (const bf16_t*)table, (bf16_t*)x_out, H, vocab);
-  else hipLaunchKernelGGL(embed_gather_kernel<float>, dim3(rows), dim3(256), 0, s, tokens, (const float*)table, (float*)x_out, H, vocab);
+  if (is_bf16) hipLaunchKernelGGL(embed_gather_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, tokens, (const bf16_t*)table, (bf16_t*)x_out, H, vocab, bad_id);
+  else hipLaunchKernelGGL(embed_gather_kernel<float>, dim3(rows), dim3(256), 0, s, tokens, (const float*)table, (float*)x_out, H, vocab, bad_id);
   return hipGetLastError();
 }
 

@@ -977,9 +977,14 @@ int decode_fused_step(ladder_ctx* c, const void* x_in, void* x_out) {
 // A kernel of an earlier call has raised the error word (its bounded in-launch wait gave up, so that call's
 // output is not valid): reported once, by the next forward call, which does nothing else.
 int check_device_error(ladder_ctx* c) {
-  if (c->err_word && *(volatile unsigned*)c->err_word != 0u) {
-    *(volatile unsigned*)c->err_word = 0u;
+  volatile unsigned* w = c->err_word;
+  if (w && w[0] != 0u) {
+    w[0] = 0u;
     return fail(c, LADDER_E_HIP, "a kernel of an earlier decode step gave up its bounded in-launch wait (attention -> output projection): that step's output is invalid");
+  }
+  if (w && w[1] != 0u) {
+    w[1] = 0u;
+    return fail(c, LADDER_E_ARG, "an earlier ladder_embed was given a token id outside [0, vocab): the embeddings it wrote for that id are those of the nearest valid id");
   }
   return LADDER_OK;
 }
@@ -1125,6 +1130,12 @@ static int init_impl(const ladder_config* cfg, void* hip_stream, ladder_ctx** ou
     INIT_HIP(hipMemcpy(c->cos_tab, ct.data(), ct.size() * 4, hipMemcpyHostToDevice));
     INIT_HIP(hipMemcpy(c->sin_tab, st.data(), st.size() * 4, hipMemcpyHostToDevice));
   }
+  // the words a kernel raises when something went wrong on the device (word 0: a bounded in-launch wait gave up;
+  // word 1: ladder_embed met a token id outside the table): host memory that the device can write, so that the
+  // host can look at them at the start of every call without synchronising anything
+  INIT_HIP(hipHostMalloc((void**)&c->err_word, 64, hipHostMallocMapped));
+  if (c->err_word) c->err_word[0] = c->err_word[1] = 0u;
+  INIT_HIP(hipHostGetDevicePointer((void**)&c->err_word_dev, c->err_word, 0));
   // workspaces
   // rows x slots of the partial-sum buffers: a skinny call (rows <= 64) may use up to 8 split-K slots
   // per shard, a wide call uses one
@@ -1165,11 +1176,6 @@ static int init_impl(const ladder_config* cfg, void* hip_stream, ladder_ctx** ou
       INIT_TRY(dev_alloc(c, (void**)&c->f_q, (size_t)32 * nq * d * 2, true));
       INIT_TRY(dev_alloc(c, (void**)&c->f_o, (size_t)32 * nq * d * 2, true));
       INIT_TRY(dev_alloc(c, (void**)&c->f_act, (size_t)32 * I * 2, true));
-      // the word a kernel raises when its bounded wait gives up: host memory that the device can write, so that
-      // the host can look at it at the start of every call without synchronising anything
-      INIT_HIP(hipHostMalloc((void**)&c->err_word, 64, hipHostMallocMapped));
-      if (c->err_word) *c->err_word = 0u;
-      INIT_HIP(hipHostGetDevicePointer((void**)&c->err_word_dev, c->err_word, 0));
       INIT_TRY(dev_alloc(c, (void**)&c->t_done, (size_t)(c->n_mod + 1) * 8, true));
       INIT_TRY(dev_alloc(c, (void**)&c->att_done, (size_t)g.n_layers * 4, true));
       // arrival tickets start at zero and are put back to zero by the last arrival of every launch
@@ -1424,7 +1430,9 @@ int ladder_embed(ladder_ctx* c, const int32_t* tokens, int32_t rows, void* x_out
   if (!c->head_table) return fail(c, LADDER_E_STATE, "the head is not loaded");
   if (rows <= 0) return fail(c, LADDER_E_ARG, "rows must be positive");
   if ((long long)rows > (long long)c->cfg.max_batch * c->cfg.max_tokens) return fail(c, LADDER_E_SHAPE, "rows exceed max_batch * max_tokens");
-  HIP_TRY(c, launch_embed_gather(tokens, c->head_table, x_out, rows, c->cfg.hidden, c->vocab, c->bf16, c->main));
+  const int rc = check_device_error(c);
+  if (rc) return rc;
+  HIP_TRY(c, launch_embed_gather(tokens, c->head_table, x_out, rows, c->cfg.hidden, c->vocab, c->err_word_dev ? c->err_word_dev + 1 : nullptr, c->bf16, c->main));
   return LADDER_OK;
 }
 

@@ -105,3 +105,27 @@ def test_greedy_tie_takes_the_lowest_index_and_errors(harness):
         ctx.load_head(head["table"].to(DEV), head["final_norm"].to(DEV), head["w_lm"].to(DEV))   # twice
     assert e.value.code == ladder.LADDER_E_STATE
     ctx.free()
+
+
+def test_token_id_outside_the_table_is_reported_by_the_next_call(harness):
+    """ladder_embed never reads outside its table, and says so afterwards: the call that meets the bad id returns
+    LADDER_OK (it had only been enqueued); once its kernel has run, the next call reports LADDER_E_ARG once."""
+    w = TINY.with_(name="tiny_gen_oor", batch=2, prefill=4)
+    ctx, cfg, layers, oh = _setup(harness, w, 50)
+    good = torch.tensor([[1, 2, 3, 4], [5, 6, 7, 49]], dtype=torch.int32, device=DEV)
+    ctx.embed(good)
+    torch.cuda.synchronize()
+    ctx.embed(good)                                             # nothing to report
+    bad = torch.tensor([[1, 2, 50, 4], [5, -1, 7, 8]], dtype=torch.int32, device=DEV)
+    emb = ctx.embed(bad)                                        # rows of the nearest valid ids, no fault
+    torch.cuda.synchronize()
+    want = gen.embed(np.clip(bad.cpu().numpy(), 0, 49), oh["table"])
+    assert np.array_equal(emb.float().cpu().double().numpy(), want)
+    with pytest.raises(ladder.LadderError) as e:
+        ctx.prefill(emb)
+    assert e.value.code == ladder.LADDER_E_ARG and "token id" in str(e.value)
+    assert ctx.position() == (0, 0)
+    ctx.prefill(ctx.embed(good))                                # reported once; normal operation again
+    torch.cuda.synchronize()
+    assert ctx.position() == (4, 2)
+    ctx.free()
