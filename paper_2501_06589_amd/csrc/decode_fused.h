@@ -14,12 +14,12 @@ enum { EPI_SWIGLU = 1, EPI_RESIDUAL = 2, EPI_QKV_ROPE = 3 };
 // weight stream: the matrix core has the time.
 //
 // Layout of a split operand matrix of M rows (M = the batch of the step) and K columns, in the order the matrix
-// core reads it: the K range is cut into k tiles of 32; a k tile holds S row slots, S = fused_slots(M) = 8, 16
-// or 32: slots 0 .. S/2-1 the high parts of rows 0 .., slots S/2 .. S-1 their low parts; a slot's 32 values
+// core reads it: the K range is cut into k tiles of 32; a k tile holds S row slots, S = fused_slots(M) = 2, 4, 8,
+// 16 or 32 (twice the batch rounded up to a power of two; 32 from 9 rows on): slots 0 .. S/2-1 the high parts of rows 0 .., slots S/2 .. S-1 their low parts; a slot's 32 values
 // are stored as four groups of 8 (16 bytes: one lane's share of the MFMA operand), group-major:
 //     element (row r, part p, column k)  at  (k / 32) * S * 32 + (((k % 32) / 8) * S + r + p * S/2) * 8 + k % 8
-// A wavefront's load of a k tile is then S * 64 contiguous bytes (512 bytes for a batch of 4) instead of 16 bytes
-// from each of 2 M rows that lie K elements apart.  Every such matrix is allocated for S = 32 (K * 64 bytes).
+// A wavefront's load of a k tile is then S * 64 contiguous bytes (512 bytes for a batch of 4, 128 for a single
+// sequence) instead of 16 bytes from each of 2 M rows that lie K elements apart.  Every such matrix is allocated for S = 32 (K * 64 bytes).
 // The queries of the attention job are the exception: a split matrix in plain rows, bf16 [32][nq * d], rows
 // 0..15 the high parts, rows 16..31 (FUSED_LOW_ROW) the low parts.
 #define FUSED_LOW_ROW 16
@@ -28,7 +28,7 @@ enum { EPI_SWIGLU = 1, EPI_RESIDUAL = 2, EPI_QKV_ROPE = 3 };
 #else
 #define FUSED_HD
 #endif
-static inline FUSED_HD int fused_slots(int M) { return M <= 4 ? 8 : (M <= 8 ? 16 : 32); }
+static inline FUSED_HD int fused_slots(int M) { return M <= 1 ? 2 : (M <= 2 ? 4 : (M <= 4 ? 8 : (M <= 8 ? 16 : 32))); }
 // element offset of (row, column) of the HIGH part in a split operand matrix with S slots; the low part sits
 // (S / 2) * 8 elements further
 static inline FUSED_HD size_t fused_xop_offset(int S, int row, int col) {

@@ -116,10 +116,10 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
   for (int t = 0; t < TN; ++t) acc[t] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
   const u32x4_t* wptr = reinterpret_cast<const u32x4_t*>(wp) + ((size_t)nt0 * KT) * 64 + lane;
   // operand slot of this lane (decode_fused.h): WIDE: slot b = row b of the high parts, the low parts 16 slots
-  // further; up to 8 rows: slots 0..7 high, 8..15 low = lane b as it stands; up to 4 rows the k tile has 8 slots,
-  // 0..3 high, 4..7 low, and the lanes in between repeat them
-  const int S = WIDE ? 32 : (M <= 4 ? 8 : 16);
-  const int slot = (!WIDE && M <= 4) ? ((b & 3) | ((b & 8) >> 1)) : b;
+  // further; else the k tile has S = 2, 4, 8 or 16 slots, the first half high parts, the second half low parts:
+  // lanes 0..7 of a row of 16 take the high slots (repeating them when there are fewer than 8), lanes 8..15 the low ones
+  const int S = WIDE ? 32 : fused_slots(M);
+  const int slot = WIDE ? b : ((b & ((S >> 1) - 1)) + ((b & 8) ? (S >> 1) : 0));
   const int tile_stride = S * 32;                      // elements per k tile
   const bf16_t* xbp = xop + (q * S + slot) * 8;
   constexpr int low_off = 16 * 8;                      // WIDE: the low parts' slots
