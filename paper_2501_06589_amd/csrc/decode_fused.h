@@ -86,6 +86,9 @@ struct GemvJob {
   const bf16_t* peers;
   int n_peers;
   size_t peer_stride;
+  float* x_copy;           // EPI_RESIDUAL, optional: a second f32 copy of the new rows (the caller's x_out for the last module)
+  int* pos_inc;            // EPI_RESIDUAL, optional (last launch of a step, which holds no reader of the position): the
+                           // job's first workgroup advances the position by one at its end
   // EPI_QKV_ROPE: rotary on q and k (adjacent pairs), q -> q_out (split bf16 [32][nq*d]), k and v rounded to the
   // cache's storage type and appended at *pos_dev
   bf16_t* q_out;

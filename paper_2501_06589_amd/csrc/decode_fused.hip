@@ -342,6 +342,7 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
           if (p < j.n_peers) v += bf16_to_f32(pre_peer[e][p]);
         for (int p = PRE_PEERS; p < j.n_peers; ++p) v += bf16_to_f32(j.peers[p * j.peer_stride + (size_t)row * j.N + col]);
         j.x_new[(size_t)row * j.N + col] = v;
+        if (j.x_copy) j.x_copy[(size_t)row * j.N + col] = v;
         // what the modules that read x_m multiply: x_m times their norm's gain, split
         const size_t at = fused_xop_offset(S, row, col);
         if (j.xop_a) {
@@ -366,6 +367,7 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
       if (col16 == 0 && row < j.M && j.ssq_new) j.ssq_new[(size_t)(nt0 + t) * 16 + row] = s;
     }
     if (j.t_done && tid == 0) atomicMax(j.t_done, (unsigned long long)wall_clock64());   // (emulated collectives only)
+    if (j.pos_inc && lb == 0 && tid == 0) *j.pos_inc += 1;
     return;
   }
 

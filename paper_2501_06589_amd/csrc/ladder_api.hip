@@ -844,9 +844,33 @@ void build_fused_plan(ladder_ctx* c, int B) {
 }
 
 // one decode step on stream s: x_0 from `emb`, the launch list, x_2N left in ring[2N % 3]
-int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s) {
+// x_out (may be null): the caller's f32 [B][H], written by the last module's residual update itself; the same job
+// advances the position in device memory.  (Where an emulated collective still has to end after the last launch,
+// both are left to the caller of this function: the result must not appear before its collective is over.)
+int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s, float* x_out, bool* finished) {
   const ladder_config& g = c->cfg;
   if (c->fused_plan.empty() || c->fused_plan_batch != B || c->fused_plan_peers != c->peers) build_fused_plan(c, B);
+  *finished = false;
+  if (g.reduce_delay_us == 0) {
+    // the last launch's last residual job is the last module's (every launch list ends with it)
+    FusedArgs& last = c->fused_plan.back();
+    for (int k = last.n_jobs - 1; k >= 0; --k)
+      if (last.kind[k] == JOB_GEMV && last.g[k].epi == EPI_RESIDUAL && last.g[k].completes_stream == c->n_mod) {
+        bool reads_pos = false;
+        for (int q = 0; q < last.n_jobs; ++q) reads_pos = reads_pos || last.kind[q] == JOB_ATTN || (last.kind[q] == JOB_GEMV && last.g[q].epi == EPI_QKV_ROPE);
+        // (a residual job cut in parts: every part copies its rows, the first part advances the position)
+        const bool fold = x_out != nullptr && !reads_pos;
+        bool first = true;
+        for (int q = 0; q < last.n_jobs; ++q)
+          if (last.kind[q] == JOB_GEMV && last.g[q].epi == EPI_RESIDUAL && last.g[q].completes_stream == c->n_mod) {
+            last.g[q].x_copy = fold ? x_out : nullptr;
+            last.g[q].pos_inc = (fold && first) ? c->pos_dev : nullptr;
+            first = false;
+          }
+        *finished = fold;
+        break;
+      }
+  }
   auto events = [&](hipEvent_t (&e)[2]) -> hipError_t {
     e[0] = e[1] = nullptr;
     if (!c->prof) return hipSuccess;
@@ -926,7 +950,8 @@ int decode_graph_step(ladder_ctx* c, const void* x_in, void* x_out) {
     hipGraph_t graph = nullptr;
     DBG("capture: begin (batch %d)", B);
     HIP_TRY(c, hipStreamBeginCapture(c->s_attn, hipStreamCaptureModeThreadLocal));
-    int rc = c->fused ? fused_body(c, c->emb_stage, B, c->s_attn) : forward_body(c, c->emb_stage, B, 1, 0, nullptr);
+    bool finished = false;
+    int rc = c->fused ? fused_body(c, c->emb_stage, B, c->s_attn, nullptr, &finished) : forward_body(c, c->emb_stage, B, 1, 0, nullptr);
     DBG("capture: body recorded rc=%d", rc);
     if (rc == LADDER_OK) {
       DBG("capture: inc_pos");
@@ -966,11 +991,14 @@ int decode_fused_step(ladder_ctx* c, const void* x_in, void* x_out) {
   const int B = c->batch, H = c->cfg.hidden;
   int rc = fence_in(c);
   if (rc) return rc;
-  rc = fused_body(c, x_in, B, c->s_attn);
+  bool finished = false;
+  rc = fused_body(c, x_in, B, c->s_attn, (float*)x_out, &finished);
   if (rc) return rc;
-  HIP_TRY(c, hipMemcpyAsync(x_out, c->x_ring[c->n_mod % 3], (size_t)B * H * 4, hipMemcpyDeviceToDevice, c->s_attn));
-  hipLaunchKernelGGL(inc_pos_kernel, dim3(1), dim3(1), 0, c->s_attn, c->pos_dev);
-  HIP_TRY(c, hipGetLastError());
+  if (!finished) {   // (the last launch has not delivered the result and advanced the position itself)
+    HIP_TRY(c, hipMemcpyAsync(x_out, c->x_ring[c->n_mod % 3], (size_t)B * H * 4, hipMemcpyDeviceToDevice, c->s_attn));
+    hipLaunchKernelGGL(inc_pos_kernel, dim3(1), dim3(1), 0, c->s_attn, c->pos_dev);
+    HIP_TRY(c, hipGetLastError());
+  }
   return fence_out(c);
 }
 
