@@ -80,6 +80,28 @@ __device__ __forceinline__ float other_half(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128 /* row_ror:8 */, 0xF, 0xF, false));
 }
 
+// Cross-lane sums on the DPP path of the vector ALU (a __shfl_xor goes through the LDS crossbar instead: some
+// sixty cycles each, in a dependent chain).  All 64 lanes must be active.
+template <int CTRL>
+__device__ __forceinline__ float dpp_read(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+// every lane: the sum over its row of 16 lanes (neighbour, other pair, other quad of 8 mirrored, other half mirrored)
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_read<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_read<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_read<0x141>(v);   // row_half_mirror
+  v += dpp_read<0x140>(v);   // row_mirror
+  return v;
+}
+// every lane: the sum over the wavefront, rows added in the order 0, 1, 2, 3
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+  v = row16_sum(v);
+  const int i = __float_as_int(v);
+  return __int_as_float(__builtin_amdgcn_readlane(i, 0)) + __int_as_float(__builtin_amdgcn_readlane(i, 16)) +
+         __int_as_float(__builtin_amdgcn_readlane(i, 32)) + __int_as_float(__builtin_amdgcn_readlane(i, 48));
+}
+
 // ------------------------------------------------------------------------------------------------
 // skinny GEMM job: see gemv_mfma_kernel for the streaming scheme (same tiles, same pipeline).
 // A workgroup owns TN adjacent 16-column tiles and the whole K range; U k-tiles per register buffer.
@@ -255,7 +277,8 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
   }
 
   if (kt0 < kt1) {
-    for (int kt = kt0; kt < kt1; kt += KA) {
+    int kt = kt0;
+    for (; kt + KA < kt1; kt += KA) {   // full turns: both register buffers are requested again
       load(wb, xb, kt + KB);
       __builtin_amdgcn_sched_barrier(0);
       fma(wa, xa, kt);
@@ -265,6 +288,15 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
       fma(wb, xb, kt + KB);
       __builtin_amdgcn_sched_barrier(0);
     }
+    // The wavefront's last turn requests nothing beyond its range: a load left in flight here (even one clamped
+    // onto the last tile, which the caches serve) is waited for by whatever the epilogue reads first, a memory
+    // round trip at the end of every workgroup.
+    const bool second = kt + KB < kt1;   // (uniform over the wavefront)
+    if (second) load(wb, xb, kt + KB);
+    __builtin_amdgcn_sched_barrier(0);
+    fma(wa, xa, kt);
+    __builtin_amdgcn_sched_barrier(0);
+    if (second) fma(wb, xb, kt + KB);
   }
 
   // cross-wave sums through LDS: red[wave][tile][col in tile][operand column], ssq[wave][row]
@@ -285,7 +317,7 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
         const float4 t4 = *reinterpret_cast<const float4*>(j.ssq + (size_t)tile * 16 + rq * 4);
         v.x += t4.x; v.y += t4.y; v.z += t4.z; v.w += t4.w;
       }
-      v.x = wave_sum(v.x); v.y = wave_sum(v.y); v.z = wave_sum(v.z); v.w = wave_sum(v.w);
+      v.x = wave_sum_dpp(v.x); v.y = wave_sum_dpp(v.y); v.z = wave_sum_dpp(v.z); v.w = wave_sum_dpp(v.w);
       if (lane == 0) {
         float* dst = ssq + wave * 16 + rq * 4;
         dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
@@ -359,11 +391,7 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
         }
       }
       // the row's sum of squares over this tile's 16 columns (the 16 lanes that share t and row)
-      float s = v * v;
-      s += __shfl_xor(s, 1, 64);
-      s += __shfl_xor(s, 2, 64);
-      s += __shfl_xor(s, 4, 64);
-      s += __shfl_xor(s, 8, 64);
+      const float s = row16_sum(v * v);
       if (col16 == 0 && row < j.M && j.ssq_new) j.ssq_new[(size_t)(nt0 + t) * 16 + row] = s;
     }
     if (j.t_done && tid == 0) atomicMax(j.t_done, (unsigned long long)wall_clock64());   // (emulated collectives only)
@@ -440,7 +468,8 @@ __device__ __forceinline__ float ld_coherent(const float* p) {
 __device__ __forceinline__ void st_coherent_split_pair(bf16_t* hi_at, bf16_t* lo_at, int i, float v) {
   uint32_t h, l;
   split_bf16(v, h, l);
-  const uint32_t oh = __shfl_xor(h, 1, 64), ol = __shfl_xor(l, 1, 64);
+  const uint32_t oh = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)h, 0xB1, 0xF, 0xF, false);   // the neighbour lane's (quad_perm [1,0,3,2])
+  const uint32_t ol = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)l, 0xB1, 0xF, 0xF, false);
   if ((i & 1) == 0) {
     st_coherent(reinterpret_cast<uint32_t*>(hi_at), h | (oh << 16));
     st_coherent(reinterpret_cast<uint32_t*>(lo_at), l | (ol << 16));
