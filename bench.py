@@ -131,7 +131,7 @@ def run_decode(args):
     ctx = build_context(w, dev, total_steps, w.batch * max(w.prefill, 1), max_tokens=max(w.prefill, 1),
                         decode_graph=1 if args.graph else 0, overlap_modules=0 if args.no_overlap else 1,
                         decode_fused=0 if args.no_fused else (2 if args.fused_plan == "single" else 1),
-                        reduce_delay_us=args.reduce_delay_us,
+                        reduce_delay_us=args.reduce_delay_us, n_standard_layers=args.standard_layers,
                         wiring={"ladder": ladder.LADDER_WIRING_LADDER, "standard": ladder.LADDER_WIRING_STANDARD,
                                 "parallel": ladder.LADDER_WIRING_PARALLEL}[args.wiring])
     # the cache as it stands before the first decode step: a synthetic one (kept, so that every timed region can
@@ -349,6 +349,9 @@ def main():
     ap.add_argument("--no-overlap", action="store_true", help="one compute stream instead of attention / MLP streams")
     ap.add_argument("--wiring", choices=["ladder", "standard", "parallel"], default="ladder",
                     help="residual wiring of the stack (the metric is quoted on ladder; standard is the paper's Eq. 1 baseline)")
+    ap.add_argument("--standard-layers", type=int, default=0,
+                    help="hybrid stack: with --wiring ladder, the lower N layers keep the standard wiring (the paper's "
+                         "Hybrid-Ladder-8B-16L is --workload 8b --standard-layers 16)")
     ap.add_argument("--no-peers", action="store_true",
                     help="no synthetic peer partial sums: with the standard wiring and no emulated latency this is the "
                          "communication-free upper bound of the paper's comparison (result is then not the metric)")

@@ -764,10 +764,22 @@ void build_fused_plan(ladder_ctx* c, int B) {
 
   std::vector<FusedArgs>& plan = c->fused_plan;
   plan.clear();
-  const bool all_ladder = g.wiring == LADDER_WIRING_LADDER && g.n_standard_layers == 0;
   const bool paired = g.decode_fused == 1;   // (2: one job per launch whatever the wiring)
-  if (all_ladder && paired) {
-    // modules 1 and 2 both read x_0; then TWO launches per layer:
+  // layers with the standard wiring come first (all of them under LADDER_WIRING_STANDARD, the lower ones of a hybrid stack)
+  const int n_std = g.wiring == LADDER_WIRING_STANDARD ? N : g.n_standard_layers;
+  if (g.wiring != LADDER_WIRING_PARALLEL && paired) {
+    // Standard layers: the chain of Eq. 1 leaves nothing to pair, one job per launch.  The last standard layer's down
+    // projection shares its launch with the first ladder layer's QKV projection, which reads x_{2 n_std - 1}.
+    for (int l = 1; l <= n_std; ++l) {
+      plan.push_back(one(job_qkv(l, src_of(2 * l - 1))));
+      plan.push_back(att(job_att(l), {}));
+      plan.push_back(one(job_o(l, 2 * l - 1)));
+      plan.push_back(one(job_gu(l, src_of(2 * l))));
+      if (l == n_std && n_std < N) plan.push_back(qkv_down(job_qkv(n_std + 1, src_of(2 * n_std + 1)), job_dn(n_std, 2 * n_std)));
+      else plan.push_back(one(job_dn(l, 2 * l)));
+    }
+    // Ladder layers.
+    // Modules 1 and 2 both read x_0; then TWO launches per layer:
     //     { attention_l , gate/up_l , o_l }     { qkv_{l+1} , down_l }
     // Attention and gate/up, and the next layer's QKV and down, do not depend on each other under the
     // ladder wiring.  The attention workgroups are few and latency bound: beside the largest weight stream
@@ -780,8 +792,8 @@ void build_fused_plan(ladder_ctx* c, int B) {
     // coherent loads made the step 5.1 ms (an agent-scope acquire empties the L2 under the weight streams);
     // o_l at the end of the launch instead of among the first workgroups 4.1 ms (it then runs after
     // gate/up, not beside it); cutting gate/up over two launches 4.1 - 4.6 ms.
-    plan.push_back(one(job_qkv(1, 0)));
-    for (int l = 1; l <= N; ++l) {
+    if (n_std == 0) plan.push_back(one(job_qkv(1, 0)));
+    for (int l = n_std + 1; l <= N; ++l) {
       AttnJob aj = job_att(l);
       aj.done = c->att_done + (l - 1);
       GemvJob o = job_o(l, 2 * l - 1);

@@ -230,8 +230,9 @@ def test_emulated_latency_on_the_fused_schedule(harness, wiring, nstd):
     for plan in (1, 2):
         base = harness.run_case(w, gpu_only=True, decode_fused=plan, **kw)
         late = harness.run_case(w, gpu_only=True, decode_fused=plan, reduce_delay_us=200, **kw)
-        for x, y, z in zip(base.gpu, late.gpu, ref.gpu):
-            assert np.array_equal(x, y)
+        replay = harness.run_case(w, gpu_only=True, decode_fused=plan, reduce_delay_us=200, decode_graph=1, **kw)   # captured step
+        for x, y, r, z in zip(base.gpu, late.gpu, replay.gpu, ref.gpu):
+            assert np.array_equal(x, y) and np.array_equal(x, r)
             assert np.max(np.abs(x - z)) <= 1e-3 * np.sqrt(np.mean(z * z))      # (the two launch lists sum in different orders)
     # the waits are there: kernel time of a step with and without them (paired launch list)
     tensors = harness.make_tensors(w)

@@ -73,6 +73,16 @@ def test_full_depth_decode_batch4_strict(harness, name):
     assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
 
 
+def test_8b_hybrid_ladder_upper_16_layers_full_depth_strict(harness):
+    """The paper's deployable variant on the Llama-3.1-8B shape: the lower 16 layers keep the standard wiring,
+    the upper 16 are ladder layers (the Hybrid-Ladder-8B-16L variant of the paper's adaptation experiment; at the
+    switch one stream feeds a standard and a ladder module).  Full depth, batch 4, two decode steps over a synthetic cache of 2048 positions, stated tolerance."""
+    w0 = inputs.WORKLOADS["8b"]
+    w = w0.with_(name="8b_hybrid16_b4", batch=4, prefill=0, kv_preload=w0.prefill, decode_steps=2)
+    res = harness.run_case(w, kv_preload=w.kv_preload, gen_device="cuda:0", n_standard_layers=16)
+    assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
+
+
 def test_70b_r4_prefill_one_layer_all_16_sequences(harness):
     """The prefill workload's call at full size (16 sequences x 2048 tokens = 32768 rows, hidden 8192, 16 q / 2 kv
     heads, intermediate 7168, 3 synthetic peers), one layer: every one of the 2.7e8 outputs against the oracle,
