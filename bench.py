@@ -130,7 +130,7 @@ def run_decode(args):
     # the peer tensor must hold as many rows per set as the configuration announces (peer_rows)
     ctx = build_context(w, dev, total_steps, w.batch * max(w.prefill, 1), max_tokens=max(w.prefill, 1),
                         decode_graph=1 if args.graph else 0, overlap_modules=0 if args.no_overlap else 1,
-                        decode_fused=0 if args.no_fused else (2 if args.fused_plan == "single" else 1),
+                        decode_fused=0 if args.no_fused else {"paired": 1, "single": 2, "chain": 3}[args.fused_plan],
                         reduce_delay_us=args.reduce_delay_us, n_standard_layers=args.standard_layers,
                         wiring={"ladder": ladder.LADDER_WIRING_LADDER, "standard": ladder.LADDER_WIRING_STANDARD,
                                 "parallel": ladder.LADDER_WIRING_PARALLEL}[args.wiring])
@@ -360,7 +360,7 @@ def main():
                          "the known-size dispatches that scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--reduce-delay-us", type=int, default=0,
                     help="emulated all-reduce latency: every collective takes this long before the stream it completes may be read")
-    ap.add_argument("--fused-plan", choices=["paired", "single"], default="paired",
+    ap.add_argument("--fused-plan", choices=["paired", "single", "chain"], default="paired",
                     help="fused decode schedule: paired = independent jobs of neighbouring modules share a launch (default); "
                          "single = one job per launch (five per layer), which leaves each collective a module to hide behind")
     ap.add_argument("--head", action="store_true",

@@ -101,6 +101,12 @@ typedef struct {
                              share one launch where the wiring leaves them independent (ladder: two launches per
                              layer; parallel block: three); 2: one job per launch whatever the wiring (five per
                              layer), which leaves every collective a whole module to hide behind;
+                             3: the launch list of 1 as ONE launch per step (a "chained" step): persistent
+                             workgroups run the list's blocks in turn, and a module starts when the modules whose
+                             streams it reads (x_{m-2} and x_{m-1} of Algorithm 1) have raised their completion
+                             flags, not when a launch has ended; same arithmetic in the same order, same bits.
+                             It keeps one buffer per stream x_m and per layer (about 3.4 KB x hidden x n_layers
+                             more workspace at 16 rows; ladder_workspace_bytes counts it);
                              0: one kernel per operation */
   int32_t reduce_delay_us; /* emulated all-reduce latency (Fig. 2 / Table 2 of the paper vary the interconnect), 0 .. 10000.
                               Fused decode schedule: the collective that completes x_m starts when the launch
@@ -265,6 +271,30 @@ size_t ladder_weight_bytes(const ladder_config* cfg);
  * the waiting workgroups store nothing, every kernel still ends normally, and the NEXT ladder_decode_step /
  * ladder_prefill returns LADDER_E_HIP.  (1 << 20, 0) restores normal operation.  Errors: LADDER_E_ARG. */
 int ladder_set_wait_limit(ladder_ctx* ctx, int32_t max_polls, int32_t target_bias);
+
+/* Timeline of a chained decode step (decode_fused = 3), for measurement.  A chained step is one launch of
+ * persistent workgroups ("slots") that run the blocks of the step's launch list in turn (the modules of
+ * Algorithm 1 in their order, each starting when the streams it reads are complete), so events around the launch
+ * say nothing about its parts.  With the timeline on, every slot records for every block the device wall-clock
+ * time at which it took the block (and requested its first weight tiles), at which the block's inputs were
+ * complete, and at which the block ended; ladder_timeline_read returns the records of the last step.
+ *   out / cap   caller's array (host) and its capacity; *n_out receives the number of records of the step (call
+ *               with out = NULL to size the array); records beyond cap are not written.
+ *   ticks_per_us  receives the rate of the clock the times are in (may be NULL).
+ * Recording changes no result; it costs three stores per block.
+ * Errors: LADDER_E_STATE if the context does not run chained steps, replays captured steps (decode_graph = 1), or
+ * has recorded nothing yet; LADDER_E_ARG on NULL; LADDER_E_HIP if the recording buffer cannot be allocated. */
+typedef struct ladder_timeline_rec {
+  int32_t slot;          /* persistent workgroup */
+  int32_t launch;        /* index of the block's launch in the step's launch list */
+  int32_t kind;          /* LADDER_TL_* */
+  int32_t tiles;         /* 16-column weight tiles of the block (projections; 0 for attention) */
+  int64_t weight_bytes;  /* weight bytes the block streams */
+  uint64_t t_take, t_ready, t_end;
+} ladder_timeline_rec;
+enum { LADDER_TL_ATTN = 0, LADDER_TL_QKV = 1, LADDER_TL_O = 2, LADDER_TL_GATE_UP = 3, LADDER_TL_DOWN = 4 };
+int ladder_timeline_enable(ladder_ctx* ctx, int32_t on);
+int ladder_timeline_read(ladder_ctx* ctx, ladder_timeline_rec* out, int64_t cap, int64_t* n_out, double* ticks_per_us);
 
 /* Per-kernel timing for measurement.  With profiling on, every kernel launch is bracketed by HIP
  * events on the stream it is launched on; ladder_profile_read synchronises, folds the events

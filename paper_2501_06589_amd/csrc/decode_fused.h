@@ -49,16 +49,32 @@ struct GemvJob {
   const float* ssq;
   int reads_stream;        // host-side note: normed jobs read the stream x_m with this m (the kernel does not use it)
   int completes_stream;    // host-side note: a residual job after which the stream x_m is complete (a collective ends there): that m; else 0
+  int after_attention;     // host-side note: the output projection of an attention module (its operand is the attention job's output)
   const void* wp;
   int M, K, N;
   // wait_on != null: the job's x operand is produced by the attention job of the SAME launch; the
-  // workgroup starts by waiting (bounded: wait_spins polls) until *wait_on has reached wait_target, then reads
-  // that operand with device-coherent loads.  If the wait gives up, the workgroup stores nothing and raises
-  // *err_word (host-visible memory), which the next call of the library reports.
+  // workgroup starts by waiting (bounded: wait_spins polls) for the flag of that job's completion words (wait_on,
+  // FUSED_SYNC_WORDS words), then reads that operand with device-coherent loads.  If the wait gives up, the
+  // workgroup stores nothing and raises *err_word (host-visible memory), which the next call of the library reports.
   const unsigned* wait_on;
-  unsigned wait_target;
+  unsigned wait_bias;
   int wait_spins;
   unsigned* err_word;
+  // Chained step (one launch for the whole decode step): every job waits for the jobs that produce what it reads.
+  // wait_on (above) then is the flag (or, for the attention job's output, the arrival counter) of the producer
+  // of the x operand, wait_on2 that of the producer of x_old where that is another job; operands whose producer
+  // is a projection are read with ordinary loads after the wait (each such buffer is written once per launch and
+  // read by nobody before, so no cache of the chip holds an older copy of it).
+  // done_ctr != null: this job is a producer.  Its workgroups write their results with device-coherent stores,
+  // wait for them and count themselves at done_ctr (FUSED_SYNC_WORDS words); done_target = the workgroups of the
+  // whole projection (its jobs share done_ctr), done_ord0 = the ordinal of this job's first workgroup among them.
+  // wait_on / wait_on2 point at such words of a producer (the job polls their flag); wait_bias is added to the
+  // value the flag must reach (0; a test makes the wait fail with it).
+  const unsigned* wait_on2;
+  int coherent_x;          // chained step: the x operand is read with device-coherent loads (a buffer that is written more than once per launch)
+  unsigned* done_ctr;
+  unsigned done_target;
+  unsigned done_ord0;
   // Emulated collective latency (both null / 0 in normal operation).  t_ready: the job reads a stream whose
   // collective ends delay_ticks (wall clock) after the time stored there by an earlier launch; its workgroups
   // hold back until then (bounded).  t_done: every workgroup of this (residual) job leaves the time it ended there
@@ -115,10 +131,21 @@ struct AttnJob {
   int B, nq, nkv, max_seq;
   int n_splits, split_len; // split s covers positions [s*split_len, (s+1)*split_len); split_len % 64 == 0
   const int* pos_dev;      // position of the new token; positions 0..*pos_dev are visible
-  unsigned* done;          // if non-null: incremented by the workgroup that has written the final output of its
-                           // (sequence, kv head), once its device-coherent stores have completed; a projection
-                           // job of the same launch waits on it
+  unsigned* done;          // if non-null: completion words (FUSED_SYNC_WORDS) at which the workgroup that has written the
+                           // final output of its (sequence, kv head) counts itself, once its device-coherent stores
+                           // have completed; a projection job of the same launch waits on them
+  // chained step: the job starts by waiting (bounded) for the flag of the completion words at wait_on: those of the
+  // QKV projection that writes q and appends to the cache
+  const unsigned* wait_on;
+  unsigned wait_bias;
+  int wait_spins;
+  unsigned* err_word;
 };
+
+// completion words of one producer (a projection, the attention job of a layer): 10 cache lines of 32 words
+// (sub-counters 0..7, the top counter, the flag that consumers poll); zero at the start of every step
+#define FUSED_SYNC_WORDS 320
+#define FUSED_SYNC_FLAG_WORD 288
 
 #define FUSED_MAX_LDS_BYTES (72 * 1024)
 #define FUSED_MAX_JOBS 4
@@ -133,6 +160,34 @@ struct FusedArgs {
 };
 
 hipError_t launch_fused_decode(const FusedArgs& fa, int d, int g, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+
+// Chained step: ONE launch of persistent workgroups runs the whole list of launches of a step.  Workgroup w of the
+// launch (a "slot") runs the blocks w, w + n_slots, ... of every launch of the list in turn; a job starts when the
+// jobs it reads from have raised their flags.  An item is what a workgroup needs to request its first weight tiles
+// before the job's descriptor has arrived from memory.
+struct StepItem {
+  const void* wp;          // GEMV job: the job's weights
+  const bf16_t* xb;        //           and operand
+  uint16_t kt;             // K / 32
+  uint16_t group0;
+  uint16_t lb;             // block index within the job
+  uint16_t job;            // index into the GEMV or the attention job table
+  uint8_t kind;            // descriptor byte: JOB_* | (tiles per workgroup - 1) << 2 | coherent operand loads << 5; 0 ends the list
+  uint8_t M;
+  uint16_t pad0;
+  uint32_t pad1;
+};
+// the item of block lb of a job; hipErrorInvalidValue if the job is outside what the kernel has code for
+hipError_t fused_chain_item(const GemvJob& j, int job_index, int lb, StepItem* out);
+hipError_t fused_chain_attn_item(const AttnJob& a, int job_index, int lb, StepItem* out);
+// persistent workgroups that are resident together on a device of n_cu compute units (0: the kernel does not fit)
+int fused_chain_slots(int d, int g, int n_cu);
+// items: [n_slots][n_items] (device), each slot's list ended by an item of kind 0 (n_items includes it)
+// timeline (null in normal operation): u64 [n_slots][n_items][3], the wall-clock times at which a slot took an item,
+// had waited for its inputs, and had finished it
+hipError_t launch_fused_chain(const StepItem* items, int n_items, const GemvJob* gemv_jobs, const AttnJob* attn_jobs,
+                              float* x_out, unsigned long long* timeline, int n_slots, int lds_bytes, int d, int g,
+                              hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t fused_decode_prepare(int d, int g);   // once per context, before the first launch
 size_t fused_attn_lds_bytes(int d, int g);
 size_t fused_gemv_lds_bytes();

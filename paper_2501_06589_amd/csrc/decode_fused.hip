@@ -53,8 +53,21 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 // k tiles per register buffer (two buffers) of a one-tile / a two-tile workgroup: 4 KiB of weights in flight
 // per wavefront.  With the round-robin assignment of k tiles below, 2 beat 4 (3.57 against 3.65 ms per step;
 // 1 gave 4.04, 3 gave 3.74: its turns do not divide the k range)
+#ifndef FUSED_U
 #define FUSED_U 2
+#endif
+#ifndef FUSED_U2
 #define FUSED_U2 1
+#endif
+#ifndef FUSED_U3
+#define FUSED_U3 1
+#endif
+#ifndef FUSED_U4
+#define FUSED_U4 1
+#endif
+#ifndef FUSED_POLL_SLEEP
+#define FUSED_POLL_SLEEP 8
+#endif
 #define FUSED_LDS_FLOATS 9216   // attention job: per-wave statistics and outputs
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -69,15 +82,29 @@ __device__ __forceinline__ void unpack8f(const uint4 v, float f[8]) {
 }
 
 // v as two bf16 numbers: hi = bf16(v), lo = bf16(v - hi); hi + lo carries 16 significant bits of v
+// (the subtraction is kept out of fused multiply-adds: where v is a product, fma(a, b, -hi) would take the low part
+// from the unrounded product, and whether the compiler forms it depends on the code around the call)
 __device__ __forceinline__ void split_bf16(float v, uint32_t& hi, uint32_t& lo) {
+#pragma clang fp contract(off)
   hi = f32_to_bf16(v);
-  lo = f32_to_bf16(v - __uint_as_float(hi << 16));
+  const float rest = v - __uint_as_float(hi << 16);
+  lo = f32_to_bf16(rest);
 }
 
 // the value that lane ^ 8 holds (DPP rotation by 8 within each row of 16 lanes): joins the two halves of a split
 // operand's result, whose high parts sit in operand columns 0..7 and low parts in columns 8..15
 __device__ __forceinline__ float other_half(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128 /* row_ror:8 */, 0xF, 0xF, false));
+}
+
+// The thread index as a value the compiler knows nothing about.  A job is inlined into a loop over a
+// workgroup's jobs (chained step): everything derived from the plain thread index is loop invariant, and the
+// compiler would compute the LDS addresses and lane masks of every job variant ahead of the loop and keep them
+// in private memory.
+__device__ __forceinline__ int opaque_tid() {
+  int t = (int)threadIdx.x;
+  asm volatile("" : "+v"(t));
+  return t;
 }
 
 // Cross-lane sums on the DPP path of the vector ALU (a __shfl_xor goes through the LDS crossbar instead: some
@@ -102,6 +129,76 @@ __device__ __forceinline__ float wave_sum_dpp(float v) {
          __int_as_float(__builtin_amdgcn_readlane(i, 32)) + __int_as_float(__builtin_amdgcn_readlane(i, 48));
 }
 
+// Device-coherent stores / loads (agent-scope relaxed atomics: written through to memory, read past the caches
+// that are not coherent across the chip) for the few values one workgroup hands to another inside a launch.
+// A producer waits until its coherent stores have completed (s_waitcnt) before it takes a ticket or raises a
+// counter; a consumer reads the data with coherent loads after it has seen the ticket or the counter.  No
+// fence on either side: an agent-scope release writes back, and an acquire invalidates, the whole L2 of the XCD
+// under the weight streams that run beside (1.2 - 2.5 us each on this path).
+__device__ __forceinline__ void st_coherent(uint32_t* p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coherent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coherent(bf16_t* p, bf16_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_coherent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// stores a split value whose high part belongs at hi_at and whose low part at lo_at, for an element with an even
+// index i whose neighbour i ^ 1 lies right behind it: lanes i and i ^ 1 pair up for one 32-bit coherent store
+// each (all lanes of the wave must call; ok = this pair is to be stored, the same on both of its lanes)
+__device__ __forceinline__ void st_coherent_split_pair(bf16_t* hi_at, bf16_t* lo_at, int i, float v, bool ok = true) {
+  uint32_t h, l;
+  split_bf16(v, h, l);
+  const uint32_t oh = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)h, 0xB1, 0xF, 0xF, false);   // the neighbour lane's (quad_perm [1,0,3,2])
+  const uint32_t ol = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)l, 0xB1, 0xF, 0xF, false);
+  if ((i & 1) == 0 && ok) {
+    st_coherent(reinterpret_cast<uint32_t*>(hi_at), h | (oh << 16));
+    st_coherent(reinterpret_cast<uint32_t*>(lo_at), l | (ol << 16));
+  }
+}
+
+// Completion words of a producer (a projection, or the attention job of a layer): FUSED_SYNC_WORDS words = ten cache
+// lines: eight sub-counters, a top counter, and the flag that the consumers poll.  A producer workgroup whose
+// coherent stores have completed counts itself; the one that completes the count raises the flag.  Hundreds of
+// atomics on ONE line queue up behind each other, and behind the loads of whoever polls that line (microseconds
+// for a whole projection): so the workgroups of a large producer count on eight lines by their ordinal, the last of
+// each line on the ninth, and nobody polls a line that is counted on.  (Measured against counting without waiting
+// for the atomics' results and letting every consumer poll all eight counters: that made every hand-off 2 - 3 us
+// longer, the polls of 512 workgroups on eight lines being traffic of their own.)
+__device__ __forceinline__ void sync_count(unsigned* words, unsigned ordinal, unsigned total) {
+  bool last;
+  if (total > 16u) {
+    const unsigned k = ordinal & 7u;
+    const unsigned n_k = (total + 7u - k) >> 3;   // workgroups with this ordinal mod 8
+    last = atomicAdd(words + 32u * k, 1u) == n_k - 1u && atomicAdd(words + 32u * 8u, 1u) == 7u;
+  } else {
+    last = atomicAdd(words + 32u * 8u, 1u) == total - 1u;
+  }
+  if (last) __hip_atomic_store(words + FUSED_SYNC_FLAG_WORD, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// lane 0 of a wavefront polls the first producer's flag, lane 1 the second's (or the first's again): true once both
+// are up (bias: a test's way of making the wait fail), false after `spins` polls (all 64 lanes must call)
+__device__ __forceinline__ bool sync_wait(const unsigned* w1, const unsigned* w2, unsigned bias, int spins, int lane) {
+  const unsigned* const word = ((lane & 1) ? w2 : w1) + FUSED_SYNC_FLAG_WORD;
+  for (int spin = 0; spin < spins; ++spin) {
+    const unsigned v = lane < 2 ? __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ~0u;
+    if (__all(v >= 1u + bias)) return true;
+    __builtin_amdgcn_s_sleep(FUSED_POLL_SLEEP);
+  }
+  return false;
+}
+// A producer job of a chained step: the workgroup's coherent stores have completed, count it.
+__device__ __forceinline__ void gemv_signal_done(const GemvJob& j, int lb) {
+  if (!j.done_ctr) return;
+  __builtin_amdgcn_s_waitcnt(0);   // this thread's coherent stores have completed
+  __syncthreads();
+  if (threadIdx.x == 0) sync_count(j.done_ctr, j.done_ord0 + (unsigned)lb, j.done_target);
+}
+
 // ------------------------------------------------------------------------------------------------
 // skinny GEMM job: see gemv_mfma_kernel for the streaming scheme (same tiles, same pipeline).
 // A workgroup owns TN adjacent 16-column tiles and the whole K range; U k-tiles per register buffer.
@@ -116,13 +213,21 @@ __device__ __forceinline__ float wave_sum_dpp(float v) {
 // else one: lanes 0..7 of a row of 16 carry the high parts of rows 0..7, lanes 8..15 their low parts.
 // Operand columns beyond the rows in use hold whatever their slots hold (finite): a column of the operand only
 // reaches its own column of the result, which nobody reads.
-template <int U, int TN, bool COH, bool WIDE>
-__device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const bf16_t* xop, int KT, int group0, int M, int lb,
-                                         float* smem, unsigned* s_flag) {
+// CHAIN: the job is part of a chained step: other jobs of the same launch read what it writes, so the results go
+// out with device-coherent stores (else: ordinary stores, the launch's end publishes them), and it may be waiting for
+// any of its inputs, so the operand is requested behind the waits (else, unless COH: at once, with the weights).
+// x_out: where a job with x_copy set leaves its second copy of the new rows, if not null (the chained step hands the
+// caller's buffer over as a kernel argument; else x_copy itself is the place).  t_ready: if not null, thread 0
+// leaves the wall-clock time there at which the job's waits were over.
+// Returns false if a wait gave up (nothing stored, error word raised).
+template <int U, int TN, bool COH, bool WIDE, bool CHAIN>
+__device__ __forceinline__ bool gemv_job(const GemvJob& j, const void* wp, const bf16_t* xop, int KT, int group0, int M, int lb,
+                                         float* smem, unsigned* s_flag, float* x_out, unsigned long long* t_ready) {
+  constexpr bool EARLY_X = !COH && !CHAIN;
   constexpr int WAVES = FUSED_WAVES;
   constexpr int XP = WIDE ? 2 : 1;   // operand registers per k tile
   const int grp = group0 + lb;
-  const int tid = threadIdx.x;
+  const int tid = opaque_tid();
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int b = lane & 15, q = lane >> 4;
   const int nt0 = grp * TN;
@@ -178,44 +283,72 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
   };
   // the first tiles depend on nothing but the (preloaded) arguments: requested before anything else; the operand
   // of a job that waits for its producer only behind the wait
+  // both register buffers
   if (kt0 < kt1) loadw(wa, kt0);
-  if (!COH && kt0 < kt1) loadx(xa, kt0);
+  if (kt0 + KB < kt1) loadw(wb, kt0 + KB);
+  if (EARLY_X && kt0 < kt1) loadx(xa, kt0);
+  if (EARLY_X && kt0 + KB < kt1) loadx(xb, kt0 + KB);
   __builtin_amdgcn_sched_barrier(0);
 
   if (j.wait_on) {
-    // The x operand comes from the attention job of this launch.  Its workgroups have lower block indices,
-    // so they were dispatched before this one and wait for nothing: the counter always arrives.  The wait is
-    // bounded all the same, so that the kernel ends whatever happens; a workgroup whose wait gives up stores
+    // What the job reads comes from other jobs of this launch.  A workgroup only waits for workgroups that come
+    // before it in the launch's order and that wait, in turn, only for earlier ones: the words always arrive.  The
+    // wait is bounded all the same, so that the kernel ends whatever happens; a workgroup whose wait gives up stores
     // nothing and raises the error word, which the host reads at the library's next call.
-    if (tid == 0) {
-      unsigned arrived = 0u;
-      for (int spin = 0; spin < j.wait_spins; ++spin) {
-        if (__hip_atomic_load(j.wait_on, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= j.wait_target) { arrived = 1u; break; }
-        __builtin_amdgcn_s_sleep(16);
+    if (wave == 0) {
+      const bool arrived = sync_wait(j.wait_on, j.wait_on2 ? j.wait_on2 : j.wait_on, j.wait_bias, j.wait_spins, lane);
+      if (lane == 0) {
+        *s_flag = arrived ? 1u : 0u;
+        if (!arrived && j.err_word) __hip_atomic_store(j.err_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
       }
-      *s_flag = arrived;
-      if (!arrived && j.err_word) __hip_atomic_store(j.err_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
-    __syncthreads();   // (workgroup-scope ordering; the operand itself is read with device-coherent loads, so no
-                       // cache invalidation is needed: an agent-scope acquire per workgroup would flush the L2
-                       // under the weight streams that run beside)
-    if (*s_flag == 0u) return;
+    __syncthreads();   // (workgroup-scope ordering.  No cache invalidation: the attention output is read with
+                       // device-coherent loads, and what a projection of the same launch has written is in no cache
+                       // of this XCD yet, having been read by nobody before; an agent-scope acquire per workgroup
+                       // would flush the L2 under the weight streams that run beside)
+    if (*s_flag == 0u) return false;
   }
 
   if (j.t_ready) {
     // emulated collective: the stream this job reads counts as reduced delay_ticks after the time its producer
     // left; a wait on the clock alone (it ends whatever other workgroups do), bounded all the same
     if (tid == 0) {
-      const unsigned long long t1 = *j.t_ready + j.delay_ticks;
+      const unsigned long long t1 = __hip_atomic_load(j.t_ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + j.delay_ticks;
       for (int spin = 0; spin < (1 << 20); ++spin) {
         if (wall_clock64() >= t1) break;
-        __builtin_amdgcn_s_sleep(8);
+        __builtin_amdgcn_s_sleep(FUSED_POLL_SLEEP);
       }
     }
     __syncthreads();
   }
 
-  if (COH && kt0 < kt1) loadx(xa, kt0);
+  if (t_ready && tid == 0) *t_ready = wall_clock64();
+  if (!EARLY_X && kt0 < kt1) loadx(xa, kt0);
+  if (!EARLY_X && kt0 + KB < kt1) loadx(xb, kt0 + KB);
+  // results: coherent stores in a chained step (a split value's two halves as 32-bit stores of a column pair, all
+  // lanes of the wavefront taking part), ordinary stores else
+  auto store_f32 = [&](float* p, float v) {
+    if (CHAIN) st_coherent(p, v);
+    else *p = v;
+  };
+  auto store_u32 = [&](uint32_t* p, uint32_t v) {
+    if (CHAIN) st_coherent(p, v);
+    else *p = v;
+  };
+  auto store_b16 = [&](bf16_t* p, bf16_t v) {
+    if (CHAIN) st_coherent(p, v);
+    else *p = v;
+  };
+  auto store_split = [&](bf16_t* hi_at, bf16_t* lo_at, int i, float v, bool ok) {
+    if (CHAIN) {
+      st_coherent_split_pair(hi_at, lo_at, i, v, ok);
+    } else if (ok) {
+      uint32_t hi, lo;
+      split_bf16(v, hi, lo);
+      *hi_at = (bf16_t)hi;
+      *lo_at = (bf16_t)lo;
+    }
+  };
   auto fma = [&](const u32x4_t (&wv)[TN][U], const u32x4_t (&xv)[U][XP], int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -277,26 +410,24 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
   }
 
   if (kt0 < kt1) {
+    // buffer a holds the tiles of kt, buffer b those of kt + KB (where the range reaches that far): each is
+    // requested again, a turn ahead, as soon as it has been used.  Nothing is requested beyond the range: a load
+    // left in flight at the end (even one clamped onto the last tile, which the caches serve) is waited for by
+    // whatever the epilogue reads first, a memory round trip at the end of every workgroup.
     int kt = kt0;
-    for (; kt + KA < kt1; kt += KA) {   // full turns: both register buffers are requested again
-      load(wb, xb, kt + KB);
-      __builtin_amdgcn_sched_barrier(0);
+    for (; kt + KA < kt1; kt += KA) {
       fma(wa, xa, kt);
       __builtin_amdgcn_sched_barrier(0);
       load(wa, xa, kt + KA);
       __builtin_amdgcn_sched_barrier(0);
       fma(wb, xb, kt + KB);
       __builtin_amdgcn_sched_barrier(0);
+      if (kt + KA + KB < kt1) load(wb, xb, kt + KA + KB);   // (uniform over the wavefront)
+      __builtin_amdgcn_sched_barrier(0);
     }
-    // The wavefront's last turn requests nothing beyond its range: a load left in flight here (even one clamped
-    // onto the last tile, which the caches serve) is waited for by whatever the epilogue reads first, a memory
-    // round trip at the end of every workgroup.
-    const bool second = kt + KB < kt1;   // (uniform over the wavefront)
-    if (second) load(wb, xb, kt + KB);
-    __builtin_amdgcn_sched_barrier(0);
     fma(wa, xa, kt);
     __builtin_amdgcn_sched_barrier(0);
-    if (second) fma(wb, xb, kt + KB);
+    if (kt + KB < kt1) fma(wb, xb, kt + KB);
   }
 
   // cross-wave sums through LDS: red[wave][tile][col in tile][operand column], ssq[wave][row]
@@ -344,19 +475,20 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
   if (j.epi == EPI_SWIGLU) {
     // tile columns 0..7 = gate columns 8nt..8nt+7, columns 8..15 = the matching up columns
     const int I = j.N >> 1;
-    if (tid < TN * 128) {
+    if (tid < TN * 128) {   // (whole wavefronts: the lanes of a column pair store together)
       const int t = tid >> 7, row = (tid >> 3) & 15, c8 = tid & 7;
       const int col = (nt0 + t) * 8 + c8;
-      if (row < j.M && col < I) {
+      const bool ok = row < j.M && col < I;   // (I is even: a pair is in or out as a whole)
+      float v = 0.f;
+      if (ok) {
         const float g = out_of(t, c8, row), u = out_of(t, c8 + 8, row);
-        uint32_t hi, lo;
-        split_bf16(g / (1.0f + __expf(-g)) * u, hi, lo);
-        const size_t at = fused_xop_offset(S, row, col);
-        j.act[at] = (bf16_t)hi;
-        j.act[at + (S / 2) * 8] = (bf16_t)lo;
+        v = g / (1.0f + __expf(-g)) * u;
       }
+      bf16_t* const at = j.act + fused_xop_offset(S, ok ? row : 0, ok ? col : 0);
+      store_split(at, at + (S / 2) * 8, c8, v, ok);
     }
-    return;
+    if (CHAIN) gemv_signal_done(j, lb);
+    return true;
   }
 
   if (j.epi == EPI_RESIDUAL) {
@@ -366,37 +498,30 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
       if (idx >= TN * 256) break;   // (uniform over a wavefront: TN * 256 is a multiple of 64)
       const int t = idx >> 8, row = (idx >> 4) & 15, col16 = idx & 15;
       const int col = (nt0 + t) * 16 + col16;
+      const bool ok = row < j.M;
       float v = 0.f;
-      if (row < j.M) {
+      if (ok) {
         v = pre_old[e] + out_of(t, col16, row);
 #pragma unroll
         for (int p = 0; p < PRE_PEERS; ++p)
           if (p < j.n_peers) v += bf16_to_f32(pre_peer[e][p]);
         for (int p = PRE_PEERS; p < j.n_peers; ++p) v += bf16_to_f32(j.peers[p * j.peer_stride + (size_t)row * j.N + col]);
-        j.x_new[(size_t)row * j.N + col] = v;
-        if (j.x_copy) j.x_copy[(size_t)row * j.N + col] = v;
-        // what the modules that read x_m multiply: x_m times their norm's gain, split
-        const size_t at = fused_xop_offset(S, row, col);
-        if (j.xop_a) {
-          uint32_t hi, lo;
-          split_bf16(v * bf16_to_f32(pre_ga[e]), hi, lo);
-          j.xop_a[at] = (bf16_t)hi;
-          j.xop_a[at + (S / 2) * 8] = (bf16_t)lo;
-        }
-        if (j.xop_b) {
-          uint32_t hi, lo;
-          split_bf16(v * bf16_to_f32(pre_gb[e]), hi, lo);
-          j.xop_b[at] = (bf16_t)hi;
-          j.xop_b[at + (S / 2) * 8] = (bf16_t)lo;
-        }
+        store_f32(j.x_new + (size_t)row * j.N + col, v);
+        if (j.x_copy) (x_out ? x_out : j.x_copy)[(size_t)row * j.N + col] = v;
       }
+      // what the modules that read x_m multiply: x_m times their norm's gain, split (the lanes of a column pair
+      // store together, so all lanes of the wavefront take part)
+      const size_t at = fused_xop_offset(S, ok ? row : 0, col);
+      if (j.xop_a) store_split(j.xop_a + at, j.xop_a + at + (S / 2) * 8, col16, v * bf16_to_f32(pre_ga[e]), ok);
+      if (j.xop_b) store_split(j.xop_b + at, j.xop_b + at + (S / 2) * 8, col16, v * bf16_to_f32(pre_gb[e]), ok);
       // the row's sum of squares over this tile's 16 columns (the 16 lanes that share t and row)
       const float s = row16_sum(v * v);
-      if (col16 == 0 && row < j.M && j.ssq_new) j.ssq_new[(size_t)(nt0 + t) * 16 + row] = s;
+      if (col16 == 0 && ok && j.ssq_new) store_f32(j.ssq_new + (size_t)(nt0 + t) * 16 + row, s);
     }
     if (j.t_done && tid == 0) atomicMax(j.t_done, (unsigned long long)wall_clock64());   // (emulated collectives only)
+    if (CHAIN) gemv_signal_done(j, lb);
     if (j.pos_inc && lb == 0 && tid == 0) *j.pos_inc += 1;
-    return;
+    return true;
   }
 
   // EPI_QKV_ROPE: TN*8 adjacent pairs in this workgroup's columns, all inside one head
@@ -419,20 +544,22 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
         split_bf16(e, eh, el);
         split_bf16(o, oh, ol);
         const size_t at = (size_t)row * j.nq * j.d + col;
-        *reinterpret_cast<uint32_t*>(j.q_out + at) = eh | (oh << 16);
-        *reinterpret_cast<uint32_t*>(j.q_out + (size_t)FUSED_LOW_ROW * j.nq * j.d + at) = el | (ol << 16);
+        store_u32(reinterpret_cast<uint32_t*>(j.q_out + at), eh | (oh << 16));
+        store_u32(reinterpret_cast<uint32_t*>(j.q_out + (size_t)FUSED_LOW_ROW * j.nq * j.d + at), el | (ol << 16));
       } else if (head < j.nq + j.nkv) {
         const int kvh = head - j.nq;
-        *reinterpret_cast<uint32_t*>(j.cache_k + (((size_t)row * j.nkv + kvh) * j.max_seq + pos) * j.d + 2 * jj) =
-            pack_bf16(e, o);
+        store_u32(reinterpret_cast<uint32_t*>(j.cache_k + (((size_t)row * j.nkv + kvh) * j.max_seq + pos) * j.d + 2 * jj),
+                  pack_bf16(e, o));
       } else {
         const int kvh = head - j.nq - j.nkv;
         bf16_t* vt = j.cache_v + (((size_t)row * j.nkv + kvh) * j.d + 2 * jj) * j.max_seq + pos;
-        vt[0] = f32_to_bf16(e);
-        vt[j.max_seq] = f32_to_bf16(o);
+        store_b16(vt, f32_to_bf16(e));
+        store_b16(vt + j.max_seq, f32_to_bf16(o));
       }
     }
   }
+  if (CHAIN) gemv_signal_done(j, lb);
+  return true;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -447,53 +574,40 @@ __device__ __forceinline__ void gemv_job(const GemvJob& j, const void* wp, const
 // The 8 wavefronts take the 32-key blocks of the split round robin, each with its own running
 // softmax and no barrier in the loop; they merge once, through LDS, at the end.
 // ------------------------------------------------------------------------------------------------
-// Device-coherent stores / loads (agent-scope relaxed atomics: written through to memory, read past the caches
-// that are not coherent across the chip) for the few values one workgroup hands to another inside a launch.
-// A producer waits until its coherent stores have completed (s_waitcnt) before it takes a ticket or raises a
-// counter; a consumer reads the data with coherent loads after it has seen the ticket or the counter.  No
-// fence on either side: an agent-scope release writes back, and an acquire invalidates, the whole L2 of the XCD
-// under the weight streams that run beside (1.2 - 2.5 us each on this path).
-__device__ __forceinline__ void st_coherent(uint32_t* p, uint32_t v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_coherent(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float ld_coherent(const float* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// stores a split value whose high part belongs at hi_at and whose low part at lo_at, for an element with an even
-// index i whose neighbour i ^ 1 lies right behind it: lanes i and i ^ 1 pair up for one 32-bit coherent store
-// each (all lanes of the wave must call)
-__device__ __forceinline__ void st_coherent_split_pair(bf16_t* hi_at, bf16_t* lo_at, int i, float v) {
-  uint32_t h, l;
-  split_bf16(v, h, l);
-  const uint32_t oh = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)h, 0xB1, 0xF, 0xF, false);   // the neighbour lane's (quad_perm [1,0,3,2])
-  const uint32_t ol = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)l, 0xB1, 0xF, 0xF, false);
-  if ((i & 1) == 0) {
-    st_coherent(reinterpret_cast<uint32_t*>(hi_at), h | (oh << 16));
-    st_coherent(reinterpret_cast<uint32_t*>(lo_at), l | (ol << 16));
-  }
-}
-
 // The workgroup has stored the final attention output of its (sequence, kv head) with coherent stores: wait for
 // them and count it, for the projection job of the same launch that consumes it.
 // (The counter is the word the consumers poll.  That is affordable for these few increments only: an atomic
 // on a cache line that hundreds of workgroups poll takes microseconds, and the workgroup keeps its CU slot
 // until the atomic has completed.  A producer job of many workgroups must count on one line and have the
 // workgroup that completes the count set a flag on another line, which the consumers poll.)
-__device__ __forceinline__ void attn_signal_done(const AttnJob& a) {
+__device__ __forceinline__ void attn_signal_done(const AttnJob& a, int ordinal) {
   if (!a.done) return;
   __builtin_amdgcn_s_waitcnt(0);   // this thread's coherent stores of the output have completed
   __syncthreads();
-  if (threadIdx.x == 0) atomicAdd(a.done, 1u);
+  if (threadIdx.x == 0) sync_count(a.done, (unsigned)ordinal, (unsigned)(a.B * a.nkv));
 }
 
+// Returns false if the job's wait gave up (nothing stored, error word raised).
 template <int D, int G>
-__device__ __forceinline__ void attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag) {
+__device__ __forceinline__ bool attn_job(const AttnJob& a, int lb, float* smem, unsigned* s_flag, unsigned long long* t_ready) {
   constexpr int DS = D / 32, DT = D / 16;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int b = threadIdx.x & 15, q = (threadIdx.x & 63) >> 4;   // (valid up to the end of the key loop: see below)
+  const int tid0 = opaque_tid();
+  const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
+  if (a.wait_on) {
+    // chained step: q and the new cache rows come from the QKV projection of the same launch (see gemv_job)
+    if (wave == 0) {
+      const bool arrived = sync_wait(a.wait_on, a.wait_on, a.wait_bias, a.wait_spins, tid0 & 63);
+      if (tid0 == 0) {
+        *s_flag = arrived ? 1u : 0u;
+        if (!arrived && a.err_word) __hip_atomic_store(a.err_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      }
+    }
+    __syncthreads();
+    if (*s_flag == 0u) return false;
+    __syncthreads();   // (s_flag is written again below)
+  }
+  if (t_ready && tid0 == 0) *t_ready = wall_clock64();
+  const int b = tid0 & 15, q = (tid0 & 63) >> 4;   // (valid up to the end of the key loop: see below)
   const int sp = lb % a.n_splits, kvh = (lb / a.n_splits) % a.nkv, bi = lb / (a.n_splits * a.nkv);
   const int pbeg = sp * a.split_len;
   const float scale = 1.0f / sqrtf((float)D);
@@ -534,7 +648,7 @@ __device__ __forceinline__ void attn_job(const AttnJob& a, int lb, float* smem, 
     }
   }
   const int n_pos = *a.pos_dev + 1;
-  if (pbeg >= n_pos) return;  // nothing visible in this split: the workgroup leaves, no ticket taken
+  if (pbeg >= n_pos) return true;  // nothing visible in this split: the workgroup leaves, no ticket taken
   const int pend = min(n_pos, pbeg + a.split_len);
   f32x4_t oacc[DT];
 #pragma unroll
@@ -605,7 +719,9 @@ __device__ __forceinline__ void attn_job(const AttnJob& a, int lb, float* smem, 
   lrun += __shfl_xor(lrun, 32, 64);
   // (the lane's coordinates are taken afresh from the hardware here, so that the ones above need not stay in
   // registers across the key loop, where every register is wanted for rows in flight)
-  const int lane_m = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+  unsigned zero_m = 0u;
+  asm volatile("" : "+v"(zero_m));   // (so that this is computed here and not kept from the top of an enclosing loop)
+  const int lane_m = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, zero_m));
   const int tid_m = wave * 64 + lane_m;
   float* wm = smem;                          // [WAVES][16]
   float* wl = wm + FUSED_WAVES * 16;         // [WAVES][16]
@@ -653,8 +769,8 @@ __device__ __forceinline__ void attn_job(const AttnJob& a, int lb, float* smem, 
     }
   }
   if (a.n_splits == 1) {
-    attn_signal_done(a);
-    return;
+    attn_signal_done(a, bi * a.nkv + kvh);
+    return true;
   }
 
   // several splits: the last one to arrive merges them (fixed order)
@@ -664,10 +780,10 @@ __device__ __forceinline__ void attn_job(const AttnJob& a, int lb, float* smem, 
   if (tid_m == 0) {
     const unsigned t = atomicAdd(a.tickets + bi * a.nkv + kvh, 1u);
     *s_flag = t;
-    if (t == (unsigned)n_active - 1) a.tickets[bi * a.nkv + kvh] = 0u;  // ready for the next launch
+    if (t == (unsigned)n_active - 1) st_coherent(a.tickets + bi * a.nkv + kvh, 0u);  // ready for the next attention job
   }
   __syncthreads();
-  if (*s_flag != (unsigned)n_active - 1) return;
+  if (*s_flag != (unsigned)n_active - 1) return true;
   // The last arrival reads the other splits' partial results with coherent loads.  Every thread merges its
   // own output elements from all splits, sixteen splits per pass with all of the pass's loads issued
   // together (one memory round trip per pass), in split order.
@@ -703,7 +819,8 @@ __device__ __forceinline__ void attn_job(const AttnJob& a, int lb, float* smem, 
         st_coherent_split_pair(at, at + (So / 2) * 8, i, o / l);
       }
   }
-  attn_signal_done(a);
+  attn_signal_done(a, bi * a.nkv + kvh);
+  return true;
 }
 
 
@@ -748,7 +865,7 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(const vo
   const kernarg_ptr_t ka = (kernarg_ptr_t)__builtin_amdgcn_kernarg_segment_ptr();
   if ((kb & FUSED_KIND_MASK) == (unsigned)JOB_ATTN) {
     const AttnJob& aj = *(const AttnJob*)(ka + offsetof(FusedKernelParams, fa) + offsetof(FusedArgs, a));
-    attn_job<D, G>(aj, lb, smem, &s_flag);
+    (void)attn_job<D, G>(aj, lb, smem, &s_flag, nullptr);
   } else {
     const GemvJob& j = *(const GemvJob*)(ka + offsetof(FusedKernelParams, fa) + offsetof(FusedArgs, g) + (size_t)job * sizeof(GemvJob));
     const unsigned slot = kb >> FUSED_KIND_SLOT_SHIFT;   // which preloaded pointer pair: 0, 1, or 3 = none
@@ -760,10 +877,12 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(const vo
     if (slot == 3) { wp = j.wp; xop = j.xb; KT = j.K >> 5; group0 = j.group0; M = j.M; }
     const unsigned tn = ((kb >> FUSED_KIND_TN_SHIFT) & 3u) + 1u;
     // more than 8 rows: high and low operand parts are two MFMA operands (else they share one)
-#define FUSED_GEMV(U_, TN_, COH_)                                                              \
-  do {                                                                                         \
-    if (M > 8) gemv_job<U_, TN_, COH_, true>(j, wp, xop, KT, group0, M, lb, smem, &s_flag);    \
-    else gemv_job<U_, TN_, COH_, false>(j, wp, xop, KT, group0, M, lb, smem, &s_flag);         \
+    // (the one wait of these launches is for the attention output, read with coherent loads; every other operand
+    // was complete before the launch: requested at once)
+#define FUSED_GEMV(U_, TN_, COH_)                                                                                  \
+  do {                                                                                                             \
+    if (M > 8) (void)gemv_job<U_, TN_, COH_, true, false>(j, wp, xop, KT, group0, M, lb, smem, &s_flag, nullptr, nullptr);  \
+    else (void)gemv_job<U_, TN_, COH_, false, false>(j, wp, xop, KT, group0, M, lb, smem, &s_flag, nullptr, nullptr);       \
   } while (0)
     if (kb & FUSED_KIND_WAITS) {
       if (tn == 4) FUSED_GEMV(1, 4, true);
@@ -779,6 +898,93 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_decode_kernel(const vo
       FUSED_GEMV(FUSED_U, 1, false);
     }
 #undef FUSED_GEMV
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Chained step: the whole launch list of a decode step in ONE launch of persistent workgroups.
+// Workgroup w (a "slot"; the launch has as many as are resident together) runs the blocks w, w + n_slots, ... of
+// every launch of the list, in the list's order.  Where the list relies on one launch ending before the next
+// begins, a job now waits for the flags of the jobs that produce what it reads (gemv_job, attn_job): a
+// workgroup requests its first weight tiles, then sleeps on the flag.  What this saves is the end of every launch
+// (the chip draining while the last workgroups finish, the caches written back), its start (descriptor loads,
+// the first memory round trip with nothing in flight) and the gap between the two; and the two chains that the
+// ladder wiring leaves independent (attention side, MLP side) drift against each other instead of meeting at
+// every launch boundary.
+// Every wait is for a block that comes earlier in (launch, block) order, and every slot runs its blocks in that
+// order: the earliest unfinished block of the step never waits for anything unfinished, so the step always ends
+// (the waits are bounded all the same; a workgroup whose wait gives up leaves the kernel).
+// A slot's item list is read in chunks of 32 items into LDS; an item carries what the first requests need.
+// ------------------------------------------------------------------------------------------------
+#define FUSED_CHAIN_CHUNK 32
+#define FUSED_KIND_COH 32u
+static_assert(sizeof(StepItem) == 32, "the kernel reads an item as two 16-byte words");
+template <int D, int G>
+__global__ __launch_bounds__(FUSED_THREADS, 4) void fused_chain_kernel(const StepItem* __restrict__ items, int n_items,
+                                                                      const GemvJob* __restrict__ gemv_jobs,
+                                                                      const AttnJob* __restrict__ attn_jobs, float* x_out,
+                                                                      unsigned long long* timeline) {
+  extern __shared__ float smem[];
+  __shared__ unsigned s_flag;
+  __shared__ uint4 s_items[2 * FUSED_CHAIN_CHUNK];
+  // the job tables are read-only for the launch: scalar loads (constant address space), as for kernel arguments
+  typedef __attribute__((address_space(4))) const char* const_ptr_t;
+  const const_ptr_t gj = (const_ptr_t)(unsigned long long)gemv_jobs;
+  const const_ptr_t aj = (const_ptr_t)(unsigned long long)attn_jobs;
+  const uint4* mine = reinterpret_cast<const uint4*>(items + (size_t)blockIdx.x * n_items);
+  for (int it = 0; it < n_items; ++it) {
+    const int ic = it % FUSED_CHAIN_CHUNK;
+    if (ic == 0) {
+      if ((int)threadIdx.x < 2 * FUSED_CHAIN_CHUNK && 2 * it + (int)threadIdx.x < 2 * n_items)
+        s_items[threadIdx.x] = mine[2 * it + threadIdx.x];
+      __syncthreads();
+    }
+    const uint4 i0 = s_items[2 * ic], i1 = s_items[2 * ic + 1];
+    const unsigned kb = (unsigned)__builtin_amdgcn_readfirstlane((int)i1.z) & 0xFFu;
+    if (kb == 0u) break;
+    const unsigned geo = (unsigned)__builtin_amdgcn_readfirstlane((int)i1.x);
+    const unsigned lbj = (unsigned)__builtin_amdgcn_readfirstlane((int)i1.y);
+    const int lb = (int)(lbj & 0xFFFFu), job = (int)(lbj >> 16);
+    // timeline (measurement; null in normal operation): when the slot took the item, when its waits were over, when it ended
+    unsigned long long* const tl = timeline ? timeline + ((size_t)blockIdx.x * n_items + it) * 3 : nullptr;
+    if (tl && threadIdx.x == 0) tl[0] = wall_clock64();
+    bool ok;
+    if ((kb & FUSED_KIND_MASK) == (unsigned)JOB_ATTN) {
+      ok = attn_job<D, G>(*(const AttnJob*)(aj + (size_t)job * sizeof(AttnJob)), lb, smem, &s_flag, tl ? tl + 1 : nullptr);
+    } else {
+      const GemvJob& j = *(const GemvJob*)(gj + (size_t)job * sizeof(GemvJob));
+      const unsigned long long wpu = (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)i0.x) |
+                                     ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)i0.y) << 32);
+      const unsigned long long xpu = (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)i0.z) |
+                                     ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)i0.w) << 32);
+      const void* wp = (const void*)wpu;
+      const bf16_t* xop = (const bf16_t*)xpu;
+      const int KT = (int)(geo & 0xFFFFu), group0 = (int)(geo >> 16);
+      const int M = (int)(((unsigned)__builtin_amdgcn_readfirstlane((int)i1.z) >> 8) & 0xFFu);
+      const unsigned tn = ((kb >> FUSED_KIND_TN_SHIFT) & 3u) + 1u;
+#define CHAIN_GEMV(U_, TN_, COH_)                                                                                   \
+  do {                                                                                                              \
+    if (M > 8) ok = gemv_job<U_, TN_, COH_, true, true>(j, wp, xop, KT, group0, M, lb, smem, &s_flag, x_out, tl ? tl + 1 : nullptr);   \
+    else ok = gemv_job<U_, TN_, COH_, false, true>(j, wp, xop, KT, group0, M, lb, smem, &s_flag, x_out, tl ? tl + 1 : nullptr);        \
+  } while (0)
+      if (kb & FUSED_KIND_COH) {
+        if (tn == 4) CHAIN_GEMV(FUSED_U4, 4, true);
+        else if (tn == 2) CHAIN_GEMV(FUSED_U2, 2, true);
+        else CHAIN_GEMV(FUSED_U, 1, true);
+      } else if (tn == 4) {
+        CHAIN_GEMV(FUSED_U4, 4, false);
+      } else if (tn == 3) {
+        CHAIN_GEMV(FUSED_U3, 3, false);
+      } else if (tn == 2) {
+        CHAIN_GEMV(FUSED_U2, 2, false);
+      } else {
+        CHAIN_GEMV(FUSED_U, 1, false);
+      }
+#undef CHAIN_GEMV
+    }
+    if (!ok) break;      // (the same for the whole workgroup)
+    __syncthreads();     // the job's LDS is free again; the item chunk may be overwritten
+    if (tl && threadIdx.x == 0) tl[2] = wall_clock64();
   }
 }
 
@@ -826,6 +1032,47 @@ hipError_t launch_embed(const EmbedArgs& a, hipStream_t s, hipEvent_t ev0, hipEv
   return hipGetLastError();
 }
 
+// what the kernels take for granted about a GEMV job
+static bool gemv_job_valid(const GemvJob& j) {
+  const int tn = j.tn >= 2 ? j.tn : 1;
+  if (j.ldx != j.K) return false;   // (the x rows are taken to be K elements apart)
+  // tiles per workgroup the kernels have code for: 1, 2 and 4 for every job, 3 for jobs with ordinary operand loads
+  if (tn > 4) return false;
+  if (j.M < 1 || j.M > 16 || (j.K & 31) || (j.N & 15) || j.K <= 0) return false;
+  if (j.normed && !j.ssq) return false;
+  if (j.wait_on && j.wait_spins <= 0) return false;
+  if (j.wait_on2 && !j.wait_on) return false;
+  if (j.done_ctr && j.done_target == 0) return false;
+  if (j.epi == EPI_RESIDUAL && ((j.xop_a && !j.gain_a) || (j.xop_b && !j.gain_b) || !j.x_old || !j.x_new)) return false;
+  if (j.epi == EPI_SWIGLU && (!j.act || ((j.N / 2) & 1))) return false;
+  return j.epi == EPI_RESIDUAL || j.epi == EPI_SWIGLU || j.epi == EPI_QKV_ROPE;
+}
+
+hipError_t fused_chain_item(const GemvJob& j, int job_index, int lb, StepItem* out) {
+  if (!gemv_job_valid(j) || !out) return hipErrorInvalidValue;
+  const int tn = j.tn >= 2 ? j.tn : 1, kt = j.K >> 5;
+  if (kt > 0xFFFF || j.group0 < 0 || j.group0 > 0xFFFF || lb < 0 || lb > 0xFFFF || job_index < 0 || job_index > 0xFFFF)
+    return hipErrorInvalidValue;
+  const bool coh = j.coherent_x != 0;
+  if (tn == 3 && coh) return hipErrorInvalidValue;
+  StepItem it{};
+  it.wp = j.wp; it.xb = j.xb; it.kt = (uint16_t)kt; it.group0 = (uint16_t)j.group0; it.lb = (uint16_t)lb; it.job = (uint16_t)job_index;
+  it.kind = (uint8_t)((unsigned)JOB_GEMV | ((unsigned)(tn - 1) << FUSED_KIND_TN_SHIFT) | (coh ? FUSED_KIND_COH : 0u));
+  it.M = (uint8_t)j.M;
+  *out = it;
+  return hipSuccess;
+}
+
+hipError_t fused_chain_attn_item(const AttnJob& a, int job_index, int lb, StepItem* out) {
+  if (!out || lb < 0 || lb > 0xFFFF || job_index < 0 || job_index > 0xFFFF) return hipErrorInvalidValue;
+  if (a.wait_on && a.wait_spins <= 0) return hipErrorInvalidValue;
+  if (a.B < 1 || a.B > 16 || a.n_splits < 1 || (a.split_len & 63)) return hipErrorInvalidValue;
+  StepItem it{};
+  it.lb = (uint16_t)lb; it.job = (uint16_t)job_index; it.kind = (uint8_t)JOB_ATTN; it.M = (uint8_t)a.B;
+  *out = it;
+  return hipSuccess;
+}
+
 template <int D>
 static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
   const dim3 block(FUSED_THREADS);
@@ -842,7 +1089,7 @@ static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStrea
     if (i < fa.n_jobs && fa.kind[i] == JOB_ATTN && i != 0) return hipErrorInvalidValue;   // (the kernel counts on it)
     if (i < fa.n_jobs && fa.kind[i] == JOB_GEMV) {
       const GemvJob& j = fa.g[i];
-      if (j.ldx != j.K) return hipErrorInvalidValue;   // (the kernel takes the x rows to be K elements apart)
+      if (!gemv_job_valid(j) || j.wait_on2 || j.done_ctr) return hipErrorInvalidValue;   // (the last two: chained steps only)
       const int kt = j.K >> 5, gi = n_gemv++;
       unsigned slot = 3;
       if (gi < 3 && kt <= 0xFFFF && j.group0 >= 0 && j.group0 <= 0xFFFF && j.M >= 1 && j.M <= 0xFFFF &&
@@ -858,12 +1105,7 @@ static hipError_t launch_fused_d(const FusedArgs& fa, int g, dim3 grid, hipStrea
       }
       // tiles per workgroup the kernel has code for: 1, 2 and 4 for every job, 3 for jobs without a wait
       const int tn = j.tn >= 2 ? j.tn : 1;
-      if (tn > 4 || (tn == 3 && j.wait_on)) return hipErrorInvalidValue;
-      // what the kernel takes for granted about the operands
-      if (j.M < 1 || j.M > 16 || (j.K & 31) || (j.N & 15)) return hipErrorInvalidValue;
-      if (j.normed && !j.ssq) return hipErrorInvalidValue;
-      if (j.wait_on && j.wait_spins <= 0) return hipErrorInvalidValue;
-      if (j.epi == EPI_RESIDUAL && ((j.xop_a && !j.gain_a) || (j.xop_b && !j.gain_b) || !j.x_old || !j.x_new)) return hipErrorInvalidValue;
+      if (tn == 3 && j.wait_on) return hipErrorInvalidValue;
       kb |= (unsigned)(tn - 1) << FUSED_KIND_TN_SHIFT;
       if (j.wait_on) kb |= FUSED_KIND_WAITS;
       kb |= slot << FUSED_KIND_SLOT_SHIFT;
@@ -913,6 +1155,51 @@ static hipError_t prepare_d(int g) {
 hipError_t fused_decode_prepare(int d, int g) {
   if (d == 128) return prepare_d<128>(g);
   if (d == 64) return prepare_d<64>(g);
+  return hipErrorInvalidValue;
+}
+
+template <int D, int GQ>
+static hipError_t launch_chain_dg(const StepItem* items, int n_items, const GemvJob* gj, const AttnJob* aj, float* x_out,
+                                  unsigned long long* tl, int n_slots, int lds_bytes, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+  const dim3 grid(n_slots), block(FUSED_THREADS);
+  if (ev0 || ev1) hipExtLaunchKernelGGL((fused_chain_kernel<D, GQ>), grid, block, lds_bytes, s, ev0, ev1, 0, items, n_items, gj, aj, x_out, tl);
+  else hipLaunchKernelGGL((fused_chain_kernel<D, GQ>), grid, block, lds_bytes, s, items, n_items, gj, aj, x_out, tl);
+  return hipGetLastError();
+}
+template <int D>
+static const void* chain_kernel_of(int g) {
+  switch (g) {
+    case 1: return (const void*)fused_chain_kernel<D, 1>;
+    case 2: return (const void*)fused_chain_kernel<D, 2>;
+    case 4: return (const void*)fused_chain_kernel<D, 4>;
+    case 8: return (const void*)fused_chain_kernel<D, 8>;
+  }
+  return nullptr;
+}
+
+int fused_chain_slots(int d, int g, int n_cu) {
+  const void* k = d == 128 ? chain_kernel_of<128>(g) : d == 64 ? chain_kernel_of<64>(g) : nullptr;
+  if (!k || n_cu <= 0) return 0;
+  if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, FUSED_MAX_LDS_BYTES) != hipSuccess) return 0;
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k, FUSED_THREADS, FUSED_MAX_LDS_BYTES) != hipSuccess) return 0;
+  return std::min(per_cu, 2) * n_cu;   // (the launch lists are laid out for two workgroups per CU)
+}
+
+hipError_t launch_fused_chain(const StepItem* items, int n_items, const GemvJob* gemv_jobs, const AttnJob* attn_jobs,
+                              float* x_out, unsigned long long* timeline, int n_slots, int lds_bytes, int d, int g,
+                              hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+  if (!items || n_items <= 0 || n_slots <= 0 || lds_bytes <= 0 || lds_bytes > FUSED_MAX_LDS_BYTES) return hipErrorInvalidValue;
+#define CHAIN_LAUNCH(D_)                                                                                                    \
+  switch (g) {                                                                                                              \
+    case 1: return launch_chain_dg<D_, 1>(items, n_items, gemv_jobs, attn_jobs, x_out, timeline, n_slots, lds_bytes, s, ev0, ev1);    \
+    case 2: return launch_chain_dg<D_, 2>(items, n_items, gemv_jobs, attn_jobs, x_out, timeline, n_slots, lds_bytes, s, ev0, ev1);    \
+    case 4: return launch_chain_dg<D_, 4>(items, n_items, gemv_jobs, attn_jobs, x_out, timeline, n_slots, lds_bytes, s, ev0, ev1);    \
+    case 8: return launch_chain_dg<D_, 8>(items, n_items, gemv_jobs, attn_jobs, x_out, timeline, n_slots, lds_bytes, s, ev0, ev1);    \
+  }
+  if (d == 128) { CHAIN_LAUNCH(128) }
+  if (d == 64) { CHAIN_LAUNCH(64) }
+#undef CHAIN_LAUNCH
   return hipErrorInvalidValue;
 }
 

@@ -24,6 +24,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <array>
 #include <string>
 #include <algorithm>
 #include <vector>
@@ -120,13 +121,34 @@ struct ladder_ctx {
   // fused decode path: ring of three residual buffers (x_m lives in ring[m % 3]), arrival tickets, and
   // the launch list of one step
   bool fused = false;
-  float* x_ring[3] = {nullptr, nullptr, nullptr};
+  // (chained step: no buffer is written twice within the one launch of a step, so the ring has a slot per stream,
+  // ring_n = 2N + 1, and q and the SwiGLU output have a buffer per layer, n_fbuf = N; else ring_n = 3, n_fbuf = 1)
+  int ring_n = 3, n_fbuf = 1;
+  std::vector<float*> x_ring;
   // what the projections multiply: x_m times the gain of the reading module's RMSNorm, as a split bf16 matrix
   // [32][H] (decode_fused.h); slot [m % 3][reader & 1] (a stream has at most one odd = attention and one even =
   // MLP reader); and the rows' sums of squares per 16-column tile, [H/16][16]
-  bf16_t* xop_ring[3][2] = {{nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}};
-  float* ssq_ring[3] = {nullptr, nullptr, nullptr};
-  bf16_t *f_q = nullptr, *f_o = nullptr, *f_act = nullptr;   // split q, attention output, SwiGLU output: [32][width]
+  std::vector<std::array<bf16_t*, 2>> xop_ring;
+  std::vector<float*> ssq_ring;
+  std::vector<bf16_t*> f_q, f_act;   // split q, SwiGLU output: [32][width]
+  std::vector<bf16_t*> f_o;          // attention output
+  // chained step (decode_fused = 3): persistent workgroups, the step's launch list as per-slot item lists and
+  // job tables in device memory, completion words of the producer projections
+  bool chain = false;
+  int chain_slots = 0, chain_items = 0, chain_lds = 0;
+  size_t chain_items_cap = 0;         // items per slot the device array has room for
+  int chain_gemv_cap = 0, chain_attn_cap = 0;
+  StepItem* chain_items_dev = nullptr;
+  GemvJob* chain_gemv_dev = nullptr;
+  AttnJob* chain_attn_dev = nullptr;
+  // timeline of a chained step (measurement): per slot and item the times of taking, readiness and end, and what
+  // the host knows of the item
+  struct ChainMeta { int launch, kind, tiles; long long weight_bytes; };
+  std::vector<std::vector<ChainMeta>> chain_meta;   // [slot][item]
+  unsigned long long* chain_tl_dev = nullptr;
+  bool timeline_on = false;
+  unsigned* sync_words = nullptr;     // completion words of the projections, [4 N] x FUSED_SYNC_WORDS, behind att_done in one allocation
+  int n_zero_words = 0;               // words the embedding kernel clears at the start of a step
   unsigned* err_word = nullptr;   // host-visible word that a kernel raises when its bounded in-launch wait gives up
   unsigned* err_word_dev = nullptr;   // its device address
   int wait_spins = 1 << 20;       // polls of that wait (about a second); a test shortens it
@@ -139,7 +161,7 @@ struct ladder_ctx {
   int fused_plan_batch = 0;
   int n_cu = 256;                 // compute units of the device (workgroup slots of a fused launch = 2 per CU)
   int wall_khz = 100000;          // rate of the device's wall clock (delay_kernel)
-  unsigned* att_done = nullptr;   // fused decode: per layer, how many (sequence, kv head) attention outputs are final
+  unsigned* att_done = nullptr;   // fused decode: per layer, completion words (FUSED_SYNC_WORDS) of the attention job: how many (sequence, kv head) outputs are final
   // generation head (ladder_load_head)
   char* head_table = nullptr;     // T [vocab][H]
   char* head_gain = nullptr;      // T [H]
@@ -254,7 +276,7 @@ int check_config(const ladder_config* g, std::string& why) {
   if (g->n_real_shards > g->tp_degree) { why = "n_real_shards exceeds tp_degree"; return LADDER_E_SHAPE; }
   if (g->max_tokens > g->max_seq) { why = "max_tokens exceeds max_seq"; return LADDER_E_SHAPE; }
   if ((g->decode_graph != 0 && g->decode_graph != 1) || (g->overlap_modules != 0 && g->overlap_modules != 1)) { why = "decode_graph / overlap_modules must be 0 or 1"; return LADDER_E_ARG; }
-  if (g->decode_fused < 0 || g->decode_fused > 2) { why = "decode_fused must be 0, 1 or 2"; return LADDER_E_ARG; }
+  if (g->decode_fused < 0 || g->decode_fused > 3) { why = "decode_fused must be 0, 1, 2 or 3"; return LADDER_E_ARG; }
   if (g->reduce_delay_us < 0 || g->reduce_delay_us > 10000) { why = "reduce_delay_us must be in 0 .. 10000"; return LADDER_E_ARG; }
   if (g->peer_pool < 0 || g->peer_rows < 0) { why = "peer_pool / peer_rows negative"; return LADDER_E_ARG; }
   if (g->tp_degree > g->n_real_shards && g->peer_pool > 0 && g->peer_rows <= 0) { why = "peer_rows must be positive when peers are used"; return LADDER_E_SHAPE; }
@@ -595,17 +617,22 @@ void build_fused_plan(ladder_ctx* c, int B) {
   // attention workgroups than CUs.
   int n_splits = std::min((g.max_seq + 255) / 256, std::max(1, c->n_cu / (B * nkv)));
   n_splits = std::max(1, std::min(n_splits, (g.max_seq + 63) / 64));
+#ifdef FUSED_SPLITS_MAX
+  n_splits = std::min(n_splits, FUSED_SPLITS_MAX);
+#endif
   const int split_len = ((g.max_seq + n_splits - 1) / n_splits + 63) / 64 * 64;
   n_splits = (g.max_seq + split_len - 1) / split_len;
   auto layer = [&](int l) -> LayerStore& { return c->store[(size_t)(l - 1)]; };  // l = 1..N (one shard)
+  auto R = [&](int m) { return (size_t)(m % c->ring_n); };            // ring slot of stream x_m
+  auto F = [&](int l) { return (size_t)((l - 1) % c->n_fbuf); };      // q / SwiGLU buffer of layer l
 
   auto job_qkv = [&](int l, int src) {
     GemvJob j{};
-    j.xb = c->xop_ring[src % 3][1]; j.ldx = H; j.normed = 1; j.eps = g.rms_eps; j.ssq = c->ssq_ring[src % 3];
+    j.xb = c->xop_ring[R(src)][1]; j.ldx = H; j.normed = 1; j.eps = g.rms_eps; j.ssq = c->ssq_ring[R(src)];
     j.reads_stream = src;
     j.wp = layer(l).pqkv; j.M = B; j.K = H; j.N = c->nqkv;
     j.n_groups = c->nqkv / 16; j.epi = EPI_QKV_ROPE;
-    j.q_out = c->f_q;
+    j.q_out = c->f_q[F(l)];
     j.cache_k = (bf16_t*)layer(l).cache_k; j.cache_v = (bf16_t*)layer(l).cache_v;
     j.cos_tab = c->cos_tab; j.sin_tab = c->sin_tab; j.pos_dev = c->pos_dev;
     j.nq = nq; j.nkv = nkv; j.d = d; j.max_seq = c->s_cap;
@@ -618,17 +645,17 @@ void build_fused_plan(ladder_ctx* c, int B) {
   // unless the two modules of a layer are added in the other order)
   auto residual = [&](GemvJob& j, int m, int at) {
     j.N = H; j.n_groups = H / 16; j.epi = EPI_RESIDUAL;
-    j.x_old = c->x_ring[(at - 1) % 3]; j.x_new = c->x_ring[at % 3];
+    j.x_old = c->x_ring[R(at - 1)]; j.x_new = c->x_ring[R(at)];
     // the modules that read what this job leaves in slot `at` (x_at; under the parallel wiring the odd slots hold
     // an intermediate sum that nobody reads): each gets its operand, the new rows times its norm's gain
     int cons[2];
     const int nc = consumers_of(c, at, cons);
     for (int i = 0; i < nc; ++i) {
       const int cm = cons[i], cl = (cm - 1) / 2;
-      if (cm & 1) { j.xop_a = c->xop_ring[at % 3][1]; j.gain_a = (const bf16_t*)c->gain_attn[cl]; }
-      else { j.xop_b = c->xop_ring[at % 3][0]; j.gain_b = (const bf16_t*)c->gain_mlp[cl]; }
+      if (cm & 1) { j.xop_a = c->xop_ring[R(at)][1]; j.gain_a = (const bf16_t*)c->gain_attn[cl]; }
+      else { j.xop_b = c->xop_ring[R(at)][0]; j.gain_b = (const bf16_t*)c->gain_mlp[cl]; }
     }
-    if (nc > 0) j.ssq_new = c->ssq_ring[at % 3];
+    if (nc > 0) j.ssq_new = c->ssq_ring[R(at)];
     // a collective ends every module (x_at is then complete); the parallel block has one per layer, after the
     // second of its two local additions (the odd slots hold the intermediate sum)
     if (g.wiring != LADDER_WIRING_PARALLEL || (at & 1) == 0) j.completes_stream = at;
@@ -639,7 +666,7 @@ void build_fused_plan(ladder_ctx* c, int B) {
   };
   auto job_o = [&](int l, int m, int at = -1) {
     GemvJob j{};
-    j.xb = c->f_o; j.ldx = nqd; j.wp = layer(l).po; j.M = B; j.K = nqd;
+    j.xb = c->f_o[F(l)]; j.ldx = nqd; j.wp = layer(l).po; j.M = B; j.K = nqd; j.after_attention = 1;
     residual(j, m, at < 0 ? m : at);
     // its K range is short: two tiles per workgroup halve the number of (latency-bound) workgroups
     if (j.n_groups % 2 == 0) { j.tn = 2; j.n_groups /= 2; }
@@ -647,10 +674,10 @@ void build_fused_plan(ladder_ctx* c, int B) {
   };
   auto job_gu = [&](int l, int src) {
     GemvJob j{};
-    j.xb = c->xop_ring[src % 3][0]; j.ldx = H; j.normed = 1; j.eps = g.rms_eps; j.ssq = c->ssq_ring[src % 3];
+    j.xb = c->xop_ring[R(src)][0]; j.ldx = H; j.normed = 1; j.eps = g.rms_eps; j.ssq = c->ssq_ring[R(src)];
     j.reads_stream = src;
     j.wp = layer(l).pgu; j.M = B; j.K = H; j.N = 2 * I;
-    j.n_groups = 2 * I / 16; j.epi = EPI_SWIGLU; j.act = c->f_act;
+    j.n_groups = 2 * I / 16; j.epi = EPI_SWIGLU; j.act = c->f_act[F(l)];
     // every workgroup reads the batch's rows of x over its whole K range (from L2): at 13 rows and more that
     // traffic is worth halving with two tiles per workgroup (70B shard, batch 14 / 16: 5.42 -> 5.09 / 5.80 -> 5.31
     // ms per step; batch 12 and less: slower; for QKV and down: slower at every batch)
@@ -666,14 +693,15 @@ void build_fused_plan(ladder_ctx* c, int B) {
   };
   auto job_dn = [&](int l, int m, int at = -1) {
     GemvJob j{};
-    j.xb = c->f_act; j.ldx = I; j.wp = layer(l).pd; j.M = B; j.K = I;
+    j.xb = c->f_act[F(l)]; j.ldx = I; j.wp = layer(l).pd; j.M = B; j.K = I;
     residual(j, m, at < 0 ? m : at);
     return j;
   };
   auto job_att = [&](int l) {
     AttnJob a{};
-    a.q = c->f_q; a.cache_k = (const bf16_t*)layer(l).cache_k; a.cache_v = (const bf16_t*)layer(l).cache_v;
-    a.part_o = c->att_o; a.part_ml = c->att_ml; a.o = c->f_o; a.tickets = c->tk_att;
+    a.q = c->f_q[F(l)]; a.cache_k = (const bf16_t*)layer(l).cache_k; a.cache_v = (const bf16_t*)layer(l).cache_v;
+    if (c->chain) a.done = c->att_done + (size_t)(l - 1) * FUSED_SYNC_WORDS;   // (every attention job of a chained step is a producer)
+    a.part_o = c->att_o; a.part_ml = c->att_ml; a.o = c->f_o[F(l)]; a.tickets = c->tk_att;
     a.B = B; a.nq = nq; a.nkv = nkv; a.max_seq = c->s_cap; a.n_splits = n_splits; a.split_len = split_len;
     a.pos_dev = c->pos_dev;
     return a;
@@ -764,7 +792,7 @@ void build_fused_plan(ladder_ctx* c, int B) {
 
   std::vector<FusedArgs>& plan = c->fused_plan;
   plan.clear();
-  const bool paired = g.decode_fused == 1;   // (2: one job per launch whatever the wiring)
+  const bool paired = g.decode_fused == 1 || g.decode_fused == 3;   // (2: one job per launch whatever the wiring)
   // layers with the standard wiring come first (all of them under LADDER_WIRING_STANDARD, the lower ones of a hybrid stack)
   const int n_std = g.wiring == LADDER_WIRING_STANDARD ? N : g.n_standard_layers;
   if (g.wiring != LADDER_WIRING_PARALLEL && paired) {
@@ -795,9 +823,9 @@ void build_fused_plan(ladder_ctx* c, int B) {
     if (n_std == 0) plan.push_back(one(job_qkv(1, 0)));
     for (int l = n_std + 1; l <= N; ++l) {
       AttnJob aj = job_att(l);
-      aj.done = c->att_done + (l - 1);
+      aj.done = c->att_done + (size_t)(l - 1) * FUSED_SYNC_WORDS;
       GemvJob o = job_o(l, 2 * l - 1);
-      o.wait_on = aj.done; o.wait_target = (unsigned)(B * nkv) + c->wait_bias; o.wait_spins = c->wait_spins; o.err_word = c->err_word_dev;
+      o.wait_on = aj.done; o.wait_bias = c->wait_bias; o.wait_spins = c->wait_spins; o.err_word = c->err_word_dev;
       // block order: attention, as many gate/up workgroups as leave every CU one long workgroup, o_l (resident
       // from the start, asleep until attention is done, then beside the rest of gate/up), the rest of gate/up
       GemvJob gu_a = job_gu(l, 2 * l - 2), gu_b = gu_a;
@@ -855,15 +883,163 @@ void build_fused_plan(ladder_ctx* c, int B) {
   c->fused_plan_peers = c->peers;
 }
 
+// Chained step: turns the launch list into the item lists and job tables of ONE persistent launch.
+// Every buffer the jobs hand to each other is written once per step here, so "who produces what a job reads" is a
+// lookup by address: the job waits for that producer's completion words (a projection's, or the attention job's),
+// at which every producer workgroup counts itself.  Block b of launch p goes to slot b mod n_slots, the slots' lists in launch order: that keeps
+// the placement the launch list was laid out for (the first n_cu blocks of a launch on a CU each).
+// Must not run under stream capture (it allocates nothing, but copies the tables synchronously).
+int build_chain(ladder_ctx* c, int B) {
+  const ladder_config& g = c->cfg;
+  struct Ready { const unsigned* word; };
+  std::vector<std::pair<const void*, Ready>> ready;   // (buffer, what to wait for before reading it), latest last
+  auto find_ready = [&](const void* buf) -> const Ready* {
+    if (!buf) return nullptr;
+    for (size_t i = ready.size(); i-- > 0;)
+      if (ready[i].first == buf) return &ready[i].second;
+    return nullptr;
+  };
+  auto set_ready = [&](const void* buf, const Ready& r) {
+    if (!buf) return;
+    for (auto& e : ready)
+      if (e.first == buf) { e.second = r; return; }
+    ready.push_back({buf, r});
+  };
+  // the projections (by their weights: the parts of one projection share them) and their workgroup counts
+  std::vector<const void*> proj;
+  std::vector<unsigned> proj_total, proj_seen;
+  auto proj_of = [&](const void* wp) {
+    for (size_t i = 0; i < proj.size(); ++i)
+      if (proj[i] == wp) return (int)i;
+    proj.push_back(wp); proj_total.push_back(0u); proj_seen.push_back(0u);
+    return (int)proj.size() - 1;
+  };
+  for (const FusedArgs& fa : c->fused_plan)
+    for (int k = 0; k < fa.n_jobs; ++k)
+      if (fa.kind[k] == JOB_GEMV) proj_total[(size_t)proj_of(fa.g[k].wp)] += (unsigned)fa.g[k].n_groups;
+  if ((int)proj.size() > 4 * g.n_layers) return fail(c, LADDER_E_ARG, "chained step: more projections than completion words");
+
+  std::vector<GemvJob> gemv;
+  std::vector<AttnJob> attn;
+  std::vector<std::vector<StepItem>> slot((size_t)c->chain_slots);
+  c->chain_meta.assign((size_t)c->chain_slots, {});
+  int lds = 0, launch_index = -1;
+  for (FusedArgs& fa : c->fused_plan) {
+    ++launch_index;
+    lds = std::max(lds, fa.lds_bytes);
+    int job_index[FUSED_MAX_JOBS];
+    for (int k = 0; k < fa.n_jobs; ++k) {
+      if (fa.kind[k] == JOB_ATTN) {
+        AttnJob& a = fa.a;
+        if (const Ready* r = find_ready(a.q)) { a.wait_on = r->word; a.wait_bias = c->wait_bias; }
+        a.wait_spins = c->wait_spins; a.err_word = c->err_word_dev;
+        if (!a.done) return fail(c, LADDER_E_ARG, "chained step: an attention job without an arrival counter");
+        set_ready(a.o, Ready{a.done});
+        job_index[k] = (int)attn.size();
+        attn.push_back(a);
+      } else {
+        GemvJob& j = fa.g[k];
+        const int pi = proj_of(j.wp);
+        j.wait_on = nullptr; j.wait_on2 = nullptr; j.coherent_x = 0;
+        j.wait_bias = c->wait_bias;
+        if (const Ready* r = find_ready(j.xb)) j.wait_on = r->word;
+        if (j.epi == EPI_RESIDUAL)
+          if (const Ready* r = find_ready(j.x_old)) {
+            if (!j.wait_on) j.wait_on = r->word;
+            else if (r->word != j.wait_on) j.wait_on2 = r->word;
+          }
+        j.wait_spins = c->wait_spins; j.err_word = c->err_word_dev;
+        j.done_ctr = c->sync_words + (size_t)pi * FUSED_SYNC_WORDS;
+        j.done_target = proj_total[(size_t)pi];
+        j.done_ord0 = proj_seen[(size_t)pi];
+        proj_seen[(size_t)pi] += (unsigned)j.n_groups;
+        job_index[k] = (int)gemv.size();
+        gemv.push_back(j);
+      }
+    }
+    // what this launch's projections write is ready when their flag is up (registered after the launch's jobs have
+    // looked up their own inputs: no job reads what a later block of its own launch writes)
+    for (int k = 0; k < fa.n_jobs; ++k) {
+      if (fa.kind[k] != JOB_GEMV) continue;
+      const GemvJob& j = fa.g[k];
+      const Ready r{j.done_ctr};
+      if (j.epi == EPI_SWIGLU) set_ready(j.act, r);
+      if (j.epi == EPI_RESIDUAL) { set_ready(j.x_new, r); set_ready(j.xop_a, r); set_ready(j.xop_b, r); }
+      if (j.epi == EPI_QKV_ROPE) set_ready(j.q_out, r);
+    }
+    const int total = fa.block_end[fa.n_jobs - 1];
+    for (int b = 0, k = 0; b < total; ++b) {
+      while (b >= fa.block_end[k]) ++k;
+      const int lb = b - (k > 0 ? fa.block_end[k - 1] : 0);
+      StepItem it{};
+      const hipError_t e = fa.kind[k] == JOB_ATTN ? fused_chain_attn_item(attn[(size_t)job_index[k]], job_index[k], lb, &it)
+                                                  : fused_chain_item(gemv[(size_t)job_index[k]], job_index[k], lb, &it);
+      if (e != hipSuccess) return fail(c, LADDER_E_ARG, "chained step: a job of the launch list is outside what the kernel runs");
+      slot[(size_t)(b % c->chain_slots)].push_back(it);
+      ladder_ctx::ChainMeta meta{launch_index, LADDER_TL_ATTN, 0, 0};
+      if (fa.kind[k] == JOB_GEMV) {
+        const GemvJob& j = fa.g[k];
+        meta.kind = j.epi == EPI_QKV_ROPE ? LADDER_TL_QKV : j.epi == EPI_SWIGLU ? LADDER_TL_GATE_UP : j.after_attention ? LADDER_TL_O : LADDER_TL_DOWN;
+        meta.tiles = std::max(1, j.tn);
+        meta.weight_bytes = (long long)meta.tiles * j.K * 32;
+      }
+      c->chain_meta[(size_t)(b % c->chain_slots)].push_back(meta);
+    }
+  }
+  size_t n_items = 0;
+  for (const auto& v : slot) n_items = std::max(n_items, v.size());
+  n_items += 1;   // the end marker
+  if (n_items > c->chain_items_cap || (int)gemv.size() > c->chain_gemv_cap || (int)attn.size() > c->chain_attn_cap)
+    return fail(c, LADDER_E_ARG, "chained step: the launch list is longer than the tables sized at init");
+  std::vector<StepItem> flat((size_t)c->chain_slots * n_items);   // (zero items: kind 0 ends a list)
+  for (size_t w = 0; w < slot.size(); ++w) std::copy(slot[w].begin(), slot[w].end(), flat.begin() + w * n_items);
+  HIP_TRY(c, hipStreamSynchronize(c->s_attn));   // (a step that reads the old tables may still be running)
+  HIP_TRY(c, hipMemcpy(c->chain_items_dev, flat.data(), flat.size() * sizeof(StepItem), hipMemcpyHostToDevice));
+  HIP_TRY(c, hipMemcpy(c->chain_gemv_dev, gemv.data(), gemv.size() * sizeof(GemvJob), hipMemcpyHostToDevice));
+  if (!attn.empty()) HIP_TRY(c, hipMemcpy(c->chain_attn_dev, attn.data(), attn.size() * sizeof(AttnJob), hipMemcpyHostToDevice));
+  c->chain_items = (int)n_items;
+  c->chain_lds = lds;
+  return LADDER_OK;
+}
+
+// the launch list (and, for a chained step, its tables on the device) for a step of B sequences: built at the
+// first step and again after a change of the batch, the peers or the wait limits
+int ensure_fused_plan(ladder_ctx* c, int B) {
+  if (!c->fused_plan.empty() && c->fused_plan_batch == B && c->fused_plan_peers == c->peers) return LADDER_OK;
+  build_fused_plan(c, B);
+  if (c->chain) {
+    // the last module's residual update delivers the result and advances the position itself (where an emulated
+    // collective still has to end after the launch, both are left to the caller)
+    if (c->cfg.reduce_delay_us == 0) {
+      bool first = true;
+      for (FusedArgs& fa : c->fused_plan)
+        for (int k = 0; k < fa.n_jobs; ++k)
+          if (fa.kind[k] == JOB_GEMV && fa.g[k].epi == EPI_RESIDUAL && fa.g[k].completes_stream == c->n_mod) {
+            fa.g[k].x_copy = fa.g[k].x_new;   // (the kernel's x_out argument takes its place when there is one)
+            fa.g[k].pos_inc = first ? c->pos_dev : nullptr;
+            first = false;
+          }
+    }
+    const int rc = build_chain(c, B);
+    if (rc) { c->fused_plan.clear(); return rc; }
+  }
+  return LADDER_OK;
+}
+
 // one decode step on stream s: x_0 from `emb`, the launch list, x_2N left in ring[2N % 3]
 // x_out (may be null): the caller's f32 [B][H], written by the last module's residual update itself; the same job
 // advances the position in device memory.  (Where an emulated collective still has to end after the last launch,
 // both are left to the caller of this function: the result must not appear before its collective is over.)
-int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s, float* x_out, bool* finished) {
+// *finished: bit 0 = the result is in x_out, bit 1 = the position has been advanced
+enum { FUSED_DELIVERED = 1, FUSED_ADVANCED = 2 };
+int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s, float* x_out, int* finished) {
   const ladder_config& g = c->cfg;
-  if (c->fused_plan.empty() || c->fused_plan_batch != B || c->fused_plan_peers != c->peers) build_fused_plan(c, B);
-  *finished = false;
-  if (g.reduce_delay_us == 0) {
+  {
+    const int rc = ensure_fused_plan(c, B);
+    if (rc) return rc;
+  }
+  *finished = 0;
+  if (g.reduce_delay_us == 0 && !c->chain) {
     // the last launch's last residual job is the last module's (every launch list ends with it)
     FusedArgs& last = c->fused_plan.back();
     for (int k = last.n_jobs - 1; k >= 0; --k)
@@ -879,7 +1055,7 @@ int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s, float* x_ou
             last.g[q].pos_inc = (fold && first) ? c->pos_dev : nullptr;
             first = false;
           }
-        *finished = fold;
+        *finished = fold ? (FUSED_DELIVERED | FUSED_ADVANCED) : 0;
         break;
       }
   }
@@ -903,7 +1079,7 @@ int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s, float* x_ou
     // x_0 and the operands of the modules that read it (module 1, and module 2 where its lag is 2)
     EmbedArgs ea{};
     ea.emb = (const bf16_t*)emb; ea.x0 = c->x_ring[0]; ea.ssq = c->ssq_ring[0]; ea.rows = B; ea.H = g.hidden;
-    ea.zero_words = c->att_done; ea.n_zero = g.n_layers;
+    ea.zero_words = c->att_done; ea.n_zero = c->n_zero_words;
     int cons[2];
     const int nc = consumers_of(c, 0, cons);
     for (int i = 0; i < nc; ++i) {
@@ -915,10 +1091,19 @@ int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s, float* x_ou
   }
   if (c->prof) c->prof_pending.push_back({LADDER_K_OTHER, e[0], e[1]});
   const int gq = g.n_q_heads / g.n_kv_heads;
-  for (const FusedArgs& fa : c->fused_plan) {
+  if (c->chain) {
     HIP_TRY(c, events(e));
-    HIP_TRY(c, launch_fused_decode(fa, g.head_dim, gq, s, e[0], e[1]));
+    HIP_TRY(c, launch_fused_chain(c->chain_items_dev, c->chain_items, c->chain_gemv_dev, c->chain_attn_dev, x_out,
+                                  c->timeline_on ? c->chain_tl_dev : nullptr, c->chain_slots, c->chain_lds, g.head_dim, gq,
+                                  s, e[0], e[1]));
     if (c->prof) c->prof_pending.push_back({LADDER_K_FUSED_DECODE, e[0], e[1]});
+    if (g.reduce_delay_us == 0) *finished = FUSED_ADVANCED | (x_out ? FUSED_DELIVERED : 0);
+  } else {
+    for (const FusedArgs& fa : c->fused_plan) {
+      HIP_TRY(c, events(e));
+      HIP_TRY(c, launch_fused_decode(fa, g.head_dim, gq, s, e[0], e[1]));
+      if (c->prof) c->prof_pending.push_back({LADDER_K_FUSED_DECODE, e[0], e[1]});
+    }
   }
   if (g.reduce_delay_us > 0) {   // x_2N is complete when the last module's emulated collective is
     const unsigned long long ticks = (unsigned long long)g.reduce_delay_us * (unsigned long long)c->wall_khz / 1000ull;
@@ -959,13 +1144,17 @@ int decode_graph_step(ladder_ctx* c, const void* x_in, void* x_out) {
       c->graph_exec = nullptr;
     }
     c->graph_stale = false;
+    if (c->fused) {   // (the launch list is built outside the capture: a chained step copies tables to the device)
+      const int rcp = ensure_fused_plan(c, B);
+      if (rcp) return rcp;
+    }
     hipGraph_t graph = nullptr;
     DBG("capture: begin (batch %d)", B);
     HIP_TRY(c, hipStreamBeginCapture(c->s_attn, hipStreamCaptureModeThreadLocal));
-    bool finished = false;
+    int finished = 0;
     int rc = c->fused ? fused_body(c, c->emb_stage, B, c->s_attn, nullptr, &finished) : forward_body(c, c->emb_stage, B, 1, 0, nullptr);
     DBG("capture: body recorded rc=%d", rc);
-    if (rc == LADDER_OK) {
+    if (rc == LADDER_OK && !(finished & FUSED_ADVANCED)) {
       DBG("capture: inc_pos");
       hipLaunchKernelGGL(inc_pos_kernel, dim3(1), dim3(1), 0, c->s_attn, c->pos_dev);
       hipError_t e = hipGetLastError();
@@ -993,7 +1182,7 @@ int decode_graph_step(ladder_ctx* c, const void* x_in, void* x_out) {
   DBG("graph launch");
   HIP_TRY(c, hipGraphLaunch(c->graph_exec, c->s_attn));
   DBG("graph launched");
-  const float* result = c->fused ? c->x_ring[c->n_mod % 3] : c->x;
+  const float* result = c->fused ? c->x_ring[(size_t)(c->n_mod % c->ring_n)] : c->x;
   HIP_TRY(c, hipMemcpyAsync(x_out, result, (size_t)B * H * 4, hipMemcpyDeviceToDevice, c->s_attn));
   return fence_out(c);
 }
@@ -1003,11 +1192,13 @@ int decode_fused_step(ladder_ctx* c, const void* x_in, void* x_out) {
   const int B = c->batch, H = c->cfg.hidden;
   int rc = fence_in(c);
   if (rc) return rc;
-  bool finished = false;
+  int finished = 0;
   rc = fused_body(c, x_in, B, c->s_attn, (float*)x_out, &finished);
   if (rc) return rc;
-  if (!finished) {   // (the last launch has not delivered the result and advanced the position itself)
-    HIP_TRY(c, hipMemcpyAsync(x_out, c->x_ring[c->n_mod % 3], (size_t)B * H * 4, hipMemcpyDeviceToDevice, c->s_attn));
+  // (what the last launch has not done itself)
+  if (!(finished & FUSED_DELIVERED))
+    HIP_TRY(c, hipMemcpyAsync(x_out, c->x_ring[(size_t)(c->n_mod % c->ring_n)], (size_t)B * H * 4, hipMemcpyDeviceToDevice, c->s_attn));
+  if (!(finished & FUSED_ADVANCED)) {
     hipLaunchKernelGGL(inc_pos_kernel, dim3(1), dim3(1), 0, c->s_attn, c->pos_dev);
     HIP_TRY(c, hipGetLastError());
   }
@@ -1208,16 +1399,52 @@ static int init_impl(const ladder_config* cfg, void* hip_stream, ladder_ctx** ou
       INIT_HIP(hipGetDevice(&dev_id));
       INIT_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev_id));
       if (n_cu > 0) c->n_cu = n_cu;
-      for (int i = 0; i < 3; ++i) {
-        INIT_TRY(dev_alloc(c, (void**)&c->x_ring[i], (size_t)16 * H * 4, true));
-        for (int k = 0; k < 2; ++k) INIT_TRY(dev_alloc(c, (void**)&c->xop_ring[i][k], (size_t)32 * H * 2, true));
-        INIT_TRY(dev_alloc(c, (void**)&c->ssq_ring[i], (size_t)(H / 16) * 16 * 4, true));
+      c->chain = g.decode_fused == 3;
+      if (c->chain) {
+        // persistent workgroups: as many as are resident together (a sizing pass assumes two per CU)
+        c->chain_slots = c->dry ? 2 * c->n_cu : fused_chain_slots(d, (int)gq, c->n_cu);
+        if (c->chain_slots <= 0) {
+          c->err = "the chained decode kernel does not fit this device";
+          return bail(LADDER_E_HIP);
+        }
+        c->ring_n = c->n_mod + 1;
+        c->n_fbuf = g.n_layers;
       }
-      INIT_TRY(dev_alloc(c, (void**)&c->f_q, (size_t)32 * nq * d * 2, true));
-      INIT_TRY(dev_alloc(c, (void**)&c->f_o, (size_t)32 * nq * d * 2, true));
-      INIT_TRY(dev_alloc(c, (void**)&c->f_act, (size_t)32 * I * 2, true));
+      c->x_ring.assign((size_t)c->ring_n, nullptr);
+      c->xop_ring.assign((size_t)c->ring_n, std::array<bf16_t*, 2>{nullptr, nullptr});
+      c->ssq_ring.assign((size_t)c->ring_n, nullptr);
+      c->f_q.assign((size_t)c->n_fbuf, nullptr);
+      c->f_act.assign((size_t)c->n_fbuf, nullptr);
+      c->f_o.assign((size_t)c->n_fbuf, nullptr);
+      // (a chained step sizes its buffers for the rows it can have, not for 16: it has one of each per stream)
+      const size_t ring_rows = c->chain ? (size_t)g.max_batch : 16, ring_slots = c->chain ? (size_t)fused_slots(g.max_batch) : 32;
+      for (int i = 0; i < c->ring_n; ++i) {
+        INIT_TRY(dev_alloc(c, (void**)&c->x_ring[(size_t)i], ring_rows * H * 4, true));
+        for (int k = 0; k < 2; ++k) INIT_TRY(dev_alloc(c, (void**)&c->xop_ring[(size_t)i][(size_t)k], ring_slots * H * 2, true));
+        INIT_TRY(dev_alloc(c, (void**)&c->ssq_ring[(size_t)i], (size_t)(H / 16) * 16 * 4, true));
+      }
+      for (int i = 0; i < c->n_fbuf; ++i) {
+        INIT_TRY(dev_alloc(c, (void**)&c->f_q[(size_t)i], (size_t)32 * nq * d * 2, true));
+        INIT_TRY(dev_alloc(c, (void**)&c->f_act[(size_t)i], ring_slots * I * 2, true));
+        INIT_TRY(dev_alloc(c, (void**)&c->f_o[(size_t)i], (size_t)32 * nq * d * 2, true));
+      }
       INIT_TRY(dev_alloc(c, (void**)&c->t_done, (size_t)(c->n_mod + 1) * 8, true));
-      INIT_TRY(dev_alloc(c, (void**)&c->att_done, (size_t)g.n_layers * 4, true));
+      // arrival counters of the attention jobs (a cache line each) and, for a chained step, the completion words of
+      // its projections behind them: one range, cleared by the embedding kernel at the start of every step
+      c->n_zero_words = g.n_layers * FUSED_SYNC_WORDS * (c->chain ? 5 : 1);
+      INIT_TRY(dev_alloc(c, (void**)&c->att_done, (size_t)c->n_zero_words * 4, true));
+      c->sync_words = c->att_done + (size_t)g.n_layers * FUSED_SYNC_WORDS;
+      if (c->chain) {
+        // tables of the persistent launch, sized for the longest launch list a batch can have: at most 5 N + 1
+        // launches, whose blocks (all projections' tiles and the attention workgroups) are dealt out over the slots
+        const size_t blocks_max = (size_t)(c->nqkv + 2 * H + 2 * I) / 16 + (size_t)std::max(c->n_cu, g.max_batch * nkv);
+        c->chain_items_cap = (size_t)(5 * g.n_layers + 1) * (1 + (blocks_max + (size_t)c->chain_slots - 1) / (size_t)c->chain_slots) + 1;
+        c->chain_gemv_cap = 8 * g.n_layers + 8;
+        c->chain_attn_cap = g.n_layers;
+        INIT_TRY(dev_alloc(c, (void**)&c->chain_items_dev, (size_t)c->chain_slots * c->chain_items_cap * sizeof(StepItem), false));
+        INIT_TRY(dev_alloc(c, (void**)&c->chain_gemv_dev, (size_t)c->chain_gemv_cap * sizeof(GemvJob), false));
+        INIT_TRY(dev_alloc(c, (void**)&c->chain_attn_dev, (size_t)c->chain_attn_cap * sizeof(AttnJob), false));
+      }
       // arrival tickets start at zero and are put back to zero by the last arrival of every launch
       INIT_TRY(dev_alloc(c, (void**)&c->tk_att, (size_t)g.max_batch * nkv * 4, true));
     }
@@ -1530,6 +1757,41 @@ int ladder_calibration_copy(ladder_ctx* c, void* dst, const void* src, size_t by
   const int blocks = (int)std::min<size_t>((n16 + 255) / 256, 256 * 32);
   hipLaunchKernelGGL(calibration_copy_kernel, dim3(blocks), dim3(256), 0, c->main, (const uint4*)src, (uint4*)dst, n16);
   HIP_TRY(c, hipGetLastError());
+  return LADDER_OK;
+}
+
+int ladder_timeline_enable(ladder_ctx* c, int32_t on) {
+  if (!c) return LADDER_E_ARG;
+  if (!c->chain) return fail(c, LADDER_E_STATE, "the timeline belongs to the chained decode step (decode_fused = 3 on the fused path)");
+  if (on && c->cfg.decode_graph) return fail(c, LADDER_E_STATE, "the timeline is recorded by eager steps (decode_graph = 0)");
+  if (on && !c->chain_tl_dev) {
+    const size_t bytes = (size_t)c->chain_slots * c->chain_items_cap * 3 * sizeof(unsigned long long);
+    const int rc = dev_alloc(c, (void**)&c->chain_tl_dev, bytes, true);
+    if (rc) return rc;
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->s_attn));
+  c->timeline_on = on != 0;
+  return LADDER_OK;
+}
+
+int ladder_timeline_read(ladder_ctx* c, ladder_timeline_rec* out, int64_t cap, int64_t* n_out, double* ticks_per_us) {
+  if (!c || !n_out) return LADDER_E_ARG;
+  if (!c->chain || !c->chain_tl_dev) return fail(c, LADDER_E_STATE, "no timeline: ladder_timeline_enable first");
+  if (c->fused_plan.empty() || c->chain_items <= 0) return fail(c, LADDER_E_STATE, "no timeline: no decode step has run");
+  HIP_TRY(c, hipStreamSynchronize(c->s_attn));
+  const size_t n_items = (size_t)c->chain_items;
+  std::vector<unsigned long long> t((size_t)c->chain_slots * n_items * 3);
+  HIP_TRY(c, hipMemcpy(t.data(), c->chain_tl_dev, t.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+  int64_t n = 0;
+  for (size_t w = 0; w < c->chain_meta.size(); ++w)
+    for (size_t i = 0; i < c->chain_meta[w].size(); ++i, ++n) {
+      if (!out || n >= cap) continue;
+      const ladder_ctx::ChainMeta& m = c->chain_meta[w][i];
+      const unsigned long long* ts = t.data() + (w * n_items + i) * 3;
+      out[n] = ladder_timeline_rec{(int32_t)w, m.launch, m.kind, m.tiles, m.weight_bytes, ts[0], ts[1], ts[2]};
+    }
+  *n_out = n;
+  if (ticks_per_us) *ticks_per_us = (double)c->wall_khz / 1000.0;
   return LADDER_OK;
 }
 

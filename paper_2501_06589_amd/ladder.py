@@ -55,6 +55,8 @@ EXPORTS = {
     "ladder_profile_read": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
     "ladder_profile_reset": (C.c_int, [C.c_void_p]),
     "ladder_calibration_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
+    "ladder_timeline_enable": (C.c_int, [C.c_void_p, C.c_int32]),
+    "ladder_timeline_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
     "ladder_load_head": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]),
     "ladder_embed": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "ladder_head": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
@@ -255,6 +257,21 @@ class Ladder:
 
     def set_wait_limit(self, max_polls: int, target_bias: int):
         self._check(self._lib.ladder_set_wait_limit(self._h, max_polls, target_bias))
+
+    def timeline_enable(self, on: bool):
+        """Chained decode steps record, per persistent workgroup and block, when it was taken, ready and done."""
+        self._check(self._lib.ladder_timeline_enable(self._h, 1 if on else 0))
+
+    def timeline(self):
+        """Records of the last chained step: (numpy structured array, clock ticks per microsecond)."""
+        import numpy as np
+        dt = np.dtype([("slot", "<i4"), ("launch", "<i4"), ("kind", "<i4"), ("tiles", "<i4"), ("weight_bytes", "<i8"),
+                       ("t_take", "<u8"), ("t_ready", "<u8"), ("t_end", "<u8")])
+        n, rate = C.c_int64(0), C.c_double(0.0)
+        self._check(self._lib.ladder_timeline_read(self._h, None, 0, C.byref(n), C.byref(rate)))
+        out = np.zeros(n.value, dtype=dt)
+        self._check(self._lib.ladder_timeline_read(self._h, out.ctypes.data, n.value, C.byref(n), C.byref(rate)))
+        return out, rate.value
 
     def profile_enable(self, on: bool):
         self._check(self._lib.ladder_profile_enable(self._h, 1 if on else 0))
