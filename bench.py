@@ -218,16 +218,20 @@ def run_decode(args):
     if fused:
         # fused path: every launch is the same kernel (one or two projections and/or the attention of
         # one layer); algorithmic bytes of a step (weights + visible KV + peers) over its launches
-        kernel_name = "fused_decode_kernel (decode: weight-streaming skinny GEMM jobs + split-KV attention job)"
         n_gemv, ms_gemv = prof["fused_decode"]
+        chained = n_gemv == prof_steps     # one launch per step: the chained step
+        kernel_name = ("fused_chain_kernel (a whole decode step: persistent workgroups run the step's weight-streaming skinny "
+                       "GEMM jobs and split-KV attention jobs, which meet at completion flags)" if chained else
+                       "fused_decode_kernel (decode: weight-streaming skinny GEMM jobs + split-KV attention job)")
         gemv_bytes_per_launch = step_bytes / (n_gemv / prof_steps)
     else:
+        chained = False
         kernel_name = "gemv_mfma_kernel (decode weight-streaming skinny GEMM)"
         n_gemv, ms_gemv = prof["gemv"]
         gemv_bytes_per_launch = wb / (4 * w.n_layers * w.n_real_shards)   # 4 projections per layer and shard
     avg_ms = ms_gemv / max(n_gemv, 1)
     achieved = gemv_bytes_per_launch / (avg_ms * 1e-3) / 1e9 if n_gemv else 0.0
-    kname = "fused_decode" if fused else "gemv"
+    kname = ("fused_chain" if chained else "fused_decode") if fused else "gemv"
     traffic_file = os.path.join("profiles", f"{kname}_hbm_traffic_{w.name}.md")
     traffic = read_profile_value(os.path.join(ROOT, traffic_file), "traffic_bytes_per_launch")
     trace_file = os.path.join("profiles", f"{kname}_kernel_{w.name}.md")
@@ -238,7 +242,8 @@ def run_decode(args):
                 "algorithmic_bytes_per_launch": gemv_bytes_per_launch,
                 "avg_launch_ms": avg_ms, "launches": n_gemv,
                 "duration_source": f"HIP events attached to every dispatch of {prof_steps} steps after the timed regions, "
-                                   "on the stream the kernel is launched on; excludes the ~1.5 us between launches",
+                                   "on the stream the kernel is launched on" +
+                                   ("" if chained else "; excludes the ~1.5 us between launches"),
                 # the same figures from the committed rocprofv3 kernel trace (a separate run of this command)
                 "rocprofv3": ({"avg_launch_us": prof_avg_us, "frac": gemv_bytes_per_launch / (prof_avg_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                                "source": trace_file} if prof_avg_us else None),
@@ -360,9 +365,11 @@ def main():
                          "the known-size dispatches that scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--reduce-delay-us", type=int, default=0,
                     help="emulated all-reduce latency: every collective takes this long before the stream it completes may be read")
-    ap.add_argument("--fused-plan", choices=["paired", "single", "chain"], default="paired",
-                    help="fused decode schedule: paired = independent jobs of neighbouring modules share a launch (default); "
-                         "single = one job per launch (five per layer), which leaves each collective a module to hide behind")
+    ap.add_argument("--fused-plan", choices=["paired", "single", "chain"], default="chain",
+                    help="fused decode schedule: chain = the paired launch list as ONE launch of persistent workgroups per "
+                         "step, jobs meeting at completion flags (default); paired = independent jobs of neighbouring modules "
+                         "share a launch; single = one job per launch (five per layer), which leaves each collective a module "
+                         "to hide behind")
     ap.add_argument("--head", action="store_true",
                     help="decode mode: generate for real (token embedding -> stack -> final norm + output projection of "
                          "this rank's vocabulary slice -> greedy token, fed back); the metric is quoted without it")

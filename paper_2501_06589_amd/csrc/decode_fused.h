@@ -57,6 +57,8 @@ struct GemvJob {
   // FUSED_SYNC_WORDS words), then reads that operand with device-coherent loads.  If the wait gives up, the
   // workgroup stores nothing and raises *err_word (host-visible memory), which the next call of the library reports.
   const unsigned* wait_on;
+  unsigned wait_flags;     // 0: that producer counts itself and raises one flag; else: it has this many workgroups, each
+                           // with a flag word of its own (see sync_count in decode_fused.hip)
   unsigned wait_bias;
   int wait_spins;
   unsigned* err_word;
@@ -71,10 +73,12 @@ struct GemvJob {
   // wait_on / wait_on2 point at such words of a producer (the job polls their flag); wait_bias is added to the
   // value the flag must reach (0; a test makes the wait fail with it).
   const unsigned* wait_on2;
+  unsigned wait_flags2;
   int coherent_x;          // chained step: the x operand is read with device-coherent loads (a buffer that is written more than once per launch)
   unsigned* done_ctr;
   unsigned done_target;
   unsigned done_ord0;
+  int done_flagged;        // the producer's workgroups raise a flag word each instead of counting themselves
   // Emulated collective latency (both null / 0 in normal operation).  t_ready: the job reads a stream whose
   // collective ends delay_ticks (wall clock) after the time stored there by an earlier launch; its workgroups
   // hold back until then (bounded).  t_done: every workgroup of this (residual) job leaves the time it ended there
@@ -137,9 +141,11 @@ struct AttnJob {
   // chained step: the job starts by waiting (bounded) for the flag of the completion words at wait_on: those of the
   // QKV projection that writes q and appends to the cache
   const unsigned* wait_on;
+  unsigned wait_flags;     // as in GemvJob
   unsigned wait_bias;
   int wait_spins;
   unsigned* err_word;
+  int done_flagged;        // the workgroups that write final outputs raise a flag word each at `done` (else: count themselves)
 };
 
 // completion words of one producer (a projection, the attention job of a layer): 10 cache lines of 32 words

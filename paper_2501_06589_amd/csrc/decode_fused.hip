@@ -52,22 +52,14 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 
 // k tiles per register buffer (two buffers) of a one-tile / a two-tile workgroup: 4 KiB of weights in flight
 // per wavefront.  With the round-robin assignment of k tiles below, 2 beat 4 (3.57 against 3.65 ms per step;
-// 1 gave 4.04, 3 gave 3.74: its turns do not divide the k range)
-#ifndef FUSED_U
+// 1 gave 4.04, 3 gave 3.74: its turns do not divide the k range).  Two-tile workgroups take two k tiles per
+// buffer as well: in a chained step 3.26 -> 3.23 ms per step (the output projection's whole weight share, 64 KiB,
+// is then requested before its wait); as separate launches that costs 1.4 %, accepted so that both schedules sum
+// in the same order and give the same bits (the k tiles a wavefront takes follow from this number).  Three- and
+// four-tile workgroups: one (two: 2.6 % slower).
 #define FUSED_U 2
-#endif
-#ifndef FUSED_U2
-#define FUSED_U2 1
-#endif
-#ifndef FUSED_U3
-#define FUSED_U3 1
-#endif
-#ifndef FUSED_U4
-#define FUSED_U4 1
-#endif
-#ifndef FUSED_POLL_SLEEP
-#define FUSED_POLL_SLEEP 8
-#endif
+#define FUSED_U2 2
+#define FUSED_POLL_SLEEP 8      // s_sleep units (64 clocks) between two polls of a wait (2 measured the same)
 #define FUSED_LDS_FLOATS 9216   // attention job: per-wave statistics and outputs
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -161,15 +153,24 @@ __device__ __forceinline__ void st_coherent_split_pair(bf16_t* hi_at, bf16_t* lo
   }
 }
 
-// Completion words of a producer (a projection, or the attention job of a layer): FUSED_SYNC_WORDS words = ten cache
-// lines: eight sub-counters, a top counter, and the flag that the consumers poll.  A producer workgroup whose
-// coherent stores have completed counts itself; the one that completes the count raises the flag.  Hundreds of
-// atomics on ONE line queue up behind each other, and behind the loads of whoever polls that line (microseconds
-// for a whole projection): so the workgroups of a large producer count on eight lines by their ordinal, the last of
-// each line on the ninth, and nobody polls a line that is counted on.  (Measured against counting without waiting
-// for the atomics' results and letting every consumer poll all eight counters: that made every hand-off 2 - 3 us
-// longer, the polls of 512 workgroups on eight lines being traffic of their own.)
-__device__ __forceinline__ void sync_count(unsigned* words, unsigned ordinal, unsigned total) {
+// Completion words of a producer (a projection, or the attention job of a layer): FUSED_SYNC_WORDS words, used in
+// one of two ways.
+// Counted: ten cache lines = eight sub-counters, a top counter, and the flag that the consumers poll.  A producer
+// workgroup whose coherent stores have completed counts itself; the one that completes the count raises the flag.
+// Hundreds of atomics on ONE line queue up behind each other, and behind the loads of whoever polls that line
+// (microseconds for a whole projection): so the workgroups of a large producer count on eight lines by their
+// ordinal, the last of each line on the ninth, and nobody polls a line that is counted on.  (Measured against
+// counting without waiting for the atomics' results and letting every consumer poll all eight counters: that made
+// every hand-off 2 - 3 us longer, the polls of 512 workgroups on eight lines being traffic of their own.)
+// Flagged (n_flags > 0, at most 256): word i is the flag of producer workgroup i, which stores a 1 there, and a
+// consumer polls all n_flags words with one load of its first wavefront.  No atomic, so the producer's end is a
+// memory round trip (or two) shorter; the polls read up to eight lines instead of one, which is affordable where
+// the producer is small or its consumers are few (the host decides).
+__device__ __forceinline__ void sync_count(unsigned* words, unsigned ordinal, unsigned total, bool flagged) {
+  if (flagged) {
+    __hip_atomic_store(words + ordinal, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return;
+  }
   bool last;
   if (total > 16u) {
     const unsigned k = ordinal & 7u;
@@ -180,13 +181,31 @@ __device__ __forceinline__ void sync_count(unsigned* words, unsigned ordinal, un
   }
   if (last) __hip_atomic_store(words + FUSED_SYNC_FLAG_WORD, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// lane 0 of a wavefront polls the first producer's flag, lane 1 the second's (or the first's again): true once both
-// are up (bias: a test's way of making the wait fail), false after `spins` polls (all 64 lanes must call)
-__device__ __forceinline__ bool sync_wait(const unsigned* w1, const unsigned* w2, unsigned bias, int spins, int lane) {
-  const unsigned* const word = ((lane & 1) ? w2 : w1) + FUSED_SYNC_FLAG_WORD;
+// One poll of a producer's words by a whole wavefront: counted (n_flags = 0): lane 0 reads the flag; flagged: lane i
+// reads the words 4i .. 4i+3 (two 8-byte coherent loads).  True if every word in use has reached 1 + bias (bias: a
+// test's way of making the wait fail).
+__device__ __forceinline__ bool sync_poll(const unsigned* words, unsigned n_flags, unsigned bias, int lane) {
+  bool ok = true;
+  if (n_flags == 0u) {
+    if (lane == 0) ok = __hip_atomic_load(words + FUSED_SYNC_FLAG_WORD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= 1u + bias;
+  } else if (4u * (unsigned)lane < n_flags) {
+    const unsigned long long* p = reinterpret_cast<const unsigned long long*>(words) + 2 * lane;
+    const unsigned long long a = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long b = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned w[4] = {(unsigned)a, (unsigned)(a >> 32), (unsigned)b, (unsigned)(b >> 32)};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (4u * (unsigned)lane + (unsigned)i < n_flags) ok = ok && w[i] >= 1u + bias;
+  }
+  return ok;
+}
+// waits (bounded) for one or two producers (w2 null: one); all 64 lanes of the wavefront must call
+__device__ __forceinline__ bool sync_wait(const unsigned* w1, unsigned n1, const unsigned* w2, unsigned n2, unsigned bias,
+                                          int spins, int lane) {
   for (int spin = 0; spin < spins; ++spin) {
-    const unsigned v = lane < 2 ? __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ~0u;
-    if (__all(v >= 1u + bias)) return true;
+    bool ok = sync_poll(w1, n1, bias, lane);
+    if (w2) ok = sync_poll(w2, n2, bias, lane) && ok;   // (both polls' loads are in flight together)
+    if (__all(ok)) return true;
     __builtin_amdgcn_s_sleep(FUSED_POLL_SLEEP);
   }
   return false;
@@ -196,7 +215,7 @@ __device__ __forceinline__ void gemv_signal_done(const GemvJob& j, int lb) {
   if (!j.done_ctr) return;
   __builtin_amdgcn_s_waitcnt(0);   // this thread's coherent stores have completed
   __syncthreads();
-  if (threadIdx.x == 0) sync_count(j.done_ctr, j.done_ord0 + (unsigned)lb, j.done_target);
+  if (threadIdx.x == 0) sync_count(j.done_ctr, j.done_ord0 + (unsigned)lb, j.done_target, j.done_flagged != 0);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -296,7 +315,7 @@ __device__ __forceinline__ bool gemv_job(const GemvJob& j, const void* wp, const
     // wait is bounded all the same, so that the kernel ends whatever happens; a workgroup whose wait gives up stores
     // nothing and raises the error word, which the host reads at the library's next call.
     if (wave == 0) {
-      const bool arrived = sync_wait(j.wait_on, j.wait_on2 ? j.wait_on2 : j.wait_on, j.wait_bias, j.wait_spins, lane);
+      const bool arrived = sync_wait(j.wait_on, j.wait_flags, j.wait_on2, j.wait_flags2, j.wait_bias, j.wait_spins, lane);
       if (lane == 0) {
         *s_flag = arrived ? 1u : 0u;
         if (!arrived && j.err_word) __hip_atomic_store(j.err_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
@@ -584,7 +603,7 @@ __device__ __forceinline__ void attn_signal_done(const AttnJob& a, int ordinal) 
   if (!a.done) return;
   __builtin_amdgcn_s_waitcnt(0);   // this thread's coherent stores of the output have completed
   __syncthreads();
-  if (threadIdx.x == 0) sync_count(a.done, (unsigned)ordinal, (unsigned)(a.B * a.nkv));
+  if (threadIdx.x == 0) sync_count(a.done, (unsigned)ordinal, (unsigned)(a.B * a.nkv), a.done_flagged != 0);
 }
 
 // Returns false if the job's wait gave up (nothing stored, error word raised).
@@ -596,7 +615,7 @@ __device__ __forceinline__ bool attn_job(const AttnJob& a, int lb, float* smem, 
   if (a.wait_on) {
     // chained step: q and the new cache rows come from the QKV projection of the same launch (see gemv_job)
     if (wave == 0) {
-      const bool arrived = sync_wait(a.wait_on, a.wait_on, a.wait_bias, a.wait_spins, tid0 & 63);
+      const bool arrived = sync_wait(a.wait_on, a.wait_flags, nullptr, 0u, a.wait_bias, a.wait_spins, tid0 & 63);
       if (tid0 == 0) {
         *s_flag = arrived ? 1u : 0u;
         if (!arrived && a.err_word) __hip_atomic_store(a.err_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
@@ -968,13 +987,13 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_chain_kernel(const Ste
     else ok = gemv_job<U_, TN_, COH_, false, true>(j, wp, xop, KT, group0, M, lb, smem, &s_flag, x_out, tl ? tl + 1 : nullptr);        \
   } while (0)
       if (kb & FUSED_KIND_COH) {
-        if (tn == 4) CHAIN_GEMV(FUSED_U4, 4, true);
+        if (tn == 4) CHAIN_GEMV(1, 4, true);
         else if (tn == 2) CHAIN_GEMV(FUSED_U2, 2, true);
         else CHAIN_GEMV(FUSED_U, 1, true);
       } else if (tn == 4) {
-        CHAIN_GEMV(FUSED_U4, 4, false);
+        CHAIN_GEMV(1, 4, false);
       } else if (tn == 3) {
-        CHAIN_GEMV(FUSED_U3, 3, false);
+        CHAIN_GEMV(1, 3, false);
       } else if (tn == 2) {
         CHAIN_GEMV(FUSED_U2, 2, false);
       } else {

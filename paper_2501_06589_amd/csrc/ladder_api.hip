@@ -617,9 +617,7 @@ void build_fused_plan(ladder_ctx* c, int B) {
   // attention workgroups than CUs.
   int n_splits = std::min((g.max_seq + 255) / 256, std::max(1, c->n_cu / (B * nkv)));
   n_splits = std::max(1, std::min(n_splits, (g.max_seq + 63) / 64));
-#ifdef FUSED_SPLITS_MAX
-  n_splits = std::min(n_splits, FUSED_SPLITS_MAX);
-#endif
+
   const int split_len = ((g.max_seq + n_splits - 1) / n_splits + 63) / 64 * 64;
   n_splits = (g.max_seq + split_len - 1) / split_len;
   auto layer = [&](int l) -> LayerStore& { return c->store[(size_t)(l - 1)]; };  // l = 1..N (one shard)
@@ -825,7 +823,8 @@ void build_fused_plan(ladder_ctx* c, int B) {
       AttnJob aj = job_att(l);
       aj.done = c->att_done + (size_t)(l - 1) * FUSED_SYNC_WORDS;
       GemvJob o = job_o(l, 2 * l - 1);
-      o.wait_on = aj.done; o.wait_bias = c->wait_bias; o.wait_spins = c->wait_spins; o.err_word = c->err_word_dev;
+      aj.done_flagged = 1;   // (a flag word per (sequence, kv head), polled by o_l's workgroups: no atomic at the attention job's end)
+      o.wait_on = aj.done; o.wait_flags = (unsigned)(B * nkv); o.wait_bias = c->wait_bias; o.wait_spins = c->wait_spins; o.err_word = c->err_word_dev;
       // block order: attention, as many gate/up workgroups as leave every CU one long workgroup, o_l (resident
       // from the start, asleep until attention is done, then beside the rest of gate/up), the rest of gate/up
       GemvJob gu_a = job_gu(l, 2 * l - 2), gu_b = gu_a;
@@ -891,81 +890,121 @@ void build_fused_plan(ladder_ctx* c, int B) {
 // Must not run under stream capture (it allocates nothing, but copies the tables synchronously).
 int build_chain(ladder_ctx* c, int B) {
   const ladder_config& g = c->cfg;
-  struct Ready { const unsigned* word; };
-  std::vector<std::pair<const void*, Ready>> ready;   // (buffer, what to wait for before reading it), latest last
-  auto find_ready = [&](const void* buf) -> const Ready* {
-    if (!buf) return nullptr;
-    for (size_t i = ready.size(); i-- > 0;)
-      if (ready[i].first == buf) return &ready[i].second;
-    return nullptr;
+  (void)B;
+  // The producers of a step: every projection (by its weights: the parts of one projection share them) and every
+  // attention job.  words: its completion words; blocks: its workgroups (attention: those that write final outputs);
+  // polls: the workgroups that wait for it.
+  struct Producer { const void* key; unsigned* words; unsigned blocks, seen, polls; bool flagged; };
+  std::vector<Producer> prod;
+  auto producer_of = [&](const void* key) {
+    for (size_t i = 0; i < prod.size(); ++i)
+      if (prod[i].key == key) return (int)i;
+    prod.push_back(Producer{key, nullptr, 0u, 0u, 0u, false});
+    return (int)prod.size() - 1;
   };
-  auto set_ready = [&](const void* buf, const Ready& r) {
+  std::vector<std::pair<const void*, int>> ready;   // (buffer, the producer that completes it), latest last
+  auto find_ready = [&](const void* buf) {
+    if (buf)
+      for (size_t i = ready.size(); i-- > 0;)
+        if (ready[i].first == buf) return ready[i].second;
+    return -1;
+  };
+  auto set_ready = [&](const void* buf, int p) {
     if (!buf) return;
     for (auto& e : ready)
-      if (e.first == buf) { e.second = r; return; }
-    ready.push_back({buf, r});
+      if (e.first == buf) { e.second = p; return; }
+    ready.push_back({buf, p});
   };
-  // the projections (by their weights: the parts of one projection share them) and their workgroup counts
-  std::vector<const void*> proj;
-  std::vector<unsigned> proj_total, proj_seen;
-  auto proj_of = [&](const void* wp) {
-    for (size_t i = 0; i < proj.size(); ++i)
-      if (proj[i] == wp) return (int)i;
-    proj.push_back(wp); proj_total.push_back(0u); proj_seen.push_back(0u);
-    return (int)proj.size() - 1;
-  };
-  for (const FusedArgs& fa : c->fused_plan)
-    for (int k = 0; k < fa.n_jobs; ++k)
-      if (fa.kind[k] == JOB_GEMV) proj_total[(size_t)proj_of(fa.g[k].wp)] += (unsigned)fa.g[k].n_groups;
-  if ((int)proj.size() > 4 * g.n_layers) return fail(c, LADDER_E_ARG, "chained step: more projections than completion words");
-
-  std::vector<GemvJob> gemv;
-  std::vector<AttnJob> attn;
-  std::vector<std::vector<StepItem>> slot((size_t)c->chain_slots);
-  c->chain_meta.assign((size_t)c->chain_slots, {});
-  int lds = 0, launch_index = -1;
-  for (FusedArgs& fa : c->fused_plan) {
-    ++launch_index;
-    lds = std::max(lds, fa.lds_bytes);
-    int job_index[FUSED_MAX_JOBS];
+  // pass 1: who waits for whom (dep[launch][job] = up to two producers), the producers' sizes
+  std::vector<std::array<std::array<int, 2>, FUSED_MAX_JOBS>> dep(c->fused_plan.size());
+  int n_attn = 0;
+  for (size_t p = 0; p < c->fused_plan.size(); ++p) {
+    const FusedArgs& fa = c->fused_plan[p];
     for (int k = 0; k < fa.n_jobs; ++k) {
+      dep[p][(size_t)k] = {-1, -1};
+      const int blocks = fa.block_end[k] - (k > 0 ? fa.block_end[k - 1] : 0);
       if (fa.kind[k] == JOB_ATTN) {
-        AttnJob& a = fa.a;
-        if (const Ready* r = find_ready(a.q)) { a.wait_on = r->word; a.wait_bias = c->wait_bias; }
-        a.wait_spins = c->wait_spins; a.err_word = c->err_word_dev;
-        if (!a.done) return fail(c, LADDER_E_ARG, "chained step: an attention job without an arrival counter");
-        set_ready(a.o, Ready{a.done});
-        job_index[k] = (int)attn.size();
-        attn.push_back(a);
+        const AttnJob& a = fa.a;
+        if (!a.done) return fail(c, LADDER_E_ARG, "chained step: an attention job without completion words");
+        dep[p][(size_t)k][0] = find_ready(a.q);
+        const int me = producer_of(a.done);
+        prod[(size_t)me].words = a.done;
+        prod[(size_t)me].blocks = (unsigned)(a.B * a.nkv);
+        set_ready(a.o, me);
+        ++n_attn;
       } else {
-        GemvJob& j = fa.g[k];
-        const int pi = proj_of(j.wp);
-        j.wait_on = nullptr; j.wait_on2 = nullptr; j.coherent_x = 0;
-        j.wait_bias = c->wait_bias;
-        if (const Ready* r = find_ready(j.xb)) j.wait_on = r->word;
-        if (j.epi == EPI_RESIDUAL)
-          if (const Ready* r = find_ready(j.x_old)) {
-            if (!j.wait_on) j.wait_on = r->word;
-            else if (r->word != j.wait_on) j.wait_on2 = r->word;
-          }
-        j.wait_spins = c->wait_spins; j.err_word = c->err_word_dev;
-        j.done_ctr = c->sync_words + (size_t)pi * FUSED_SYNC_WORDS;
-        j.done_target = proj_total[(size_t)pi];
-        j.done_ord0 = proj_seen[(size_t)pi];
-        proj_seen[(size_t)pi] += (unsigned)j.n_groups;
-        job_index[k] = (int)gemv.size();
-        gemv.push_back(j);
+        const GemvJob& j = fa.g[k];
+        dep[p][(size_t)k][0] = find_ready(j.xb);
+        if (j.epi == EPI_RESIDUAL) {
+          const int d2 = find_ready(j.x_old);
+          if (dep[p][(size_t)k][0] < 0) dep[p][(size_t)k][0] = d2;
+          else if (d2 != dep[p][(size_t)k][0]) dep[p][(size_t)k][1] = d2;
+        }
+        prod[(size_t)producer_of(j.wp)].blocks += (unsigned)j.n_groups;
       }
+      for (int d : dep[p][(size_t)k])
+        if (d >= 0) prod[(size_t)d].polls += (unsigned)blocks;
     }
-    // what this launch's projections write is ready when their flag is up (registered after the launch's jobs have
+    // what this launch's projections write is complete when they are (registered after the launch's jobs have
     // looked up their own inputs: no job reads what a later block of its own launch writes)
     for (int k = 0; k < fa.n_jobs; ++k) {
       if (fa.kind[k] != JOB_GEMV) continue;
       const GemvJob& j = fa.g[k];
-      const Ready r{j.done_ctr};
-      if (j.epi == EPI_SWIGLU) set_ready(j.act, r);
-      if (j.epi == EPI_RESIDUAL) { set_ready(j.x_new, r); set_ready(j.xop_a, r); set_ready(j.xop_b, r); }
-      if (j.epi == EPI_QKV_ROPE) set_ready(j.q_out, r);
+      const int me = producer_of(j.wp);
+      if (j.epi == EPI_SWIGLU) set_ready(j.act, me);
+      if (j.epi == EPI_RESIDUAL) { set_ready(j.x_new, me); set_ready(j.xop_a, me); set_ready(j.xop_b, me); }
+      if (j.epi == EPI_QKV_ROPE) set_ready(j.q_out, me);
+    }
+  }
+  if ((int)prod.size() - n_attn > 4 * g.n_layers) return fail(c, LADDER_E_ARG, "chained step: more projections than completion words");
+  // completion words of the projections; a producer's workgroups raise a flag word each (no atomics at its end)
+  // where the polls stay cheap: lines polled x workgroups polling them, per round, at most 512 (the attention
+  // job's few outputs polled by an output projection; a QKV projection polled by the attention workgroups)
+  {
+    int n_proj = 0;
+    for (Producer& pr : prod) {
+      if (!pr.words) pr.words = c->sync_words + (size_t)(n_proj++) * FUSED_SYNC_WORDS;
+      const unsigned lines = (pr.blocks + 31u) / 32u;
+      // (measured at the 70B shard: limit 1300, which adds gate/up -> down: 3.23 -> 3.32 ms per step; 2100, which adds
+      // the output projection: 3.42; everything flagged: 3.70; nothing flagged: 3.24)
+      pr.flagged = pr.blocks <= 256u && lines * pr.polls <= 512u;
+    }
+  }
+  // pass 2: the jobs' tables and the slots' item lists
+  std::vector<GemvJob> gemv;
+  std::vector<AttnJob> attn;
+  std::vector<std::vector<StepItem>> slot((size_t)c->chain_slots);
+  c->chain_meta.assign((size_t)c->chain_slots, {});
+  int lds = 0;
+  for (size_t p = 0; p < c->fused_plan.size(); ++p) {
+    FusedArgs& fa = c->fused_plan[p];
+    lds = std::max(lds, fa.lds_bytes);
+    int job_index[FUSED_MAX_JOBS];
+    for (int k = 0; k < fa.n_jobs; ++k) {
+      const int d1 = dep[p][(size_t)k][0], d2 = dep[p][(size_t)k][1];
+      if (fa.kind[k] == JOB_ATTN) {
+        AttnJob& a = fa.a;
+        a.wait_on = nullptr;
+        if (d1 >= 0) { a.wait_on = prod[(size_t)d1].words; a.wait_flags = prod[(size_t)d1].flagged ? prod[(size_t)d1].blocks : 0u; }
+        a.wait_bias = c->wait_bias; a.wait_spins = c->wait_spins; a.err_word = c->err_word_dev;
+        a.done_flagged = prod[(size_t)producer_of(a.done)].flagged ? 1 : 0;
+        job_index[k] = (int)attn.size();
+        attn.push_back(a);
+      } else {
+        GemvJob& j = fa.g[k];
+        Producer& me = prod[(size_t)producer_of(j.wp)];
+        j.wait_on = nullptr; j.wait_on2 = nullptr; j.coherent_x = 0;
+        if (d1 >= 0) { j.wait_on = prod[(size_t)d1].words; j.wait_flags = prod[(size_t)d1].flagged ? prod[(size_t)d1].blocks : 0u; }
+        if (d2 >= 0) { j.wait_on2 = prod[(size_t)d2].words; j.wait_flags2 = prod[(size_t)d2].flagged ? prod[(size_t)d2].blocks : 0u; }
+        j.wait_bias = c->wait_bias; j.wait_spins = c->wait_spins; j.err_word = c->err_word_dev;
+        j.done_ctr = me.words;
+        j.done_target = me.blocks;
+        j.done_ord0 = me.seen;
+        j.done_flagged = me.flagged ? 1 : 0;
+        me.seen += (unsigned)j.n_groups;
+        job_index[k] = (int)gemv.size();
+        gemv.push_back(j);
+      }
     }
     const int total = fa.block_end[fa.n_jobs - 1];
     for (int b = 0, k = 0; b < total; ++b) {
@@ -976,7 +1015,7 @@ int build_chain(ladder_ctx* c, int B) {
                                                   : fused_chain_item(gemv[(size_t)job_index[k]], job_index[k], lb, &it);
       if (e != hipSuccess) return fail(c, LADDER_E_ARG, "chained step: a job of the launch list is outside what the kernel runs");
       slot[(size_t)(b % c->chain_slots)].push_back(it);
-      ladder_ctx::ChainMeta meta{launch_index, LADDER_TL_ATTN, 0, 0};
+      ladder_ctx::ChainMeta meta{(int)p, LADDER_TL_ATTN, 0, 0};
       if (fa.kind[k] == JOB_GEMV) {
         const GemvJob& j = fa.g[k];
         meta.kind = j.epi == EPI_QKV_ROPE ? LADDER_TL_QKV : j.epi == EPI_SWIGLU ? LADDER_TL_GATE_UP : j.after_attention ? LADDER_TL_O : LADDER_TL_DOWN;
@@ -1211,7 +1250,11 @@ int check_device_error(ladder_ctx* c) {
   volatile unsigned* w = c->err_word;
   if (w && w[0] != 0u) {
     w[0] = 0u;
-    return fail(c, LADDER_E_HIP, "a kernel of an earlier decode step gave up its bounded in-launch wait (attention -> output projection): that step's output is invalid");
+    // (workgroups that gave up stored nothing; where the step's last job advances the position itself, that may
+    // not have happened: the device's copy is put back in step with the host's count)
+    hipLaunchKernelGGL(set_pos_kernel, dim3(1), dim3(1), 0, c->main, c->pos_dev, c->pos);
+    (void)hipGetLastError();
+    return fail(c, LADDER_E_HIP, "a kernel of an earlier decode step gave up a bounded in-launch wait (a job waiting for the job that produces its input): that step's output is invalid");
   }
   if (w && w[1] != 0u) {
     w[1] = 0u;

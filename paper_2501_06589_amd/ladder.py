@@ -105,7 +105,7 @@ def make_config(**kw) -> ladder_config:
     cfg = ladder_config()
     defaults = dict(tp_degree=1, n_real_shards=1, dtype=LADDER_BF16, wiring=LADDER_WIRING_LADDER,
                     n_standard_layers=0, reduce_on_side_stream=1, peer_pool=0, peer_rows=0,
-                    kernel_path=LADDER_PATH_AUTO, overlap_modules=1, decode_graph=0, decode_fused=1, reduce_delay_us=0,
+                    kernel_path=LADDER_PATH_AUTO, overlap_modules=1, decode_graph=0, decode_fused=3, reduce_delay_us=0,
                     rms_eps=1e-5, rope_theta=1e4)
     defaults.update(kw)
     known = {n for n, _ in ladder_config._fields_}

@@ -41,7 +41,8 @@ def test_sizing_calls_agree_with_a_live_context(harness, w):
     assert wt <= 1.1 * w.n_layers * w.n_real_shards * w.params_per_layer() * esz + 4096
 
 
-def test_in_launch_wait_that_gives_up_is_reported_by_the_next_call(harness):
+@pytest.mark.parametrize("fused", [1, 3])
+def test_in_launch_wait_that_gives_up_is_reported_by_the_next_call(harness, fused):
     """The output projection's bounded wait for its layer's attention workgroups: with a target that no count can
     reach and four polls, the wait gives up; every kernel still ends normally (the stream synchronises), the step
     itself returns LADDER_OK (it had only been enqueued), and the NEXT forward call reports LADDER_E_HIP, does
@@ -49,7 +50,7 @@ def test_in_launch_wait_that_gives_up_is_reported_by_the_next_call(harness):
     w = R8_SMALL
     tensors = harness.make_tensors(w)
     peers = inputs.peer_partials(w, w.batch)
-    ctx = harness.build_gpu(w, tensors, peers, max_seq=200)
+    ctx = harness.build_gpu(w, tensors, peers, max_seq=200, decode_fused=fused)
     for i in range(w.n_layers):
         k, v = inputs.kv_cache(w, i, 0, w.batch, 50)
         ctx.load_kv(i, 0, k.to(DEV), v.to(DEV))
@@ -68,15 +69,17 @@ def test_in_launch_wait_that_gives_up_is_reported_by_the_next_call(harness):
     out = ctx.decode_step(x)                 # condition cleared, normal operation again
     torch.cuda.synchronize()
     assert torch.isfinite(out).all()
+    assert ctx.position() == (pos[0] + 1, pos[1])
     ctx.decode_step(x)
     torch.cuda.synchronize()
+    assert ctx.position() == (pos[0] + 2, pos[1])
     with pytest.raises(ladder.LadderError) as e:
         ctx.set_wait_limit(0, 0)
     assert e.value.code == ladder.LADDER_E_ARG
     ctx.free()
 
 
-@pytest.mark.parametrize("fused", [1, 0])
+@pytest.mark.parametrize("fused", [1, 0, 3])
 def test_peers_changed_under_a_captured_decode_step(harness, fused):
     """decode_graph = 1: a step replayed from the captured graph, then another set of peer partial sums, then
     none at all: every step against the oracle with the peers in force at that step (a captured step carries the

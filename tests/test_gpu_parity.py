@@ -357,25 +357,28 @@ def test_full_width_70b_r8_decode_one_layer_strict(harness):
 
 def test_full_size_70b_r8_decode_all_80_layers_strict(harness):
     """The headline decode workload at full size and depth, in the launch configuration of the default
-    bench run (161 fused launches per step); two decode steps, every output element against the oracle at
-    the stated tolerance: max |gpu - oracle| <= 2e-2 RMS over all 80 layers."""
+    bench run (a chained step: the 161-launch list of a step as one launch of persistent workgroups); two decode
+    steps, every output element against the oracle at the stated tolerance: max |gpu - oracle| <= 2e-2 RMS over
+    all 80 layers."""
     w = inputs.WORKLOADS["70b_r8_decode"]
     res = harness.run_case(w, decode_steps=2, kv_preload=w.kv_preload, gen_device="cuda:0", max_seq=BENCH_MAX_SEQ)
     assert len(res.errs) == 2 and max(res.errs) < TOL_BF16, res.errs
 
 
 def test_full_size_70b_r8_decode_schedules_agree(harness):
-    """Same workload, 12 layers: the fused schedule (stated tolerance) and its graph replay (same bits), and the
-    one-kernel-per-operation schedule on two streams (single bf16 operands: per-module budget)."""
+    """Same workload, 12 layers: the chained step (stated tolerance), its graph replay and the same launch list as
+    separate launches (same bits), and the one-kernel-per-operation schedule on two streams (single bf16 operands:
+    per-module budget)."""
     w = inputs.WORKLOADS["70b_r8_decode"].with_(name="70b_r8_decode_12", n_layers=12)
     kw = dict(decode_steps=3, kv_preload=w.kv_preload, gen_device="cuda:0", max_seq=BENCH_MAX_SEQ)
     fused = harness.run_case(w, **kw)
     graph = harness.run_case(w, gpu_only=True, decode_graph=1, **kw)
+    paired = harness.run_case(w, gpu_only=True, decode_fused=1, **kw)
     plain = harness.run_case(w, decode_fused=0, **kw)
     assert max(fused.errs) < TOL_BF16, fused.errs
     budget_check(plain.gpu, plain.ref, w.n_layers, PLAIN_DECODE_RMS_PER_SQRT_MODULE, PLAIN_DECODE_MAX_OVER_RMS, "per-operation decode, 12 layers")
-    for x, y in zip(fused.gpu, graph.gpu):
-        assert np.array_equal(x, y)
+    for x, y, z in zip(fused.gpu, graph.gpu, paired.gpu):
+        assert np.array_equal(x, y) and np.array_equal(x, z)
 
 
 def test_full_width_70b_r4_prefill_against_oracle(harness):
