@@ -976,8 +976,12 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_chain_kernel(const Ste
                                      ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)i0.y) << 32);
       const unsigned long long xpu = (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)i0.z) |
                                      ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)i0.w) << 32);
-      const void* wp = (const void*)wpu;
-      const bf16_t* xop = (const bf16_t*)xpu;
+      // (pointers into global memory, and said to be: through a pointer of unknown address space every load is a
+      // flat load, which counts as an LDS and scalar-memory operation too, so that each wait for a descriptor field
+      // would wait for all weight tiles in flight)
+      typedef __attribute__((address_space(1))) const char* global_ptr_t;
+      const void* wp = (const void*)(global_ptr_t)wpu;
+      const bf16_t* xop = (const bf16_t*)(global_ptr_t)xpu;
       const int KT = (int)(geo & 0xFFFFu), group0 = (int)(geo >> 16);
       const int M = (int)(((unsigned)__builtin_amdgcn_readfirstlane((int)i1.z) >> 8) & 0xFFu);
       const unsigned tn = ((kb >> FUSED_KIND_TN_SHIFT) & 3u) + 1u;

@@ -100,7 +100,7 @@ def run_case(w: inputs.Workload, *, decode_steps: Optional[int] = None, kv_prelo
     errs = []
     for g, r in zip(gpu_out, ref_out):
         assert g.shape == r.shape, (g.shape, r.shape)
-        assert np.all(np.isfinite(g))
+        assert np.all(np.isfinite(g)), ("non-finite", int(np.sum(~np.isfinite(g))), g.size)
         errs.append(float(np.max(np.abs(g - r)) / np.sqrt(np.mean(r * r))))
     rms_errs = [float(np.sqrt(np.mean((g - r) ** 2) / np.mean(r * r))) for g, r in zip(gpu_out, ref_out)]
     say(f"[case] {w.name}: max errs = {['%.2e' % v for v in errs]} rms errs = {['%.2e' % v for v in rms_errs]}")
