@@ -1,6 +1,6 @@
 // ladder_cdriver: a host-only C++ program that drives the C-ABI of libladder.so without Python.
 //
-//   ladder_cdriver [--layers N] [--steps K] [--warmup W] [--kv S] [--copies C]
+//   ladder_cdriver [--layers N] [--steps K] [--warmup W] [--kv S] [--copies C] [--fused F]   (F = decode_fused: 3 chained step (default), 1, 2, 0)
 //   ladder_cdriver --prefill 1 [--layers N] [--steps K] [--warmup W] [--batch B] [--tokens T]
 //
 // With --prefill 1 it builds the prefill workload's shard instead (one rank at R = 4: hidden 8192, 16 q / 2 kv heads,
@@ -134,6 +134,7 @@ int main(int argc, char** argv) {
   const int warmup = arg_int(argc, argv, "--warmup", 4);
   const int kv = arg_int(argc, argv, "--kv", 1024);
   const int copies = arg_int(argc, argv, "--copies", 4);
+  const int fused = arg_int(argc, argv, "--fused", 3);
   const int H = 8192, NQ = 8, NKV = 1, D = 128, I = 3584, R = 8, B = 4;
   if (n_layers < 1 || steps < 1 || warmup < 0 || kv < 1 || copies < 0) {
     fprintf(stderr, "bad arguments\n");
@@ -146,7 +147,7 @@ int main(int argc, char** argv) {
   cfg.tp_degree = R; cfg.n_real_shards = 1; cfg.max_batch = B; cfg.max_seq = kv + warmup + steps + 8;
   cfg.max_tokens = 1; cfg.dtype = LADDER_BF16; cfg.wiring = LADDER_WIRING_LADDER; cfg.n_standard_layers = 0;
   cfg.reduce_on_side_stream = 1; cfg.peer_pool = 2; cfg.peer_rows = B; cfg.kernel_path = LADDER_PATH_AUTO;
-  cfg.overlap_modules = 1; cfg.decode_graph = 0; cfg.decode_fused = 1; cfg.rms_eps = 1e-5f; cfg.rope_theta = 500000.0f;
+  cfg.overlap_modules = 1; cfg.decode_graph = 0; cfg.decode_fused = fused; cfg.rms_eps = 1e-5f; cfg.rope_theta = 500000.0f;
 
   ladder_ctx* ctx = nullptr;
   LADDER_OK_OR_DIE(ladder_init(&cfg, nullptr, &ctx));
