@@ -835,6 +835,16 @@ void build_fused_plan(ladder_ctx* c, int B) {
       // 4.06 -> 3.86 ms per step, 70B R = 4 shard at batch 16 8.89 -> 8.61; with the R = 8 shard's K range of
       // 1024, batch 8 and 16, it cost 1 - 2 %).
       if (n_splits * nkv * B + blocks_of(gu_a) + blocks_of(o) > 2 * c->n_cu && nqd >= 2048 && o.tn == 2 && o.n_groups % 2 == 0) { o.tn = 4; o.n_groups /= 2; }
+      // Chained step: a workgroup slot runs its blocks one after the other, each ending with its stores' round trip
+      // and its count before the next one's first request, so a launch of several rounds of small blocks pays
+      // that per round: gate/up takes more tiles per workgroup until the launch fits the slots (or four tiles).
+      if (c->chain)
+        while (n_splits * nkv * B + blocks_of(gu_a) + blocks_of(o) > c->chain_slots && std::max(1, gu_a.tn) < 4 &&
+               gu_a.n_groups % 2 == 0 && std::max(1, gu_a.tn) != 3) {
+          gu_a.tn = 2 * std::max(1, gu_a.tn);
+          gu_a.n_groups /= 2;
+          gu_b = gu_a;
+        }
       const int n_a = std::min(gu_a.n_groups / 2, c->n_cu / 2);   // (any position in the first half measured the same)
       gu_a.n_groups = n_a;
       gu_b.group0 = n_a; gu_b.n_groups -= n_a;
@@ -1006,15 +1016,23 @@ int build_chain(ladder_ctx* c, int B) {
         gemv.push_back(j);
       }
     }
+    // Which slot runs which block: where a launch has more blocks than there are slots, the hardware would hand the
+    // next block to the first workgroup slot that becomes free; here each block goes, in block order, to the slot
+    // with the least work of this launch so far (a block's work: its weight bytes plus a fixed part; ties: the
+    // lowest slot).  Up to n_slots blocks that is block b on slot b.
     const int total = fa.block_end[fa.n_jobs - 1];
+    std::vector<long long> load((size_t)c->chain_slots, 0);
     for (int b = 0, k = 0; b < total; ++b) {
       while (b >= fa.block_end[k]) ++k;
       const int lb = b - (k > 0 ? fa.block_end[k - 1] : 0);
+      const long long work = 96 * 1024 + (fa.kind[k] == JOB_GEMV ? (long long)std::max(1, fa.g[k].tn) * fa.g[k].K * 32 : 128 * 1024);
+      const int sl = b < c->chain_slots ? b : (int)(std::min_element(load.begin(), load.end()) - load.begin());
+      load[(size_t)sl] += work;
       StepItem it{};
       const hipError_t e = fa.kind[k] == JOB_ATTN ? fused_chain_attn_item(attn[(size_t)job_index[k]], job_index[k], lb, &it)
                                                   : fused_chain_item(gemv[(size_t)job_index[k]], job_index[k], lb, &it);
       if (e != hipSuccess) return fail(c, LADDER_E_ARG, "chained step: a job of the launch list is outside what the kernel runs");
-      slot[(size_t)(b % c->chain_slots)].push_back(it);
+      slot[(size_t)sl].push_back(it);
       ladder_ctx::ChainMeta meta{(int)p, LADDER_TL_ATTN, 0, 0};
       if (fa.kind[k] == JOB_GEMV) {
         const GemvJob& j = fa.g[k];
@@ -1022,7 +1040,7 @@ int build_chain(ladder_ctx* c, int B) {
         meta.tiles = std::max(1, j.tn);
         meta.weight_bytes = (long long)meta.tiles * j.K * 32;
       }
-      c->chain_meta[(size_t)(b % c->chain_slots)].push_back(meta);
+      c->chain_meta[(size_t)sl].push_back(meta);
     }
   }
   size_t n_items = 0;
