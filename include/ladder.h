@@ -109,10 +109,12 @@ typedef struct {
                              more workspace at 16 rows; ladder_workspace_bytes counts it);
                              0: one kernel per operation */
   int32_t reduce_delay_us; /* emulated all-reduce latency (Fig. 2 / Table 2 of the paper vary the interconnect), 0 .. 10000.
-                              Fused decode schedule: the collective that completes x_m starts when the launch
-                              holding module m's residual update ends, lasts this many microseconds on a side
-                              stream, and the launches whose projections read x_m wait for it; the arithmetic
-                              is unchanged (same bits).  One kernel per operation: a timed wait of that length in
+                              Fused decode schedules: the collective that completes x_m starts when the last
+                              workgroup of module m's residual update ends (the workgroups leave the device's
+                              wall-clock time) and lasts this many microseconds; the projections that read x_m
+                              hold their workgroups back until then (a bounded wait on the clock, inside the
+                              launch), while the other jobs run; the arithmetic is unchanged (same bits).
+                              One kernel per operation: a timed wait of that length in
                               front of every partial-sum reduce, on the stream the reduce runs on.
                               (LADDER_WIRING_PARALLEL: one collective per layer.) */
   float rms_eps;          /* RMSNorm epsilon (inside the square root) */
@@ -265,11 +267,13 @@ size_t ladder_device_bytes(const ladder_ctx* ctx);
 size_t ladder_workspace_bytes(const ladder_config* cfg);
 size_t ladder_weight_bytes(const ladder_config* cfg);
 
-/* Test hook for the one in-launch wait of the fused decode schedule (the output projection of a layer waits,
- * inside the launch, for that layer's attention workgroups; the wait is bounded): max_polls polls instead of
- * 2^20, and target_bias added to the count it waits for.  With a bias no count can reach, the wait gives up:
- * the waiting workgroups store nothing, every kernel still ends normally, and the NEXT ladder_decode_step /
- * ladder_prefill returns LADDER_E_HIP.  (1 << 20, 0) restores normal operation.  Errors: LADDER_E_ARG. */
+/* Test hook for the in-launch waits of the fused decode schedules (decode_fused = 1: the output projection of a
+ * layer waits, inside the launch, for that layer's attention workgroups; decode_fused = 3: every job of the
+ * chained step waits for the jobs that produce what it reads; all such waits are bounded): max_polls polls instead
+ * of 2^20, and target_bias added to the value a wait polls for.  With a bias no producer can reach, the waits give
+ * up: the waiting workgroups store nothing, every kernel still ends normally, and the NEXT ladder_decode_step /
+ * ladder_prefill returns LADDER_E_HIP (and puts the device's copy of the position back in step with the host's).
+ * (1 << 20, 0) restores normal operation.  Errors: LADDER_E_ARG. */
 int ladder_set_wait_limit(ladder_ctx* ctx, int32_t max_polls, int32_t target_bias);
 
 /* Timeline of a chained decode step (decode_fused = 3), for measurement.  A chained step is one launch of
