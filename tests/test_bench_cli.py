@@ -16,8 +16,8 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_profiled_figures_are_read_from_the_committed_summaries():
     sys.path.insert(0, ROOT)
     import bench
-    t = bench.read_profile_value(os.path.join(ROOT, "profiles", "fused_decode_hbm_traffic_70b_r8_decode.md"), "traffic_bytes_per_launch")
-    assert t is not None and 90e6 < t < 140e6, t   # bytes per launch; algorithmic: 107.9e6
+    t = bench.read_profile_value(os.path.join(ROOT, "profiles", "fused_chain_hbm_traffic_70b_r8_decode.md"), "traffic_bytes_per_launch")
+    assert t is not None and 15e9 < t < 21e9, t   # bytes per launch = per decode step (chained); algorithmic: 17.4e9
     assert bench.read_profile_value(os.path.join(ROOT, "profiles", "no_such_file.md"), "traffic_bytes_per_launch") is None
-    us = bench.read_profile_value(os.path.join(ROOT, "profiles", "fused_decode_kernel_70b_r8_decode.md"), "rocprofv3_avg_launch_us")
-    assert us is not None and 10 < us < 40, us
+    us = bench.read_profile_value(os.path.join(ROOT, "profiles", "fused_chain_kernel_70b_r8_decode.md"), "rocprofv3_avg_launch_us")
+    assert us is not None and 2000 < us < 5000, us   # one launch per step
