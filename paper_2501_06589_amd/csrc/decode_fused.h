@@ -149,7 +149,8 @@ struct AttnJob {
 };
 
 // completion words of one producer (a projection, the attention job of a layer): 10 cache lines of 32 words
-// (sub-counters 0..7, the top counter, the flag that consumers poll); zero at the start of every step
+// (sub-counters 0..7 on lines 0..7; eight flag words, which consumers poll, at the start of line 9); zero at the
+// start of every step
 #define FUSED_SYNC_WORDS 320
 #define FUSED_SYNC_FLAG_WORD 288
 

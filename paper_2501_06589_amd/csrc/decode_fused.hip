@@ -155,13 +155,15 @@ __device__ __forceinline__ void st_coherent_split_pair(bf16_t* hi_at, bf16_t* lo
 
 // Completion words of a producer (a projection, or the attention job of a layer): FUSED_SYNC_WORDS words, used in
 // one of two ways.
-// Counted: ten cache lines = eight sub-counters, a top counter, and the flag that the consumers poll.  A producer
-// workgroup whose coherent stores have completed counts itself; the one that completes the count raises the flag.
-// Hundreds of atomics on ONE line queue up behind each other, and behind the loads of whoever polls that line
-// (microseconds for a whole projection): so the workgroups of a large producer count on eight lines by their
-// ordinal, the last of each line on the ninth, and nobody polls a line that is counted on.  (Measured against
-// counting without waiting for the atomics' results and letting every consumer poll all eight counters: that made
-// every hand-off 2 - 3 us longer, the polls of 512 workgroups on eight lines being traffic of their own.)
+// Counted: eight sub-counters, a cache line each, and ONE further line of eight flag words that the consumers
+// poll.  A producer workgroup whose coherent stores have completed counts itself on the sub-counter of its ordinal
+// mod 8; the one that completes a sub-counter raises that counter's flag word, and a consumer goes on when all
+// eight are up (one 32-byte load per poll).  Hundreds of atomics on ONE line queue up behind each other, and behind
+// the loads of whoever polls that line (microseconds for a whole projection): hence eight lines to count on and
+// nobody polling a line that is counted on.  (A ninth counter for the eight finishers, whose last raised a single
+// flag, cost every hand-off one more atomic round trip.  Counting without waiting for the atomics' results and
+// letting every consumer poll all eight counters made every hand-off 2 - 3 us longer, the polls of 512 workgroups
+// on eight lines being traffic of their own.)
 // Flagged (n_flags > 0, at most 256): word i is the flag of producer workgroup i, which stores a 1 there, and a
 // consumer polls all n_flags words with one load of its first wavefront.  No atomic, so the producer's end is a
 // memory round trip (or two) shorter; the polls read up to eight lines instead of one, which is affordable where
@@ -171,23 +173,28 @@ __device__ __forceinline__ void sync_count(unsigned* words, unsigned ordinal, un
     __hip_atomic_store(words + ordinal, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return;
   }
-  bool last;
   if (total > 16u) {
     const unsigned k = ordinal & 7u;
-    const unsigned n_k = (total + 7u - k) >> 3;   // workgroups with this ordinal mod 8
-    last = atomicAdd(words + 32u * k, 1u) == n_k - 1u && atomicAdd(words + 32u * 8u, 1u) == 7u;
-  } else {
-    last = atomicAdd(words + 32u * 8u, 1u) == total - 1u;
+    const unsigned n_k = (total + 7u - k) >> 3;   // workgroups with this ordinal mod 8 (at least two)
+    if (atomicAdd(words + 32u * k, 1u) == n_k - 1u)
+      __hip_atomic_store(words + FUSED_SYNC_FLAG_WORD + k, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  } else if (atomicAdd(words, 1u) == total - 1u) {   // a small producer: one counter, its finisher raises all eight words
+#pragma unroll
+    for (unsigned k = 0; k < 8u; ++k)
+      __hip_atomic_store(words + FUSED_SYNC_FLAG_WORD + k, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  if (last) __hip_atomic_store(words + FUSED_SYNC_FLAG_WORD, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// One poll of a producer's words by a whole wavefront: counted (n_flags = 0): lane 0 reads the flag; flagged: lane i
-// reads the words 4i .. 4i+3 (two 8-byte coherent loads).  True if every word in use has reached 1 + bias (bias: a
+// One poll of a producer's words by a whole wavefront: counted (n_flags = 0): lanes 0..3 read the eight flag words,
+// two each; flagged: lane i reads the words 4i .. 4i+3 (two 8-byte coherent loads).  True if every word in use has reached 1 + bias (bias: a
 // test's way of making the wait fail).
 __device__ __forceinline__ bool sync_poll(const unsigned* words, unsigned n_flags, unsigned bias, int lane) {
   bool ok = true;
   if (n_flags == 0u) {
-    if (lane == 0) ok = __hip_atomic_load(words + FUSED_SYNC_FLAG_WORD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= 1u + bias;
+    if (lane < 4) {
+      const unsigned long long v = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(words + FUSED_SYNC_FLAG_WORD) + lane,
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      ok = (unsigned)v >= 1u + bias && (unsigned)(v >> 32) >= 1u + bias;
+    }
   } else if (4u * (unsigned)lane < n_flags) {
     const unsigned long long* p = reinterpret_cast<const unsigned long long*>(words) + 2 * lane;
     const unsigned long long a = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
