@@ -821,10 +821,13 @@ __device__ __forceinline__ bool attn_job(const AttnJob& a, int lb, float* smem, 
       float ms[SP], ls[SP], os[SP];
 #pragma unroll
       for (int k = 0; k < SP; ++k) {
-        const int s = min(s0 + k, n_active - 1);
-        ms[k] = ld_coherent(a.part_ml + ((pbase + s) * G + h) * 2 + 0);
-        ls[k] = ld_coherent(a.part_ml + ((pbase + s) * G + h) * 2 + 1);
-        os[k] = ld_coherent(a.part_o + (pbase + s) * G * D + i);
+        ms[k] = -INFINITY; ls[k] = 0.f; os[k] = 0.f;
+        if (s0 + k < n_active) {   // (uniform: no request for a split that is not there)
+          const int s = s0 + k;
+          ms[k] = ld_coherent(a.part_ml + ((pbase + s) * G + h) * 2 + 0);
+          ls[k] = ld_coherent(a.part_ml + ((pbase + s) * G + h) * 2 + 1);
+          os[k] = ld_coherent(a.part_o + (pbase + s) * G * D + i);
+        }
       }
       float mnew = m;
 #pragma unroll
