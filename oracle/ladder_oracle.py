@@ -18,7 +18,10 @@ section "Tensor Parallelism Background" for the sharding rule and Eq. 1):
   * the ladder recurrence   x*_m = h_m(x_{m-2}),  x_m = AllReduce(x*_m) + x_{m-1}
     (Eq. 2), in an index form (`forward_eq2`) and in the variable-passing form
     of Algorithm 1 (`forward_alg1`), plus the standard wiring of Eq. 1 and a
-    per-module mix of both (hybrid) through `src_lag`.
+    per-module mix of both (hybrid) through `src_lag`;
+  * a pipeline stage (`stage_alg1`): a run of layers that takes and returns the
+    three tensors Algorithm 1 passes from block to block (section "Compatibility
+    with other Parallelism Techniques").
 
 Readings where the paper is silent (all listed in the design document):
 modules 1 and 2 both read x_0; after the last layer the two outstanding module
@@ -32,7 +35,8 @@ they are stored (weights, embeddings and peer partials arrive already rounded).
 Pins (tests, CPU only): shard-sum == unsharded; ladder == standard when the
 in-between module outputs are zero; cached decode == full recompute; Eq.-2
 form == Algorithm-1 form; single-layer closed form; staleness of inputs;
-op-level agreement with torch float64 library routines; rotary / softmax /
+a pipeline stage's three tensors == the index form's x_{2N-2}, h_{2N-1}, h_{2N},
+and stages in a row == one stage; op-level agreement with torch float64 library routines; rotary / softmax /
 norm invariants; causality; brute force with python loops on hand-sized
 models.  The paper prints no numeric example, so no printed value pins it.
 """
@@ -298,6 +302,38 @@ def forward_alg1(emb: np.ndarray, layers: Sequence[Layer], cfg: OracleConfig,
     for h in outstanding:
         stream = stream + h
     return stream
+
+
+def stage_alg1(residual: np.ndarray, attn_out: Optional[np.ndarray], mlp_out: Optional[np.ndarray],
+               layers: Sequence[Layer], cfg: OracleConfig, state: Optional[State] = None,
+               peers: Optional[np.ndarray] = None, module_offset: int = 0):
+    """One pipeline stage (section "Compatibility with other Parallelism Techniques"): the layers of `layers`
+    (cfg.n_layers of them, with their own caches in `state`) as a run of Algorithm 1 blocks that starts from
+    what the previous stage hands over and returns what the next stage needs -- three tensors [B, T, H]:
+
+        residual   the stream without the last two module outputs,
+        attn_out   the reduced output of the last attention module,
+        mlp_out    the reduced output of the last MLP module.
+
+    A block first adds the previous block's attention output to the residual, runs its attention module on the
+    normed residual, then adds the previous block's MLP output and runs its MLP module (ladder wiring only).
+    The first stage gets residual = embeddings and no outputs (None = zeros); the model's output is the sum of
+    the three tensors the last stage returns.  `module_offset` = number of modules in the stages before this
+    one; it only selects which synthetic peer partial sums a module's reduction adds (global module index)."""
+    residual = np.asarray(residual, dtype=F64).copy()
+    prev_attn = np.zeros_like(residual) if attn_out is None else np.asarray(attn_out, dtype=F64)
+    prev_mlp = np.zeros_like(residual) if mlp_out is None else np.asarray(mlp_out, dtype=F64)
+    s0 = state.pos if state is not None else 0
+    for l in range(1, cfg.n_layers + 1):
+        residual = residual + prev_attn
+        m = 2 * l - 1
+        prev_attn = all_reduce(module_offset + m, module_partials(m, residual, layers, cfg, state, s0), peers, cfg)
+        residual = residual + prev_mlp
+        m = 2 * l
+        prev_mlp = all_reduce(module_offset + m, module_partials(m, residual, layers, cfg, state, s0), peers, cfg)
+    if state is not None:
+        state.pos = s0 + residual.shape[1]
+    return residual, prev_attn, prev_mlp
 
 
 # ---------------------------------------------------------------------------

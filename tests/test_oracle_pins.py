@@ -240,6 +240,44 @@ def test_eq2_form_equals_alg1_form():
     assert sa.pos == sb.pos == 6
 
 
+def test_pipeline_stage_hands_over_the_index_forms_tensors():
+    """Section "Compatibility with other Parallelism Techniques": what a stage returns is the stream without
+    the last two module outputs and those two outputs, each by itself (a swap or a dropped term fails), and a
+    model cut into stages is the same model."""
+    layers, cfg = rand_model(n_layers=5, n_shards=2)
+    emb = RNG.normal(size=(2, 4, cfg.hidden))
+    peers = RNG.normal(size=(4, 2, 8, cfg.hidden)) * 0.1
+    trace = {}
+    full = lo.forward_eq2(emb, layers, cfg, peers=peers, trace=trace)
+    n_mod = 2 * cfg.n_layers
+    r, a, m = lo.stage_alg1(emb, None, None, layers, cfg, peers=peers)
+    assert np.max(np.abs(r - trace["x"][n_mod - 2])) < 1e-12
+    assert np.max(np.abs(a - trace["h"][n_mod - 1])) < 1e-12
+    assert np.max(np.abs(m - trace["h"][n_mod])) < 1e-12
+    assert np.max(np.abs(r + a + m - full)) < 1e-12
+    assert np.max(np.abs(a - m)) > 1e-3            # (the two outputs are not interchangeable)
+    # cut after 2 and after 3 layers, with caches, prefill then one decode step
+    import dataclasses
+    cuts = [(0, 2), (2, 3), (3, 5)]
+    whole = lo.State.empty(cfg, 2, 2, 8)
+    stages = [(layers[i:j], dataclasses.replace(cfg, n_layers=j - i), lo.State.empty(dataclasses.replace(cfg, n_layers=j - i), 2, 2, 8), 2 * i)
+              for i, j in cuts]
+    for x in (emb, RNG.normal(size=(2, 1, cfg.hidden))):
+        want = lo.stage_alg1(x, None, None, layers, cfg, whole, peers)
+        got = (x, None, None)
+        for ly, scfg, st, off in stages:
+            got = lo.stage_alg1(*got, ly, scfg, st, peers, module_offset=off)
+        for w, g_ in zip(want, got):
+            assert np.max(np.abs(w - g_)) < 1e-12
+    assert whole.pos == 5 and all(st.pos == 5 for _, _, st, _ in stages)
+    # the intermediate hand-off matters: feeding a later stage the summed stream instead is another function
+    mid = lo.stage_alg1(emb, None, None, layers[:2], stages[0][1], None, peers)
+    merged = lo.stage_alg1(mid[0] + mid[1] + mid[2], None, None, layers[2:], dataclasses.replace(cfg, n_layers=3), None, peers, 4)
+    split = lo.stage_alg1(*mid, layers[2:], dataclasses.replace(cfg, n_layers=3), None, peers, 4)
+    assert np.max(np.abs(sum(merged) - sum(split))) > 1e-3
+    assert np.max(np.abs(sum(split) - full)) < 1e-12
+
+
 def zero_field(layers, name):
     out = []
     for ly in layers:
