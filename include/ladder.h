@@ -191,6 +191,31 @@ int ladder_prefill(ladder_ctx* ctx, const void* x_in, int32_t B, int32_t T, void
  * is then invalid; the failing call itself does nothing and clears the condition). */
 int ladder_decode_step(ladder_ctx* ctx, const void* x_in, void* x_out);
 
+/* ---- pipeline stages (section "Compatibility with other Parallelism Techniques") ------------------
+ *
+ * A context whose layers are one pipeline stage of a deeper model: instead of embeddings it takes, and instead
+ * of x_2N it leaves, the three tensors that Algorithm 1 passes from block to block, with every reduction they
+ * depend on complete (at a stage boundary the asynchronous AllReduce has to be waited for):
+ *   residual   the stream without the outputs of the last two modules,
+ *   attn       the reduced output of the last attention module,
+ *   mlp        the reduced output of the last MLP module.
+ * The first block of the stage adds attn_in to the residual before its attention module and mlp_in before its
+ * MLP module, as every later block does with its predecessor's outputs.  The first stage is given the
+ * embeddings (as f32) in residual_in and NULL for attn_in and mlp_in (= zeros); the model's output x_2N is the
+ * sum of the three tensors the last stage leaves.  The outputs are computed as differences of consecutive
+ * streams (fp32: residual_out + attn_out reproduces the stream the stage held to within one rounding).
+ * Otherwise as ladder_prefill / ladder_decode_step (cache, position, batch, errors).  The synthetic peer partial
+ * sums of the stage's module m are set (m mod peer_pool) of THIS context.
+ *   residual_in, attn_in, mlp_in      device f32 [B][T][H] ([B][H] for a decode step), 16-byte aligned, caller-owned
+ *   residual_out, attn_out, mlp_out   device f32, same shape, distinct buffers; may be the input buffers
+ * Decode steps are launched eagerly also in a context that replays ladder_decode_step from a captured graph.
+ * Errors: LADDER_E_ARG (null residual_in / outputs, misaligned or coinciding outputs), LADDER_E_STATE also when
+ * a layer of the context has the standard or the parallel wiring (the hand-over is the ladder wiring's). */
+int ladder_prefill_stage(ladder_ctx* ctx, const float* residual_in, const float* attn_in, const float* mlp_in,
+                         int32_t B, int32_t T, float* residual_out, float* attn_out, float* mlp_out);
+int ladder_decode_step_stage(ladder_ctx* ctx, const float* residual_in, const float* attn_in, const float* mlp_in,
+                             float* residual_out, float* attn_out, float* mlp_out);
+
 /* Ends the block stack of ladder_init: releases everything the context owns (synchronises its streams
  * first).  NULL is a no-op. */
 void ladder_free(ladder_ctx* ctx);

@@ -202,8 +202,15 @@ size_t fused_gemv_lds_bytes();
 // rows, H columns) of the (at most two) modules that read x_0 (each times that module's gain), the sums of
 // squares per tile and row; also clears
 // n_zero words at zero_words (the step's arrival counters).
+// A pipeline stage that is not the first starts from three fp32 tensors instead (res non-null, emb null; att and
+// mlp may be null = zeros): x_{-1} = res + att is what operand a is made of, with its sums of squares in ssq_a,
+// x_0 = x_{-1} + mlp is the stream, operand b and ssq.  With emb both are the embeddings (ssq_a, if given, = ssq).
 struct EmbedArgs {
   const bf16_t* emb;
+  const float* res;
+  const float* att;
+  const float* mlp;
+  float* ssq_a;            // [H/16][16] or null
   float* x0;
   bf16_t* xop_a;
   const bf16_t* gain_a;

@@ -1029,14 +1029,20 @@ __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a) {
   const bool ok = i < n;
   const int ic = min(i, n - 1);
   const int row = ic / a.H, col = ic % a.H;
-  const float v = bf16_to_f32(a.emb[ic]);
+  float v, vp;   // x_0, and what module 1 reads (x_{-1}: the same rows unless a pipeline stage hands over)
+  if (a.res) {
+    vp = a.res[ic] + (a.att ? a.att[ic] : 0.f);
+    v = vp + (a.mlp ? a.mlp[ic] : 0.f);
+  } else {
+    v = vp = bf16_to_f32(a.emb[ic]);
+  }
   if (ok) {
     a.x0[ic] = v;
     const int S = fused_slots(a.rows);
     const size_t at = fused_xop_offset(S, row, col);
     if (a.xop_a) {
       uint32_t hi, lo;
-      split_bf16(v * bf16_to_f32(a.gain_a[col]), hi, lo);
+      split_bf16(vp * bf16_to_f32(a.gain_a[col]), hi, lo);
       a.xop_a[at] = (bf16_t)hi;
       a.xop_a[at + (S / 2) * 8] = (bf16_t)lo;
     }
@@ -1053,11 +1059,20 @@ __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a) {
   s += __shfl_xor(s, 4, 64);
   s += __shfl_xor(s, 8, 64);
   if (ok && (col & 15) == 0) a.ssq[(size_t)(col >> 4) * 16 + row] = s;
+  if (a.ssq_a) {
+    float sp = ok ? vp * vp : 0.f;
+    sp += __shfl_xor(sp, 1, 64);
+    sp += __shfl_xor(sp, 2, 64);
+    sp += __shfl_xor(sp, 4, 64);
+    sp += __shfl_xor(sp, 8, 64);
+    if (ok && (col & 15) == 0) a.ssq_a[(size_t)(col >> 4) * 16 + row] = sp;
+  }
   if (i < a.n_zero) a.zero_words[i] = 0u;
 }
 
 hipError_t launch_embed(const EmbedArgs& a, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
-  if (a.rows <= 0 || a.rows > 16 || a.H <= 0 || (a.H & 15) || !a.emb || !a.x0 || !a.ssq) return hipErrorInvalidValue;
+  if (a.rows <= 0 || a.rows > 16 || a.H <= 0 || (a.H & 15) || (!a.emb == !a.res) || !a.x0 || !a.ssq) return hipErrorInvalidValue;
+  if (!a.res && (a.att || a.mlp)) return hipErrorInvalidValue;
   if ((a.xop_a && !a.gain_a) || (a.xop_b && !a.gain_b)) return hipErrorInvalidValue;
   const dim3 grid((std::max(a.rows * a.H, a.n_zero) + 255) / 256), block(256);
   if (ev0 || ev1) hipExtLaunchKernelGGL(embed_kernel, grid, block, 0, s, ev0, ev1, 0, a);

@@ -130,6 +130,7 @@ struct ladder_ctx {
   // MLP reader); and the rows' sums of squares per 16-column tile, [H/16][16]
   std::vector<std::array<bf16_t*, 2>> xop_ring;
   std::vector<float*> ssq_ring;
+  float* ssq_first = nullptr;   // sums of squares of what module 1 reads when its lag is 2 (x_0, or a stage's x_{-1})
   std::vector<bf16_t*> f_q, f_act;   // split q, SwiGLU output: [32][width]
   std::vector<bf16_t*> f_o;          // attention output
   // chained step (decode_fused = 3): persistent workgroups, the step's launch list as per-slot item lists and
@@ -502,6 +503,52 @@ __global__ __launch_bounds__(64) void wait_until_kernel(const unsigned long long
   }
 }
 
+// What a pipeline stage takes from the stage before it and hands to the next one (section "Compatibility with other
+// Parallelism Techniques"): the stream without the last two module outputs, and those two outputs, fp32 [rows][H].
+struct StageIo {
+  const float *res, *att, *mlp;     // in (att, mlp: null = zeros)
+  float *r_out, *a_out, *m_out;     // out
+};
+
+// r = x_{2N-2}, a = x_{2N-1} - x_{2N-2}, m = x_{2N} - x_{2N-1}, element by element (the inputs may be the outputs:
+// every thread reads its element of all three before it writes)
+__global__ __launch_bounds__(256) void stage_out_kernel(const float4* x2, const float4* x1, const float4* x0,
+                                                        float4* r, float4* a, float4* m, size_t n4) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
+    const float4 v2 = x2[i], v1 = x1[i], v0 = x0[i];
+    r[i] = v2;
+    a[i] = make_float4(v1.x - v2.x, v1.y - v2.y, v1.z - v2.z, v1.w - v2.w);
+    m[i] = make_float4(v0.x - v1.x, v0.y - v1.y, v0.z - v1.z, v0.w - v1.w);
+  }
+}
+int launch_stage_out(ladder_ctx* c, const float* x2, const float* x1, const float* x0, const StageIo& st, int rows, hipStream_t s) {
+  const size_t n4 = (size_t)rows * c->cfg.hidden / 4;   // (hidden is a multiple of 4: checked at init for every path)
+  const unsigned grid = (unsigned)std::min<size_t>((n4 + 255) / 256, 4096);
+  HIP_TRY(c, timed(c, LADDER_K_OTHER, s, [&] {
+    hipLaunchKernelGGL(stage_out_kernel, dim3(grid), dim3(256), 0, s, (const float4*)x2, (const float4*)x1, (const float4*)x0,
+                       (float4*)st.r_out, (float4*)st.a_out, (float4*)st.m_out, n4);
+    return hipGetLastError();
+  }));
+  return LADDER_OK;
+}
+
+// the start of a stage that is handed three tensors: x_{-1} = res + att (module 1 reads it), x_0 = x_{-1} + mlp (the
+// stream; module 2 reads it); ladder wiring in both modules
+int run_stage_in(ladder_ctx* c, const StageIo& st, int rows, hipStream_t s) {
+  const ladder_config& g = c->cfg;
+  HIP_TRY(c, hipMemcpyAsync(c->x, st.res, (size_t)rows * g.hidden * 4, hipMemcpyDeviceToDevice, s));
+  for (int cm = 1; cm <= 2; ++cm) {
+    ReduceNormArgs a{};
+    a.x = c->x; a.rows = rows; a.H = g.hidden; a.eps = g.rms_eps;
+    a.parts = cm == 1 ? st.att : st.mlp; a.n_parts = a.parts ? 1 : 0; a.part_stride = (size_t)rows * g.hidden;
+    a.out_a = c->y[cm & 1];
+    a.gain_a = cm == 1 ? (const void*)c->gain_attn[0] : (const void*)c->gain_mlp[0];
+    c->y_scale[cm & 1] = nullptr;   // normed rows
+    HIP_TRY(c, timed(c, LADDER_K_REDUCE_NORM, s, [&] { return launch_reduce_norm(a, c->bf16, s); }));
+  }
+  return LADDER_OK;
+}
+
 int run_reduce(ladder_ctx* c, int m, int rows, int n_slots, const void* emb, float* x_out, hipStream_t s) {
   const ladder_config& g = c->cfg;
   ReduceNormArgs a{};
@@ -547,12 +594,13 @@ int run_reduce(ladder_ctx* c, int m, int rows, int n_slots, const void* emb, flo
 //     residual is updated in place, in module order) through an event.
 //   else reduce_on_side_stream: all modules on s_attn, all reduces on the side stream.
 //   else (and for every call with more than 64 rows): everything in order on s_attn.
-int forward_body(ladder_ctx* c, const void* x_in, int B, int T, int pos0, void* x_out) {
+int forward_body(ladder_ctx* c, const void* x_in, int B, int T, int pos0, void* x_out, const StageIo* st = nullptr) {
   const int rows = B * T;
   // calls with more than 64 rows (prefill) run in order on one stream: each of their kernels fills the
   // chip, and the same work measured 4 % (reduce on the side stream) to 16 % (two module streams) slower
   // when spread over streams
-  const bool small = rows <= 64;
+  // (and so does a pipeline stage's call: its hand-over reads the stream between the last modules)
+  const bool small = rows <= 64 && !st;
   const bool overlap = small && c->cfg.overlap_modules != 0;
   const bool side = small && !overlap && c->cfg.reduce_on_side_stream != 0;
   hipStream_t s0 = c->s_attn;
@@ -561,8 +609,9 @@ int forward_body(ladder_ctx* c, const void* x_in, int B, int T, int pos0, void* 
   // (the skinny kernels have no such epilogue, several real shards would each add to the residual, and the
   // emulated collective latency wants the reduce as a step of its own)
   const bool fuse = c->fast && rows > 64 && c->cfg.n_real_shards == 1 && c->cfg.reduce_delay_us == 0;
-  int rc = run_reduce(c, 0, rows, 0, x_in, c->n_mod == 0 ? (float*)x_out : nullptr, s0);
+  int rc = st ? run_stage_in(c, *st, rows, s0) : run_reduce(c, 0, rows, 0, x_in, c->n_mod == 0 ? (float*)x_out : nullptr, s0);
   if (rc) return rc;
+  const size_t x_bytes = (size_t)rows * c->cfg.hidden * 4;
   if (overlap && c->n_mod >= 2) {  // fork: the MLP stream starts once x_0 and its normed copies exist
     HIP_TRY(c, hipEventRecord(c->ev_fork, s0));
     HIP_TRY(c, hipStreamWaitEvent(c->s_mlp, c->ev_fork, 0));
@@ -573,17 +622,26 @@ int forward_body(ladder_ctx* c, const void* x_in, int B, int T, int pos0, void* 
     const int src = m - lag_of(c, m);
     if (src >= 1 && reduce_stream(src) != sm) HIP_TRY(c, hipStreamWaitEvent(sm, c->ev_red[src & 1], 0));
     int n_slots = 0;
+    // (a stage's hand-over: the stream as it is before the last attention module's output joins it ...)
+    if (st && m == c->n_mod - 1) HIP_TRY(c, hipMemcpyAsync(st->r_out, c->x, x_bytes, hipMemcpyDeviceToDevice, s0));
     rc = run_module(c, m, B, T, pos0, sm, &n_slots, fuse, m == c->n_mod ? (float*)x_out : nullptr);
     if (rc) return rc;
-    if (n_slots < 0) continue;   // the module has updated the residual itself (wide calls run on one stream)
-    if (rs != sm) {
-      HIP_TRY(c, hipEventRecord(c->ev_mod[m & 1], sm));
-      HIP_TRY(c, hipStreamWaitEvent(rs, c->ev_mod[m & 1], 0));
+    if (n_slots >= 0) {   // (else the module has updated the residual itself: wide calls run on one stream)
+      if (rs != sm) {
+        HIP_TRY(c, hipEventRecord(c->ev_mod[m & 1], sm));
+        HIP_TRY(c, hipStreamWaitEvent(rs, c->ev_mod[m & 1], 0));
+      }
+      if (m >= 2 && reduce_stream(m - 1) != rs) HIP_TRY(c, hipStreamWaitEvent(rs, c->ev_red[(m - 1) & 1], 0));
+      rc = run_reduce(c, m, rows, n_slots, nullptr, m == c->n_mod ? (float*)x_out : nullptr, rs);
+      if (rc) return rc;
+      if (overlap || side) HIP_TRY(c, hipEventRecord(c->ev_red[m & 1], rs));
     }
-    if (m >= 2 && reduce_stream(m - 1) != rs) HIP_TRY(c, hipStreamWaitEvent(rs, c->ev_red[(m - 1) & 1], 0));
-    rc = run_reduce(c, m, rows, n_slots, nullptr, m == c->n_mod ? (float*)x_out : nullptr, rs);
-    if (rc) return rc;
-    if (overlap || side) HIP_TRY(c, hipEventRecord(c->ev_red[m & 1], rs));
+    // (... and after it has; the two outputs are the differences of consecutive streams)
+    if (st && m == c->n_mod - 1) HIP_TRY(c, hipMemcpyAsync(st->a_out, c->x, x_bytes, hipMemcpyDeviceToDevice, s0));
+    if (st && m == c->n_mod) {
+      rc = launch_stage_out(c, st->r_out, st->a_out, c->x, *st, rows, s0);
+      if (rc) return rc;
+    }
   }
   // join: the last reduce is after every module and every earlier reduce
   if (c->n_mod >= 1 && reduce_stream(c->n_mod) != s0) HIP_TRY(c, hipStreamWaitEvent(s0, c->ev_red[c->n_mod & 1], 0));
@@ -628,6 +686,7 @@ void build_fused_plan(ladder_ctx* c, int B) {
     GemvJob j{};
     j.xb = c->xop_ring[R(src)][1]; j.ldx = H; j.normed = 1; j.eps = g.rms_eps; j.ssq = c->ssq_ring[R(src)];
     j.reads_stream = src;
+    if (l == 1 && lag_of(c, 1) == 2) j.ssq = c->ssq_first;   // (x_{-1}: x_0 itself unless a pipeline stage hands over)
     j.wp = layer(l).pqkv; j.M = B; j.K = H; j.N = c->nqkv;
     j.n_groups = c->nqkv / 16; j.epi = EPI_QKV_ROPE;
     j.q_out = c->f_q[F(l)];
@@ -1095,7 +1154,7 @@ int ensure_fused_plan(ladder_ctx* c, int B) {
 // both are left to the caller of this function: the result must not appear before its collective is over.)
 // *finished: bit 0 = the result is in x_out, bit 1 = the position has been advanced
 enum { FUSED_DELIVERED = 1, FUSED_ADVANCED = 2 };
-int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s, float* x_out, int* finished) {
+int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s, float* x_out, int* finished, const StageIo* st = nullptr) {
   const ladder_config& g = c->cfg;
   {
     const int rc = ensure_fused_plan(c, B);
@@ -1142,6 +1201,8 @@ int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s, float* x_ou
     // x_0 and the operands of the modules that read it (module 1, and module 2 where its lag is 2)
     EmbedArgs ea{};
     ea.emb = (const bf16_t*)emb; ea.x0 = c->x_ring[0]; ea.ssq = c->ssq_ring[0]; ea.rows = B; ea.H = g.hidden;
+    if (st) { ea.emb = nullptr; ea.res = st->res; ea.att = st->att; ea.mlp = st->mlp; }
+    if (lag_of(c, 1) == 2) ea.ssq_a = c->ssq_first;
     ea.zero_words = c->att_done; ea.n_zero = c->n_zero_words;
     int cons[2];
     const int nc = consumers_of(c, 0, cons);
@@ -1175,6 +1236,11 @@ int fused_body(ladder_ctx* c, const void* emb, int B, hipStream_t s, float* x_ou
       return hipGetLastError();
     }));
   }
+  if (st) {   // the last three streams of the step are still in their ring slots (the ring has at least three)
+    auto X = [&](int m) { return c->x_ring[(size_t)(m % c->ring_n)]; };
+    const int rc = launch_stage_out(c, X(c->n_mod - 2), X(c->n_mod - 1), X(c->n_mod), *st, B, s);
+    if (rc) return rc;
+  }
   return LADDER_OK;
 }
 
@@ -1189,10 +1255,10 @@ int fence_out(ladder_ctx* c) {
   return LADDER_OK;
 }
 
-int forward(ladder_ctx* c, const void* x_in, int B, int T, int pos0, void* x_out) {
+int forward(ladder_ctx* c, const void* x_in, int B, int T, int pos0, void* x_out, const StageIo* st = nullptr) {
   int rc = fence_in(c);
   if (rc) return rc;
-  rc = forward_body(c, x_in, B, T, pos0, x_out);
+  rc = forward_body(c, x_in, B, T, pos0, x_out, st);
   if (rc) return rc;
   return fence_out(c);
 }
@@ -1250,16 +1316,17 @@ int decode_graph_step(ladder_ctx* c, const void* x_in, void* x_out) {
   return fence_out(c);
 }
 
-// one decode step of the fused path, launched eagerly
-int decode_fused_step(ladder_ctx* c, const void* x_in, void* x_out) {
+// one decode step of the fused path, launched eagerly (st: a pipeline stage's step, which takes and leaves its
+// three tensors instead of x_in / x_out)
+int decode_fused_step(ladder_ctx* c, const void* x_in, void* x_out, const StageIo* st = nullptr) {
   const int B = c->batch, H = c->cfg.hidden;
   int rc = fence_in(c);
   if (rc) return rc;
   int finished = 0;
-  rc = fused_body(c, x_in, B, c->s_attn, (float*)x_out, &finished);
+  rc = fused_body(c, x_in, B, c->s_attn, (float*)x_out, &finished, st);
   if (rc) return rc;
   // (what the last launch has not done itself)
-  if (!(finished & FUSED_DELIVERED))
+  if (!st && !(finished & FUSED_DELIVERED))
     HIP_TRY(c, hipMemcpyAsync(x_out, c->x_ring[(size_t)(c->n_mod % c->ring_n)], (size_t)B * H * 4, hipMemcpyDeviceToDevice, c->s_attn));
   if (!(finished & FUSED_ADVANCED)) {
     hipLaunchKernelGGL(inc_pos_kernel, dim3(1), dim3(1), 0, c->s_attn, c->pos_dev);
@@ -1495,6 +1562,7 @@ static int init_impl(const ladder_config* cfg, void* hip_stream, ladder_ctx** ou
         INIT_TRY(dev_alloc(c, (void**)&c->f_act[(size_t)i], ring_slots * I * 2, true));
         INIT_TRY(dev_alloc(c, (void**)&c->f_o[(size_t)i], (size_t)32 * nq * d * 2, true));
       }
+      INIT_TRY(dev_alloc(c, (void**)&c->ssq_first, (size_t)(H / 16) * 16 * 4, true));
       INIT_TRY(dev_alloc(c, (void**)&c->t_done, (size_t)(c->n_mod + 1) * 8, true));
       // arrival counters of the attention jobs (a cache line each) and, for a chained step, the completion words of
       // its projections behind them: one range, cleared by the embedding kernel at the start of every step
@@ -1663,6 +1731,70 @@ int ladder_decode_step(ladder_ctx* c, const void* x_in, void* x_out) {
     if (rc) return rc;
   } else {
     rc = forward(c, x_in, c->batch, 1, c->pos, x_out);
+    if (rc) return rc;
+    hipLaunchKernelGGL(inc_pos_kernel, dim3(1), dim3(1), 0, c->main, c->pos_dev);
+    HIP_TRY(c, hipGetLastError());
+  }
+  c->pos += 1;
+  return LADDER_OK;
+}
+
+static int stage_args(ladder_ctx* c, const float* res, const float* att, const float* mlp, float* r, float* a, float* m, StageIo* st) {
+  if (!res || !r || !a || !m) return fail(c, LADDER_E_ARG, "null residual_in / output tensor");
+  if (r == a || r == m || a == m) return fail(c, LADDER_E_ARG, "the three output tensors must be distinct");
+  for (const void* p : {(const void*)res, (const void*)att, (const void*)mlp, (const void*)r, (const void*)a, (const void*)m})
+    if ((uintptr_t)p & 15) return fail(c, LADDER_E_ARG, "stage tensors must be 16-byte aligned");
+  for (int q = 1; q <= c->n_mod; ++q)
+    if (lag_of(c, q) != 2) return fail(c, LADDER_E_STATE, "pipeline-stage calls need the ladder wiring in every layer");
+  *st = StageIo{res, att, mlp, r, a, m};
+  return LADDER_OK;
+}
+
+int ladder_prefill_stage(ladder_ctx* c, const float* residual_in, const float* attn_in, const float* mlp_in, int32_t B, int32_t T,
+                         float* residual_out, float* attn_out, float* mlp_out) {
+  if (!c) return LADDER_E_ARG;
+  StageIo st{};
+  int rc = stage_args(c, residual_in, attn_in, mlp_in, residual_out, attn_out, mlp_out, &st);
+  if (rc) return rc;
+  const ladder_config& g = c->cfg;
+  if (B <= 0 || T <= 0) return fail(c, LADDER_E_ARG, "B and T must be positive");
+  if (B > g.max_batch) return fail(c, LADDER_E_SHAPE, "B exceeds max_batch");
+  if (T > g.max_seq) return fail(c, LADDER_E_OVERFLOW, "T exceeds max_seq");
+  if (T > g.max_tokens) return fail(c, LADDER_E_SHAPE, "T exceeds max_tokens");
+  if (c->peers && B * T > g.peer_rows) return fail(c, LADDER_E_SHAPE, "B*T exceeds peer_rows");
+  rc = check_device_error(c);
+  if (rc) return rc;
+  rc = all_loaded(c);
+  if (rc) return rc;
+  rc = forward(c, nullptr, B, T, 0, nullptr, &st);
+  if (rc) return rc;
+  for (auto& X : c->store) { X.kv_B = 0; X.kv_S = 0; }
+  c->pos = T;
+  c->batch = B;
+  hipLaunchKernelGGL(set_pos_kernel, dim3(1), dim3(1), 0, c->main, c->pos_dev, T);
+  HIP_TRY(c, hipGetLastError());
+  return LADDER_OK;
+}
+
+int ladder_decode_step_stage(ladder_ctx* c, const float* residual_in, const float* attn_in, const float* mlp_in,
+                             float* residual_out, float* attn_out, float* mlp_out) {
+  if (!c) return LADDER_E_ARG;
+  StageIo st{};
+  int rc = stage_args(c, residual_in, attn_in, mlp_in, residual_out, attn_out, mlp_out, &st);
+  if (rc) return rc;
+  if (c->batch <= 0 || c->pos <= 0) return fail(c, LADDER_E_STATE, "decode before prefill / load_kv");
+  if (c->pos + 1 > c->cfg.max_seq) return fail(c, LADDER_E_OVERFLOW, "KV cache is full");
+  if (c->peers && c->batch > c->cfg.peer_rows) return fail(c, LADDER_E_SHAPE, "batch exceeds peer_rows");
+  rc = check_device_error(c);
+  if (rc) return rc;
+  rc = all_loaded(c);
+  if (rc) return rc;
+  // (launched eagerly also where ladder_decode_step replays a captured graph: the graph holds that call's staging)
+  if (c->fused) {
+    rc = decode_fused_step(c, nullptr, nullptr, &st);
+    if (rc) return rc;
+  } else {
+    rc = forward(c, nullptr, c->batch, 1, c->pos, nullptr, &st);
     if (rc) return rc;
     hipLaunchKernelGGL(inc_pos_kernel, dim3(1), dim3(1), 0, c->main, c->pos_dev);
     HIP_TRY(c, hipGetLastError());

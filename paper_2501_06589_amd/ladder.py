@@ -44,6 +44,8 @@ EXPORTS = {
     "ladder_load_kv": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]),
     "ladder_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]),
     "ladder_decode_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "ladder_prefill_stage": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "ladder_decode_step_stage": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "ladder_free": (None, [C.c_void_p]),
     "ladder_last_error": (C.c_char_p, [C.c_void_p]),
     "ladder_position": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
@@ -207,6 +209,30 @@ class Ladder:
         self._want("x_out", x_out, max(batch, 1) * self.cfg.hidden, storage=False)
         self._check(self._lib.ladder_decode_step(self._h, _ptr(x_in), _ptr(x_out)))
         return x_out
+
+    # -- pipeline stages: (residual, attn_out, mlp_out) in, the same three out
+    def _stage_io(self, handoff, n):
+        import torch
+        res, att, mlp = handoff
+        self._want("residual_in", res, n, storage=False)
+        for name, t in (("attn_in", att), ("mlp_in", mlp)):
+            if t is not None:
+                self._want(name, t, n, storage=False)
+        outs = tuple(torch.empty(res.shape, dtype=torch.float32, device=res.device) for _ in range(3))
+        return (res, att, mlp), outs
+
+    def prefill_stage(self, handoff):
+        """handoff: (residual, attn_out, mlp_out), f32 device [B][T][H]; attn_out / mlp_out may be None (first stage)."""
+        b, t, _ = handoff[0].shape
+        ins, outs = self._stage_io(handoff, b * t * self.cfg.hidden)
+        self._check(self._lib.ladder_prefill_stage(self._h, *[_ptr(x) for x in ins], b, t, *[_ptr(x) for x in outs]))
+        return outs
+
+    def decode_step_stage(self, handoff):
+        _, batch = self.position()
+        ins, outs = self._stage_io(handoff, max(batch, 1) * self.cfg.hidden)
+        self._check(self._lib.ladder_decode_step_stage(self._h, *[_ptr(x) for x in ins], *[_ptr(x) for x in outs]))
+        return outs
 
     # -- generation head
     def load_head(self, table, final_norm, w_lm):
