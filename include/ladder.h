@@ -274,7 +274,8 @@ int ladder_head_static(ladder_ctx* ctx, const float* x, int32_t rows, int32_t* t
 /* ---- helpers ---------------------------------------------------------------------------- */
 
 /* Text of the last error of this context (or of the last failed ladder_init / sizing call when ctx is NULL).
- * The pointer stays valid until the next failing call. */
+ * The pointer stays valid until the next failing call.  (With LADDER_DEBUG set in the environment the library
+ * also writes the host-side steps of graph capture and of the per-operation schedule to stderr.) */
 const char* ladder_last_error(const ladder_ctx* ctx);
 
 /* Where the context stands in the prefill-then-decode run (section "Setup"): current number of cached

@@ -8,10 +8,8 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 
 // workgroup tile of the large-M GEMM: 16 row tiles (256 x 256) at one wave per SIMD, or 8 (128 x 256) at two
-#ifndef GEMM_WM_LARGE
 #define GEMM_WM_LARGE 8
 #define GEMM_WAVES_LARGE 2
-#endif
 
 __device__ __forceinline__ void unpack8(const uint4 v, float (&f)[8]) {
   f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
@@ -212,12 +210,8 @@ __global__ __launch_bounds__(256, MIN_WAVES) void gemm_mfma_kernel(GemmArgs a) {
   // Workgroups are handed to the 8 XCDs round robin by block index and every XCD has its own L2: block
   // index i is mapped to position (i % 8) * (n / 8) + i / 8 of the tile order, so that each XCD works
   // through one contiguous eighth of it and neighbours in the order (which share operands) meet in one L2.
-#ifndef GEMM_NO_XCD_REMAP
   const int nblk = gridDim.x, nblk8 = nblk & ~7;
   const int bid = (int)blockIdx.x < nblk8 ? ((int)blockIdx.x & 7) * (nblk8 >> 3) + ((int)blockIdx.x >> 3) : (int)blockIdx.x;
-#else
-  const int bid = blockIdx.x;
-#endif
   // grouped rasterisation: GROUP_M row blocks share one column block back to back
   const int per_group = GEMM_GROUP_M * tiles_n;
   const int group = bid / per_group, in_group = bid % per_group;
@@ -356,9 +350,7 @@ static hipError_t launch_gemm_wm(const GemmArgs& a, hipStream_t s) {
 // and no register staging; 971 -> 1129, 908 -> 993, 1098 -> 1271, 1158 -> 1338 TFLOP/s on the QKV / O / down /
 // gate-up shapes of the 70B R = 4 shard at 32768 rows.
 // ------------------------------------------------------------------------------------------------
-#ifndef GEMM2_GROUP_M
 #define GEMM2_GROUP_M 4
-#endif
 #define GEMM2_LDSP(p) ((__attribute__((address_space(3))) void*)(p))
 #define GEMM2_GLBP(p) ((const __attribute__((address_space(1))) void*)(p))
 
@@ -664,12 +656,8 @@ static hipError_t launch_gemm_lds(const GemmArgs& a, hipStream_t s) {
 }
 
 static bool gemm_takes_lds_kernel(const GemmArgs& a) {
-#ifndef GEMM_NO_LDS_KERNEL
   // 256 x 256 tiles, one per CU, when they fill the chip at least once; else the smaller tiles
   return (long)((a.M + 255) / 256) * ((a.N + 255) / 256) >= 256 && (a.K & 63) == 0 && a.K >= 256;
-#else
-  return false;
-#endif
 }
 
 int gemm_ssq_parts(const GemmArgs& a) { return gemm_takes_lds_kernel(a) ? (a.N + 255) / 256 : (a.N + 63) / 64; }
@@ -685,10 +673,8 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
                           (a.xh_a && !a.gain_a) || (a.xh_b && !a.gain_b)))
     return hipErrorInvalidValue;
   if (gemm_takes_lds_kernel(a)) return launch_gemm_lds(a, s);
-#ifndef GEMM_NO_SMALL_TILE_RULE
   // few rows: where 128-row tiles would not give every CU a workgroup, 64-row tiles (1.2B shape, 1024 rows: 9.0 -> 8.4 ms per call)
   if (a.M > 64 && (long)((a.M + 127) / 128) * ((a.N + 255) / 256) < 256) return launch_gemm_wm<4, 2>(a, s);
-#endif
   if (a.M >= 1024) return launch_gemm_wm<GEMM_WM_LARGE, GEMM_WAVES_LARGE>(a, s);
   if (a.M > 64) return launch_gemm_wm<8, 2>(a, s);   // 128 x 256
   return launch_gemm_wm<4, 2>(a, s);                 //  64 x 256
@@ -995,11 +981,9 @@ __global__ __launch_bounds__(256, QT <= 3 ? 2 : 1) void attn_prefill_lds_kernel(
   }
 }
 
-#ifndef ATTN_LDS_QT
 #define ATTN_LDS_QT 3   // 16-query tiles per wavefront.  Measured on 16 x 2048 tokens, 16 q / 2 kv heads, d = 128:
                         // 2 tiles 0.80 ms, 3 tiles 0.55 ms, 4 tiles 1.45 ms per layer (4 leaves one wavefront
                         // per SIMD, which cannot hide the global -> LDS latency; 2 doubles the LDS reads per flop)
-#endif
 template <int D>
 static hipError_t launch_attn_prefill_lds(const AttnPrefillArgs& a, hipStream_t s) {
   const int g = a.nq / a.nkv;
