@@ -307,33 +307,29 @@ def forward_alg1(emb: np.ndarray, layers: Sequence[Layer], cfg: OracleConfig,
 def stage_alg1(residual: np.ndarray, attn_out: Optional[np.ndarray], mlp_out: Optional[np.ndarray],
                layers: Sequence[Layer], cfg: OracleConfig, state: Optional[State] = None,
                peers: Optional[np.ndarray] = None, module_offset: int = 0):
-    """One pipeline stage (section "Compatibility with other Parallelism Techniques"): the layers of `layers`
-    (cfg.n_layers of them, with their own caches in `state`) as a run of Algorithm 1 blocks that starts from
-    what the previous stage hands over and returns what the next stage needs -- three tensors [B, T, H]:
+    """One pipeline stage (section "Compatibility with other Parallelism Techniques"): the modules of `layers`
+    (cfg.n_layers layers, with their own caches in `state`) in the variable-passing form of `forward_alg1`, except
+    that the run neither starts from nothing outstanding nor ends by adding what is: it starts from what the stage
+    before hands over and returns what the next stage needs -- three tensors [B, T, H]:
 
-        residual   the stream without the last two module outputs,
+        residual   the stream without the outputs of the last two modules,
         attn_out   the reduced output of the last attention module,
-        mlp_out    the reduced output of the last MLP module.
+        mlp_out    the reduced output of the last MLP module          (ladder wiring only).
 
-    A block first adds the previous block's attention output to the residual, runs its attention module on the
-    normed residual, then adds the previous block's MLP output and runs its MLP module (ladder wiring only).
-    The first stage gets residual = embeddings and no outputs (None = zeros); the model's output is the sum of
-    the three tensors the last stage returns.  `module_offset` = number of modules in the stages before this
-    one; it only selects which synthetic peer partial sums a module's reduction adds (global module index)."""
-    residual = np.asarray(residual, dtype=F64).copy()
-    prev_attn = np.zeros_like(residual) if attn_out is None else np.asarray(attn_out, dtype=F64)
-    prev_mlp = np.zeros_like(residual) if mlp_out is None else np.asarray(mlp_out, dtype=F64)
+    The first stage gets residual = embeddings and no outputs (None = zeros, which add nothing); the model's
+    output x_2N is the sum of the three tensors the last stage returns.  `module_offset` = number of modules in
+    the stages before this one; it only selects which synthetic peer partial sums a module's reduction adds."""
+    stream = np.asarray(residual, dtype=F64).copy()
+    zero = np.zeros_like(stream)
+    outstanding = [zero if attn_out is None else np.asarray(attn_out, dtype=F64),     # oldest first: the outputs of
+                   zero if mlp_out is None else np.asarray(mlp_out, dtype=F64)]       # the two modules before module 1
     s0 = state.pos if state is not None else 0
-    for l in range(1, cfg.n_layers + 1):
-        residual = residual + prev_attn
-        m = 2 * l - 1
-        prev_attn = all_reduce(module_offset + m, module_partials(m, residual, layers, cfg, state, s0), peers, cfg)
-        residual = residual + prev_mlp
-        m = 2 * l
-        prev_mlp = all_reduce(module_offset + m, module_partials(m, residual, layers, cfg, state, s0), peers, cfg)
+    for m in range(1, 2 * cfg.n_layers + 1):
+        stream = stream + outstanding.pop(0)       # module m reads the stream up to the output of module m-2
+        outstanding.append(all_reduce(module_offset + m, module_partials(m, stream, layers, cfg, state, s0), peers, cfg))
     if state is not None:
-        state.pos = s0 + residual.shape[1]
-    return residual, prev_attn, prev_mlp
+        state.pos = s0 + stream.shape[1]
+    return stream, outstanding[0], outstanding[1]
 
 
 # ---------------------------------------------------------------------------

@@ -16,7 +16,7 @@ PIN_FUNCS = [
     pins.test_eq2_form_equals_alg1_form, pins.test_ladder_reduces_to_standard_when_in_between_outputs_vanish,
     pins.test_kv_cached_decode_equals_full_recompute, pins.test_module_input_is_two_modules_stale,
     pins.test_causality_and_batch_independence, pins.test_reduce_is_linear_in_peer_partials,
-    lambda: pins.test_brute_force_tiny(2, 2),
+    lambda: pins.test_brute_force_tiny(2, 2), pins.test_pipeline_stage_hands_over_the_index_forms_tensors,
 ]
 
 
@@ -116,6 +116,28 @@ def m_round_truncate(a):
     return np.ldexp(np.trunc(m * 256.0) / 256.0, e)
 
 
+def m_stage_outputs_swapped(residual, attn_out, mlp_out, *a, **k):
+    r, x, y = _orig["stage_alg1"](residual, attn_out, mlp_out, *a, **k)
+    return r, y, x
+
+
+def m_stage_inputs_swapped(residual, attn_out, mlp_out, *a, **k):
+    return _orig["stage_alg1"](residual, mlp_out, attn_out, *a, **k)
+
+
+def m_stage_drops_handed_over_mlp(residual, attn_out, mlp_out, *a, **k):
+    return _orig["stage_alg1"](residual, attn_out, None, *a, **k)
+
+
+def m_stage_residual_complete(residual, attn_out, mlp_out, *a, **k):
+    r, x, y = _orig["stage_alg1"](residual, attn_out, mlp_out, *a, **k)
+    return r + x, x, y          # hands over the stream with the attention output already in it, and the output again
+
+
+def m_stage_ignores_module_offset(residual, attn_out, mlp_out, layers, cfg, state=None, peers=None, module_offset=0):
+    return _orig["stage_alg1"](residual, attn_out, mlp_out, layers, cfg, state, peers, 1 if module_offset else 0)
+
+
 MUTANTS = {
     "rope": [m_rope_sign, m_rope_halfsplit, m_rope_freq],
     "rmsnorm": [m_norm_eps_outside, m_norm_no_gain, m_norm_mean_subtracted],
@@ -125,6 +147,8 @@ MUTANTS = {
     "all_reduce": [m_allreduce_drop_peer, m_allreduce_pool_shift, m_allreduce_first_only],
     "_lags": [m_lags_three, m_lags_parallel_as_ladder, m_lags_parallel_swapped],
     "round_bf16": [m_round_truncate],
+    "stage_alg1": [m_stage_outputs_swapped, m_stage_inputs_swapped, m_stage_drops_handed_over_mlp, m_stage_residual_complete,
+                   m_stage_ignores_module_offset],
 }
 _orig = {k: getattr(lo, k) for k in MUTANTS}
 
