@@ -30,20 +30,20 @@ def harness():
     return gpu_harness
 
 
-def run_stages(harness, w, cuts, *, kv_preload=0, steps=3, **cfg_override):
+def run_stages(harness, w, cuts, *, kv_preload=0, steps=3, gen_device="cpu", **cfg_override):
     """The model of workload `w` as one context and as the stages `cuts` = [(first layer, end layer), ...]; returns
     per call: (per stage [(gpu three, oracle three)], gpu x_2N of the one context, oracle x_2N)."""
     from oracle import from_torch
     from oracle import ladder_oracle as lo
     harness.say(f"[stage case] {w.name} L={w.n_layers} cuts={cuts} kv={kv_preload} T={w.prefill} steps={steps} cfg={cfg_override}")
-    tensors = harness.make_tensors(w)
+    tensors = harness.make_tensors(w, gen_device)     # (full-width cases generate on the GPU: seconds instead of minutes)
     rows = w.batch * max(w.prefill, 1)
-    peers = inputs.peer_partials(w, rows) if w.n_peers else None
+    peers = inputs.peer_partials(w, rows, gen_device) if w.n_peers else None
     whole = harness.build_gpu(w, tensors, peers, **cfg_override)
     stages = [harness.build_gpu(w.with_(n_layers=j - i), tensors[i:j], peers, **cfg_override) for i, j in cuts]
     cfg = from_torch.config_from_workload(w)
     layers = [from_torch.layer_from_tensors([{k: v.cpu() for k, v in t.items()} for t in tensors[i]]) for i in range(w.n_layers)]
-    opeers = from_torch.to_f64(peers) if peers is not None else None
+    opeers = from_torch.to_f64(peers.cpu()) if peers is not None else None
     o_whole = lo.State.empty(cfg, w.n_real_shards, w.batch, w.max_seq + kv_preload)
     o_cfgs = [dataclasses.replace(cfg, n_layers=j - i) for i, j in cuts]
     o_states = [lo.State.empty(c, w.n_real_shards, w.batch, w.max_seq + kv_preload) for c in o_cfgs]
@@ -51,23 +51,23 @@ def run_stages(harness, w, cuts, *, kv_preload=0, steps=3, **cfg_override):
         for i in range(w.n_layers):
             s = next(k for k, (a, b) in enumerate(cuts) if a <= i < b)
             for r in range(w.n_real_shards):
-                k, v = inputs.kv_cache(w, i, r, w.batch, kv_preload)
+                k, v = inputs.kv_cache(w, i, r, w.batch, kv_preload, gen_device)
                 whole.load_kv(i, r, k.to(DEV), v.to(DEV))
                 stages[s].load_kv(i - cuts[s][0], r, k.to(DEV), v.to(DEV))
-                from_torch.load_kv(o_whole, i, r, k, v)
-                from_torch.load_kv(o_states[s], i - cuts[s][0], r, k, v)
+                from_torch.load_kv(o_whole, i, r, k.cpu(), v.cpu())
+                from_torch.load_kv(o_states[s], i - cuts[s][0], r, k.cpu(), v.cpu())
         o_whole.pos = kv_preload
         for st in o_states:
             st.pos = kv_preload
     calls = []
     if not kv_preload:
-        calls.append(("prefill", inputs.embeddings(w, w.batch, w.prefill, inputs.SEED_PREFILL)))
+        calls.append(("prefill", inputs.embeddings(w, w.batch, w.prefill, inputs.SEED_PREFILL, gen_device)))
     for step in range(steps):
-        calls.append(("decode", inputs.embeddings(w, w.batch, 1, inputs.SEED_DECODE0 + step)))
+        calls.append(("decode", inputs.embeddings(w, w.batch, 1, inputs.SEED_DECODE0 + step, gen_device)))
     out = []
     for kind, emb in calls:
         harness.say(f"[stage case] {kind} {tuple(emb.shape)}")
-        e64 = from_torch.to_f64(emb)
+        e64 = from_torch.to_f64(emb.cpu())
         if kind == "prefill":
             x_whole = whole.prefill(emb.to(DEV)).cpu().double().numpy()
             hand = (emb.float().to(DEV), None, None)
@@ -124,6 +124,14 @@ def test_decode_stages_match_oracle_and_one_context(harness, fused):
     preloaded caches, decode steps in the chained step, the launch list and the per-operation schedule."""
     out = run_stages(harness, R8_STAGED, [(0, 2), (2, 3), (3, 5)], kv_preload=200, steps=3, decode_fused=fused)
     check(harness, out, TOL_BF16, f"decode_fused={fused}")
+
+
+def test_decode_stages_full_width_70b_r8(harness):
+    """The headline shard's real width (hidden 8192, 8 q / 1 kv heads, intermediate 3584, batch 4, 7 peers, 1024
+    cached positions), two layers as two stages of one layer each, chained step."""
+    w = inputs.WORKLOADS["70b_r8_decode"].with_(name="r8_full_width_staged", n_layers=2, decode_steps=2)
+    out = run_stages(harness, w, [(0, 1), (1, 2)], kv_preload=w.kv_preload, steps=2, gen_device=DEV, decode_fused=3)
+    check(harness, out, TOL_BF16, "70B R = 8 width")
 
 
 def test_prefill_then_decode_stages_bf16(harness):
