@@ -307,7 +307,9 @@ int ladder_set_wait_limit(ladder_ctx* ctx, int32_t max_polls, int32_t target_bia
  * Algorithm 1 in their order, each starting when the streams it reads are complete), so events around the launch
  * say nothing about its parts.  With the timeline on, every slot records for every block the device wall-clock
  * time at which it took the block (and requested its first weight tiles), at which the block's inputs were
- * complete, and at which the block ended; ladder_timeline_read returns the records of the last step.
+ * complete, and at which the block ended; ladder_timeline_read returns the records of the last step.  (Where a
+ * launch of the list has more blocks than there are slots, the blocks beyond the slots are not dealt out beforehand
+ * but taken, one at a time, by slots that have finished their own block of that launch; those are not recorded.)
  *   out / cap   caller's array (host) and its capacity; *n_out receives the number of records of the step (call
  *               with out = NULL to size the array); records beyond cap are not written.
  *   ticks_per_us  receives the rate of the clock the times are in (may be NULL).

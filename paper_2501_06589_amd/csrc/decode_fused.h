@@ -3,7 +3,7 @@
 
 #include "common.h"
 
-enum { JOB_NONE = 0, JOB_GEMV = 1, JOB_ATTN = 2 };
+enum { JOB_NONE = 0, JOB_GEMV = 1, JOB_ATTN = 2, JOB_CLAIM = 3 };   // (JOB_CLAIM: chained steps only, see StepItem)
 enum { EPI_SWIGLU = 1, EPI_RESIDUAL = 2, EPI_QKV_ROPE = 3 };
 
 // Operands of the matrix core on this path are SPLIT: a value v travels as two bf16 numbers, high = bf16(v) and
@@ -154,7 +154,7 @@ struct AttnJob {
 #define FUSED_SYNC_WORDS 320
 #define FUSED_SYNC_FLAG_WORD 288
 
-#define FUSED_MAX_LDS_BYTES (72 * 1024)
+#define FUSED_MAX_LDS_BYTES (48 * 1024)   // (the largest job needs 36.6 KiB; two workgroups per CU must fit with the chained kernel's static 13 KiB)
 #define FUSED_MAX_JOBS 4
 
 struct FusedArgs {
@@ -184,6 +184,16 @@ struct StepItem {
   uint16_t pad0;
   uint32_t pad1;
 };
+// Where a launch of the list has more blocks than there are slots, the blocks beyond the slots (at most
+// FUSED_CLAIM_MAX of them) are not dealt out beforehand: they form the launch's surplus list, and a slot that has
+// finished its own block of that launch takes blocks from it, one at a time (an atomic counter, zero at the start of
+// the step), before it goes on to the next launch -- as a hardware dispatcher hands the next workgroup to the first
+// free CU.  A JOB_CLAIM item in a slot's list says where: wp = the surplus list (StepItem[pad1], device), xb = its
+// counter word, pad1 = its length.  The (launch, block) order that the waits rely on still holds: a block waits for
+// earlier blocks only, and the earliest unfinished block is either on a slot that has reached it or in a surplus list
+// that every slot passes after its own block of that launch.
+#define FUSED_CLAIM_MAX 384
+hipError_t fused_chain_claim_item(const StepItem* surplus_dev, unsigned* counter_dev, int n, StepItem* out);
 // the item of block lb of a job; hipErrorInvalidValue if the job is outside what the kernel has code for
 hipError_t fused_chain_item(const GemvJob& j, int job_index, int lb, StepItem* out);
 hipError_t fused_chain_attn_item(const AttnJob& a, int job_index, int lb, StepItem* out);

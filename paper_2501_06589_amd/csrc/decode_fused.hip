@@ -955,12 +955,18 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_chain_kernel(const Ste
                                                                       unsigned long long* timeline) {
   extern __shared__ float smem[];
   __shared__ unsigned s_flag;
+  __shared__ unsigned s_claim, s_claim_n;
   __shared__ uint4 s_items[2 * FUSED_CHAIN_CHUNK];
+  __shared__ uint4 s_surplus[2 * FUSED_CLAIM_MAX];
   // the job tables are read-only for the launch: scalar loads (constant address space), as for kernel arguments
   typedef __attribute__((address_space(4))) const char* const_ptr_t;
+  typedef __attribute__((address_space(1))) const char* global_ptr_t;
   const const_ptr_t gj = (const_ptr_t)(unsigned long long)gemv_jobs;
   const const_ptr_t aj = (const_ptr_t)(unsigned long long)attn_jobs;
   const uint4* mine = reinterpret_cast<const uint4*>(items + (size_t)blockIdx.x * n_items);
+  // (whether the slot is inside a surplus list is kept in LDS, not in a register that would stay live across the
+  // jobs' code: the kernel is at its register limit)
+  if (threadIdx.x == 0) s_claim_n = 0u;
   for (int it = 0; it < n_items; ++it) {
     const int ic = it % FUSED_CHAIN_CHUNK;
     if (ic == 0) {
@@ -968,14 +974,42 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_chain_kernel(const Ste
         s_items[threadIdx.x] = mine[2 * it + threadIdx.x];
       __syncthreads();
     }
-    const uint4 i0 = s_items[2 * ic], i1 = s_items[2 * ic + 1];
-    const unsigned kb = (unsigned)__builtin_amdgcn_readfirstlane((int)i1.z) & 0xFFu;
+    uint4 i0 = s_items[2 * ic], i1 = s_items[2 * ic + 1];
+    unsigned kb = (unsigned)__builtin_amdgcn_readfirstlane((int)i1.z) & 0xFFu;
     if (kb == 0u) break;
+    bool taken_block = false;
+    if ((kb & FUSED_KIND_MASK) == (unsigned)JOB_CLAIM) {
+      // a surplus list: the slot stays on this item, taking one block per visit, until the list is used up
+      const unsigned n = min((unsigned)__builtin_amdgcn_readfirstlane((int)i1.w), (unsigned)FUSED_CLAIM_MAX);
+      if (__builtin_amdgcn_readfirstlane((int)s_claim_n) == 0) {   // first visit: the list into LDS
+        const unsigned long long lp = (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)i0.x) |
+                                      ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)i0.y) << 32);
+        const uint4* list = (const uint4*)(global_ptr_t)lp;
+        for (unsigned k = threadIdx.x; k < 2u * n; k += FUSED_THREADS) s_surplus[k] = list[k];
+      }
+      if (threadIdx.x == 0) {
+        const unsigned long long cp = (unsigned long long)i0.z | ((unsigned long long)i0.w << 32);
+        s_claim = __hip_atomic_fetch_add((unsigned*)cp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      __syncthreads();     // (every thread has read s_claim_n; the list and the number taken are in LDS)
+      const unsigned taken = (unsigned)__builtin_amdgcn_readfirstlane((int)s_claim);
+      if (threadIdx.x == 0) s_claim_n = taken < n ? n : 0u;   // (read next at the next visit of a list, behind a block's barriers)
+      if (taken >= n) {
+        __syncthreads();   // (every thread has read s_claim: the next list's first visit may follow at once)
+        continue;
+      }
+      i0 = s_surplus[2 * taken];
+      i1 = s_surplus[2 * taken + 1];
+      kb = (unsigned)__builtin_amdgcn_readfirstlane((int)i1.z) & 0xFFu;
+      taken_block = true;
+      --it;   // the same item again after this block (s_claim and s_surplus are next written behind its __syncthreads)
+    }
+    // timeline (measurement; null in normal operation): when the slot took the item, when its waits were over, when it
+    // ended (blocks taken from a surplus list are not recorded)
+    unsigned long long* const tl = (timeline && !taken_block) ? timeline + ((size_t)blockIdx.x * n_items + it) * 3 : nullptr;
     const unsigned geo = (unsigned)__builtin_amdgcn_readfirstlane((int)i1.x);
     const unsigned lbj = (unsigned)__builtin_amdgcn_readfirstlane((int)i1.y);
     const int lb = (int)(lbj & 0xFFFFu), job = (int)(lbj >> 16);
-    // timeline (measurement; null in normal operation): when the slot took the item, when its waits were over, when it ended
-    unsigned long long* const tl = timeline ? timeline + ((size_t)blockIdx.x * n_items + it) * 3 : nullptr;
     if (tl && threadIdx.x == 0) tl[0] = wall_clock64();
     bool ok;
     if ((kb & FUSED_KIND_MASK) == (unsigned)JOB_ATTN) {
@@ -989,7 +1023,6 @@ __global__ __launch_bounds__(FUSED_THREADS, 4) void fused_chain_kernel(const Ste
       // (pointers into global memory, and said to be: through a pointer of unknown address space every load is a
       // flat load, which counts as an LDS and scalar-memory operation too, so that each wait for a descriptor field
       // would wait for all weight tiles in flight)
-      typedef __attribute__((address_space(1))) const char* global_ptr_t;
       const void* wp = (const void*)(global_ptr_t)wpu;
       const bf16_t* xop = (const bf16_t*)(global_ptr_t)xpu;
       const int KT = (int)(geo & 0xFFFFu), group0 = (int)(geo >> 16);
@@ -1107,6 +1140,14 @@ hipError_t fused_chain_item(const GemvJob& j, int job_index, int lb, StepItem* o
   it.wp = j.wp; it.xb = j.xb; it.kt = (uint16_t)kt; it.group0 = (uint16_t)j.group0; it.lb = (uint16_t)lb; it.job = (uint16_t)job_index;
   it.kind = (uint8_t)((unsigned)JOB_GEMV | ((unsigned)(tn - 1) << FUSED_KIND_TN_SHIFT) | (coh ? FUSED_KIND_COH : 0u));
   it.M = (uint8_t)j.M;
+  *out = it;
+  return hipSuccess;
+}
+
+hipError_t fused_chain_claim_item(const StepItem* surplus_dev, unsigned* counter_dev, int n, StepItem* out) {
+  if (!surplus_dev || !counter_dev || !out || n < 1 || n > FUSED_CLAIM_MAX) return hipErrorInvalidValue;
+  StepItem it{};
+  it.wp = surplus_dev; it.xb = reinterpret_cast<const bf16_t*>(counter_dev); it.kind = (uint8_t)JOB_CLAIM; it.pad1 = (uint32_t)n;
   *out = it;
   return hipSuccess;
 }

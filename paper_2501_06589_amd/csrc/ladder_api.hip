@@ -130,6 +130,9 @@ struct ladder_ctx {
   // MLP reader); and the rows' sums of squares per 16-column tile, [H/16][16]
   std::vector<std::array<bf16_t*, 2>> xop_ring;
   std::vector<float*> ssq_ring;
+  StepItem* chain_surplus_dev = nullptr;   // chained step: the launches' surplus lists, FUSED_CLAIM_MAX items per launch
+  unsigned* chain_claim_ctr = nullptr;     // their counters (a cache line each, in the range the embedding kernel clears)
+  int chain_launch_cap = 0;
   float* ssq_first = nullptr;   // sums of squares of what module 1 reads when its lag is 2 (x_0, or a stage's x_{-1})
   std::vector<bf16_t*> f_q, f_act;   // split q, SwiGLU output: [32][width]
   std::vector<bf16_t*> f_o;          // attention output
@@ -894,16 +897,6 @@ void build_fused_plan(ladder_ctx* c, int B) {
       // 4.06 -> 3.86 ms per step, 70B R = 4 shard at batch 16 8.89 -> 8.61; with the R = 8 shard's K range of
       // 1024, batch 8 and 16, it cost 1 - 2 %).
       if (n_splits * nkv * B + blocks_of(gu_a) + blocks_of(o) > 2 * c->n_cu && nqd >= 2048 && o.tn == 2 && o.n_groups % 2 == 0) { o.tn = 4; o.n_groups /= 2; }
-      // Chained step: a workgroup slot runs its blocks one after the other, each ending with its stores' round trip
-      // and its count before the next one's first request, so a launch of several rounds of small blocks pays
-      // that per round: gate/up takes more tiles per workgroup until the launch fits the slots (or four tiles).
-      if (c->chain)
-        while (n_splits * nkv * B + blocks_of(gu_a) + blocks_of(o) > c->chain_slots && std::max(1, gu_a.tn) < 4 &&
-               gu_a.n_groups % 2 == 0 && std::max(1, gu_a.tn) != 3) {
-          gu_a.tn = 2 * std::max(1, gu_a.tn);
-          gu_a.n_groups /= 2;
-          gu_b = gu_a;
-        }
       const int n_a = std::min(gu_a.n_groups / 2, c->n_cu / 2);   // (any position in the first half measured the same)
       gu_a.n_groups = n_a;
       gu_b.group0 = n_a; gu_b.n_groups -= n_a;
@@ -1043,6 +1036,8 @@ int build_chain(ladder_ctx* c, int B) {
   std::vector<GemvJob> gemv;
   std::vector<AttnJob> attn;
   std::vector<std::vector<StepItem>> slot((size_t)c->chain_slots);
+  std::vector<StepItem> surplus(c->fused_plan.size() * FUSED_CLAIM_MAX);
+  size_t n_surplus_lists = 0;   // launches up to the last one that has a list
   c->chain_meta.assign((size_t)c->chain_slots, {});
   int lds = 0;
   for (size_t p = 0; p < c->fused_plan.size(); ++p) {
@@ -1075,12 +1070,15 @@ int build_chain(ladder_ctx* c, int B) {
         gemv.push_back(j);
       }
     }
-    // Which slot runs which block: where a launch has more blocks than there are slots, the hardware would hand the
-    // next block to the first workgroup slot that becomes free; here each block goes, in block order, to the slot
-    // with the least work of this launch so far (a block's work: its weight bytes plus a fixed part; ties: the
-    // lowest slot).  Up to n_slots blocks that is block b on slot b.
+    // Which slot runs which block: block b < n_slots on slot b.  Where a launch has more blocks than there are slots,
+    // the hardware would hand the next block to the first workgroup slot that becomes free: the last FUSED_CLAIM_MAX
+    // of the blocks beyond the slots form the launch's surplus list, from which the slots take blocks as they finish
+    // (decode_fused.h); any blocks between the two go, in block order, to the slot with the least work of this launch
+    // so far (a block's work: its weight bytes plus a fixed part; ties: the lowest slot).
     const int total = fa.block_end[fa.n_jobs - 1];
     std::vector<long long> load((size_t)c->chain_slots, 0);
+    const int n_dyn = std::min(std::max(0, total - c->chain_slots), (int)FUSED_CLAIM_MAX);
+    if (n_dyn > 0 && (int)p >= c->chain_launch_cap) return fail(c, LADDER_E_ARG, "chained step: more launches than surplus lists sized at init");
     for (int b = 0, k = 0; b < total; ++b) {
       while (b >= fa.block_end[k]) ++k;
       const int lb = b - (k > 0 ? fa.block_end[k - 1] : 0);
@@ -1091,12 +1089,16 @@ int build_chain(ladder_ctx* c, int B) {
       const long long att_work = fa.kind[0] == JOB_ATTN ? (96 + 128) * 1024 : 0;
       const long long work = fa.kind[k] == JOB_ATTN ? att_work
                              : 96 * 1024 + (long long)std::max(1, fa.g[k].tn) * fa.g[k].K * 32 + (fa.g[k].after_attention ? att_work : 0);
-      const int sl = b < c->chain_slots ? b : (int)(std::min_element(load.begin(), load.end()) - load.begin());
-      load[(size_t)sl] += work;
       StepItem it{};
       const hipError_t e = fa.kind[k] == JOB_ATTN ? fused_chain_attn_item(attn[(size_t)job_index[k]], job_index[k], lb, &it)
                                                   : fused_chain_item(gemv[(size_t)job_index[k]], job_index[k], lb, &it);
       if (e != hipSuccess) return fail(c, LADDER_E_ARG, "chained step: a job of the launch list is outside what the kernel runs");
+      if (b >= total - n_dyn) {
+        surplus[p * FUSED_CLAIM_MAX + (size_t)(b - (total - n_dyn))] = it;
+        continue;
+      }
+      const int sl = b < c->chain_slots ? b : (int)(std::min_element(load.begin(), load.end()) - load.begin());
+      load[(size_t)sl] += work;
       slot[(size_t)sl].push_back(it);
       ladder_ctx::ChainMeta meta{(int)p, LADDER_TL_ATTN, 0, 0};
       if (fa.kind[k] == JOB_GEMV) {
@@ -1106,6 +1108,16 @@ int build_chain(ladder_ctx* c, int B) {
         meta.weight_bytes = (long long)meta.tiles * j.K * 32;
       }
       c->chain_meta[(size_t)sl].push_back(meta);
+    }
+    if (n_dyn > 0) {
+      StepItem it{};
+      if (fused_chain_claim_item(c->chain_surplus_dev + p * FUSED_CLAIM_MAX, c->chain_claim_ctr + p * 32, n_dyn, &it) != hipSuccess)
+        return fail(c, LADDER_E_ARG, "chained step: a surplus list is outside what the kernel runs");
+      for (size_t w = 0; w < slot.size(); ++w) {
+        slot[w].push_back(it);
+        c->chain_meta[w].push_back(ladder_ctx::ChainMeta{(int)p, -1, 0, 0});   // (not a block: skipped by the timeline)
+      }
+      n_surplus_lists = p + 1;
     }
   }
   size_t n_items = 0;
@@ -1119,6 +1131,7 @@ int build_chain(ladder_ctx* c, int B) {
   HIP_TRY(c, hipMemcpy(c->chain_items_dev, flat.data(), flat.size() * sizeof(StepItem), hipMemcpyHostToDevice));
   HIP_TRY(c, hipMemcpy(c->chain_gemv_dev, gemv.data(), gemv.size() * sizeof(GemvJob), hipMemcpyHostToDevice));
   if (!attn.empty()) HIP_TRY(c, hipMemcpy(c->chain_attn_dev, attn.data(), attn.size() * sizeof(AttnJob), hipMemcpyHostToDevice));
+  if (n_surplus_lists) HIP_TRY(c, hipMemcpy(c->chain_surplus_dev, surplus.data(), n_surplus_lists * FUSED_CLAIM_MAX * sizeof(StepItem), hipMemcpyHostToDevice));
   c->chain_items = (int)n_items;
   c->chain_lds = lds;
   return LADDER_OK;
@@ -1537,8 +1550,9 @@ static int init_impl(const ladder_config* cfg, void* hip_stream, ladder_ctx** ou
       if (c->chain) {
         // persistent workgroups: as many as are resident together (a sizing pass assumes two per CU)
         c->chain_slots = c->dry ? 2 * c->n_cu : fused_chain_slots(d, (int)gq, c->n_cu);
-        if (c->chain_slots <= 0) {
-          c->err = "the chained decode kernel does not fit this device";
+        // (the launch lists are laid out for two resident workgroups per CU; with one, a step takes half as long again)
+        if (c->chain_slots < 2 * c->n_cu) {
+          c->err = "the chained decode kernel does not fit this device with two workgroups per CU";
           return bail(LADDER_E_HIP);
         }
         c->ring_n = c->n_mod + 1;
@@ -1566,9 +1580,11 @@ static int init_impl(const ladder_config* cfg, void* hip_stream, ladder_ctx** ou
       INIT_TRY(dev_alloc(c, (void**)&c->t_done, (size_t)(c->n_mod + 1) * 8, true));
       // arrival counters of the attention jobs (a cache line each) and, for a chained step, the completion words of
       // its projections behind them: one range, cleared by the embedding kernel at the start of every step
-      c->n_zero_words = g.n_layers * FUSED_SYNC_WORDS * (c->chain ? 5 : 1);
+      c->chain_launch_cap = c->chain ? 5 * g.n_layers + 1 : 0;
+      c->n_zero_words = g.n_layers * FUSED_SYNC_WORDS * (c->chain ? 5 : 1) + c->chain_launch_cap * 32;
       INIT_TRY(dev_alloc(c, (void**)&c->att_done, (size_t)c->n_zero_words * 4, true));
       c->sync_words = c->att_done + (size_t)g.n_layers * FUSED_SYNC_WORDS;
+      c->chain_claim_ctr = c->att_done + (size_t)g.n_layers * FUSED_SYNC_WORDS * 5;   // (behind the projections' words)
       if (c->chain) {
         // tables of the persistent launch, sized for the longest launch list a batch can have: at most 5 N + 1
         // launches, whose blocks (all projections' tiles and the attention workgroups) are dealt out over the slots
@@ -1579,6 +1595,7 @@ static int init_impl(const ladder_config* cfg, void* hip_stream, ladder_ctx** ou
         INIT_TRY(dev_alloc(c, (void**)&c->chain_items_dev, (size_t)c->chain_slots * c->chain_items_cap * sizeof(StepItem), false));
         INIT_TRY(dev_alloc(c, (void**)&c->chain_gemv_dev, (size_t)c->chain_gemv_cap * sizeof(GemvJob), false));
         INIT_TRY(dev_alloc(c, (void**)&c->chain_attn_dev, (size_t)c->chain_attn_cap * sizeof(AttnJob), false));
+        INIT_TRY(dev_alloc(c, (void**)&c->chain_surplus_dev, (size_t)c->chain_launch_cap * FUSED_CLAIM_MAX * sizeof(StepItem), false));
       }
       // arrival tickets start at zero and are put back to zero by the last arrival of every launch
       INIT_TRY(dev_alloc(c, (void**)&c->tk_att, (size_t)g.max_batch * nkv * 4, true));
@@ -1984,8 +2001,9 @@ int ladder_timeline_read(ladder_ctx* c, ladder_timeline_rec* out, int64_t cap, i
   int64_t n = 0;
   for (size_t w = 0; w < c->chain_meta.size(); ++w)
     for (size_t i = 0; i < c->chain_meta[w].size(); ++i, ++n) {
-      if (!out || n >= cap) continue;
       const ladder_ctx::ChainMeta& m = c->chain_meta[w][i];
+      if (m.kind < 0) { --n; continue; }   // (a surplus list's item: its blocks are not recorded)
+      if (!out || n >= cap) continue;
       const unsigned long long* ts = t.data() + (w * n_items + i) * 3;
       out[n] = ladder_timeline_rec{(int32_t)w, m.launch, m.kind, m.tiles, m.weight_bytes, ts[0], ts[1], ts[2]};
     }

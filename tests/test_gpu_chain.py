@@ -80,6 +80,34 @@ def test_chained_step_long_context_split_attention(harness, kv, batch, nq, nkv, 
         assert np.array_equal(x, y)
 
 
+def test_chained_step_launches_with_more_blocks_than_slots(harness):
+    """A launch list whose launches have more blocks than the device has workgroup slots (576 gate/up tiles + 128 workgroups of the output
+    projection + attention against 512 slots): the blocks beyond the slots sit in the launch's surplus list and are taken
+    by whichever slot gets there first.  Which slot runs a block changes nothing in its arithmetic: against the oracle,
+    bit for bit against separate launches, and the same bits again on a second run."""
+    w = R8_SMALL.with_(name="r8_surplus_chain", n_layers=2, hidden=4096, inter=4608, batch=8, decode_steps=3)
+    res = harness.run_case(w, kv_preload=300, decode_fused=3)
+    assert len(res.errs) == 3 and max(res.errs) < TOL_BF16, res.errs
+    ref = harness.run_case(w, kv_preload=300, gpu_only=True, decode_fused=1)
+    again = harness.run_case(w, kv_preload=300, gpu_only=True, decode_fused=3, decode_graph=1)
+    for x, y, z in zip(res.gpu, ref.gpu, again.gpu):
+        assert np.array_equal(x, y) and np.array_equal(x, z)
+    # the timeline records the blocks that were dealt out beforehand only: fewer gate/up tiles than the layers have
+    tensors = harness.make_tensors(w)
+    ctx = harness.build_gpu(w, tensors, inputs.peer_partials(w, w.batch), max_seq=400, decode_fused=3)
+    for i in range(w.n_layers):
+        k, v = inputs.kv_cache(w, i, 0, w.batch, 50)
+        ctx.load_kv(i, 0, k.to("cuda:0"), v.to("cuda:0"))
+    x = inputs.embeddings(w, w.batch, 1, inputs.SEED_DECODE0)[:, 0].contiguous().to("cuda:0")
+    ctx.timeline_enable(True)
+    ctx.decode_step(x)
+    rec, _ = ctx.timeline()
+    gu = rec[rec["kind"] == 3]
+    assert 0 < gu["tiles"].sum() < 2 * w.inter // 16 * w.n_layers, gu["tiles"].sum()
+    assert rec["slot"].max() + 1 == 2 * torch.cuda.get_device_properties(0).multi_processor_count
+    ctx.free()
+
+
 def test_chained_step_with_emulated_collective_latency_same_bits(harness):
     """reduce_delay_us on a chained step: the projections that read a stream hold back until its emulated
     collective is over; the arithmetic does not change."""
