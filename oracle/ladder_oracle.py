@@ -23,7 +23,7 @@ section "Tensor Parallelism Background" for the sharding rule and Eq. 1):
     three tensors Algorithm 1 passes from block to block (section "Compatibility
     with other Parallelism Techniques").
 
-Readings where the paper is silent (all listed in the design document):
+Readings where the paper is silent:
 modules 1 and 2 both read x_0; after the last layer the two outstanding module
 outputs are added (x_2N); RMSNorm with eps inside the square root; rotary
 embedding on adjacent pairs (2j, 2j+1) with angle pos * theta^(-2j/d) and no

@@ -16,7 +16,7 @@ step relies on wrap-around.  A tensor that must be identical on both sides is
 generated once and copied, never generated twice on different devices
 (float64 log/cos may differ by an ulp between libraries).
 
-Recipe (stated again in the design document): projection weights N(0, 0.02^2);
+Recipe: projection weights N(0, 0.02^2);
 norm gains 1 + 0.02*N(0,1) (so that a forgotten gain multiply is visible);
 input embeddings N(0,1); synthetic peer partials N(0, 0.02^2); synthetic
 KV-cache entries N(0,1).  Seeds: 0 weights, 1 prefill embeddings, 2+step
