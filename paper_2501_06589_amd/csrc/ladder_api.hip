@@ -746,9 +746,11 @@ void build_fused_plan(ladder_ctx* c, int B) {
     // tiles: 70B shard at R = 8, batch 4: 3.51 -> 3.41 ms)
     // (measured: batch 1 - 6 faster, 7 - 12 slower)
     if ((B >= 13 || H <= 2048 || (j.n_groups / 2 <= c->n_cu && B <= 6)) && j.n_groups % 2 == 0) { j.tn = 2; j.n_groups /= 2; }
-    // (13 rows and more, and enough tiles that quadruples still give most CUs a workgroup: four tiles per
-    // workgroup halve the operand traffic once more)
-    if (B >= 13 && j.tn == 2 && j.n_groups % 2 == 0 && 4 * (j.n_groups / 2) >= 3 * c->n_cu) { j.tn = 4; j.n_groups /= 2; }
+    // (13 rows and more, and more pairs than the chip holds workgroups: four tiles per workgroup halve the operand
+    // traffic once more.  Where the pairs fit, quadruples leave CUs without a workgroup: 70B R = 4 shard at batch 16,
+    // 448 pairs against 224 quadruples: chained step 8.36 against 10.30 ms, separate launches 9.15 against 9.17; 8B
+    // shape at batch 16, 896 pairs against 448 quadruples: 3.91 against 3.88 and 4.06 against 4.00)
+    if (B >= 13 && j.tn == 2 && j.n_groups % 2 == 0 && j.n_groups > 2 * c->n_cu) { j.tn = 4; j.n_groups /= 2; }
     return j;
   };
   auto job_dn = [&](int l, int m, int at = -1) {

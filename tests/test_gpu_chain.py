@@ -58,7 +58,7 @@ def test_chained_step_other_geometries(harness):
                                                  inter=512, batch=16, prefill=0, kv_preload=70, decode_steps=3)
     res = harness.run_case(w, kv_preload=70, decode_fused=3)
     assert max(res.errs) < TOL_BF16, res.errs
-    w = R8_SMALL.with_(name="r8_small_gu4_chain", inter=6144, batch=14, decode_steps=3)
+    w = R8_SMALL.with_(name="r8_small_gu4_chain", inter=8704, batch=14, decode_steps=3)
     res = harness.run_case(w, kv_preload=100, decode_fused=3)
     assert len(res.errs) == 3 and max(res.errs) < TOL_BF16, res.errs
     w = R8_SMALL.with_(name="r8_small_b1_chain", batch=1, decode_steps=3)

@@ -278,8 +278,9 @@ def test_fused_decode_matches_oracle(harness, wiring, nstd):
 
 
 def test_fused_decode_four_tile_gate_up_at_large_batch(harness):
-    """13 rows and more with enough gate/up tiles (here 768 on 256 CUs): four tiles per workgroup."""
-    w = R8_SMALL.with_(name="r8_small_gu4", inter=6144, batch=14, decode_steps=3)
+    """13 rows and more with more pairs of gate/up tiles than the chip holds workgroups (here 544 pairs, 512 slots): four
+    tiles per workgroup."""
+    w = R8_SMALL.with_(name="r8_small_gu4", inter=8704, batch=14, decode_steps=3)
     res = harness.run_case(w, kv_preload=100, decode_fused=1)
     assert len(res.errs) == 3 and max(res.errs) < TOL_BF16, res.errs
 
