@@ -899,6 +899,15 @@ void build_fused_plan(ladder_ctx* c, int B) {
       // 4.06 -> 3.86 ms per step, 70B R = 4 shard at batch 16 8.89 -> 8.61; with the R = 8 shard's K range of
       // 1024, batch 8 and 16, it cost 1 - 2 %).
       if (n_splits * nkv * B + blocks_of(gu_a) + blocks_of(o) > 2 * c->n_cu && nqd >= 2048 && o.tn == 2 && o.n_groups % 2 == 0) { o.tn = 4; o.n_groups /= 2; }
+      // Chained step: a slot ends every block with its stores' round trip and its count before it asks for the next
+      // one, so where single gate/up tiles make more blocks than there are slots, pairs (same sums in the same order:
+      // same bits).  8B shape at batch 1 / 4 / 8: 2.52 / 2.75 / 3.22 -> 2.46 / 2.64 / 3.02 ms per step; R = 8 shard at
+      // batch 8 / 12: 4.24 / 5.83 -> 3.98 / 4.67; quadruples instead: slower than pairs, except the 8B shape at batch 8
+      // (3.00).  With separate launches the hardware refills a slot at once and single tiles stay ahead at 7 - 12 rows.
+      if (c->chain && std::max(1, gu_a.tn) == 1 && gu_a.n_groups % 2 == 0 &&
+          n_splits * nkv * B + blocks_of(gu_a) + blocks_of(o) > c->chain_slots) {
+        gu_a.tn = 2; gu_a.n_groups /= 2; gu_b = gu_a;
+      }
       const int n_a = std::min(gu_a.n_groups / 2, c->n_cu / 2);   // (any position in the first half measured the same)
       gu_a.n_groups = n_a;
       gu_b.group0 = n_a; gu_b.n_groups -= n_a;

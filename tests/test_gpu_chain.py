@@ -81,11 +81,12 @@ def test_chained_step_long_context_split_attention(harness, kv, batch, nq, nkv, 
 
 
 def test_chained_step_launches_with_more_blocks_than_slots(harness):
-    """A launch list whose launches have more blocks than the device has workgroup slots (576 gate/up tiles + 128 workgroups of the output
-    projection + attention against 512 slots): the blocks beyond the slots sit in the launch's surplus list and are taken
-    by whichever slot gets there first.  Which slot runs a block changes nothing in its arithmetic: against the oracle,
-    bit for bit against separate launches, and the same bits again on a second run."""
-    w = R8_SMALL.with_(name="r8_surplus_chain", n_layers=2, hidden=4096, inter=4608, batch=8, decode_steps=3)
+    """A launch list whose launches have more blocks than the device has workgroup slots (512 pairs of gate/up tiles +
+    128 workgroups of the output projection + attention against 512 slots): the blocks beyond the slots sit in the
+    launch's surplus list and are taken by whichever slot gets there first.  Which slot runs a block changes nothing in
+    its arithmetic, nor does it that the chained step takes the gate/up tiles in pairs where separate launches take
+    them one by one: against the oracle, bit for bit against separate launches, and the same bits again on a second run."""
+    w = R8_SMALL.with_(name="r8_surplus_chain", n_layers=2, hidden=4096, inter=8192, batch=8, decode_steps=3)
     res = harness.run_case(w, kv_preload=300, decode_fused=3)
     assert len(res.errs) == 3 and max(res.errs) < TOL_BF16, res.errs
     ref = harness.run_case(w, kv_preload=300, gpu_only=True, decode_fused=1)
