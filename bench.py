@@ -37,7 +37,8 @@ def log(msg):
     print(msg, file=sys.stderr, flush=True)
 
 
-def build_context(w, device, extra_seq, peers_rows, **override):
+def build_context(w, device, extra_seq, peers_rows, layer0=0, **override):
+    """A context with the workload's layers layer0 .. layer0 + w.n_layers - 1 (layer0 > 0: a later pipeline stage)."""
     import torch
     from paper_2501_06589_amd import inputs, ladder
     cfg = ladder.config_for(w, max_seq=w.prefill + w.kv_preload + extra_seq, **override)
@@ -45,7 +46,7 @@ def build_context(w, device, extra_seq, peers_rows, **override):
     t0 = time.time()
     for i in range(w.n_layers):
         for r in range(w.n_real_shards):
-            ctx.load_layer(i, r, inputs.layer_weights(w, i, r, device))
+            ctx.load_layer(i, r, inputs.layer_weights(w, layer0 + i, r, device))
         if i % 16 == 15:
             torch.cuda.synchronize()
             log(f"[bench] weights: {i + 1}/{w.n_layers} layers generated and packed ({time.time() - t0:.1f}s)")
@@ -274,6 +275,71 @@ def run_decode(args):
     }
 
 
+def run_decode_stages(args):
+    """Decode steps through a pipeline of --stages contexts on the one GPU, each holding a run of the workload's layers
+    and handing residual, attention output and MLP output to the next one in device memory (section "Compatibility
+    with other Parallelism Techniques"): what the stage boundary costs beside the same layers in one context."""
+    import torch
+    from paper_2501_06589_amd import inputs, ladder
+    w = inputs.WORKLOADS[args.workload]
+    if args.layers:
+        w = w.with_(n_layers=args.layers)
+    if args.batch:
+        w = w.with_(batch=args.batch)
+    if args.kv and w.kv_preload:
+        w = w.with_(kv_preload=args.kv)
+    if not w.kv_preload:
+        raise SystemExit("--stages needs a workload with a preloaded cache (70b_r8_decode)")
+    dev = "cuda:0"
+    total_steps = args.warmup + args.steps
+    k = args.stages
+    cuts = [(w.n_layers * s // k, w.n_layers * (s + 1) // k) for s in range(k)]
+    plan = 0 if args.no_fused else {"paired": 1, "single": 2, "chain": 3}[args.fused_plan]
+    stages = [build_context(w.with_(n_layers=b - a), dev, total_steps, w.batch, layer0=a, max_tokens=1, decode_fused=plan)
+              for a, b in cuts]
+    kv = [[inputs.kv_cache(w, i, r, w.batch, w.kv_preload, dev) for r in range(w.n_real_shards)] for i in range(w.n_layers)]
+
+    def reset_cache():
+        for s, (a, b) in enumerate(cuts):
+            for i in range(a, b):
+                for r in range(w.n_real_shards):
+                    stages[s].load_kv(i - a, r, kv[i][r][0], kv[i][r][1])
+
+    xs = torch.stack([inputs.embeddings(w, w.batch, 1, inputs.SEED_DECODE0 + i, dev)[:, 0] for i in range(total_steps)]).float()
+    out = None
+
+    def step(i):
+        nonlocal out
+        hand = (xs[i], None, None)
+        for ctx in stages:
+            hand = ctx.decode_step_stage(hand)
+        out = hand[0] + hand[1] + hand[2]          # x_2N
+
+    rep_ms = []
+    for rep in range(max(1, args.reps)):
+        reset_cache()
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(args.warmup + i)
+        torch.cuda.synchronize()
+        rep_ms.append((time.perf_counter() - t0) * 1e3 / args.steps)
+        assert torch.isfinite(out).all()
+    ms_per_step = sorted(rep_ms)[len(rep_ms) // 2]
+    for ctx in stages:
+        ctx.free()
+    return {
+        "metric": "decode_tokens_per_s", "value": w.batch / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "repetitions": {"n": len(rep_ms), "ms_per_step": rep_ms, "reported": "median"},
+        "config": {"workload": w.name, "n_layers": w.n_layers, "batch": w.batch, "pipeline_stages": k, "layers_per_stage": [b - a for a, b in cuts],
+                   "note": "all stages on the one GPU, one after the other; the hand-over stays in device memory"},
+    }
+
+
 def run_prefill(args):
     import torch
     from paper_2501_06589_amd import inputs, ladder
@@ -374,6 +440,9 @@ def main():
                     help="decode mode: generate for real (token embedding -> stack -> final norm + output projection of "
                          "this rank's vocabulary slice -> greedy token, fed back); the metric is quoted without it")
     ap.add_argument("--no-fused", action="store_true", help="one kernel per operation instead of the fused decode launches")
+    ap.add_argument("--stages", type=int, default=0,
+                    help="decode: the workload's layers as this many pipeline-stage contexts that hand residual, attention "
+                         "output and MLP output to one another (ladder_decode_step_stage); prints the step time only")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (one process, one MI355X); "
@@ -385,6 +454,9 @@ def main():
         steps_given, warmup_given = args.steps, args.warmup
         args.steps = 256 if args.steps is None else args.steps
         args.warmup = 16 if args.warmup is None else args.warmup
+        if args.stages > 0:
+            print(json.dumps(run_decode_stages(args)))
+            return
         res = run_decode(args)
         if both:
             # the other half of the metric: the prefill workload on a fresh context (the decode context has been freed)
