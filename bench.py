@@ -129,7 +129,7 @@ def run_decode(args):
     total_steps = args.warmup + args.steps + prof_steps
     reps = max(1, args.reps)
     # the peer tensor must hold as many rows per set as the configuration announces (peer_rows)
-    ctx = build_context(w, dev, total_steps, w.batch * max(w.prefill, 1), max_tokens=max(w.prefill, 1),
+    ctx = build_context(w, dev, total_steps + (3 if args.timeline else 0), w.batch * max(w.prefill, 1), max_tokens=max(w.prefill, 1),
                         decode_graph=1 if args.graph else 0, overlap_modules=0 if args.no_overlap else 1,
                         decode_fused=0 if args.no_fused else {"paired": 1, "single": 2, "chain": 3}[args.fused_plan],
                         reduce_delay_us=args.reduce_delay_us, n_standard_layers=args.standard_layers,
@@ -252,6 +252,7 @@ def run_decode(args):
                 "frac_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS}
     per_class = {k: {"launches": n, "avg_us": (ms / n * 1e3 if n else 0.0), "ms_per_step": ms / prof_steps}
                  for k, (n, ms) in prof.items() if n}
+    timeline = chain_timeline(ctx, xs[args.warmup], out) if (args.timeline and chained) else None
     ctx.free()
     del ctx, kv
     torch.cuda.empty_cache()
@@ -272,7 +273,44 @@ def run_decode(args):
                 "measured_copy_GBps": copy_gbps,
                 "frac_of_measured_copy_whole_step": (whole_gbps / copy_gbps) if copy_gbps else None},
         "roofline": roofline, "kernel_classes": per_class, "cpu_baseline": cpu,
+        **({"timeline": timeline} if timeline else {}),
     }
+
+
+def chain_timeline(ctx, x, out):
+    """Inside a chained decode step (one launch, so events around it say nothing about its parts): the library's
+    timeline of one step, reduced to the steady state of the middle layers.  Per kind of job the time from its first
+    block's inputs being complete to its last block's end, the distance between consecutive layers, and the two phases
+    of a ladder layer: {attention -> o || gate/up} and {qkv || down}.  Microseconds."""
+    import numpy as np
+    for _ in range(2):
+        ctx.decode_step(x, out)
+    ctx.timeline_enable(True)
+    ctx.decode_step(x, out)
+    rec, rate = ctx.timeline()
+    ctx.timeline_enable(False)
+    names = ["attention", "qkv", "o", "gate_up", "down"]
+    launches = sorted(set(rec["launch"].tolist()))
+    mid = [L for L in launches if len(launches) // 4 <= launches.index(L) < 3 * len(launches) // 4]
+    span = {}
+    for L in mid:
+        for k in range(5):
+            r = rec[(rec["launch"] == L) & (rec["kind"] == k)]
+            if len(r):
+                span[(L, k)] = (float(r["t_ready"].min()) / rate, float(r["t_end"].max()) / rate, int(len(r)))
+    dur = {names[k]: [e - b for (L, kk), (b, e, n) in span.items() if kk == k] for k in range(5)}
+    att = sorted(L for (L, k) in span if k == 0)
+    period = [span[(b, 0)][0] - span[(a, 0)][0] for a, b in zip(att, att[1:])]
+    # phases of a ladder layer: launch L holds attention, gate/up and o; launch L + 1 the next layer's qkv and down
+    ph_a = [max(span[(L, 2)][1], span[(L, 3)][1]) - min(span[(L, 0)][0], span[(L, 3)][0]) for L in att if (L, 2) in span and (L, 3) in span]
+    ph_b = [max(span[(L + 1, 1)][1], span[(L + 1, 4)][1]) - min(span[(L + 1, 1)][0], span[(L + 1, 4)][0])
+            for L in att if (L + 1, 1) in span and (L + 1, 4) in span]
+    mean = lambda v: (sum(v) / len(v)) if v else None
+    return {"unit": "us", "layers_averaged": len(att), "blocks_recorded": int(len(rec)),
+            "period_per_layer": mean(period),
+            "first_ready_to_last_end": {k: mean(v) for k, v in dur.items() if v},
+            "phase_attention_o_beside_gate_up": mean(ph_a), "phase_qkv_beside_down": mean(ph_b),
+            "note": "blocks taken from a launch's surplus list are not recorded"}
 
 
 def run_decode_stages(args):
@@ -440,6 +478,8 @@ def main():
                     help="decode mode: generate for real (token embedding -> stack -> final norm + output projection of "
                          "this rank's vocabulary slice -> greedy token, fed back); the metric is quoted without it")
     ap.add_argument("--no-fused", action="store_true", help="one kernel per operation instead of the fused decode launches")
+    ap.add_argument("--timeline", action="store_true",
+                    help="decode, chained step: add the library's timeline of one step (per kind of job and per phase of a layer)")
     ap.add_argument("--stages", type=int, default=0,
                     help="decode: the workload's layers as this many pipeline-stage contexts that hand residual, attention "
                          "output and MLP output to one another (ladder_decode_step_stage); prints the step time only")
